@@ -1,0 +1,248 @@
+/*
+ * compressed_layer.h - C ABI of the MI355X compressed-layer inference library.
+ *
+ * The library runs a fully-connected or convolutional layer directly from its
+ * compressed form: pruned weights kept as relative-indexed entries per block,
+ * value indices into a shared-weight codebook, and both entry arrays Huffman
+ * coded (Sec. III-B and IV-A of "Efficient Inferencing of Compressed Deep Neural
+ * Networks").  Decoding, codebook lookup and the sparse-weight x dense-activation
+ * product all run in HIP kernels written for gfx950.
+ *
+ * Conventions
+ *  - Plain C.  Every function returns an int32_t status: CL_OK (0) or a negative
+ *    CL_E* code; cl_last_error() gives a thread-local message for the last
+ *    failure on the calling thread.  Nothing aborts or throws across the ABI.
+ *  - "host" pointers are ordinary CPU memory; "device" pointers (prefix d_) are
+ *    GPU global memory of the current HIP device.  All tensors are owned by the
+ *    caller; cl_layer handles are owned by the library and released with
+ *    cl_layer_free().
+ *  - Device entry points enqueue work on the given hipStream_t (passed as
+ *    void*, NULL = the null stream) and return without synchronising.
+ *  - Matrices are row-major.  W is M x K (outputs x inputs), activations are
+ *    X[B][K] and Y[B][M] (one image per row).
+ *  - Without a usable HIP device the device entry points fail with CL_EHIP; there
+ *    is no CPU fallback.
+ */
+#ifndef COMPRESSED_LAYER_H
+#define COMPRESSED_LAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CL_OK = 0,
+    CL_EINVAL = -1,       /* bad argument (null pointer, size out of range, ...)   */
+    CL_ENOMEM = -2,       /* host or device allocation failed                      */
+    CL_ECORRUPT = -3,     /* a serialized layer failed validation                  */
+    CL_EUNSUPPORTED = -4, /* valid request this build cannot serve                 */
+    CL_EHIP = -5          /* a HIP runtime call failed / no device                 */
+};
+
+/* Bits per chunk of the compressed stream; the only value this build accepts. */
+#define CL_CHUNK_BITS 4096
+/* No chunk holds more entries than this. */
+#define CL_MAX_CHUNK_ENTRIES 1024
+/* Longest Huffman codeword the format allows. */
+#define CL_MAX_CODE_LEN 12
+
+/* Kernel selection for the forward entry points. */
+enum {
+    CL_PATH_AUTO = 0,     /* library picks from batch size and layer density        */
+    CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
+    CL_PATH_MFMA_F32 = 2  /* decode blocks to dense LDS tiles, fp32 MFMA             */
+};
+
+/* How a weight matrix is compressed.
+ *  M, K          W is M x K; the layer computes b = W a + v (Eq. 1-2).
+ *  weight_bits   r: a value index has r bits, i.e. at most 2^r - 1 shared non-zero
+ *                values plus the reserved index 0 (Sec. III-B; 5 for FC, 8 for
+ *                CONV layers in Sec. V-A).  1..8.
+ *  index_bits    k: a relative index has k bits; a run of more than 2^k - 1 zeros
+ *                is broken by padding entries (Sec. III-B; 4 AlexNet, 5 VGG-16).
+ *                1..8.
+ *  block_h/w     bh x bw blocks, stored contiguously block after block in the
+ *                order Algorithm 2 visits them (Sec. IV-A).  Inside a block the
+ *                positions run down the rows of a column first, so the relative
+ *                index is a row gap; (M, 1) gives plain CSC columns.  Edge blocks
+ *                keep their true, smaller shape.
+ *  chunk_bits    must be CL_CHUNK_BITS (0 is taken as that).
+ *  max_code_len  limit on Huffman codeword length, 0 = CL_MAX_CODE_LEN; must be
+ *                >= max(weight_bits, index_bits) and <= CL_MAX_CODE_LEN. */
+typedef struct {
+    int32_t M, K;
+    int32_t weight_bits;
+    int32_t index_bits;
+    int32_t block_h, block_w;
+    int32_t chunk_bits;
+    int32_t max_code_len;
+} cl_layer_desc;
+
+typedef struct cl_layer cl_layer;
+
+/* Size and content figures of a compressed layer. */
+typedef struct {
+    int64_t nnz;            /* surviving weights                                     */
+    int64_t padding;        /* padding entries (value index 0)                       */
+    int64_t entries;        /* nnz + padding                                         */
+    int64_t n_blocks;
+    int64_t n_chunks;
+    int64_t val_bits;       /* Huffman-coded bits of the value-index array           */
+    int64_t idx_bits;       /* Huffman-coded bits of the relative-index array        */
+    int64_t val_bits_unlimited; /* same arrays under unrestricted Huffman codes:     */
+    int64_t idx_bits_unlimited; /*   what the length limit costs                     */
+    int64_t payload_bytes;  /* chunk payloads (512 B each)                           */
+    int64_t table_bytes;    /* chunk table + lane gaps + block_ptr + panel table     */
+    int64_t model_bytes;    /* payload + tables + codebook + code lengths: the bytes */
+                            /*   a forward pass has to fetch                         */
+    int64_t lut_bytes;      /* decode tables derived at load time (not stored)       */
+    int32_t val_max_len, idx_max_len;
+} cl_stats;
+
+/* One record per chunk (plus one sentinel record at index n_chunks whose sym_off
+ * is the total entry count).  A chunk is 4096 bits: the value-index codewords of
+ * entries [sym_off, next sym_off) from bit 0, then - from the next multiple of 64
+ * bits - the relative-index codewords of the same entries.  This pair of start
+ * addresses is the per-chunk form of the row_ptr 2-tuple of Sec. III-B.
+ *  blk0    block that entry sym_off belongs to
+ *  pos0    sum of (z + 1) over the entries of block blk0 that precede the chunk,
+ *          i.e. the carry of the position prefix sum (Algorithm 1 step 7)         */
+typedef struct {
+    uint32_t sym_off;
+    uint32_t blk0;
+    uint32_t pos0;
+    uint16_t val_bits;
+    uint16_t idx_bits;
+} cl_chunk_meta;
+
+/* Read-only view of the host copy of a layer, for inspection and tests.  The
+ * pointers stay valid until cl_layer_free().
+ *  val_code / idx_code   codeword of each symbol with bit j = the j-th bit written
+ *                        to the stream; stream bit b is bit (b mod 8) of byte b/8.
+ *  lane_gap              32 bytes per chunk; nibble l (low nibble first) is, for
+ *                        the 64-bit slice l of the chunk, the distance from the
+ *                        slice start to the first codeword that starts in it.     */
+typedef struct {
+    cl_layer_desc desc;
+    const float *codebook;         /* 2^r                                            */
+    const uint8_t *val_len;        /* 2^r                                            */
+    const uint32_t *val_code;      /* 2^r                                            */
+    const uint8_t *idx_len;        /* 2^k                                            */
+    const uint32_t *idx_code;      /* 2^k                                            */
+    const uint32_t *block_ptr;     /* n_blocks + 1, entry offsets                    */
+    const uint32_t *panel_chunk;   /* n_panels + 1, first chunk of each block row    */
+    const cl_chunk_meta *chunk_meta; /* n_chunks + 1                                 */
+    const uint8_t *lane_gap;       /* 32 * n_chunks                                  */
+    const uint8_t *payload;        /* 512 * n_chunks (+ 16 bytes of zero padding)    */
+    int64_t n_blocks, n_chunks, n_entries;
+    int32_t n_panels;
+} cl_host_view;
+
+const char *cl_last_error(void);
+
+/* Sec. III-B pipeline on the host: quantise the surviving weights of W to the
+ * codebook, build the relative-indexed entries block by block, Huffman-code both
+ * arrays (length-limited, canonical) and lay the codewords out in 4096-bit chunks
+ * with their chunk table.
+ *  W_host      M*K fp32, already pruned: a pruned weight is exactly 0.  Non-finite
+ *              values are rejected.
+ *  codebook    2^r fp32 with codebook[0] == 0, or NULL for a linear codebook:
+ *              2^r - 1 centres equally spaced between the smallest and largest
+ *              surviving weight.  Each surviving weight takes the nearest centre
+ *              (fp64 distance, ties to the lower index) among indices 1..2^r - 1.
+ *  out         receives a new handle (host copy only; see cl_layer_upload).
+ * Errors: CL_EINVAL for bad descriptors (including M*K or the entry count
+ * exceeding 2^31 - 1), null pointers, non-finite weights, codebook[0] != 0. */
+int32_t cl_compress_layer(const cl_layer_desc *desc, const float *W_host,
+                          const float *codebook_or_null, cl_layer **out);
+
+/* Copy the layer (payload, tables, codebook, decode tables) to the current HIP
+ * device.  Synchronous.  Must precede any device entry point.  Idempotent. */
+int32_t cl_layer_upload(cl_layer *layer);
+
+int32_t cl_layer_free(cl_layer *layer);
+int32_t cl_layer_stats(const cl_layer *layer, cl_stats *out);
+int32_t cl_layer_host_view(const cl_layer *layer, cl_host_view *out);
+
+/* Relocatable byte image of a layer (the paper's use case keeps many compressed
+ * models resident, Sec. II).  Call with buf == NULL to get the size in *bytes;
+ * then with a buffer of at least that size.  cl_layer_deserialize validates the
+ * image completely (every chunk is decoded on the host) and returns CL_ECORRUPT
+ * for anything inconsistent. */
+int32_t cl_layer_serialize(const cl_layer *layer, void *buf, size_t *bytes);
+int32_t cl_layer_deserialize(const void *buf, size_t bytes, cl_layer **out);
+
+/* Algorithm 1 steps 5-8 / Algorithm 2 steps 5-9 on the GPU, for the whole layer:
+ * Huffman-decode both arrays, prefix-sum the relative indices, look the values up
+ * and arrange them.  Any output pointer may be NULL.
+ *  d_val_sym, d_idx_sym   entries bytes each: the decoded value indices and
+ *                         relative indices in entry order
+ *  d_block_ptr            n_blocks + 1 uint32 entry offsets
+ *  d_dense                M*K fp32, the matrix the layer multiplies by           */
+int32_t cl_decode_layer(const cl_layer *layer, uint8_t *d_val_sym, uint8_t *d_idx_sym,
+                        uint32_t *d_block_ptr, float *d_dense, void *stream);
+
+/* Device scratch a forward call needs for (batch, path).  May be 0. */
+int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path, size_t *out);
+
+/* Y = act(X W^T + v) straight from the compressed layer (Eq. 1-2 with the
+ * decoding steps of Algorithm 2 fused in).
+ *  d_X     batch x K fp32        d_bias  M fp32 or NULL
+ *  d_Y     batch x M fp32, overwritten
+ *  relu    non-zero applies max(0, .)
+ *  path    CL_PATH_*; CL_PATH_SPARSE accumulates with floating-point atomics, so
+ *          the summation order (not the tolerance) varies from run to run
+ *  d_workspace / workspace_bytes   at least cl_fc_workspace_bytes(); may be NULL
+ *          when that is 0
+ * Errors: CL_EINVAL (null pointers, batch < 1, workspace too small, layer not
+ * uploaded) - nothing is launched then. */
+int32_t cl_compressed_fc_forward(const cl_layer *layer, const float *d_X, const float *d_bias_or_null,
+                                 float *d_Y, int32_t batch, int32_t relu, int32_t path,
+                                 void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* Convolution geometry.  The layer's matrix has M = out_channels rows and
+ * K = (C / groups) * R * S columns, row oc being filter oc flattened as
+ * ((c * R + r) * S + s) (Sec. III-A: filters become rows, receptive fields
+ * columns).  Output channel oc of group oc / (out_channels / groups) sees only
+ * that group's input channels.  Zero padding. */
+typedef struct {
+    int32_t C, H, W;
+    int32_t R, S;
+    int32_t stride, pad, groups;
+    int32_t out_channels;
+} cl_conv_desc;
+
+int32_t cl_conv_workspace_bytes(const cl_layer *layer, const cl_conv_desc *conv, int32_t batch,
+                                int32_t path, size_t *out);
+
+/* d_X: batch x C x H x W fp32 (NCHW); d_Y: batch x out_channels x P x Q fp32 with
+ * P = (H + 2 pad - R) / stride + 1, Q likewise. */
+int32_t cl_compressed_conv_forward(const cl_layer *layer, const cl_conv_desc *conv, const float *d_X,
+                                   const float *d_bias_or_null, float *d_Y, int32_t batch, int32_t relu,
+                                   int32_t path, void *d_workspace, size_t workspace_bytes, void *stream);
+
+/* Variable batch sizes per layer (Sec. V-C): the dynamic program over
+ * <layer, batch, reserved memory> that minimises time per image subject to
+ * A + IN(i,B) + WS(i) + OUT(i,B) <= TOT and, optionally, a latency threshold.
+ *  time_ms            n_layers x n_batches, Time(i, batch_set[j]), row-major
+ *  batch_set          n_batches candidate batch sizes, ascending
+ *  in/out_bytes_per_image  n_layers each (IN and OUT are linear in the batch)
+ *  ws_bytes           n_layers
+ *  mem_step_bytes     granularity of the reserved-memory axis; reservations round up
+ *  latency_cap_ms     <= 0 means none
+ *  out_batch_per_layer  n_layers; out_ms_per_image  the optimum, +inf (and
+ *                     CL_EUNSUPPORTED) when no plan is feasible
+ * Host only. */
+int32_t cl_plan_batches(int32_t n_layers, const int32_t *batch_set, int32_t n_batches,
+                        const double *time_ms, const int64_t *in_bytes_per_image,
+                        const int64_t *out_bytes_per_image, const int64_t *ws_bytes,
+                        int64_t tot_bytes, int64_t mem_step_bytes, double latency_cap_ms,
+                        int32_t *out_batch_per_layer, double *out_ms_per_image);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMPRESSED_LAYER_H */

@@ -1,0 +1,9 @@
+"""MI355X-native inference from pruned, codebook-quantised, Huffman-coded layers.
+
+``binding`` mirrors the C ABI declared in include/compressed_layer.h;
+``workloads`` draws the seeded synthetic inputs.  The HIP library is loaded on
+first use and there is no CPU fallback.
+"""
+from .binding import (PATH_AUTO, PATH_MFMA_F32, PATH_SPARSE, CLError, Layer, compress_layer,  # noqa: F401
+                      compressed_conv_forward, compressed_fc_forward, conv_workspace_bytes, decode_layer,
+                      fc_workspace_bytes, layer_deserialize, plan_batches)

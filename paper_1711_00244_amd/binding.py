@@ -1,0 +1,289 @@
+"""ctypes binding over libcompressed_layer.so: argument marshalling only.
+
+Every step of the path (decode, prefix sums, codebook lookup, multiply) runs in
+the library's HIP kernels.  Tensors are torch CUDA tensors used as raw device
+memory; the stream is torch's current stream.  There is no fallback: if the
+library is missing or was not built, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+CL_OK, CL_EINVAL, CL_ENOMEM, CL_ECORRUPT, CL_EUNSUPPORTED, CL_EHIP = 0, -1, -2, -3, -4, -5
+PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32 = 0, 1, 2
+CHUNK_BITS, MAX_CHUNK_ENTRIES, MAX_CODE_LEN = 4096, 1024, 12
+
+EXPORTS = [
+    "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
+    "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
+    "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_conv_workspace_bytes",
+    "cl_compressed_conv_forward", "cl_plan_batches",
+]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("M", "K", "weight_bits", "index_bits", "block_h", "block_w", "chunk_bits", "max_code_len")]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("nnz", "padding", "entries", "n_blocks", "n_chunks", "val_bits", "idx_bits",
+                                         "val_bits_unlimited", "idx_bits_unlimited", "payload_bytes", "table_bytes",
+                                         "model_bytes", "lut_bytes")] + [("val_max_len", C.c_int32), ("idx_max_len", C.c_int32)]
+
+
+class ChunkMeta(C.Structure):
+    _fields_ = [("sym_off", C.c_uint32), ("blk0", C.c_uint32), ("pos0", C.c_uint32), ("val_bits", C.c_uint16), ("idx_bits", C.c_uint16)]
+
+
+class HostView(C.Structure):
+    _fields_ = [("desc", LayerDesc), ("codebook", C.POINTER(C.c_float)), ("val_len", C.POINTER(C.c_uint8)),
+                ("val_code", C.POINTER(C.c_uint32)), ("idx_len", C.POINTER(C.c_uint8)), ("idx_code", C.POINTER(C.c_uint32)),
+                ("block_ptr", C.POINTER(C.c_uint32)), ("panel_chunk", C.POINTER(C.c_uint32)),
+                ("chunk_meta", C.POINTER(ChunkMeta)), ("lane_gap", C.POINTER(C.c_uint8)), ("payload", C.POINTER(C.c_uint8)),
+                ("n_blocks", C.c_int64), ("n_chunks", C.c_int64), ("n_entries", C.c_int64), ("n_panels", C.c_int32)]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("C", "H", "W", "R", "S", "stride", "pad", "groups", "out_channels")]
+
+
+class CLError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"[{code}] {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def lib():
+    """Load the built library; build it only if no built library is there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library()
+    L = C.CDLL(_build.LIB)
+    p, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.cl_last_error.restype = C.c_char_p
+    L.cl_compress_layer.argtypes = [C.POINTER(LayerDesc), p, p, C.POINTER(p)]
+    L.cl_layer_upload.argtypes = [p]
+    L.cl_layer_free.argtypes = [p]
+    L.cl_layer_stats.argtypes = [p, C.POINTER(Stats)]
+    L.cl_layer_host_view.argtypes = [p, C.POINTER(HostView)]
+    L.cl_layer_serialize.argtypes = [p, p, C.POINTER(sz)]
+    L.cl_layer_deserialize.argtypes = [p, sz, C.POINTER(p)]
+    L.cl_decode_layer.argtypes = [p, p, p, p, p, p]
+    L.cl_fc_workspace_bytes.argtypes = [p, i32, i32, C.POINTER(sz)]
+    L.cl_compressed_fc_forward.argtypes = [p, p, p, p, i32, i32, i32, p, sz, p]
+    L.cl_conv_workspace_bytes.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
+    L.cl_compressed_conv_forward.argtypes = [p, C.POINTER(ConvDesc), p, p, p, i32, i32, i32, p, sz, p]
+    L.cl_plan_batches.argtypes = [i32, p, i32, p, p, p, p, i64, i64, C.c_double, p, C.POINTER(C.c_double)]
+    for name in EXPORTS:
+        if name != "cl_last_error":
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != CL_OK:
+        raise CLError(rc, lib().cl_last_error().decode())
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _dev_ptr(t):
+    """Raw device address of a torch CUDA tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Layer:
+    """Owns a cl_layer handle."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("layer was freed")
+        return self._h
+
+    def free(self):
+        if self._h:
+            lib().cl_layer_free(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    # -- mirrors of the C entry points ------------------------------------- #
+    def upload(self):
+        _check(lib().cl_layer_upload(self.handle))
+        return self
+
+    def stats(self) -> dict:
+        s = Stats()
+        _check(lib().cl_layer_stats(self.handle, C.byref(s)))
+        return {n: getattr(s, n) for n, _ in Stats._fields_}
+
+    def host_view(self) -> dict:
+        """numpy copies of the host sections."""
+        v = HostView()
+        _check(lib().cl_layer_host_view(self.handle, C.byref(v)))
+        d = v.desc
+        nval, nidx = 1 << d.weight_bits, 1 << d.index_bits
+
+        def arr(ptr, n, dt):
+            if n == 0:
+                return np.zeros(0, dt)
+            return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dt, copy=True)
+
+        nc = int(v.n_chunks)
+        meta = np.zeros(nc + 1, dtype=[("sym_off", "<u4"), ("blk0", "<u4"), ("pos0", "<u4"), ("val_bits", "<u2"), ("idx_bits", "<u2")])
+        C.memmove(meta.ctypes.data, v.chunk_meta, meta.nbytes)
+        return dict(desc={n: getattr(d, n) for n, _ in LayerDesc._fields_},
+                    codebook=arr(v.codebook, nval, np.float32), val_len=arr(v.val_len, nval, np.uint8),
+                    val_code=arr(v.val_code, nval, np.uint32), idx_len=arr(v.idx_len, nidx, np.uint8),
+                    idx_code=arr(v.idx_code, nidx, np.uint32), block_ptr=arr(v.block_ptr, int(v.n_blocks) + 1, np.uint32),
+                    panel_chunk=arr(v.panel_chunk, int(v.n_panels) + 1, np.uint32), chunk_meta=meta,
+                    lane_gap=arr(v.lane_gap, nc * 32, np.uint8), payload=arr(v.payload, nc * 512 + 16, np.uint8),
+                    n_blocks=int(v.n_blocks), n_chunks=nc, n_entries=int(v.n_entries), n_panels=int(v.n_panels))
+
+    def serialize(self) -> bytes:
+        n = C.c_size_t(0)
+        _check(lib().cl_layer_serialize(self.handle, None, C.byref(n)))
+        buf = C.create_string_buffer(n.value)
+        _check(lib().cl_layer_serialize(self.handle, buf, C.byref(n)))
+        return buf.raw[:n.value]
+
+
+def compress_layer(W, weight_bits, index_bits, block_h, block_w, codebook=None, max_code_len=0, upload=False) -> Layer:
+    W = np.ascontiguousarray(W, np.float32)
+    if W.ndim != 2:
+        raise ValueError("W must be M x K")
+    d = LayerDesc(W.shape[0], W.shape[1], weight_bits, index_bits, block_h, block_w, CHUNK_BITS, max_code_len)
+    cb = None if codebook is None else np.ascontiguousarray(codebook, np.float32)
+    if cb is not None and cb.size != (1 << weight_bits):
+        raise ValueError("codebook must have 2^weight_bits entries")
+    out = C.c_void_p()
+    _check(lib().cl_compress_layer(C.byref(d), _np_ptr(W), _np_ptr(cb), C.byref(out)))
+    layer = Layer(out.value)
+    if upload:
+        layer.upload()
+    return layer
+
+
+def layer_deserialize(data: bytes) -> Layer:
+    out = C.c_void_p()
+    _check(lib().cl_layer_deserialize(data, len(data), C.byref(out)))
+    return Layer(out.value)
+
+
+def decode_layer(layer: Layer, want_dense=True):
+    """-> (val_sym, idx_sym, block_ptr, dense or None) as torch CUDA tensors."""
+    import torch
+    st = layer.stats()
+    hv = Stats  # noqa: F841 (kept for symmetry with the C names)
+    v = HostView()
+    _check(lib().cl_layer_host_view(layer.handle, C.byref(v)))
+    dev = torch.device("cuda")
+    val = torch.empty(st["entries"], dtype=torch.uint8, device=dev)
+    idx = torch.empty(st["entries"], dtype=torch.uint8, device=dev)
+    bp = torch.empty(st["n_blocks"] + 1, dtype=torch.int32, device=dev)
+    dense = torch.empty((v.desc.M, v.desc.K), dtype=torch.float32, device=dev) if want_dense else None
+    _check(lib().cl_decode_layer(layer.handle, _dev_ptr(val), _dev_ptr(idx), _dev_ptr(bp), _dev_ptr(dense), _stream()))
+    return val, idx, bp, dense
+
+
+def fc_workspace_bytes(layer: Layer, batch: int, path: int = PATH_AUTO) -> int:
+    n = C.c_size_t(0)
+    _check(lib().cl_fc_workspace_bytes(layer.handle, batch, path, C.byref(n)))
+    return n.value
+
+
+def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO, out=None, workspace=None):
+    """X: (B, K) fp32 CUDA tensor -> Y: (B, M) fp32 CUDA tensor."""
+    import torch
+    v = HostView()
+    _check(lib().cl_layer_host_view(layer.handle, C.byref(v)))
+    M, K = v.desc.M, v.desc.K
+    if X.dtype != torch.float32 or X.dim() != 2 or X.shape[1] != K:
+        raise ValueError(f"X must be (B, {K}) float32")
+    B = X.shape[0]
+    Y = out if out is not None else torch.empty((B, M), dtype=torch.float32, device=X.device)
+    need = fc_workspace_bytes(layer, B, path)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().cl_compressed_fc_forward(layer.handle, _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B, int(relu), path,
+                                          _dev_ptr(workspace), wbytes, _stream()))
+    return Y
+
+
+def conv_workspace_bytes(layer: Layer, conv: dict, batch: int, path: int = PATH_AUTO) -> int:
+    cd = ConvDesc(conv["C"], conv["H"], conv["W"], conv["R"], conv["S"], conv["stride"], conv["pad"], conv["groups"], conv["OC"])
+    n = C.c_size_t(0)
+    _check(lib().cl_conv_workspace_bytes(layer.handle, C.byref(cd), batch, path, C.byref(n)))
+    return n.value
+
+
+def compressed_conv_forward(layer: Layer, conv: dict, X, bias=None, relu=False, path=PATH_AUTO, out=None, workspace=None):
+    """X: (B, C, H, W) fp32 CUDA tensor -> (B, OC, P, Q)."""
+    import torch
+    cd = ConvDesc(conv["C"], conv["H"], conv["W"], conv["R"], conv["S"], conv["stride"], conv["pad"], conv["groups"], conv["OC"])
+    B = X.shape[0]
+    P = (conv["H"] + 2 * conv["pad"] - conv["R"]) // conv["stride"] + 1
+    Q = (conv["W"] + 2 * conv["pad"] - conv["S"]) // conv["stride"] + 1
+    Y = out if out is not None else torch.empty((B, conv["OC"], P, Q), dtype=torch.float32, device=X.device)
+    need = conv_workspace_bytes(layer, conv, B, path)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().cl_compressed_conv_forward(layer.handle, C.byref(cd), _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B,
+                                            int(relu), path, _dev_ptr(workspace), wbytes, _stream()))
+    return Y
+
+
+def plan_batches(time_ms, batch_set, in_bytes_per_image, out_bytes_per_image, ws_bytes, tot_bytes, mem_step_bytes,
+                 latency_cap_ms=None):
+    """-> (ms_per_image, [batch per layer]) or (inf, None) when nothing is feasible."""
+    t = np.ascontiguousarray(time_ms, np.float64)
+    f, nb = t.shape
+    bs = np.ascontiguousarray(batch_set, np.int32)
+    inb = np.ascontiguousarray(in_bytes_per_image, np.int64)
+    outb = np.ascontiguousarray(out_bytes_per_image, np.int64)
+    ws = np.ascontiguousarray(ws_bytes, np.int64)
+    assert bs.size == nb and inb.size == f and outb.size == f and ws.size == f
+    plan = np.zeros(f, np.int32)
+    ms = C.c_double(0)
+    rc = lib().cl_plan_batches(f, _np_ptr(bs), nb, _np_ptr(t), _np_ptr(inb), _np_ptr(outb), _np_ptr(ws), int(tot_bytes),
+                               int(mem_step_bytes), float(latency_cap_ms or 0.0), _np_ptr(plan), C.byref(ms))
+    if rc == CL_EUNSUPPORTED:
+        return float("inf"), None
+    _check(rc)
+    return ms.value, plan.tolist()

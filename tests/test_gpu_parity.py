@@ -1,0 +1,144 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Decoded symbols, block pointers and the rebuilt dense
+matrix must be bit-exact; layer outputs must agree within a normwise relative
+error of 1e-5 (fp32 accumulation against the oracle's fp64)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1711_00244_amd as cl
+from paper_1711_00244_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def rand_pruned(rng, M, K, d, sigma=0.02):
+    W = (rng.standard_normal((M, K)) * sigma).astype(np.float32)
+    W[W == 0] = 1e-3
+    W *= rng.random((M, K)) < d
+    W[W == 0] = 0.0
+    return W
+
+
+def rel_err(Y, ref):
+    return float(np.abs(Y.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def check_decode(W, r, k, bh, bw, codebook=None, max_code_len=0):
+    torch = torch_cuda()
+    L = cl.compress_layer(W, r, k, bh, bw, codebook=codebook, max_code_len=max_code_len, upload=True)
+    m = oracle.compress_layer(W, r, k, bh, bw, codebook=codebook)
+    oval, oidx, obp = oracle.decode_layer(m)
+    oW = oracle.dense_weights(m, oval, oidx, obp)
+    val, idx, bp, dense = cl.decode_layer(L)
+    torch.cuda.synchronize()
+    assert np.array_equal(val.cpu().numpy(), oval)
+    assert np.array_equal(idx.cpu().numpy(), oidx)
+    assert np.array_equal(bp.cpu().numpy().astype(np.int64), obp)
+    assert np.array_equal(dense.cpu().numpy(), oW)          # bit-exact fp32
+    return L, m, oW
+
+
+DECODE_CASES = [(64, 48, 64, 1, 0.1, 5, 4), (64, 48, 16, 16, 0.3, 5, 4), (100, 70, 32, 24, 0.09, 5, 4),
+                (200, 333, 128, 128, 0.09, 5, 4), (33, 129, 128, 128, 0.84, 8, 8), (50, 50, 7, 50, 0.02, 3, 2),
+                (1, 1, 1, 1, 1.0, 1, 1), (40, 1, 40, 1, 0.5, 8, 1), (96, 363, 96, 363, 0.84, 8, 8),
+                (300, 200, 128, 128, 0.04, 5, 5), (128, 256, 128, 128, 0.0, 5, 4), (128, 256, 128, 128, 1.0, 5, 4),
+                (1000, 520, 128, 128, 0.25, 5, 4), (1024, 1024, 1024, 1, 0.1, 5, 4), (515, 700, 128, 128, 0.001, 5, 4)]
+
+
+@pytest.mark.parametrize("M,K,bh,bw,d,r,k", DECODE_CASES)
+def test_decode_layer_bit_exact(M, K, bh, bw, d, r, k):
+    rng = np.random.default_rng(M * 7 + K + r)
+    check_decode(rand_pruned(rng, M, K, d), r, k, bh, bw)
+
+
+def test_decode_single_symbol_alphabets():
+    """All weights share one value and are adjacent: both arrays use one symbol
+    (1-bit codewords, 64 codewords per lane slice)."""
+    W = np.full((128, 64), 0.5, np.float32)
+    check_decode(W, 5, 4, 128, 64, codebook=np.concatenate([[0, 0.5], np.arange(30) + 1.0]).astype(np.float32))
+
+
+@pytest.mark.parametrize("M,K,bh,bw,d,r,k", [(200, 333, 128, 128, 0.09, 5, 4), (1000, 520, 128, 128, 0.25, 5, 4),
+                                              (64, 48, 64, 1, 0.1, 5, 4), (1024, 1024, 1024, 1, 0.1, 5, 4),
+                                              (300, 200, 64, 32, 0.04, 5, 5), (96, 363, 96, 363, 0.84, 8, 8),
+                                              (130, 70, 16, 16, 0.3, 5, 4), (128, 256, 128, 128, 0.0, 5, 4)])
+@pytest.mark.parametrize("B", [1, 3, 8])
+def test_fc_forward_sparse_path(M, K, bh, bw, d, r, k, B):
+    torch = torch_cuda()
+    rng = np.random.default_rng(M + K * 3 + B)
+    W = rand_pruned(rng, M, K, d)
+    L, m, oW = check_decode(W, r, k, bh, bw)
+    X = np.maximum(rng.standard_normal((B, K)), 0).astype(np.float32)
+    bias = rng.standard_normal(M).astype(np.float32) * 0.1
+    for use_bias, relu in [(False, False), (True, True)]:
+        ref = oracle.fc_forward(oW, X, bias if use_bias else None, relu)
+        Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda() if use_bias else None,
+                                     relu=relu, path=cl.PATH_SPARSE)
+        torch.cuda.synchronize()
+        assert Y.shape == (B, M)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+
+
+def test_fc_forward_repeatable_within_tolerance():
+    """Atomic accumulation: the summation order may differ between runs, the
+    result stays inside the tolerance and the decode stays bit-identical."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(77)
+    W = rand_pruned(rng, 512, 768, 0.09)
+    L, m, oW = check_decode(W, 5, 4, 128, 128)
+    X = torch.from_numpy(np.maximum(rng.standard_normal((4, 768)), 0).astype(np.float32)).cuda()
+    ref = oracle.fc_forward(oW, X.cpu().numpy())
+    first = cl.decode_layer(L)[3].clone()
+    for _ in range(20):
+        Y = cl.compressed_fc_forward(L, X, path=cl.PATH_SPARSE)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+        assert torch.equal(cl.decode_layer(L)[3], first)
+
+
+def test_config1_full_size():
+    """configs[0]: 1024x1024, 10 % density, 5-bit codebook, 4-bit relative index,
+    plain CSC columns (blocks of M x 1), batch 1."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(1, 0)
+    for bh, bw in [(spec.M, 1), (128, 128)]:
+        L, m, oW = check_decode(W, spec.r, spec.k, bh, bw)
+        X = wl.activations(1, 1)
+        ref = oracle.fc_forward(oW, X)
+        Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), path=cl.PATH_SPARSE)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+
+
+def test_config2_alexnet_fc6_full_size():
+    """configs[1]: AlexNet fc6 shape at full size, batch 1 and 8, in the launch
+    configuration the benchmark times (128 x 128 blocks)."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(2, 0)
+    L, m, oW = check_decode(W, spec.r, spec.k, 128, 128)
+    for B in (1, 8):
+        X = wl.activations(2, B)
+        ref = oracle.fc_forward(oW, X, nthreads=8)
+        Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), path=cl.PATH_SPARSE)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+
+
+def test_forward_rejects_bad_arguments():
+    torch = torch_cuda()
+    L = cl.compress_layer(np.eye(8, dtype=np.float32), 5, 4, 8, 8)
+    X = torch.zeros((1, 8), device="cuda")
+    with pytest.raises(cl.CLError) as e:           # not uploaded
+        cl.compressed_fc_forward(L, X)
+    assert e.value.code == binding.CL_EINVAL
+    L.upload()
+    import ctypes as C
+    rc = binding.lib().cl_compressed_fc_forward(L.handle, None, None, C.c_void_p(X.data_ptr()), 1, 0, 0, None, 0, None)
+    assert rc == binding.CL_EINVAL
+    rc = binding.lib().cl_compressed_fc_forward(L.handle, C.c_void_p(X.data_ptr()), None, C.c_void_p(X.data_ptr()), 0, 0, 0, None, 0, None)
+    assert rc == binding.CL_EINVAL
