@@ -45,7 +45,7 @@ enum {
 /* Bits per chunk of the compressed stream; the only value this build accepts. */
 #define CL_CHUNK_BITS 4096
 /* No chunk holds more entries than this. */
-#define CL_MAX_CHUNK_ENTRIES 1024
+#define CL_MAX_CHUNK_ENTRIES 768
 /* Longest Huffman codeword the format allows. */
 #define CL_MAX_CODE_LEN 12
 
@@ -124,7 +124,8 @@ typedef struct {
  *                        to the stream; stream bit b is bit (b mod 8) of byte b/8.
  *  lane_gap              32 bytes per chunk; nibble l (low nibble first) is, for
  *                        the 64-bit slice l of the chunk, the distance from the
- *                        slice start to the first codeword that starts in it.     */
+ *                        slice start to the first codeword that starts in it
+ *                        (at most 11), or 15 when no codeword starts there.      */
 typedef struct {
     cl_layer_desc desc;
     const float *codebook;         /* 2^r                                            */
@@ -241,6 +242,15 @@ int32_t cl_plan_batches(int32_t n_layers, const int32_t *batch_set, int32_t n_ba
                         const int64_t *out_bytes_per_image, const int64_t *ws_bytes,
                         int64_t tot_bytes, int64_t mem_step_bytes, double latency_cap_ms,
                         int32_t *out_batch_per_layer, double *out_ms_per_image);
+
+/* Measurement hook for benchmarks (not part of the paper's method).  While
+ * enabled, every forward call brackets the launches of its main kernel - not the
+ * small output-initialisation and activation kernels - with a pair of HIP events
+ * on the call's stream.  cl_last_kernel_ms() waits for the most recent bracket and
+ * returns its duration in milliseconds and the number of launches it covered.
+ * Process-wide state, not thread safe; leave it off in production. */
+int32_t cl_set_kernel_timing(int32_t enable);
+int32_t cl_last_kernel_ms(float *ms, int32_t *launches);
 
 #ifdef __cplusplus
 }

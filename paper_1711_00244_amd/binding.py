@@ -16,13 +16,13 @@ from . import build as _build
 
 CL_OK, CL_EINVAL, CL_ENOMEM, CL_ECORRUPT, CL_EUNSUPPORTED, CL_EHIP = 0, -1, -2, -3, -4, -5
 PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32 = 0, 1, 2
-CHUNK_BITS, MAX_CHUNK_ENTRIES, MAX_CODE_LEN = 4096, 1024, 12
+CHUNK_BITS, MAX_CHUNK_ENTRIES, MAX_CODE_LEN = 4096, 768, 12
 
 EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
     "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_conv_workspace_bytes",
-    "cl_compressed_conv_forward", "cl_plan_batches",
+    "cl_compressed_conv_forward", "cl_plan_batches", "cl_set_kernel_timing", "cl_last_kernel_ms",
 ]
 
 
@@ -88,6 +88,8 @@ def lib():
     L.cl_conv_workspace_bytes.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
     L.cl_compressed_conv_forward.argtypes = [p, C.POINTER(ConvDesc), p, p, p, i32, i32, i32, p, sz, p]
     L.cl_plan_batches.argtypes = [i32, p, i32, p, p, p, p, i64, i64, C.c_double, p, C.POINTER(C.c_double)]
+    L.cl_set_kernel_timing.argtypes = [i32]
+    L.cl_last_kernel_ms.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
         if name != "cl_last_error":
             getattr(L, name).restype = i32
@@ -287,3 +289,14 @@ def plan_batches(time_ms, batch_set, in_bytes_per_image, out_bytes_per_image, ws
         return float("inf"), None
     _check(rc)
     return ms.value, plan.tolist()
+
+
+def set_kernel_timing(enable: bool):
+    _check(lib().cl_set_kernel_timing(int(enable)))
+
+
+def last_kernel_ms():
+    """-> (milliseconds, launches) of the main kernel(s) of the last forward call."""
+    ms, n = C.c_float(0), C.c_int32(0)
+    _check(lib().cl_last_kernel_ms(C.byref(ms), C.byref(n)))
+    return ms.value, n.value

@@ -109,6 +109,12 @@ int32_t finalize_and_validate(cl_layer *L)
     L->idx_lut_bits = std::max(1, L->idx_lut_bits);
     build_lut(L->val_len, L->val_code, L->val_lut_bits, L->val_lut);
     build_lut(L->idx_len, L->idx_code, L->idx_lut_bits, L->idx_lut);
+    // device tables: index wide enough for a few short codewords, never narrower than the longest one
+    L->wide = d.weight_bits > 6 || d.index_bits > 6;
+    L->val_mbits = std::max(L->val_lut_bits, kMultiIndexBits);
+    L->idx_mbits = std::max(L->idx_lut_bits, kMultiIndexBits);
+    build_multi_lut(L->val_lut, L->val_lut_bits, L->val_mbits, L->wide, L->val_mlut);
+    build_multi_lut(L->idx_lut, L->idx_lut_bits, L->idx_mbits, L->wide, L->idx_mlut);
 
     if ((int64_t)L->block_ptr.size() != g.n_blocks + 1) return fail(CL_ECORRUPT, "block_ptr has the wrong size");
     if ((int64_t)L->panel_chunk.size() != (int64_t)g.nbh + 1) return fail(CL_ECORRUPT, "panel table has the wrong size");
@@ -121,8 +127,11 @@ int32_t finalize_and_validate(cl_layer *L)
     for (int64_t b = 0; b < g.n_blocks; ++b)
         if (L->block_ptr[b] > L->block_ptr[b + 1]) return fail(CL_ECORRUPT, "block_ptr is not monotone");
     if (L->panel_chunk[0] != 0 || L->panel_chunk[g.nbh] != L->n_chunks) return fail(CL_ECORRUPT, "panel table does not span the chunks");
-    for (int p = 0; p < g.nbh; ++p)
+    L->max_panel_chunks = 0;
+    for (int p = 0; p < g.nbh; ++p) {
         if (L->panel_chunk[p] > L->panel_chunk[p + 1]) return fail(CL_ECORRUPT, "panel table is not monotone");
+        L->max_panel_chunks = std::max<int64_t>(L->max_panel_chunks, (int64_t)L->panel_chunk[p + 1] - L->panel_chunk[p]);
+    }
 
     const uint32_t vmask = (1u << L->val_lut_bits) - 1u, imask = (1u << L->idx_lut_bits) - 1u;
     int64_t nnz = 0, vbits = 0, ibits = 0;
@@ -143,7 +152,7 @@ int32_t finalize_and_validate(cl_layer *L)
         const uint8_t *gap = L->gaps.data() + c * kGapBytes;
         uint8_t want_gap[kLanes];
         bool seen[kLanes];
-        std::memset(want_gap, 0, sizeof want_gap);
+        std::memset(want_gap, 15, sizeof want_gap);      // 15: no codeword starts in the slice
         std::memset(seen, 0, sizeof seen);
         // value-index sub-stream, then relative-index sub-stream
         for (int part = 0; part < 2; ++part) {
@@ -318,7 +327,7 @@ extern "C" int32_t cl_compress_layer(const cl_layer_desc *desc, const float *W, 
                 const size_t at = L->payload.size();
                 L->payload.resize(at + kChunkBytes, 0);
                 const size_t gat = L->gaps.size();
-                L->gaps.resize(gat + kGapBytes, 0);
+                L->gaps.resize(gat + kGapBytes, 0xff);        // nibble 15: no codeword starts in the slice
                 uint8_t *chunk = L->payload.data() + at;
                 uint8_t *gap = L->gaps.data() + gat;
                 bool seen[kLanes] = {false};
@@ -328,7 +337,10 @@ extern "C" int32_t cl_compress_layer(const cl_layer_desc *desc, const float *W, 
                     for (int part = 0; part < 2; ++part) {
                         int &pos = part ? ipos : vpos;
                         const int lane = pos / 64;
-                        if (!seen[lane]) { seen[lane] = true; gap[lane >> 1] |= (uint8_t)((pos % 64) << (4 * (lane & 1))); }
+                        if (!seen[lane]) {
+                            seen[lane] = true;
+                            gap[lane >> 1] = (uint8_t)((gap[lane >> 1] & ~(15u << (4 * (lane & 1)))) | ((uint32_t)(pos % 64) << (4 * (lane & 1))));
+                        }
                         if (part) { put_bits(chunk, pos, L->idx_code[z], L->idx_len[z]); pos += L->idx_len[z]; }
                         else { put_bits(chunk, pos, L->val_code[v], L->val_len[v]); pos += L->val_len[v]; }
                     }
@@ -381,7 +393,7 @@ extern "C" int32_t cl_layer_stats(const cl_layer *L, cl_stats *s)
     s->table_bytes = (int64_t)(L->meta.size() * sizeof(cl_chunk_meta) + L->gaps.size() +
                                L->block_ptr.size() * 4 + L->panel_chunk.size() * 4);
     s->model_bytes = s->payload_bytes + s->table_bytes + (int64_t)(L->codebook.size() * 4 + L->val_len.size() + L->idx_len.size());
-    s->lut_bytes = (int64_t)((L->val_lut.size() + L->idx_lut.size()) * sizeof(lut_t));
+    s->lut_bytes = (int64_t)((L->val_mlut.size() + L->idx_mlut.size()) * 4);
     s->val_max_len = L->val_lut_bits;
     s->idx_max_len = L->idx_lut_bits;
     return CL_OK;

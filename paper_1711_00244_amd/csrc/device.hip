@@ -36,10 +36,10 @@ struct LayerDev {
     const uint32_t *block_ptr;
     const uint32_t *panel_chunk;
     const float *codebook;
-    const lut_t *val_lut;
-    const lut_t *idx_lut;
+    const uint32_t *val_mlut;
+    const uint32_t *idx_mlut;
     int M, K, bh, bw, nbw;
-    int val_lut_bits, idx_lut_bits, ncode;
+    int val_mbits, idx_mbits, ncode;
     uint32_t n_chunks;
 };
 
@@ -52,15 +52,15 @@ static LayerDev make_dev(const cl_layer *L)
     d.block_ptr = L->dev.block_ptr;
     d.panel_chunk = L->dev.panel_chunk;
     d.codebook = L->dev.codebook;
-    d.val_lut = L->dev.val_lut;
-    d.idx_lut = L->dev.idx_lut;
+    d.val_mlut = L->dev.val_mlut;
+    d.idx_mlut = L->dev.idx_mlut;
     d.M = L->desc.M;
     d.K = L->desc.K;
     d.bh = L->desc.block_h;
     d.bw = L->desc.block_w;
     d.nbw = L->nbw;
-    d.val_lut_bits = L->val_lut_bits;
-    d.idx_lut_bits = L->idx_lut_bits;
+    d.val_mbits = L->val_mbits;
+    d.idx_mbits = L->idx_mbits;
     d.ncode = 1 << L->desc.weight_bits;
     d.n_chunks = (uint32_t)L->n_chunks;
     return d;
@@ -82,8 +82,6 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
     return v;
 }
 
-__device__ __forceinline__ uint32_t wave_last(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, 63); }
-
 // Orders this wavefront's LDS writes before its later LDS reads by other lanes.
 __device__ __forceinline__ void wave_lds_fence()
 {
@@ -101,6 +99,54 @@ __device__ __forceinline__ uint32_t window_bits(uint32_t w0, uint32_t w1, uint32
     return __builtin_amdgcn_alignbit(hi, lo, (uint32_t)pos & 31u);
 }
 
+// Fields of a multi-symbol decode-table entry (two layouts, see the host builder).
+template <bool WIDE>
+struct Entry {
+    static constexpr int SB = WIDE ? 8 : 6;      // bits per symbol
+    static constexpr int CAP = WIDE ? 2 : 3;     // symbols per entry
+    static constexpr int AT = SB * CAP;
+    static constexpr uint32_t SM = (1u << SB) - 1u;
+    static __device__ __forceinline__ uint32_t sym(uint32_t e, int j) { return (e >> (SB * j)) & SM; }
+    static __device__ __forceinline__ uint32_t bits(uint32_t e) { return (e >> AT) & 15u; }
+    static __device__ __forceinline__ uint32_t count(uint32_t e) { return (e >> (AT + 4)) & 3u; }
+    static __device__ __forceinline__ uint32_t first_bits(uint32_t e) { return (e >> (AT + 6)) & 15u; }
+    static __device__ __forceinline__ uint32_t sym_sum(uint32_t e)
+    {
+        uint32_t t = sym(e, 0) + sym(e, 1);
+        if (CAP > 2) t += sym(e, 2);
+        return t;
+    }
+};
+
+// Staging arrays of one wavefront: one slot per entry plus one spare slot per lane
+// that swallows the stores of absent symbols.
+constexpr int kStage = CL_MAX_CHUNK_ENTRIES + 64;
+
+// What a lane holds of its chunk before decoding starts.
+struct ChunkRaw {
+    cl_chunk_meta m;
+    uint32_t next_off;
+    uint32_t w0, w1, w2;
+    int gap;
+};
+
+// 128-bit read of the lane's 64-bit slice plus the start of the next one, the
+// lane's gap nibble and the chunk's table record.
+__device__ __forceinline__ ChunkRaw load_chunk(const LayerDev &L, uint32_t c, int lane)
+{
+    ChunkRaw r;
+    r.m = L.meta[c];
+    r.next_off = L.meta[c + 1].sym_off;
+    uint32_t w[4];
+    __builtin_memcpy(w, L.payload + (size_t)c * kChunkBytes + lane * 8, 16);
+    r.w0 = w[0];
+    r.w1 = w[1];
+    r.w2 = w[2];
+    const uint32_t gbyte = L.gaps[(size_t)c * kGapBytes + (lane >> 1)];
+    r.gap = (int)((gbyte >> (4 * (lane & 1))) & 15u);
+    return r;
+}
+
 struct ChunkInfo {
     uint32_t e0;      // first entry
     int n;            // entries in the chunk
@@ -108,51 +154,99 @@ struct ChunkInfo {
     uint32_t pos0;    // position carry of that block
 };
 
-// Huffman-decode chunk c into the wavefront's LDS staging arrays vs[] (value
-// indices) and zs[] (relative indices), both in entry order.
-// Algorithm 2 steps 5-6, for the span of the streams this chunk holds.
-__device__ __forceinline__ ChunkInfo decode_chunk(const LayerDev &L, uint32_t c, int lane,
-                                                  const lut_t *s_vlut, const lut_t *s_ilut,
-                                                  uint8_t *vs, uint8_t *zs)
+// Decode tables in LDS.
+struct Tables {
+    const uint32_t *vm, *im;
+    const float *cb;
+};
+
+// Huffman-decode a chunk (Algorithm 2 steps 5-6 for the span of the streams the
+// chunk holds) and prefix-sum its relative indices (step 7) in one go.  On return
+// the wavefront's LDS staging arrays hold, in entry order,
+//   vs[i]  the value index of entry i
+//   ss[i]  sum of (z + 1) over entries 0..i of the chunk (inclusive)
+// Pass 1 counts codewords and sums z + 1 per lane; one wavefront scan of the
+// packed pair gives every lane its first output slot and its starting sum; pass 2
+// decodes again straight into place.  Both passes take several symbols per table
+// lookup while a whole index still lies inside the lane's slice, then finish one
+// symbol at a time.
+template <typename E_T, bool WIDE>
+__device__ __forceinline__ ChunkInfo decode_chunk(const LayerDev &L, const ChunkRaw &raw, int lane,
+                                                  const Tables &T, E_T *vs, E_T *ss)
 {
-    const cl_chunk_meta m = L.meta[c];
+    using En = Entry<WIDE>;
     ChunkInfo ci;
-    ci.e0 = m.sym_off;
-    ci.n = (int)(L.meta[c + 1].sym_off - m.sym_off);
-    ci.blk0 = m.blk0;
-    ci.pos0 = m.pos0;
-    const int nv = (m.val_bits + 63) >> 6;
-
-    // 128-bit read of the lane's slice and the start of the next one
-    uint32_t w[4];
-    __builtin_memcpy(w, L.payload + (size_t)c * kChunkBytes + lane * 8, 16);
-    const uint32_t gbyte = L.gaps[(size_t)c * kGapBytes + (lane >> 1)];
-    const int gap = (int)((gbyte >> (4 * (lane & 1))) & 15u);
-
+    ci.e0 = raw.m.sym_off;
+    ci.n = (int)(raw.next_off - raw.m.sym_off);
+    ci.blk0 = raw.m.blk0;
+    ci.pos0 = raw.m.pos0;
+    const int nv = (raw.m.val_bits + 63) >> 6;
     const bool is_val = lane < nv;
     const int slice = is_val ? lane : lane - nv;
-    const int sub_bits = is_val ? (int)m.val_bits : (int)m.idx_bits;
+    const int sub_bits = is_val ? (int)raw.m.val_bits : (int)raw.m.idx_bits;
     const int limit = min(64, sub_bits - slice * 64);
-    const lut_t *lut = is_val ? s_vlut : s_ilut;
-    const uint32_t mask = (1u << (is_val ? L.val_lut_bits : L.idx_lut_bits)) - 1u;
+    const int mbits = is_val ? L.val_mbits : L.idx_mbits;
+    const uint32_t mask = (1u << mbits) - 1u;
+    const uint32_t *mlut = is_val ? T.vm : T.im;
+    const int mlimit = limit - mbits;      // a whole-index lookup at pos <= mlimit stays inside the slice
+    const uint32_t w0 = raw.w0, w1 = raw.w1, w2 = raw.w2;
 
-    // pass 1: codewords that start in this lane's slice
-    uint32_t cnt = 0;
-    for (int pos = gap; pos < limit;) {
-        const uint32_t e = lut[window_bits(w[0], w[1], w[2], pos) & mask];
-        pos += (int)(e >> 8);
+    // ---- pass 1: how many codewords start in this slice, how far they advance the position
+    uint32_t cnt = 0, adv = 0;
+    int pos = raw.gap;
+    while (pos <= mlimit) {
+        const uint32_t e = mlut[window_bits(w0, w1, w2, pos) & mask];
+        const uint32_t n = En::count(e);
+        pos += (int)En::bits(e);
+        cnt += n;
+        adv += En::sym_sum(e) + n;
+    }
+    while (pos < limit) {
+        const uint32_t e = mlut[window_bits(w0, w1, w2, pos) & mask];
+        pos += (int)En::first_bits(e);
+        adv += En::sym(e, 0) + 1u;
         ++cnt;
     }
-    // counts -> output slots
-    const uint32_t incl = wave_incl_scan(cnt);
-    const uint32_t total_val = nv > 0 ? (uint32_t)__builtin_amdgcn_readlane((int)incl, nv - 1) : 0u;
-    uint32_t off = incl - cnt - (is_val ? 0u : total_val);
-    // pass 2: decode into place
-    uint8_t *dst = is_val ? vs : zs;
-    for (int pos = gap; pos < limit;) {
-        const uint32_t e = lut[window_bits(w[0], w[1], w[2], pos) & mask];
-        pos += (int)(e >> 8);
-        if (off < (uint32_t)CL_MAX_CHUNK_ENTRIES) dst[off] = (uint8_t)(e & 0xffu);
+    // ---- counts (value + index lanes: <= 2048 in total, 12 bits) and advances (<= 2^18) share one scan
+    const uint32_t mine = cnt | ((is_val ? 0u : adv) << 12);
+    const uint32_t incl = wave_incl_scan(mine);
+    const uint32_t total_val = nv > 0 ? ((uint32_t)__builtin_amdgcn_readlane((int)incl, nv - 1) & 0xfffu) : 0u;
+    const uint32_t total_all = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63) & 0xfffu;
+    if (total_val > (uint32_t)CL_MAX_CHUNK_ENTRIES || total_all - total_val > (uint32_t)CL_MAX_CHUNK_ENTRIES ||
+        ci.n > CL_MAX_CHUNK_ENTRIES) {
+        ci.n = 0;                           // not a chunk this library wrote: skip it
+        return ci;
+    }
+    const uint32_t excl = incl - mine;
+    uint32_t off = (excl & 0xfffu) - (is_val ? 0u : total_val);
+    uint32_t run = excl >> 12;
+    // ---- pass 2: decode into place.  A value lane stores the symbols themselves, a
+    // relative-index lane stores the running sum after each symbol.
+    E_T *dst = is_val ? vs : ss;
+    const uint32_t keep = is_val ? 0u : 0xffffffffu, inc = is_val ? 0u : 1u;
+    const uint32_t spare = (uint32_t)CL_MAX_CHUNK_ENTRIES + (uint32_t)lane;
+    pos = raw.gap;
+    while (pos <= mlimit) {
+        const uint32_t e = mlut[window_bits(w0, w1, w2, pos) & mask];
+        const uint32_t n = En::count(e);
+        pos += (int)En::bits(e);
+        const uint32_t t0 = (run & keep) + En::sym(e, 0) + inc;
+        const uint32_t t1 = (t0 & keep) + En::sym(e, 1) + inc;
+        dst[off] = (E_T)t0;
+        dst[n > 1u ? off + 1u : spare] = (E_T)t1;
+        run = n > 1u ? t1 : t0;
+        if (En::CAP > 2) {
+            const uint32_t t2 = (t1 & keep) + En::sym(e, 2) + inc;
+            dst[n > 2u ? off + 2u : spare] = (E_T)t2;
+            run = n > 2u ? t2 : run;
+        }
+        off += n;
+    }
+    while (pos < limit) {
+        const uint32_t e = mlut[window_bits(w0, w1, w2, pos) & mask];
+        pos += (int)En::first_bits(e);
+        run = (run & keep) + En::sym(e, 0) + inc;
+        dst[off] = (E_T)run;
         ++off;
     }
     wave_lds_fence();
@@ -165,46 +259,17 @@ struct BlockGeom {
     int shift;        // log2(bhp) when bhp is a power of two, else -1
 };
 
-// Visit every entry of a decoded chunk with its position inside its block
-// (Algorithm 1 step 7: prefix sum of the relative indices; each entry advances the
-// position by z + 1, the carry restarts with each block).
-// f(active, v, pos, geom, entry_index) is called by all 64 lanes together.
-template <class F>
-__device__ __forceinline__ void for_each_entry(const LayerDev &L, const ChunkInfo &ci, int lane,
-                                               const uint8_t *vs, const uint8_t *zs, F &&f)
+__device__ __forceinline__ BlockGeom block_geom(const LayerDev &L, uint32_t b)
 {
-    uint32_t b = ci.blk0;
-    uint32_t carry = ci.pos0;
-    int i0 = 0;
-    const int n = min(ci.n, CL_MAX_CHUNK_ENTRIES);
-    while (i0 < n) {
-        uint32_t bend = L.block_ptr[b + 1];
-        while (bend <= ci.e0 + (uint32_t)i0) {      // block finished (or empty): next block, carry restarts
-            ++b;
-            carry = 0;
-            bend = L.block_ptr[b + 1];
-        }
-        const int seg_end = (int)min((uint32_t)n, bend - ci.e0);
-        BlockGeom g;
-        g.b = b;
-        const int brow = (int)(b / (uint32_t)L.nbw);
-        g.row_id = brow * L.bh;
-        g.col_id = (int)(b - (uint32_t)brow * (uint32_t)L.nbw) * L.bw;
-        g.bhp = min(L.bh, L.M - g.row_id);
-        g.bwp = min(L.bw, L.K - g.col_id);
-        g.shift = (g.bhp & (g.bhp - 1)) == 0 ? (31 - __builtin_clz((uint32_t)g.bhp)) : -1;
-        for (int base = i0; base < seg_end; base += 64) {
-            const int i = base + lane;
-            const bool act = i < seg_end;
-            const uint32_t v = act ? vs[i] : 0u;
-            const uint32_t z1 = act ? (uint32_t)zs[i] + 1u : 0u;
-            const uint32_t s = wave_incl_scan(z1);
-            const uint32_t pos = carry + s - 1u;
-            carry += wave_last(s);
-            f(act, v, pos, g, ci.e0 + (uint32_t)i);
-        }
-        i0 = seg_end;
-    }
+    BlockGeom g;
+    g.b = b;
+    const int brow = (int)(b / (uint32_t)L.nbw);
+    g.row_id = brow * L.bh;
+    g.col_id = (int)(b - (uint32_t)brow * (uint32_t)L.nbw) * L.bw;
+    g.bhp = min(L.bh, L.M - g.row_id);
+    g.bwp = min(L.bw, L.K - g.col_id);
+    g.shift = (g.bhp & (g.bhp - 1)) == 0 ? (31 - __builtin_clz((uint32_t)g.bhp)) : -1;
+    return g;
 }
 
 // Position inside a block -> (row, column) offsets; column-major inside the block.
@@ -215,66 +280,103 @@ __device__ __forceinline__ void split_pos(uint32_t pos, const BlockGeom &g, uint
     else { c = pos / (uint32_t)g.bhp; r = pos - c * (uint32_t)g.bhp; }
 }
 
+// Walk the chunk block by block.  Inside block b the position of entry i is the
+// chunk-wide running sum ss[i] plus `base` minus 1: the carry restarts with each
+// block, and the first block of a chunk continues from the chunk table's carry.
+// seg(g, base, i0, i1) is called once per (block, entry range) by all lanes.
+template <typename E_T, class F>
+__device__ __forceinline__ void for_each_segment(const LayerDev &L, const ChunkInfo &ci, const E_T *ss, F &&seg)
+{
+    uint32_t b = ci.blk0;
+    int i0 = 0;
+    const int n = ci.n;
+    while (i0 < n) {
+        uint32_t bend = L.block_ptr[b + 1];
+        while (bend <= ci.e0 + (uint32_t)i0) bend = L.block_ptr[++b + 1];   // finished or empty blocks
+        const int i1 = (int)min((uint32_t)n, bend - ci.e0);
+        const uint32_t base = i0 == 0 ? ci.pos0 : 0u - (uint32_t)ss[i0 - 1];
+        seg(block_geom(L, b), base, i0, i1);
+        i0 = i1;
+    }
+}
+
 // LDS carve-up shared by the chunk kernels.
+template <typename E_T>
 struct Smem {
-    lut_t *vlut;
-    lut_t *ilut;
-    float *cb;
-    uint8_t *stage;     // kWaves * 2 * CL_MAX_CHUNK_ENTRIES
+    Tables T;
+    E_T *stage;         // per wavefront: vs[kStage] then ss[kStage]
     float *extra;
 };
 
-__host__ __device__ inline size_t smem_fixed_bytes(int vbits, int ibits, int ncode)
+static size_t smem_fixed_bytes(int vmbits, int imbits, int ncode, size_t e_bytes)
 {
-    return ((size_t)1 << vbits) * sizeof(lut_t) + ((size_t)1 << ibits) * sizeof(lut_t) + (size_t)ncode * 4 +
-           (size_t)kWaves * 2 * CL_MAX_CHUNK_ENTRIES;
+    return (((size_t)1 << vmbits) + ((size_t)1 << imbits)) * sizeof(uint32_t) + (size_t)ncode * 4 +
+           (size_t)kWaves * 2 * kStage * e_bytes;
 }
 
-__device__ __forceinline__ Smem carve(uint8_t *base, const LayerDev &L)
+template <typename E_T>
+__device__ __forceinline__ Smem<E_T> carve(uint8_t *base, const LayerDev &L)
 {
-    Smem s;
-    s.vlut = (lut_t *)base;
-    s.ilut = s.vlut + (1 << L.val_lut_bits);
-    s.cb = (float *)(s.ilut + (1 << L.idx_lut_bits));
-    s.stage = (uint8_t *)(s.cb + L.ncode);
-    s.extra = (float *)(s.stage + kWaves * 2 * CL_MAX_CHUNK_ENTRIES);
+    Smem<E_T> s;
+    uint32_t *vm = (uint32_t *)base;
+    uint32_t *im = vm + (1 << L.val_mbits);
+    float *cb = (float *)(im + (1 << L.idx_mbits));
+    s.T.vm = vm;
+    s.T.im = im;
+    s.T.cb = cb;
+    s.stage = (E_T *)(cb + L.ncode);
+    s.extra = (float *)(s.stage + kWaves * 2 * kStage);
     return s;
 }
 
-__device__ __forceinline__ void load_tables(const Smem &s, const LayerDev &L)
+// Both tables have at least 2^10 entries, so they are whole numbers of 16-byte rows.
+template <typename E_T>
+__device__ __forceinline__ void load_tables(const Smem<E_T> &s, const LayerDev &L)
 {
-    // both tables are a whole number of dwords (at least 2 entries each)
-    const uint32_t *gv = (const uint32_t *)L.val_lut, *gi = (const uint32_t *)L.idx_lut;
-    uint32_t *sv = (uint32_t *)s.vlut, *si = (uint32_t *)s.ilut;
-    for (int t = threadIdx.x; t < (1 << L.val_lut_bits) / 2; t += blockDim.x) sv[t] = gv[t];
-    for (int t = threadIdx.x; t < (1 << L.idx_lut_bits) / 2; t += blockDim.x) si[t] = gi[t];
-    for (int t = threadIdx.x; t < L.ncode; t += blockDim.x) s.cb[t] = L.codebook[t];
+    const int nv4 = (1 << L.val_mbits) / 4, ni4 = (1 << L.idx_mbits) / 4;
+    const uint4 *gv = (const uint4 *)L.val_mlut, *gi = (const uint4 *)L.idx_mlut;
+    uint4 *sv = (uint4 *)s.T.vm, *si = (uint4 *)s.T.im;
+    for (int t = threadIdx.x; t < nv4 + ni4; t += blockDim.x) {
+        if (t < nv4) sv[t] = gv[t];
+        else si[t - nv4] = gi[t - nv4];
+    }
+    float *cb = (float *)s.T.cb;
+    for (int t = threadIdx.x; t < L.ncode; t += blockDim.x) cb[t] = L.codebook[t];
 }
 
 // ------------------------------------------------------------------------- //
 // decode_layer: symbols and (optionally) the dense matrix
 // ------------------------------------------------------------------------- //
+template <typename E_T, bool WIDE>
 __global__ __launch_bounds__(kThreads) void decode_kernel(LayerDev L, uint8_t *val_out, uint8_t *idx_out, float *dense)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    const Smem s = carve(smem_raw, L);
-    load_tables(s, L);
-    __syncthreads();
+    const Smem<E_T> s = carve<E_T>(smem_raw, L);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const uint32_t c = blockIdx.x * kWaves + (uint32_t)wave;
-    if (c >= L.n_chunks) return;
-    uint8_t *vs = s.stage + (size_t)wave * 2 * CL_MAX_CHUNK_ENTRIES;
-    uint8_t *zs = vs + CL_MAX_CHUNK_ENTRIES;
-    const ChunkInfo ci = decode_chunk(L, c, lane, s.vlut, s.ilut, vs, zs);
-    for_each_entry(L, ci, lane, vs, zs, [&](bool act, uint32_t v, uint32_t pos, const BlockGeom &g, uint32_t e) {
-        if (!act) return;
-        if (val_out) val_out[e] = (uint8_t)v;
-        if (idx_out) idx_out[e] = zs[e - ci.e0];
-        if (dense && v != 0 && pos < (uint32_t)g.bhp * (uint32_t)g.bwp) {
-            uint32_t r, cc;
-            split_pos(pos, g, r, cc);
-            dense[(size_t)(g.row_id + (int)r) * L.K + (size_t)(g.col_id + (int)cc)] = s.cb[v];
+    const bool have = c < L.n_chunks;
+    ChunkRaw raw{};
+    if (have) raw = load_chunk(L, c, lane);
+    load_tables(s, L);
+    __syncthreads();
+    if (!have) return;
+    E_T *vs = s.stage + (size_t)wave * 2 * kStage;
+    E_T *ss = vs + kStage;
+    const ChunkInfo ci = decode_chunk<E_T, WIDE>(L, raw, lane, s.T, vs, ss);
+    for_each_segment<E_T>(L, ci, ss, [&](const BlockGeom &g, uint32_t base, int i0, int i1) {
+        for (int i = i0 + lane; i < i1; i += 64) {
+            const uint32_t e = ci.e0 + (uint32_t)i;
+            const uint32_t v = vs[i];
+            const uint32_t sum = ss[i];
+            const uint32_t pos = sum + base - 1u;
+            if (val_out) val_out[e] = (uint8_t)v;
+            if (idx_out) idx_out[e] = (uint8_t)(sum - (i ? (uint32_t)ss[i - 1] : 0u) - 1u);
+            if (dense && v != 0 && pos < (uint32_t)g.bhp * (uint32_t)g.bwp) {
+                uint32_t r, cc;
+                split_pos(pos, g, r, cc);
+                dense[(size_t)(g.row_id + (int)r) * L.K + (size_t)(g.col_id + (int)cc)] = s.T.cb[v];
+            }
         }
     });
 }
@@ -287,46 +389,107 @@ __global__ void fill_kernel(float *p, size_t n, float v)
 // ------------------------------------------------------------------------- //
 // fused decode + sparse multiply (small batches)
 // ------------------------------------------------------------------------- //
-// Workgroup (panel p, split j) decodes its share of the chunks of block row p and
-// accumulates w * x into an LDS tile of the bh x B outputs of that block row
-// (Algorithm 2 step 12, b[row_id : row_id + bh, :] += block * a[col_id : col_id + bw, :]),
-// then adds the tile into Y.
+// Columns of activations a workgroup may stage in LDS per image.
+constexpr int kXCap = 640;
+// Largest batch tile that stages its activations in LDS.
+constexpr int kXldsMaxBt = 4;
+
+// Workgroup j of block row p takes chunks [8 j, 8 j + 8) of that block row, one per
+// wavefront, and accumulates w * x into an LDS tile of the bh x BT outputs of the
+// block row (Algorithm 2 step 12, b[row_id : row_id + bh, :] += block * a[col_id :
+// col_id + bw, :]), then adds the tile into Y.  Each lane takes one entry per
+// round.  With XLDS the activation columns the workgroup's chunks can touch are
+// staged in LDS first (when they fit kXCap); otherwise they are read from global
+// memory one round ahead.
+template <typename E_T, bool WIDE, int BT, bool XLDS>
 __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *Y,
-                                                             int B, int splits)
+                                                             int wg_per_panel)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    const Smem s = carve(smem_raw, L);
-    const int p = (int)(blockIdx.x / (uint32_t)splits), j = (int)(blockIdx.x % (uint32_t)splits);
-    const uint32_t pc0 = L.panel_chunk[p], pc1 = L.panel_chunk[p + 1];
-    const uint32_t nck = pc1 - pc0;
-    const uint32_t my0 = pc0 + (uint32_t)(((uint64_t)nck * (uint32_t)j) / (uint32_t)splits);
-    const uint32_t my1 = pc0 + (uint32_t)(((uint64_t)nck * (uint32_t)(j + 1)) / (uint32_t)splits);
-    if (my0 >= my1) return;
-    const int row_id = p * L.bh;
-    const int bhp = min(L.bh, L.M - row_id);
-    float *ytile = s.extra;      // [B][bh]
-    for (int t = threadIdx.x; t < L.bh * B; t += blockDim.x) ytile[t] = 0.0f;
-    load_tables(s, L);
-    __syncthreads();
+    const Smem<E_T> s = carve<E_T>(smem_raw, L);
+    const int p = (int)(blockIdx.x / (uint32_t)wg_per_panel), j = (int)(blockIdx.x % (uint32_t)wg_per_panel);
+    const uint32_t pc1 = L.panel_chunk[p + 1];
+    const uint32_t my0 = L.panel_chunk[p] + (uint32_t)j * kWaves;
+    if (my0 >= pc1) return;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    uint8_t *vs = s.stage + (size_t)wave * 2 * CL_MAX_CHUNK_ENTRIES;
-    uint8_t *zs = vs + CL_MAX_CHUNK_ENTRIES;
-    for (uint32_t c = my0 + (uint32_t)wave; c < my1; c += kWaves) {
-        const ChunkInfo ci = decode_chunk(L, c, lane, s.vlut, s.ilut, vs, zs);
-        for_each_entry(L, ci, lane, vs, zs, [&](bool act, uint32_t v, uint32_t pos, const BlockGeom &g, uint32_t) {
-            if (!act || v == 0 || pos >= (uint32_t)g.bhp * (uint32_t)g.bwp) return;
-            uint32_t r, cc;
-            split_pos(pos, g, r, cc);
-            const float w = s.cb[v];
-            const float *x = X + (size_t)(g.col_id + (int)cc);
-            float *y = ytile + r;
-            for (int b = 0; b < B; ++b) atomicAdd(y + (size_t)b * L.bh, w * x[(size_t)b * L.K]);
+    const uint32_t c = my0 + (uint32_t)wave;
+    const bool have = c < pc1;
+    ChunkRaw raw{};
+    if (have) raw = load_chunk(L, c, lane);
+    const int row_id = p * L.bh;
+    const int bhp = min(L.bh, L.M - row_id);
+    float *ytile = s.extra;                  // [BT][bh]
+    float *xs = ytile + (size_t)L.bh * BT;   // [BT][kXCap] when XLDS
+    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
+    // activation columns this workgroup's chunks can touch: from the first chunk's
+    // first block to the block the next workgroup starts in (or the block row's end)
+    int col_a = 0;
+    bool slab = false;
+    if (XLDS) {
+        const uint32_t c_end = min(pc1, my0 + (uint32_t)kWaves);
+        const uint32_t b_a = L.meta[my0].blk0;
+        const uint32_t b_b = c_end < pc1 ? L.meta[c_end].blk0 : (uint32_t)(p + 1) * (uint32_t)L.nbw - 1u;
+        col_a = (int)(b_a - (uint32_t)p * (uint32_t)L.nbw) * L.bw;
+        const int col_b = min(L.K, (int)(b_b - (uint32_t)p * (uint32_t)L.nbw + 1u) * L.bw);
+        const int width = col_b - col_a;
+        slab = width <= kXCap;
+        if (slab) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+                for (int t = threadIdx.x; t < width; t += blockDim.x) xs[b * kXCap + t] = X[(size_t)b * L.K + col_a + t];
+        }
+    }
+    load_tables(s, L);
+    __syncthreads();
+    if (have) {
+        E_T *vs = s.stage + (size_t)wave * 2 * kStage;
+        E_T *ss = vs + kStage;
+        const ChunkInfo ci = decode_chunk<E_T, WIDE>(L, raw, lane, s.T, vs, ss);
+        struct Round {
+            bool act;
+            uint32_t r;
+            float w;
+            float x[BT];
+        };
+        for_each_segment<E_T>(L, ci, ss, [&](const BlockGeom &g, uint32_t base, int i0, int i1) {
+            const uint32_t np = (uint32_t)g.bhp * (uint32_t)g.bwp;
+            auto fetch = [&](int at) {
+                Round q;
+                const int i = at + lane;
+                const bool in = i < i1;
+                const uint32_t v = in ? vs[i] : 0u;
+                const uint32_t pos = (in ? (uint32_t)ss[i] : 1u) + base - 1u;
+                q.act = v != 0 && pos < np;
+                uint32_t cc = 0;
+                q.r = 0;
+                if (q.act) split_pos(pos, g, q.r, cc);
+                q.w = s.T.cb[v];
+                const int col = g.col_id + (int)cc;
+                if (XLDS && slab) {
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) q.x[b] = xs[b * kXCap + (col - col_a)];
+                } else {
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) q.x[b] = q.act ? X[(size_t)b * L.K + col] : 0.0f;
+                }
+                return q;
+            };
+            Round cur = fetch(i0);
+            for (int at = i0; at < i1; at += 64) {
+                Round nxt = cur;
+                if (at + 64 < i1) nxt = fetch(at + 64);
+                if (cur.act) {
+                    float *y = ytile + cur.r;
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) atomicAdd(y + b * L.bh, cur.w * cur.x[b]);
+                }
+                cur = nxt;
+            }
         });
-        wave_lds_fence();    // staging is reused by the next chunk
     }
     __syncthreads();
-    for (int t = threadIdx.x; t < bhp * B; t += blockDim.x) {
+    for (int t = threadIdx.x; t < bhp * BT; t += blockDim.x) {
         const int b = t / bhp, r = t - b * bhp;
         const float v = ytile[b * L.bh + r];
         if (v != 0.0f) atomicAdd(Y + (size_t)b * L.M + row_id + r, v);
@@ -373,6 +536,28 @@ static int32_t device_limits(DeviceLimits &dl)
     return CL_OK;
 }
 
+// Event bracket around the main kernel of the last forward call (benchmarks only).
+struct KernelTiming {
+    bool on = false, valid = false;
+    hipEvent_t a = nullptr, b = nullptr;
+    int launches = 0;
+};
+static KernelTiming g_timing;
+
+static void timing_begin(hipStream_t st)
+{
+    if (!g_timing.on) return;
+    g_timing.launches = 0;
+    g_timing.valid = hipEventRecord(g_timing.a, st) == hipSuccess;
+}
+
+static void timing_end(hipStream_t st, int launches)
+{
+    if (!g_timing.on || !g_timing.valid) return;
+    g_timing.launches = launches;
+    g_timing.valid = hipEventRecord(g_timing.b, st) == hipSuccess;
+}
+
 void release_device(cl_layer *L)
 {
     if (L->dev.blob) {
@@ -380,6 +565,9 @@ void release_device(cl_layer *L)
         L->dev = DeviceImage{};
     }
 }
+
+// The running position sum inside a chunk is at most entries * 2^k.
+static bool sums_fit_u16(const cl_layer *L) { return ((int64_t)CL_MAX_CHUNK_ENTRIES << L->desc.index_bits) <= 65535; }
 
 static int32_t require_device(const cl_layer *L)
 {
@@ -412,8 +600,8 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
         {L->block_ptr.data(), L->block_ptr.size() * 4, 0},
         {L->panel_chunk.data(), L->panel_chunk.size() * 4, 0},
         {L->codebook.data(), L->codebook.size() * 4, 0},
-        {L->val_lut.data(), L->val_lut.size() * sizeof(lut_t), 0},
-        {L->idx_lut.data(), L->idx_lut.size() * sizeof(lut_t), 0},
+        {L->val_mlut.data(), L->val_mlut.size() * 4, 0},
+        {L->idx_mlut.data(), L->idx_mlut.size() * 4, 0},
     };
     size_t total = 0;
     for (auto &s : secs) { s.off = total; total += (s.bytes + 255) / 256 * 256; }
@@ -436,8 +624,8 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
     L->dev.block_ptr = (const uint32_t *)(blob + secs[3].off);
     L->dev.panel_chunk = (const uint32_t *)(blob + secs[4].off);
     L->dev.codebook = (const float *)(blob + secs[5].off);
-    L->dev.val_lut = (const lut_t *)(blob + secs[6].off);
-    L->dev.idx_lut = (const lut_t *)(blob + secs[7].off);
+    L->dev.val_mlut = (const uint32_t *)(blob + secs[6].off);
+    L->dev.idx_mlut = (const uint32_t *)(blob + secs[7].off);
     clear_error();
     return CL_OK;
 }
@@ -448,6 +636,8 @@ extern "C" int32_t cl_decode_layer(const cl_layer *L, uint8_t *d_val_sym, uint8_
     if (int32_t rc = require_device(L)) return rc;
     hipStream_t st = (hipStream_t)stream;
     const LayerDev D = make_dev(L);
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
     if (d_block_ptr)
         HIP_TRY(hipMemcpyAsync(d_block_ptr, L->dev.block_ptr, (size_t)(L->n_blocks + 1) * 4, hipMemcpyDeviceToDevice, st));
     if (d_dense) {
@@ -456,25 +646,27 @@ extern "C" int32_t cl_decode_layer(const cl_layer *L, uint8_t *d_val_sym, uint8_
         HIP_TRY(hipGetLastError());
     }
     if (L->n_chunks > 0 && (d_val_sym || d_idx_sym || d_dense)) {
-        const size_t lds = smem_fixed_bytes(D.val_lut_bits, D.idx_lut_bits, D.ncode);
-        const unsigned grid = (unsigned)((L->n_chunks + kWaves - 1) / kWaves);
-        hipLaunchKernelGGL(decode_kernel, dim3(grid), dim3(kThreads), lds, st, D, d_val_sym, d_idx_sym, d_dense);
+        const bool narrow = sums_fit_u16(L);
+        const size_t lds = smem_fixed_bytes(D.val_mbits, D.idx_mbits, D.ncode, narrow ? 2 : 4);
+        const dim3 grid((unsigned)((L->n_chunks + kWaves - 1) / kWaves));
+        if (lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "decode tables need %zu bytes of LDS", lds);
+#define CL_LAUNCH_DECODE(E, W)                                                                                      \
+    do {                                                                                                            \
+        if (lds > 64 * 1024)                                                                                        \
+            HIP_TRY(hipFuncSetAttribute((const void *)decode_kernel<E, W>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+        hipLaunchKernelGGL((decode_kernel<E, W>), grid, dim3(kThreads), lds, st, D, d_val_sym, d_idx_sym, d_dense); \
+    } while (0)
+        if (narrow && !L->wide) CL_LAUNCH_DECODE(uint16_t, false);
+        else if (narrow) CL_LAUNCH_DECODE(uint16_t, true);
+        else if (!L->wide) CL_LAUNCH_DECODE(uint32_t, false);
+        else CL_LAUNCH_DECODE(uint32_t, true);
+#undef CL_LAUNCH_DECODE
         HIP_TRY(hipGetLastError());
     }
     clear_error();
     return CL_OK;
 }
 
-namespace {
-// Largest batch tile whose output tile fits beside the tables in LDS.
-int sparse_batch_tile(const cl_layer *L, size_t lds_budget, int batch)
-{
-    const size_t fixed = smem_fixed_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
-    if (fixed + (size_t)L->desc.block_h * 4 > lds_budget) return 0;
-    const size_t per_image = (size_t)L->desc.block_h * 4;
-    return (int)std::min<size_t>((size_t)batch, (lds_budget - fixed) / per_image);
-}
-}  // namespace
 
 extern "C" int32_t cl_fc_workspace_bytes(const cl_layer *L, int32_t batch, int32_t path, size_t *out)
 {
@@ -508,30 +700,79 @@ extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X,
                        d_Y, d_bias, M, batch);
     HIP_TRY(hipGetLastError());
     if (L->n_chunks > 0) {
-        const size_t budget = std::min<size_t>(dl.max_lds, 64 * 1024);
-        int bt = sparse_batch_tile(L, budget, batch);
-        if (bt < 1) bt = sparse_batch_tile(L, dl.max_lds, batch);
-        if (bt < 1) return fail(CL_EUNSUPPORTED, "block_h %d needs more LDS than a workgroup has", L->desc.block_h);
-        const size_t fixed = smem_fixed_bytes(D.val_lut_bits, D.idx_lut_bits, D.ncode);
-        // enough workgroups to fill the chip twice over, at least one per block row
-        const int target = std::max(1, dl.cus) * 2;
-        const int64_t mean_chunks = std::max<int64_t>(1, L->n_chunks / std::max(1, L->n_panels));
-        int splits = (int)std::max<int64_t>(1, std::min<int64_t>((target + L->n_panels - 1) / L->n_panels, mean_chunks));
-        for (int b0 = 0; b0 < batch; b0 += bt) {
-            const int nb = std::min(bt, batch - b0);
-            const size_t lds = fixed + (size_t)L->desc.block_h * nb * 4;
-            if (lds > 64 * 1024)
-                HIP_TRY(hipFuncSetAttribute((const void *)fc_sparse_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            hipLaunchKernelGGL(fc_sparse_kernel, dim3((unsigned)(L->n_panels * splits)), dim3(kThreads), lds, st,
-                               D, d_X + (size_t)b0 * K, d_Y + (size_t)b0 * M, nb, splits);
+        const bool narrow = sums_fit_u16(L);
+        const size_t fixed = smem_fixed_bytes(D.val_mbits, D.idx_mbits, D.ncode, narrow ? 2 : 4);
+        // LDS per image: a column of the output tile, plus the staged activations for small tiles
+        auto lds_for = [&](int bt) { return fixed + (size_t)L->desc.block_h * 4 * bt + (bt <= kXldsMaxBt ? (size_t)kXCap * 4 * bt : 0); };
+        // largest power-of-two batch tile (<= 16) that fits; prefer to stay under 64 KiB
+        size_t budget = std::min<size_t>(dl.max_lds, 64 * 1024);
+        if (lds_for(1) > budget) budget = dl.max_lds;
+        if (lds_for(1) > budget) return fail(CL_EUNSUPPORTED, "block_h %d needs more LDS than a workgroup has", L->desc.block_h);
+        int bt_max = 16;
+        while (bt_max > 1 && lds_for(bt_max) > budget) bt_max >>= 1;
+        // one wavefront per chunk: each block row gets enough workgroups for its chunks
+        const int wg_per_panel = (int)((L->max_panel_chunks + kWaves - 1) / kWaves);
+        const dim3 grid((unsigned)(L->n_panels * wg_per_panel));
+        timing_begin(st);
+        int launches = 0;
+        for (int b0 = 0; b0 < batch; ++launches) {
+            int bt = bt_max;
+            while (bt > batch - b0) bt >>= 1;
+            const size_t lds = lds_for(bt);
+            const float *x = d_X + (size_t)b0 * K;
+            float *y = d_Y + (size_t)b0 * M;
+#define CL_LAUNCH_SPARSE(E, W, BTV)                                                                                \
+    do {                                                                                                           \
+        auto kern = fc_sparse_kernel<E, W, BTV, (BTV <= kXldsMaxBt)>;                                             \
+        if (lds > 64 * 1024)                                                                                       \
+            HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+        hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, st, D, x, y, wg_per_panel);                           \
+    } while (0)
+#define CL_LAUNCH_SPARSE_BT(E, W)                                   \
+    switch (bt) {                                                   \
+    case 16: CL_LAUNCH_SPARSE(E, W, 16); break;                     \
+    case 8: CL_LAUNCH_SPARSE(E, W, 8); break;                       \
+    case 4: CL_LAUNCH_SPARSE(E, W, 4); break;                       \
+    case 2: CL_LAUNCH_SPARSE(E, W, 2); break;                       \
+    default: CL_LAUNCH_SPARSE(E, W, 1); break;                      \
+    }
+            if (narrow && !L->wide) { CL_LAUNCH_SPARSE_BT(uint16_t, false) }
+            else if (narrow) { CL_LAUNCH_SPARSE_BT(uint16_t, true) }
+            else if (!L->wide) { CL_LAUNCH_SPARSE_BT(uint32_t, false) }
+            else { CL_LAUNCH_SPARSE_BT(uint32_t, true) }
+#undef CL_LAUNCH_SPARSE_BT
+#undef CL_LAUNCH_SPARSE
             HIP_TRY(hipGetLastError());
+            b0 += bt;
         }
+        timing_end(st, launches);
     }
     if (relu) {
         hipLaunchKernelGGL(relu_kernel, dim3((unsigned)std::min<size_t>((nout + 255) / 256, 2048)), dim3(256), 0, st, d_Y, nout);
         HIP_TRY(hipGetLastError());
     }
     clear_error();
+    return CL_OK;
+}
+
+extern "C" int32_t cl_set_kernel_timing(int32_t enable)
+{
+    if (enable && !g_timing.a) {
+        HIP_TRY(hipEventCreate(&g_timing.a));
+        HIP_TRY(hipEventCreate(&g_timing.b));
+    }
+    g_timing.on = enable != 0;
+    g_timing.valid = false;
+    return CL_OK;
+}
+
+extern "C" int32_t cl_last_kernel_ms(float *ms, int32_t *launches)
+{
+    if (!ms || !launches) return fail(CL_EINVAL, "null argument");
+    if (!g_timing.on || !g_timing.valid) return fail(CL_EINVAL, "no timed forward call yet");
+    HIP_TRY(hipEventSynchronize(g_timing.b));
+    HIP_TRY(hipEventElapsedTime(ms, g_timing.a, g_timing.b));
+    *launches = g_timing.launches;
     return CL_OK;
 }
 

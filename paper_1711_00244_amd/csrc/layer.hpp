@@ -12,6 +12,7 @@ namespace cl {
 constexpr int kChunkBytes = CL_CHUNK_BITS / 8;      // 512
 constexpr int kLanes = 64;                          // one 64-bit slice per lane of a wavefront
 constexpr int kGapBytes = kLanes / 2;               // a nibble per lane
+constexpr int kMultiIndexBits = 10;                 // least index width of a multi-symbol decode table
 constexpr int kPayloadPad = 16;                     // lane 63 reads 8 bytes past its slice
 
 int32_t fail(int32_t code, const char *fmt, ...);
@@ -30,8 +31,8 @@ struct DeviceImage {
     const uint32_t *block_ptr = nullptr;
     const uint32_t *panel_chunk = nullptr;
     const float *codebook = nullptr;
-    const lut_t *val_lut = nullptr;
-    const lut_t *idx_lut = nullptr;
+    const uint32_t *val_mlut = nullptr;
+    const uint32_t *idx_mlut = nullptr;
 };
 
 }  // namespace cl
@@ -41,6 +42,7 @@ struct cl_layer {
     int64_t nnz = 0, padding = 0, entries = 0, n_blocks = 0, n_chunks = 0;
     int32_t n_panels = 0;          // block rows
     int32_t nbw = 0;               // blocks across
+    int64_t max_panel_chunks = 0;  // most chunks in any block row
     int64_t val_bits = 0, idx_bits = 0, val_bits_unlimited = 0, idx_bits_unlimited = 0;
     std::vector<float> codebook;
     std::vector<uint8_t> val_len, idx_len;
@@ -48,8 +50,11 @@ struct cl_layer {
     std::vector<uint32_t> block_ptr, panel_chunk;
     std::vector<cl_chunk_meta> meta;                // n_chunks + 1
     std::vector<uint8_t> gaps, payload;
-    std::vector<cl::lut_t> val_lut, idx_lut;
-    int val_lut_bits = 1, idx_lut_bits = 1;
+    std::vector<cl::lut_t> val_lut, idx_lut;          // one symbol per lookup (host validation)
+    std::vector<uint32_t> val_mlut, idx_mlut;         // several symbols per lookup (device)
+    int val_lut_bits = 1, idx_lut_bits = 1;           // longest codeword of each code
+    int val_mbits = 1, idx_mbits = 1;                 // index width of the device tables
+    bool wide = false;                                // symbols need 8 bits in a table entry
     cl::DeviceImage dev;
 };
 
@@ -67,6 +72,8 @@ bool canonical_codes(const std::vector<uint8_t> &len, std::vector<uint32_t> &cod
 // Flat decode table indexed by the next max_len stream bits.
 void build_lut(const std::vector<uint8_t> &len, const std::vector<uint32_t> &code, int max_len,
                std::vector<lut_t> &lut);
+
+void build_multi_lut(const std::vector<lut_t> &single, int max_len, int mbits, bool wide, std::vector<uint32_t> &multi);
 
 // compress.cpp
 // Derive codes and decode tables from the stored lengths, then decode every chunk

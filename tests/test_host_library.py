@@ -62,7 +62,7 @@ def cross_decode(layer):
         gaps = hv["lane_gap"][c * 32:(c + 1) * 32]
         for lane in range(64):
             s = starts[(starts >= lane * 64) & (starts < lane * 64 + 64)]
-            want = int(s.min()) - lane * 64 if s.size else 0
+            want = int(s.min()) - lane * 64 if s.size else 15
             assert (int(gaps[lane >> 1]) >> (4 * (lane & 1))) & 15 == want
         # block / carry of the chunk's first entry, and the block-row rule
         e0 = int(m["sym_off"])
