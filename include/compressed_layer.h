@@ -44,8 +44,11 @@ enum {
 
 /* Bits per chunk of the compressed stream; the only value this build accepts. */
 #define CL_CHUNK_BITS 4096
-/* No chunk holds more entries than this. */
-#define CL_MAX_CHUNK_ENTRIES 768
+/* A chunk is up to 64 lane records of 64 bits, one per lane of a wavefront. */
+#define CL_RECORD_BITS 64
+#define CL_RECORDS_PER_CHUNK 64
+/* A record holds at most this many entries (its count field has 4 bits). */
+#define CL_MAX_RECORD_ENTRIES 15
 /* Longest Huffman codeword the format allows. */
 #define CL_MAX_CODE_LEN 12
 
@@ -66,9 +69,11 @@ enum {
  *                1..8.
  *  block_h/w     bh x bw blocks, stored contiguously block after block in the
  *                order Algorithm 2 visits them (Sec. IV-A).  Inside a block the
- *                positions run down the rows of a column first, so the relative
- *                index is a row gap; (M, 1) gives plain CSC columns.  Edge blocks
- *                keep their true, smaller shape.
+ *                positions run along a row first (the 4 x 16 re-layout of the
+ *                paper's 8 x 8 example), so the relative index is a column gap
+ *                that carries over from one row of the block to the next; a block
+ *                of one column, (M, 1), is a plain CSC column with a relative row
+ *                index.  Edge blocks keep their true, smaller shape.
  *  chunk_bits    must be CL_CHUNK_BITS (0 is taken as that).
  *  max_code_len  limit on Huffman codeword length, 0 = CL_MAX_CODE_LEN; must be
  *                >= max(weight_bits, index_bits) and <= CL_MAX_CODE_LEN. */
@@ -94,38 +99,49 @@ typedef struct {
     int64_t idx_bits;       /* Huffman-coded bits of the relative-index array        */
     int64_t val_bits_unlimited; /* same arrays under unrestricted Huffman codes:     */
     int64_t idx_bits_unlimited; /*   what the length limit costs                     */
-    int64_t payload_bytes;  /* chunk payloads (512 B each)                           */
-    int64_t table_bytes;    /* chunk table + lane gaps + block_ptr + panel table     */
+    int64_t n_records;
+    int64_t payload_bytes;  /* lane records (8 B each): counts, codewords, padding   */
+    int64_t table_bytes;    /* chunk table + block_ptr + panel table                 */
     int64_t model_bytes;    /* payload + tables + codebook + code lengths: the bytes */
                             /*   a forward pass has to fetch                         */
     int64_t lut_bytes;      /* decode tables derived at load time (not stored)       */
     int32_t val_max_len, idx_max_len;
 } cl_stats;
 
-/* One record per chunk (plus one sentinel record at index n_chunks whose sym_off
- * is the total entry count).  A chunk is 4096 bits: the value-index codewords of
- * entries [sym_off, next sym_off) from bit 0, then - from the next multiple of 64
- * bits - the relative-index codewords of the same entries.  This pair of start
- * addresses is the per-chunk form of the row_ptr 2-tuple of Sec. III-B.
- *  blk0    block that entry sym_off belongs to
- *  pos0    sum of (z + 1) over the entries of block blk0 that precede the chunk,
- *          i.e. the carry of the position prefix sum (Algorithm 1 step 7)         */
+/* Layout of the compressed streams.
+ *
+ * The entries of a block are cut into lane records of 64 bits.  Bit b of a record
+ * is bit b of its little-endian 64-bit word.
+ *   bits [0, 4)   n, the number of entries in the record (1..15)
+ *   from bit 4 upwards: the value-index codewords of those n entries, in entry
+ *                 order, each codeword's bits in the order the code tree is walked
+ *   from bit 63 downwards: the relative-index codewords of the same n entries
+ *                 (the first bit of the first codeword is bit 63, the next bit 62, ...)
+ *   the bits in between are zero.
+ * So a record carries a span of the value-index stream and the matching span of
+ * the relative-index stream, with both start addresses fixed by the layout - the
+ * per-record form of the row_ptr 2-tuple of Sec. III-B.  A record never crosses a
+ * block.
+ *
+ * A chunk is up to 64 consecutive records of one block (4096 bits when full): what
+ * one wavefront decodes.  One table entry per chunk, plus a sentinel entry at index
+ * n_chunks holding the totals:
+ *   sym_off   index of the chunk's first entry ("symbol offset")
+ *   rec_off   index of its first record (start address of the chunk in the stream)
+ *   blk       the block all its entries belong to
+ *   pos0      sum of (z + 1) over the entries of that block that precede the chunk,
+ *             i.e. the carry of the position prefix sum (Algorithm 1 step 7)       */
 typedef struct {
     uint32_t sym_off;
-    uint32_t blk0;
+    uint32_t rec_off;
+    uint32_t blk;
     uint32_t pos0;
-    uint16_t val_bits;
-    uint16_t idx_bits;
 } cl_chunk_meta;
 
 /* Read-only view of the host copy of a layer, for inspection and tests.  The
  * pointers stay valid until cl_layer_free().
- *  val_code / idx_code   codeword of each symbol with bit j = the j-th bit written
- *                        to the stream; stream bit b is bit (b mod 8) of byte b/8.
- *  lane_gap              32 bytes per chunk; nibble l (low nibble first) is, for
- *                        the 64-bit slice l of the chunk, the distance from the
- *                        slice start to the first codeword that starts in it
- *                        (at most 11), or 15 when no codeword starts there.      */
+ *  val_code / idx_code   codeword of each symbol with bit j = the j-th bit of the
+ *                        codeword in tree-walk order.                              */
 typedef struct {
     cl_layer_desc desc;
     const float *codebook;         /* 2^r                                            */
@@ -136,9 +152,8 @@ typedef struct {
     const uint32_t *block_ptr;     /* n_blocks + 1, entry offsets                    */
     const uint32_t *panel_chunk;   /* n_panels + 1, first chunk of each block row    */
     const cl_chunk_meta *chunk_meta; /* n_chunks + 1                                 */
-    const uint8_t *lane_gap;       /* 32 * n_chunks                                  */
-    const uint8_t *payload;        /* 512 * n_chunks (+ 16 bytes of zero padding)    */
-    int64_t n_blocks, n_chunks, n_entries;
+    const uint64_t *records;       /* n_records                                      */
+    int64_t n_blocks, n_chunks, n_records, n_entries;
     int32_t n_panels;
 } cl_host_view;
 
@@ -146,8 +161,8 @@ const char *cl_last_error(void);
 
 /* Sec. III-B pipeline on the host: quantise the surviving weights of W to the
  * codebook, build the relative-indexed entries block by block, Huffman-code both
- * arrays (length-limited, canonical) and lay the codewords out in 4096-bit chunks
- * with their chunk table.
+ * arrays (length-limited, canonical) and lay the codewords out in lane records and
+ * 4096-bit chunks with their chunk table.
  *  W_host      M*K fp32, already pruned: a pruned weight is exactly 0.  Non-finite
  *              values are rejected.
  *  codebook    2^r fp32 with codebook[0] == 0, or NULL for a linear codebook:

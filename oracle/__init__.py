@@ -101,7 +101,7 @@ def num_blocks(M, K, bh, bw) -> int:
     return int(_chk(lib().orc_num_blocks(M, K, bh, bw), "num_blocks"))
 
 
-def build_entries(q, bh: int, bw: int, k: int, colmajor: bool = True):
+def build_entries(q, bh: int, bw: int, k: int, colmajor: bool = False):
     """q: M x K uint8 index matrix -> (val, idx, block_ptr)."""
     q = _c(q, np.uint8)
     M, K = q.shape
@@ -160,7 +160,7 @@ def huffman_decode_span(buf, start_bit, end_bit, ln, code):
     return out[:n].copy()
 
 
-def reconstruct(val, idx, block_ptr, codebook, M, K, bh, bw, k, colmajor=True, want_q=False):
+def reconstruct(val, idx, block_ptr, codebook, M, K, bh, bw, k, colmajor=False, want_q=False):
     val = _c(val, np.uint8)
     idx = _c(idx, np.uint8)
     bp = _c(block_ptr, np.int64)
@@ -237,7 +237,7 @@ class OracleModel:
         return int(self.row_ptr[-1, 0]), int(self.row_ptr[-1, 1])
 
 
-def compress_layer(W, r, k, bh, bw, codebook=None, colmajor=True, keep=False) -> OracleModel:
+def compress_layer(W, r, k, bh, bw, codebook=None, colmajor=False, keep=False) -> OracleModel:
     """Sec. III-B pipeline on an already pruned matrix (pruned = exact zeros):
     quantise -> relative-indexed entries per block -> Huffman code each array."""
     W = _c(W, np.float32)

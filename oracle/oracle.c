@@ -122,9 +122,11 @@ int64_t orc_num_blocks(int M, int K, int bh, int bw)
 /* of the paper's example.)                                                   */
 /* READING: nothing is stored for the zeros that follow a block's last        */
 /* non-zero.                                                                   */
-/* READING: colmajor != 0 flattens a block column by column (p = c*bh' + r),  */
-/* so the gap runs along rows (CSC-style); colmajor == 0 flattens it row by   */
-/* row (p = r*bw' + c) as the paper's 8x8 -> 4x16 illustration does.          */
+/* READING: colmajor == 0 flattens a block row by row (p = r*bw' + c), as the  */
+/* paper's 8x8 -> 4x16 illustration does (a block's elements stored           */
+/* contiguously, the re-laid matrix then kept as relative-indexed CSR); a     */
+/* block of a single column then is a CSC column with a relative row index.   */
+/* colmajor != 0 flattens a block column by column (p = c*bh' + r) instead.   */
 /*                                                                            */
 /* q: M x K row-major quantised indices (0 = pruned).  With val == NULL only  */
 /* the number of entries is returned.  block_ptr (nblocks + 1, 0-based entry  */

@@ -16,7 +16,7 @@ from . import build as _build
 
 CL_OK, CL_EINVAL, CL_ENOMEM, CL_ECORRUPT, CL_EUNSUPPORTED, CL_EHIP = 0, -1, -2, -3, -4, -5
 PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32 = 0, 1, 2
-CHUNK_BITS, MAX_CHUNK_ENTRIES, MAX_CODE_LEN = 4096, 768, 12
+CHUNK_BITS, RECORD_BITS, RECORDS_PER_CHUNK, MAX_RECORD_ENTRIES, MAX_CODE_LEN = 4096, 64, 64, 15, 12
 
 EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
@@ -32,20 +32,21 @@ class LayerDesc(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("nnz", "padding", "entries", "n_blocks", "n_chunks", "val_bits", "idx_bits",
-                                         "val_bits_unlimited", "idx_bits_unlimited", "payload_bytes", "table_bytes",
+                                         "val_bits_unlimited", "idx_bits_unlimited", "n_records", "payload_bytes", "table_bytes",
                                          "model_bytes", "lut_bytes")] + [("val_max_len", C.c_int32), ("idx_max_len", C.c_int32)]
 
 
 class ChunkMeta(C.Structure):
-    _fields_ = [("sym_off", C.c_uint32), ("blk0", C.c_uint32), ("pos0", C.c_uint32), ("val_bits", C.c_uint16), ("idx_bits", C.c_uint16)]
+    _fields_ = [("sym_off", C.c_uint32), ("rec_off", C.c_uint32), ("blk", C.c_uint32), ("pos0", C.c_uint32)]
 
 
 class HostView(C.Structure):
     _fields_ = [("desc", LayerDesc), ("codebook", C.POINTER(C.c_float)), ("val_len", C.POINTER(C.c_uint8)),
                 ("val_code", C.POINTER(C.c_uint32)), ("idx_len", C.POINTER(C.c_uint8)), ("idx_code", C.POINTER(C.c_uint32)),
                 ("block_ptr", C.POINTER(C.c_uint32)), ("panel_chunk", C.POINTER(C.c_uint32)),
-                ("chunk_meta", C.POINTER(ChunkMeta)), ("lane_gap", C.POINTER(C.c_uint8)), ("payload", C.POINTER(C.c_uint8)),
-                ("n_blocks", C.c_int64), ("n_chunks", C.c_int64), ("n_entries", C.c_int64), ("n_panels", C.c_int32)]
+                ("chunk_meta", C.POINTER(ChunkMeta)), ("records", C.POINTER(C.c_uint64)),
+                ("n_blocks", C.c_int64), ("n_chunks", C.c_int64), ("n_records", C.c_int64), ("n_entries", C.c_int64),
+                ("n_panels", C.c_int32)]
 
 
 class ConvDesc(C.Structure):
@@ -166,15 +167,16 @@ class Layer:
             return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dt, copy=True)
 
         nc = int(v.n_chunks)
-        meta = np.zeros(nc + 1, dtype=[("sym_off", "<u4"), ("blk0", "<u4"), ("pos0", "<u4"), ("val_bits", "<u2"), ("idx_bits", "<u2")])
+        meta = np.zeros(nc + 1, dtype=[("sym_off", "<u4"), ("rec_off", "<u4"), ("blk", "<u4"), ("pos0", "<u4")])
         C.memmove(meta.ctypes.data, v.chunk_meta, meta.nbytes)
         return dict(desc={n: getattr(d, n) for n, _ in LayerDesc._fields_},
                     codebook=arr(v.codebook, nval, np.float32), val_len=arr(v.val_len, nval, np.uint8),
                     val_code=arr(v.val_code, nval, np.uint32), idx_len=arr(v.idx_len, nidx, np.uint8),
                     idx_code=arr(v.idx_code, nidx, np.uint32), block_ptr=arr(v.block_ptr, int(v.n_blocks) + 1, np.uint32),
                     panel_chunk=arr(v.panel_chunk, int(v.n_panels) + 1, np.uint32), chunk_meta=meta,
-                    lane_gap=arr(v.lane_gap, nc * 32, np.uint8), payload=arr(v.payload, nc * 512 + 16, np.uint8),
-                    n_blocks=int(v.n_blocks), n_chunks=nc, n_entries=int(v.n_entries), n_panels=int(v.n_panels))
+                    records=arr(v.records, int(v.n_records), np.uint64),
+                    n_blocks=int(v.n_blocks), n_chunks=nc, n_records=int(v.n_records), n_entries=int(v.n_entries),
+                    n_panels=int(v.n_panels))
 
     def serialize(self) -> bytes:
         n = C.c_size_t(0)

@@ -64,23 +64,18 @@ int32_t check_desc(cl_layer_desc &d)
     return CL_OK;
 }
 
-inline void put_bits(uint8_t *chunk, int bit, uint32_t code, int len)
+inline uint64_t bit_reverse64(uint64_t x)
 {
-    for (int j = 0; j < len; ++j, ++bit)
-        if ((code >> j) & 1u) chunk[bit >> 3] |= (uint8_t)(1u << (bit & 7));
-}
-
-inline uint32_t peek_bits(const uint8_t *chunk, int bit, int n)   // n <= 16, may read 3 bytes
-{
-    uint32_t w = chunk[bit >> 3] | (chunk[(bit >> 3) + 1] << 8) | (chunk[(bit >> 3) + 2] << 16);
-    return (w >> (bit & 7)) & ((1u << n) - 1u);
+    uint64_t r = 0;
+    for (int i = 0; i < 64; ++i) r |= ((x >> i) & 1ull) << (63 - i);
+    return r;
 }
 
 }  // namespace
 
 // --------------------------------------------------------------------------- //
 // Everything that can be derived from the stored sections is derived here, then
-// every chunk is decoded and every table entry is compared with what the decode
+// every record is decoded and every table entry is compared with what the decode
 // finds.  Used after compression (self-check) and after deserialisation.
 // --------------------------------------------------------------------------- //
 int32_t finalize_and_validate(cl_layer *L)
@@ -109,20 +104,14 @@ int32_t finalize_and_validate(cl_layer *L)
     L->idx_lut_bits = std::max(1, L->idx_lut_bits);
     build_lut(L->val_len, L->val_code, L->val_lut_bits, L->val_lut);
     build_lut(L->idx_len, L->idx_code, L->idx_lut_bits, L->idx_lut);
-    // device tables: index wide enough for a few short codewords, never narrower than the longest one
-    L->wide = d.weight_bits > 6 || d.index_bits > 6;
-    L->val_mbits = std::max(L->val_lut_bits, kMultiIndexBits);
-    L->idx_mbits = std::max(L->idx_lut_bits, kMultiIndexBits);
-    build_multi_lut(L->val_lut, L->val_lut_bits, L->val_mbits, L->wide, L->val_mlut);
-    build_multi_lut(L->idx_lut, L->idx_lut_bits, L->idx_mbits, L->wide, L->idx_mlut);
 
     if ((int64_t)L->block_ptr.size() != g.n_blocks + 1) return fail(CL_ECORRUPT, "block_ptr has the wrong size");
     if ((int64_t)L->panel_chunk.size() != (int64_t)g.nbh + 1) return fail(CL_ECORRUPT, "panel table has the wrong size");
     if (L->meta.empty()) return fail(CL_ECORRUPT, "chunk table is empty");
     L->n_chunks = (int64_t)L->meta.size() - 1;
-    if ((int64_t)L->gaps.size() != L->n_chunks * kGapBytes) return fail(CL_ECORRUPT, "lane gap table has the wrong size");
-    if ((int64_t)L->payload.size() != L->n_chunks * kChunkBytes + kPayloadPad) return fail(CL_ECORRUPT, "payload has the wrong size");
+    L->n_records = (int64_t)L->records.size();
     L->entries = L->meta[L->n_chunks].sym_off;
+    if (L->meta[L->n_chunks].rec_off != L->n_records) return fail(CL_ECORRUPT, "chunk table does not span the records");
     if (L->block_ptr[0] != 0 || L->block_ptr[g.n_blocks] != L->entries) return fail(CL_ECORRUPT, "block_ptr does not span the entries");
     for (int64_t b = 0; b < g.n_blocks; ++b)
         if (L->block_ptr[b] > L->block_ptr[b + 1]) return fail(CL_ECORRUPT, "block_ptr is not monotone");
@@ -134,69 +123,70 @@ int32_t finalize_and_validate(cl_layer *L)
     }
 
     const uint32_t vmask = (1u << L->val_lut_bits) - 1u, imask = (1u << L->idx_lut_bits) - 1u;
+    const uint32_t filler_z = (1u << d.index_bits) - 1u;
     int64_t nnz = 0, vbits = 0, ibits = 0;
-    std::vector<uint8_t> vs(CL_MAX_CHUNK_ENTRIES), zs(CL_MAX_CHUNK_ENTRIES);
+    uint64_t next_entry = 0, next_rec = 0;
+    int64_t cur_blk = -1;
+    uint64_t possum = 0;
     int panel = 0;
-    int64_t blk = 0;          // running block of the serial walk
-    uint64_t possum = 0;      // sum of (z+1) inside the running block
     for (int64_t c = 0; c < L->n_chunks; ++c) {
         const cl_chunk_meta &m = L->meta[c];
-        const uint32_t e0 = m.sym_off, e1 = L->meta[c + 1].sym_off;
-        if (e1 <= e0 || e1 - e0 > CL_MAX_CHUNK_ENTRIES) return fail(CL_ECORRUPT, "chunk %lld: bad entry range", (long long)c);
-        const int n = (int)(e1 - e0);
-        const int nv = (m.val_bits + 63) / 64;
-        if (m.val_bits < 1 || m.idx_bits < 1 || nv * 64 + m.idx_bits > CL_CHUNK_BITS)
-            return fail(CL_ECORRUPT, "chunk %lld: sub-streams do not fit", (long long)c);
+        const uint64_t r0 = m.rec_off, r1 = L->meta[c + 1].rec_off;
+        if (r0 != next_rec || r1 <= r0 || r1 - r0 > (uint64_t)kLanes || r1 > (uint64_t)L->n_records)
+            return fail(CL_ECORRUPT, "chunk %lld: bad record range", (long long)c);
+        if (m.sym_off != next_entry) return fail(CL_ECORRUPT, "chunk %lld: symbol offset is wrong", (long long)c);
+        if (m.blk >= (uint64_t)g.n_blocks || (int64_t)m.blk < cur_blk) return fail(CL_ECORRUPT, "chunk %lld: bad block", (long long)c);
+        if ((int64_t)m.blk != cur_blk) {
+            if (m.sym_off != L->block_ptr[m.blk]) return fail(CL_ECORRUPT, "chunk %lld does not start its block", (long long)c);
+            cur_blk = m.blk;
+            possum = 0;
+        }
+        if (m.pos0 != possum) return fail(CL_ECORRUPT, "chunk %lld: position carry is wrong", (long long)c);
         while (panel < g.nbh && (int64_t)L->panel_chunk[panel + 1] <= c) ++panel;
-        const uint8_t *chunk = L->payload.data() + c * kChunkBytes;
-        const uint8_t *gap = L->gaps.data() + c * kGapBytes;
-        uint8_t want_gap[kLanes];
-        bool seen[kLanes];
-        std::memset(want_gap, 15, sizeof want_gap);      // 15: no codeword starts in the slice
-        std::memset(seen, 0, sizeof seen);
-        // value-index sub-stream, then relative-index sub-stream
-        for (int part = 0; part < 2; ++part) {
-            const int base = part ? nv * 64 : 0;
-            const int end = base + (part ? m.idx_bits : m.val_bits);
-            const std::vector<lut_t> &lut = part ? L->idx_lut : L->val_lut;
-            const std::vector<uint8_t> &len = part ? L->idx_len : L->val_len;
-            const uint32_t mask = part ? imask : vmask;
-            const int lbits = part ? L->idx_lut_bits : L->val_lut_bits;
-            int pos = base;
-            for (int i = 0; i < n; ++i) {
-                if (pos >= end) return fail(CL_ECORRUPT, "chunk %lld: sub-stream %d ends early", (long long)c, part);
-                const int lane = pos / 64;
-                if (!seen[lane]) { seen[lane] = true; want_gap[lane] = (uint8_t)(pos % 64); }
-                const lut_t e = lut[peek_bits(chunk, pos, lbits) & mask];
-                const int s = e & 0xff, l = e >> 8;
-                if (len[s] != l) return fail(CL_ECORRUPT, "chunk %lld: bit pattern is not a codeword", (long long)c);
-                (part ? zs : vs)[i] = (uint8_t)s;
-                pos += l;
+        if ((int64_t)m.blk / g.nbw != panel) return fail(CL_ECORRUPT, "chunk %lld is not inside its block row", (long long)c);
+        int row_id, col_id, bhp, bwp;
+        g.block(m.blk, row_id, col_id, bhp, bwp);
+        const uint64_t np = (uint64_t)bhp * bwp;
+        for (uint64_t r = r0; r < r1; ++r) {
+            const uint64_t w = L->records[r];
+            const int n = (int)(w & 15u);
+            if (n < 1) return fail(CL_ECORRUPT, "record %llu is empty", (unsigned long long)r);
+            uint64_t vbuf = w >> kCountBits, ibuf = bit_reverse64(w);
+            int vused = 0, iused = 0;
+            for (int j = 0; j < n; ++j) {
+                const lut_t ev = L->val_lut[(uint32_t)vbuf & vmask], ei = L->idx_lut[(uint32_t)ibuf & imask];
+                const int v = ev & 0xff, lv = ev >> 8, z = ei & 0xff, li = ei >> 8;
+                if (L->val_len[v] != lv || L->idx_len[z] != li) return fail(CL_ECORRUPT, "record %llu: bit pattern is not a codeword", (unsigned long long)r);
+                vbuf >>= lv;
+                ibuf >>= li;
+                vused += lv;
+                iused += li;
+                if (kCountBits + vused + iused > CL_RECORD_BITS) return fail(CL_ECORRUPT, "record %llu overflows", (unsigned long long)r);
+                possum += (uint64_t)z + 1;
+                if (possum > np) return fail(CL_ECORRUPT, "record %llu: position leaves its block", (unsigned long long)r);
+                if (v) ++nnz;
+                else if ((uint32_t)z != filler_z) return fail(CL_ECORRUPT, "padding entry with a short gap");
             }
-            if (pos != end) return fail(CL_ECORRUPT, "chunk %lld: sub-stream %d has the wrong length", (long long)c, part);
-            (part ? ibits : vbits) += end - base;
-        }
-        for (int l = 0; l < kLanes; ++l) {
-            const int got = (gap[l >> 1] >> (4 * (l & 1))) & 15;
-            if (got != want_gap[l]) return fail(CL_ECORRUPT, "chunk %lld: lane gap %d is wrong", (long long)c, l);
-        }
-        // positions: the chunk's carry, block by block
-        for (int i = 0; i < n; ++i) {
-            const uint32_t e = e0 + i;
-            while (blk < g.n_blocks && L->block_ptr[blk + 1] <= e) { ++blk; possum = 0; }
-            if (blk >= g.n_blocks) return fail(CL_ECORRUPT, "entry beyond the last block");
-            if (i == 0) {
-                if (m.blk0 != blk || m.pos0 != possum) return fail(CL_ECORRUPT, "chunk %lld: block carry is wrong", (long long)c);
-                if (blk / g.nbw != panel) return fail(CL_ECORRUPT, "chunk %lld: not inside its block row", (long long)c);
+            // the bits between the two spans must be zero
+            const int gap_bits = CL_RECORD_BITS - kCountBits - vused - iused;
+            if (gap_bits > 0) {
+                const uint64_t mid = (w >> (kCountBits + vused)) & ((gap_bits == 64 ? 0 : (1ull << gap_bits)) - 1ull);
+                if (mid) return fail(CL_ECORRUPT, "record %llu: stray bits between its spans", (unsigned long long)r);
             }
-            if (blk / g.nbw != panel) return fail(CL_ECORRUPT, "chunk %lld spans two block rows", (long long)c);
-            int row_id, col_id, bhp, bwp;
-            g.block(blk, row_id, col_id, bhp, bwp);
-            possum += (uint64_t)zs[i] + 1;
-            if (possum > (uint64_t)bhp * bwp) return fail(CL_ECORRUPT, "chunk %lld: position leaves its block", (long long)c);
-            if (vs[i]) ++nnz;
-            else if (zs[i] != (1 << d.index_bits) - 1) return fail(CL_ECORRUPT, "padding entry with a short gap");
+            vbits += vused;
+            ibits += iused;
+            next_entry += (uint64_t)n;
         }
+        if (next_entry > L->block_ptr[m.blk + 1]) return fail(CL_ECORRUPT, "chunk %lld runs past its block", (long long)c);
+        next_rec = r1;
+    }
+    if (next_entry != (uint64_t)L->entries) return fail(CL_ECORRUPT, "records do not add up to the entry count");
+    // every non-empty block must have been covered in full
+    for (int64_t c = 0; c < L->n_chunks; ++c) {
+        const cl_chunk_meta &m = L->meta[c];
+        const bool last_of_block = c + 1 == L->n_chunks || L->meta[c + 1].blk != m.blk;
+        if (last_of_block && L->meta[c + 1].sym_off != L->block_ptr[m.blk + 1])
+            return fail(CL_ECORRUPT, "block %u is not covered by its chunks", m.blk);
     }
     L->nnz = nnz;
     L->padding = L->entries - nnz;
@@ -262,7 +252,7 @@ extern "C" int32_t cl_compress_layer(const cl_layer_desc *desc, const float *W, 
             }
             q[(size_t)i] = (uint8_t)best;
         }
-        // ---- relative-indexed entries, block after block, column-major inside a block ----
+        // ---- relative-indexed entries, block after block, row by row inside a block ----
         const int R = 1 << d.index_bits;
         std::vector<uint8_t> val, idx;
         val.reserve((size_t)(total / 8 + 16));
@@ -273,10 +263,10 @@ extern "C" int32_t cl_compress_layer(const cl_layer_desc *desc, const float *W, 
             g.block(b, row_id, col_id, bhp, bwp);
             L->block_ptr[(size_t)b] = (uint32_t)val.size();
             int64_t run = 0;   // zeros seen since the last stored element
-            for (int c = 0; c < bwp; ++c) {
-                const uint8_t *col = q.data() + (size_t)row_id * d.K + (col_id + c);
-                for (int r = 0; r < bhp; ++r) {
-                    const uint8_t s = col[(size_t)r * d.K];
+            for (int r = 0; r < bhp; ++r) {
+                const uint8_t *row = q.data() + (size_t)(row_id + r) * d.K + col_id;
+                for (int c = 0; c < bwp; ++c) {
+                    const uint8_t s = row[c];
                     if (!s) { ++run; continue; }
                     while (run >= R) { val.push_back(0); idx.push_back((uint8_t)(R - 1)); run -= R; }
                     val.push_back(s);
@@ -300,62 +290,49 @@ extern "C" int32_t cl_compress_layer(const cl_layer_desc *desc, const float *W, 
         int dummy;
         if (!canonical_codes(L->val_len, L->val_code, &dummy) || !canonical_codes(L->idx_len, L->idx_code, &dummy))
             return fail(CL_EINVAL, "internal: code construction failed");
-        // ---- chunks: as many whole entries as fit 4096 bits, never across a block row ----
+        // ---- lane records and chunks: a record takes as many whole entries as fit its 64 bits,
+        // a chunk takes up to 64 records; neither crosses a block ----
         L->panel_chunk.assign((size_t)g.nbh + 1, 0);
-        int64_t blk = 0;
-        uint64_t possum = 0;
-        for (int p = 0; p < g.nbh; ++p) {
-            L->panel_chunk[(size_t)p] = (uint32_t)L->meta.size();
-            const int64_t pe0 = L->block_ptr[(size_t)p * g.nbw], pe1 = L->block_ptr[(size_t)(p + 1) * g.nbw];
-            int64_t e = pe0;
-            while (e < pe1) {
-                // how many entries fit
-                int vb = 0, ib = 0, n = 0;
-                while (e + n < pe1 && n < CL_MAX_CHUNK_ENTRIES) {
-                    const int lv = L->val_len[val[(size_t)(e + n)]], li = L->idx_len[idx[(size_t)(e + n)]];
-                    if ((vb + lv + 63) / 64 * 64 + ib + li > CL_CHUNK_BITS) break;
-                    vb += lv; ib += li; ++n;
+        for (int64_t b = 0; b < g.n_blocks; ++b) {
+            if (b % g.nbw == 0) L->panel_chunk[(size_t)(b / g.nbw)] = (uint32_t)L->meta.size();
+            const int64_t be0 = L->block_ptr[(size_t)b], be1 = L->block_ptr[(size_t)b + 1];
+            uint64_t possum = 0;
+            int in_chunk = kLanes;
+            for (int64_t e = be0; e < be1;) {
+                if (in_chunk == kLanes) {
+                    cl_chunk_meta m;
+                    m.sym_off = (uint32_t)e;
+                    m.rec_off = (uint32_t)L->records.size();
+                    m.blk = (uint32_t)b;
+                    m.pos0 = (uint32_t)possum;
+                    L->meta.push_back(m);
+                    in_chunk = 0;
                 }
-                while (blk < g.n_blocks && (int64_t)L->block_ptr[(size_t)blk + 1] <= e) { ++blk; possum = 0; }
-                cl_chunk_meta m;
-                m.sym_off = (uint32_t)e;
-                m.blk0 = (uint32_t)blk;
-                m.pos0 = (uint32_t)possum;
-                m.val_bits = (uint16_t)vb;
-                m.idx_bits = (uint16_t)ib;
-                L->meta.push_back(m);
-                const size_t at = L->payload.size();
-                L->payload.resize(at + kChunkBytes, 0);
-                const size_t gat = L->gaps.size();
-                L->gaps.resize(gat + kGapBytes, 0xff);        // nibble 15: no codeword starts in the slice
-                uint8_t *chunk = L->payload.data() + at;
-                uint8_t *gap = L->gaps.data() + gat;
-                bool seen[kLanes] = {false};
-                int vpos = 0, ipos = (vb + 63) / 64 * 64;
-                for (int i = 0; i < n; ++i) {
-                    const uint8_t v = val[(size_t)(e + i)], z = idx[(size_t)(e + i)];
-                    for (int part = 0; part < 2; ++part) {
-                        int &pos = part ? ipos : vpos;
-                        const int lane = pos / 64;
-                        if (!seen[lane]) {
-                            seen[lane] = true;
-                            gap[lane >> 1] = (uint8_t)((gap[lane >> 1] & ~(15u << (4 * (lane & 1)))) | ((uint32_t)(pos % 64) << (4 * (lane & 1))));
-                        }
-                        if (part) { put_bits(chunk, pos, L->idx_code[z], L->idx_len[z]); pos += L->idx_len[z]; }
-                        else { put_bits(chunk, pos, L->val_code[v], L->val_len[v]); pos += L->val_len[v]; }
-                    }
-                    // keep the running block / position carry in step with the entries
-                    while (blk < g.n_blocks && (int64_t)L->block_ptr[(size_t)blk + 1] <= e + i) { ++blk; possum = 0; }
+                uint64_t rec = 0;
+                int vpos = kCountBits, itop = CL_RECORD_BITS, n = 0;     // value bits go up from vpos, index bits down from itop
+                while (e + n < be1 && n < CL_MAX_RECORD_ENTRIES) {
+                    const uint8_t v = val[(size_t)(e + n)], z = idx[(size_t)(e + n)];
+                    const int lv = L->val_len[v], li = L->idx_len[z];
+                    if (vpos + lv + li > itop) break;
+                    rec |= (uint64_t)L->val_code[v] << vpos;
+                    vpos += lv;
+                    for (int j = 0; j < li; ++j)
+                        rec |= (uint64_t)((L->idx_code[z] >> j) & 1u) << (itop - 1 - j);
+                    itop -= li;
                     possum += (uint64_t)z + 1;
+                    ++n;
                 }
+                rec |= (uint64_t)n;
+                L->records.push_back(rec);
                 e += n;
+                ++in_chunk;
             }
         }
         L->panel_chunk[(size_t)g.nbh] = (uint32_t)L->meta.size();
         cl_chunk_meta sentinel{};
         sentinel.sym_off = (uint32_t)n_entries;
+        sentinel.rec_off = (uint32_t)L->records.size();
         L->meta.push_back(sentinel);
-        L->payload.resize(L->payload.size() + kPayloadPad, 0);
     } catch (const std::bad_alloc &) {
         return fail(CL_ENOMEM, "out of memory");
     }
@@ -389,11 +366,11 @@ extern "C" int32_t cl_layer_stats(const cl_layer *L, cl_stats *s)
     s->idx_bits = L->idx_bits;
     s->val_bits_unlimited = L->val_bits_unlimited;
     s->idx_bits_unlimited = L->idx_bits_unlimited;
-    s->payload_bytes = L->n_chunks * kChunkBytes;
-    s->table_bytes = (int64_t)(L->meta.size() * sizeof(cl_chunk_meta) + L->gaps.size() +
-                               L->block_ptr.size() * 4 + L->panel_chunk.size() * 4);
+    s->n_records = L->n_records;
+    s->payload_bytes = L->n_records * 8;
+    s->table_bytes = (int64_t)(L->meta.size() * sizeof(cl_chunk_meta) + L->block_ptr.size() * 4 + L->panel_chunk.size() * 4);
     s->model_bytes = s->payload_bytes + s->table_bytes + (int64_t)(L->codebook.size() * 4 + L->val_len.size() + L->idx_len.size());
-    s->lut_bytes = (int64_t)((L->val_mlut.size() + L->idx_mlut.size()) * 4);
+    s->lut_bytes = (int64_t)((L->val_lut.size() + L->idx_lut.size()) * sizeof(lut_t));
     s->val_max_len = L->val_lut_bits;
     s->idx_max_len = L->idx_lut_bits;
     return CL_OK;
@@ -411,10 +388,10 @@ extern "C" int32_t cl_layer_host_view(const cl_layer *L, cl_host_view *v)
     v->block_ptr = L->block_ptr.data();
     v->panel_chunk = L->panel_chunk.data();
     v->chunk_meta = L->meta.data();
-    v->lane_gap = L->gaps.data();
-    v->payload = L->payload.data();
+    v->records = L->records.data();
     v->n_blocks = L->n_blocks;
     v->n_chunks = L->n_chunks;
+    v->n_records = L->n_records;
     v->n_entries = L->entries;
     v->n_panels = L->n_panels;
     return CL_OK;
@@ -429,7 +406,7 @@ struct ImageHeader {
     uint32_t version;
     uint32_t header_bytes;
     cl_layer_desc desc;
-    int64_t n_blocks, n_chunks, n_entries;
+    int64_t n_blocks, n_chunks, n_records, n_entries;
     int64_t val_bits_unlimited, idx_bits_unlimited;
     uint64_t checksum;      // FNV-1a over every byte after the header
 };
@@ -451,16 +428,17 @@ extern "C" int32_t cl_layer_serialize(const cl_layer *L, void *buf, size_t *byte
     if (!L || !bytes) return fail(CL_EINVAL, "null argument");
     const size_t need = sizeof(ImageHeader) + section_bytes(L->codebook) + section_bytes(L->val_len) +
                         section_bytes(L->idx_len) + section_bytes(L->block_ptr) + section_bytes(L->panel_chunk) +
-                        section_bytes(L->meta) + section_bytes(L->gaps) + section_bytes(L->payload);
+                        section_bytes(L->meta) + section_bytes(L->records);
     if (!buf) { *bytes = need; return CL_OK; }
     if (*bytes < need) { *bytes = need; return fail(CL_EINVAL, "buffer too small: need %zu bytes", need); }
     ImageHeader h{};
     std::memcpy(h.magic, kMagic, 8);
-    h.version = 1;
+    h.version = 2;
     h.header_bytes = sizeof(ImageHeader);
     h.desc = L->desc;
     h.n_blocks = L->n_blocks;
     h.n_chunks = L->n_chunks;
+    h.n_records = L->n_records;
     h.n_entries = L->entries;
     h.val_bits_unlimited = L->val_bits_unlimited;
     h.idx_bits_unlimited = L->idx_bits_unlimited;
@@ -472,8 +450,7 @@ extern "C" int32_t cl_layer_serialize(const cl_layer *L, void *buf, size_t *byte
     put(L->block_ptr.data(), section_bytes(L->block_ptr));
     put(L->panel_chunk.data(), section_bytes(L->panel_chunk));
     put(L->meta.data(), section_bytes(L->meta));
-    put(L->gaps.data(), section_bytes(L->gaps));
-    put(L->payload.data(), section_bytes(L->payload));
+    put(L->records.data(), section_bytes(L->records));
     h.checksum = fnv1a((const char *)buf + sizeof h, need - sizeof h);
     std::memcpy(buf, &h, sizeof h);
     *bytes = need;
@@ -487,18 +464,17 @@ extern "C" int32_t cl_layer_deserialize(const void *buf, size_t bytes, cl_layer 
     if (bytes < sizeof(ImageHeader)) return fail(CL_ECORRUPT, "image shorter than its header");
     ImageHeader h;
     std::memcpy(&h, buf, sizeof h);
-    if (std::memcmp(h.magic, kMagic, 8) || h.version != 1 || h.header_bytes != sizeof(ImageHeader))
+    if (std::memcmp(h.magic, kMagic, 8) || h.version != 2 || h.header_bytes != sizeof(ImageHeader))
         return fail(CL_ECORRUPT, "not a compressed-layer image");
     cl_layer_desc d = h.desc;
     if (check_desc(d) != CL_OK) return fail(CL_ECORRUPT, "bad descriptor: %s", cl_last_error());
     const Geometry g(d);
-    if (h.n_blocks != g.n_blocks || h.n_chunks < 0 || h.n_entries < 0 || h.n_chunks > h.n_entries ||
+    if (h.n_blocks != g.n_blocks || h.n_chunks < 0 || h.n_entries < 0 || h.n_chunks > h.n_records || h.n_records > h.n_entries ||
         h.n_entries > std::numeric_limits<int32_t>::max())
         return fail(CL_ECORRUPT, "inconsistent counts");
     const size_t nval = (size_t)1 << d.weight_bits, nidx = (size_t)1 << d.index_bits;
     const size_t need = sizeof(ImageHeader) + nval * 4 + nval + nidx + ((size_t)g.n_blocks + 1) * 4 + ((size_t)g.nbh + 1) * 4 +
-                        ((size_t)h.n_chunks + 1) * sizeof(cl_chunk_meta) + (size_t)h.n_chunks * kGapBytes +
-                        (size_t)h.n_chunks * kChunkBytes + kPayloadPad;
+                        ((size_t)h.n_chunks + 1) * sizeof(cl_chunk_meta) + (size_t)h.n_records * 8;
     if (bytes != need) return fail(CL_ECORRUPT, "image size %zu does not match its header (%zu)", bytes, need);
     if (fnv1a((const char *)buf + sizeof h, need - sizeof h) != h.checksum) return fail(CL_ECORRUPT, "checksum mismatch");
     std::unique_ptr<cl_layer> L(new (std::nothrow) cl_layer);
@@ -517,8 +493,7 @@ extern "C" int32_t cl_layer_deserialize(const void *buf, size_t bytes, cl_layer 
         get(L->block_ptr, (size_t)g.n_blocks + 1);
         get(L->panel_chunk, (size_t)g.nbh + 1);
         get(L->meta, (size_t)h.n_chunks + 1);
-        get(L->gaps, (size_t)h.n_chunks * kGapBytes);
-        get(L->payload, (size_t)h.n_chunks * kChunkBytes + kPayloadPad);
+        get(L->records, (size_t)h.n_records);
     } catch (const std::bad_alloc &) {
         return fail(CL_ENOMEM, "out of memory");
     }

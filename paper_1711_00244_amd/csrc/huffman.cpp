@@ -129,36 +129,4 @@ void build_lut(const std::vector<uint8_t> &len, const std::vector<uint32_t> &cod
     }
 }
 
-// Multi-symbol decode table indexed by the next `mbits` stream bits (mbits >= the
-// longest codeword).  An entry packs the consecutive symbols whose codewords lie
-// wholly inside the index, how many there are, the bits they consume together and
-// the length of the first codeword alone (for decoding one symbol at a time near
-// the end of a lane's slice).
-//   narrow (symbols < 64):  [0:6) [6:12) [12:18) symbols  [18:22) bits  [22:24) count  [24:28) first length
-//   wide:                   [0:8) [8:16) symbols           [16:20) bits  [20:22) count  [22:26) first length
-void build_multi_lut(const std::vector<lut_t> &single, int max_len, int mbits, bool wide, std::vector<uint32_t> &multi)
-{
-    const int bits = std::max(1, max_len);
-    const uint32_t smask = (1u << bits) - 1u;
-    const int cap = wide ? 2 : 3, sbits = wide ? 8 : 6;
-    multi.assign((size_t)1 << mbits, 0);
-    for (uint32_t i = 0; i < (1u << mbits); ++i) {
-        uint32_t idx = i, entry = 0;
-        int left = mbits, n = 0, used = 0, first = 0;
-        while (n < cap) {
-            const lut_t e = single[idx & smask];
-            const int l = e >> 8;
-            if (l > left) break;          // the next codeword is not wholly inside the index
-            entry |= (uint32_t)(e & 0xff) << (sbits * n);
-            if (n == 0) first = l;
-            ++n;
-            used += l;
-            left -= l;
-            idx >>= l;
-        }
-        const int at = sbits * cap;
-        multi[i] = entry | ((uint32_t)used << at) | ((uint32_t)n << (at + 4)) | ((uint32_t)first << (at + 6));
-    }
-}
-
 }  // namespace cl

@@ -9,11 +9,8 @@
 
 namespace cl {
 
-constexpr int kChunkBytes = CL_CHUNK_BITS / 8;      // 512
-constexpr int kLanes = 64;                          // one 64-bit slice per lane of a wavefront
-constexpr int kGapBytes = kLanes / 2;               // a nibble per lane
-constexpr int kMultiIndexBits = 10;                 // least index width of a multi-symbol decode table
-constexpr int kPayloadPad = 16;                     // lane 63 reads 8 bytes past its slice
+constexpr int kLanes = CL_RECORDS_PER_CHUNK;        // one 64-bit record per lane of a wavefront
+constexpr int kCountBits = 4;                       // width of a record's entry-count field
 
 int32_t fail(int32_t code, const char *fmt, ...);
 void clear_error();
@@ -25,36 +22,32 @@ struct DeviceImage {
     int device = -1;
     char *blob = nullptr;          // one allocation; the pointers below point into it
     size_t blob_bytes = 0;
-    const uint8_t *payload = nullptr;
+    const uint64_t *records = nullptr;
     const cl_chunk_meta *meta = nullptr;
-    const uint8_t *gaps = nullptr;
     const uint32_t *block_ptr = nullptr;
     const uint32_t *panel_chunk = nullptr;
     const float *codebook = nullptr;
-    const uint32_t *val_mlut = nullptr;
-    const uint32_t *idx_mlut = nullptr;
+    const lut_t *val_lut = nullptr;
+    const lut_t *idx_lut = nullptr;
 };
 
 }  // namespace cl
 
 struct cl_layer {
     cl_layer_desc desc{};
-    int64_t nnz = 0, padding = 0, entries = 0, n_blocks = 0, n_chunks = 0;
+    int64_t nnz = 0, padding = 0, entries = 0, n_blocks = 0, n_chunks = 0, n_records = 0;
     int32_t n_panels = 0;          // block rows
     int32_t nbw = 0;               // blocks across
     int64_t max_panel_chunks = 0;  // most chunks in any block row
     int64_t val_bits = 0, idx_bits = 0, val_bits_unlimited = 0, idx_bits_unlimited = 0;
     std::vector<float> codebook;
     std::vector<uint8_t> val_len, idx_len;
-    std::vector<uint32_t> val_code, idx_code;       // stream-order codewords
+    std::vector<uint32_t> val_code, idx_code;       // codewords, bit j = j-th bit in tree-walk order
     std::vector<uint32_t> block_ptr, panel_chunk;
     std::vector<cl_chunk_meta> meta;                // n_chunks + 1
-    std::vector<uint8_t> gaps, payload;
-    std::vector<cl::lut_t> val_lut, idx_lut;          // one symbol per lookup (host validation)
-    std::vector<uint32_t> val_mlut, idx_mlut;         // several symbols per lookup (device)
-    int val_lut_bits = 1, idx_lut_bits = 1;           // longest codeword of each code
-    int val_mbits = 1, idx_mbits = 1;                 // index width of the device tables
-    bool wide = false;                                // symbols need 8 bits in a table entry
+    std::vector<uint64_t> records;
+    std::vector<cl::lut_t> val_lut, idx_lut;        // indexed by the next val_lut_bits / idx_lut_bits stream bits
+    int val_lut_bits = 1, idx_lut_bits = 1;         // longest codeword of each code
     cl::DeviceImage dev;
 };
 
@@ -66,17 +59,15 @@ namespace cl {
 bool limited_code_lengths(const std::vector<int64_t> &counts, int limit, std::vector<uint8_t> &len);
 // Coded size under an unrestricted Huffman code (sum of merged weights).
 int64_t unlimited_code_bits(const std::vector<int64_t> &counts);
-// Canonical codewords from lengths, returned in stream order (bit j = j-th bit
-// written).  Returns false when the lengths violate Kraft's inequality.
+// Canonical codewords from lengths (bit j = j-th bit written).  Returns false when
+// the lengths violate Kraft's inequality or exceed CL_MAX_CODE_LEN.
 bool canonical_codes(const std::vector<uint8_t> &len, std::vector<uint32_t> &code, int *max_len);
 // Flat decode table indexed by the next max_len stream bits.
 void build_lut(const std::vector<uint8_t> &len, const std::vector<uint32_t> &code, int max_len,
                std::vector<lut_t> &lut);
 
-void build_multi_lut(const std::vector<lut_t> &single, int max_len, int mbits, bool wide, std::vector<uint32_t> &multi);
-
 // compress.cpp
-// Derive codes and decode tables from the stored lengths, then decode every chunk
+// Derive codes and decode tables from the stored lengths, then decode every record
 // on the host and check every table against what the decode finds.
 int32_t finalize_and_validate(cl_layer *L);
 

@@ -37,47 +37,48 @@ def test_library_exports_every_declared_symbol():
 
 
 def cross_decode(layer):
-    """Decode the library's chunks with the oracle's bit-serial tree walk and
-    re-derive every table field from the walk.  -> (val, idx)."""
+    """Decode the library's records with the oracle's bit-serial tree walk and
+    re-derive every table field from the walk.  -> (val, idx, block_ptr)."""
     hv = layer.host_view()
-    meta, payload = hv["chunk_meta"], hv["payload"]
+    meta, records = hv["chunk_meta"], hv["records"]
     vlen, vcode = hv["val_len"], hv["val_code"].astype(np.uint64)
     ilen, icode = hv["idx_len"], hv["idx_code"].astype(np.uint64)
     bp = hv["block_ptr"].astype(np.int64)
     d = hv["desc"]
     nbw = -(-d["K"] // d["block_w"])
     vals, idxs = [], []
-    blk, carry = 0, 0
+    n_seen, carry, cur_blk = 0, 0, -1
+    assert int(meta[-1]["rec_off"]) == records.size and int(meta[-1]["sym_off"]) == hv["n_entries"]
     for c in range(hv["n_chunks"]):
         m = meta[c]
-        n = int(meta[c + 1]["sym_off"]) - int(m["sym_off"])
-        assert 1 <= n <= binding.MAX_CHUNK_ENTRIES
-        chunk = payload[c * 512:(c + 1) * 512 + 8]
-        nv = (int(m["val_bits"]) + 63) // 64
-        v, vend, vpos = oracle.huffman_decode_serial(chunk, int(m["val_bits"]), 0, n, vlen, vcode, want_bitpos=True)
-        z, zend, zpos = oracle.huffman_decode_serial(chunk, nv * 64 + int(m["idx_bits"]), nv * 64, n, ilen, icode, want_bitpos=True)
-        assert vend == m["val_bits"] and zend == nv * 64 + m["idx_bits"] <= 4096
-        # lane gaps: first codeword start at or after each slice start
-        starts = np.concatenate([vpos, zpos])
-        gaps = hv["lane_gap"][c * 32:(c + 1) * 32]
-        for lane in range(64):
-            s = starts[(starts >= lane * 64) & (starts < lane * 64 + 64)]
-            want = int(s.min()) - lane * 64 if s.size else 15
-            assert (int(gaps[lane >> 1]) >> (4 * (lane & 1))) & 15 == want
-        # block / carry of the chunk's first entry, and the block-row rule
-        e0 = int(m["sym_off"])
-        while bp[blk + 1] <= e0:
-            blk, carry = blk + 1, 0
-        assert (int(m["blk0"]), int(m["pos0"])) == (blk, carry)
+        r0, r1 = int(m["rec_off"]), int(meta[c + 1]["rec_off"])
+        assert 1 <= r1 - r0 <= binding.RECORDS_PER_CHUNK
+        blk = int(m["blk"])
+        if blk != cur_blk:                       # a new block starts: its first chunk, carry back to 0
+            assert int(m["sym_off"]) == bp[blk]
+            cur_blk, carry = blk, 0
+        assert int(m["sym_off"]) == n_seen and int(m["pos0"]) == carry
         panel = blk // nbw
         assert hv["panel_chunk"][panel] <= c < hv["panel_chunk"][panel + 1]
-        for i in range(n):
-            while bp[blk + 1] <= e0 + i:
-                blk, carry = blk + 1, 0
-            assert blk // nbw == panel
-            carry += int(z[i]) + 1
-        vals.append(v)
-        idxs.append(z)
+        for r in range(r0, r1):
+            w = int(records[r])
+            n = w & 15
+            assert 1 <= n <= binding.MAX_RECORD_ENTRIES
+            fwd = np.frombuffer(w.to_bytes(8, "little"), np.uint8)
+            # the relative-index span is read from bit 63 downwards: reverse the 64 bits
+            rw = int(format(w, "064b")[::-1], 2)
+            rev = np.frombuffer(rw.to_bytes(8, "little"), np.uint8)
+            v, vend = oracle.huffman_decode_serial(fwd, 64, 4, n, vlen, vcode)
+            z, zend = oracle.huffman_decode_serial(rev, 64, 0, n, ilen, icode)
+            assert vend + zend <= 64
+            assert (w >> vend) & ((1 << (64 - vend - zend)) - 1) == 0      # zero bits between the spans
+            vals.append(v)
+            idxs.append(z)
+            n_seen += n
+            carry += int(z.astype(np.int64).sum()) + n
+        assert n_seen <= bp[blk + 1]
+        if c + 1 == hv["n_chunks"] or int(meta[c + 1]["blk"]) != blk:
+            assert n_seen == bp[blk + 1]
     cat = lambda xs: np.concatenate(xs) if xs else np.zeros(0, np.uint8)
     return cat(vals), cat(idxs), bp
 
@@ -209,7 +210,7 @@ def test_validation_catches_inconsistent_tables_even_with_a_good_checksum():
     img = bytearray(L.serialize())
     hv = L.host_view()
     hdr = len(img) - (hv["codebook"].nbytes + hv["val_len"].nbytes + hv["idx_len"].nbytes + hv["block_ptr"].nbytes +
-                      hv["panel_chunk"].nbytes + hv["chunk_meta"].nbytes + hv["lane_gap"].nbytes + hv["payload"].nbytes)
+                      hv["panel_chunk"].nbytes + hv["chunk_meta"].nbytes + hv["records"].nbytes)
 
     def reseal(buf):
         h = 1469598103934665603
@@ -221,20 +222,20 @@ def test_validation_catches_inconsistent_tables_even_with_a_good_checksum():
     assert cl.layer_deserialize(reseal(bytearray(img))).stats() == L.stats()
     off_bp = hdr + hv["codebook"].nbytes + hv["val_len"].nbytes + hv["idx_len"].nbytes
     off_meta = off_bp + hv["block_ptr"].nbytes + hv["panel_chunk"].nbytes
-    off_gap = off_meta + hv["chunk_meta"].nbytes
-    off_payload = off_gap + hv["lane_gap"].nbytes
+    off_rec = off_meta + hv["chunk_meta"].nbytes
     tampered = []
     t = bytearray(img); t[off_bp + 4] ^= 1; tampered.append(t)                 # block_ptr[1]
     t = bytearray(img); t[off_meta + 16] ^= 1; tampered.append(t)              # sym_off of chunk 1
-    t = bytearray(img); t[off_meta + 16 + 8] ^= 1; tampered.append(t)          # pos0 of chunk 1
-    t = bytearray(img); t[off_meta + 12] ^= 1; tampered.append(t)              # val_bits of chunk 0
-    t = bytearray(img); t[off_gap + 3] ^= 1; tampered.append(t)                # a lane gap
+    t = bytearray(img); t[off_meta + 16 + 4] ^= 1; tampered.append(t)          # rec_off of chunk 1
+    t = bytearray(img); t[off_meta + 16 + 8] ^= 1; tampered.append(t)          # blk of chunk 1
+    t = bytearray(img); t[off_meta + 16 + 12] ^= 1; tampered.append(t)         # pos0 of chunk 1
+    t = bytearray(img); t[off_rec] ^= 1; tampered.append(t)                    # entry count of record 0
     t = bytearray(img); t[hdr + hv["codebook"].nbytes + 5] = 1; tampered.append(t)   # a code length (breaks Kraft)
     for t in tampered:
         with pytest.raises(cl.CLError) as e:
             cl.layer_deserialize(reseal(t))
         assert e.value.code == binding.CL_ECORRUPT
-    assert off_payload < len(img)
+    assert off_rec < len(img)
 
 
 def test_format_statistics_on_benchmark_shapes():
@@ -246,11 +247,13 @@ def test_format_statistics_on_benchmark_shapes():
     q, R = 1 - spec.density, 1 << spec.k
     assert abs(st["padding"] / st["nnz"] - q ** R / (1 - q ** R)) < 0.02
     bits_per_nnz = st["model_bytes"] * 8 / st["nnz"]
-    assert 8.5 < bits_per_nnz < 11.5
-    # tables are a modest fraction of the payload
-    assert st["table_bytes"] < 0.12 * st["payload_bytes"]
-    # chunks are well filled
-    assert (st["val_bits"] + st["idx_bits"]) / (st["n_chunks"] * 4096) > 0.95
+    assert 9.0 < bits_per_nnz < 12.0
+    # tables are a small fraction of the payload
+    assert st["table_bytes"] < 0.05 * st["payload_bytes"]
+    # records are well filled: count field (4 bits) + padding stay under a fifth of the payload
+    assert (st["val_bits"] + st["idx_bits"]) / (st["n_records"] * 64) > 0.80
+    # almost all chunks are full wavefronts
+    assert st["n_records"] / st["n_chunks"] > 55
 
 
 @pytest.mark.parametrize("seed", range(25))

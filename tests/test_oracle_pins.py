@@ -55,7 +55,7 @@ def py_blocks(M, K, bh, bw):
         yield row_id, col_id, min(bh, M - row_id), min(bw, K - col_id)
 
 
-def py_entries(q, bh, bw, k, colmajor=True):
+def py_entries(q, bh, bw, k, colmajor=False):
     M, K = q.shape
     val, idx, bp = [], [], [0]
     for row_id, col_id, bhp, bwp in py_blocks(M, K, bh, bw):
@@ -210,7 +210,7 @@ def test_round_trip_and_mask(M, K, bh, bw, d):
         for b, (row_id, col_id, bhp, bwp) in enumerate(py_blocks(M, K, bh, bw)):
             e = list(zip(val[bp[b]:bp[b + 1]].tolist(), idx[bp[b]:bp[b + 1]].tolist()))
             pos = [p for p, (v, z) in zip(py_positions(e), e) if v]
-            mask = (W[row_id:row_id + bhp, col_id:col_id + bwp] != 0).T.reshape(-1)
+            mask = (W[row_id:row_id + bhp, col_id:col_id + bwp] != 0).reshape(-1)
             assert pos == np.flatnonzero(mask).tolist()
         # quantisation error bound of a linear codebook: half a step
         if W.any() and r > 1:
@@ -376,7 +376,7 @@ def test_sparse_accumulation_over_entries_equals_dense():
         e = list(zip(val[bp[b]:bp[b + 1]].tolist(), idx[bp[b]:bp[b + 1]].tolist()))
         for (v, z), p in zip(e, py_positions(e)):
             if v:
-                y[row_id + p % bhp] += float(m.codebook[v]) * float(x[col_id + p // bhp])
+                y[row_id + p // bwp] += float(m.codebook[v]) * float(x[col_id + p % bwp])
     assert np.allclose(y, oracle.compressed_fc_forward(m, x[None])[0], rtol=1e-12, atol=1e-15)
 
 
