@@ -56,7 +56,8 @@ enum {
 enum {
     CL_PATH_AUTO = 0,     /* library picks from batch size and layer density        */
     CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
-    CL_PATH_MFMA_F32 = 2  /* decode blocks to dense LDS tiles, fp32 MFMA             */
+    CL_PATH_MFMA_F32 = 2  /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
+                          /*   of at most 128 x 128, else CL_EUNSUPPORTED            */
 };
 
 /* How a weight matrix is compressed.
@@ -201,7 +202,8 @@ int32_t cl_layer_deserialize(const void *buf, size_t bytes, cl_layer **out);
 int32_t cl_decode_layer(const cl_layer *layer, uint8_t *d_val_sym, uint8_t *d_idx_sym,
                         uint32_t *d_block_ptr, float *d_dense, void *stream);
 
-/* Device scratch a forward call needs for (batch, path).  May be 0. */
+/* Device scratch a forward call needs for (batch, path): the partial output tiles
+ * of the workgroups of each block row.  Needs a HIP device (CL_EHIP otherwise). */
 int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path, size_t *out);
 
 /* Y = act(X W^T + v) straight from the compressed layer (Eq. 1-2 with the
@@ -209,8 +211,9 @@ int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path
  *  d_X     batch x K fp32        d_bias  M fp32 or NULL
  *  d_Y     batch x M fp32, overwritten
  *  relu    non-zero applies max(0, .)
- *  path    CL_PATH_*; CL_PATH_SPARSE accumulates with floating-point atomics, so
- *          the summation order (not the tolerance) varies from run to run
+ *  path    CL_PATH_*.  CL_PATH_SPARSE adds lane sums into an LDS tile with
+ *          floating-point atomics, so the last bits of Y can differ between runs;
+ *          the tiles of a block row are then added up in a fixed order
  *  d_workspace / workspace_bytes   at least cl_fc_workspace_bytes(); may be NULL
  *          when that is 0
  * Errors: CL_EINVAL (null pointers, batch < 1, workspace too small, layer not
@@ -259,10 +262,10 @@ int32_t cl_plan_batches(int32_t n_layers, const int32_t *batch_set, int32_t n_ba
                         int32_t *out_batch_per_layer, double *out_ms_per_image);
 
 /* Measurement hook for benchmarks (not part of the paper's method).  While
- * enabled, every forward call brackets the launches of its main kernel - not the
- * small output-initialisation and activation kernels - with a pair of HIP events
- * on the call's stream.  cl_last_kernel_ms() waits for the most recent bracket and
- * returns its duration in milliseconds and the number of launches it covered.
+ * enabled, every forward call brackets the first launch of its main kernel (the
+ * first batch tile; not the small reduction kernel) with a pair of HIP events on
+ * the call's stream.  cl_last_kernel_ms() waits for the most recent bracket and
+ * returns its duration in milliseconds and the number of launches it covered (1).
  * Process-wide state, not thread safe; leave it off in production. */
 int32_t cl_set_kernel_timing(int32_t enable);
 int32_t cl_last_kernel_ms(float *ms, int32_t *launches);

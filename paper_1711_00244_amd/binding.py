@@ -126,6 +126,10 @@ class Layer:
 
     def __init__(self, handle):
         self._h = C.c_void_p(handle)
+        v = HostView()
+        _check(lib().cl_layer_host_view(self._h, C.byref(v)))
+        self.M, self.K = v.desc.M, v.desc.K
+        self._ws_cache = {}
 
     @property
     def handle(self):
@@ -225,17 +229,18 @@ def decode_layer(layer: Layer, want_dense=True):
 
 
 def fc_workspace_bytes(layer: Layer, batch: int, path: int = PATH_AUTO) -> int:
-    n = C.c_size_t(0)
-    _check(lib().cl_fc_workspace_bytes(layer.handle, batch, path, C.byref(n)))
-    return n.value
+    key = (batch, path)
+    if key not in layer._ws_cache:
+        n = C.c_size_t(0)
+        _check(lib().cl_fc_workspace_bytes(layer.handle, batch, path, C.byref(n)))
+        layer._ws_cache[key] = n.value
+    return layer._ws_cache[key]
 
 
 def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO, out=None, workspace=None):
     """X: (B, K) fp32 CUDA tensor -> Y: (B, M) fp32 CUDA tensor."""
     import torch
-    v = HostView()
-    _check(lib().cl_layer_host_view(layer.handle, C.byref(v)))
-    M, K = v.desc.M, v.desc.K
+    M, K = layer.M, layer.K
     if X.dtype != torch.float32 or X.dim() != 2 or X.shape[1] != K:
         raise ValueError(f"X must be (B, {K}) float32")
     B = X.shape[0]

@@ -188,6 +188,11 @@ int32_t finalize_and_validate(cl_layer *L)
         if (last_of_block && L->meta[c + 1].sym_off != L->block_ptr[m.blk + 1])
             return fail(CL_ECORRUPT, "block %u is not covered by its chunks", m.blk);
     }
+    // first chunk of every block (blocks without entries get an empty range)
+    L->block_chunk.assign((size_t)g.n_blocks + 1, (uint32_t)L->n_chunks);
+    for (int64_t c = L->n_chunks - 1; c >= 0; --c) L->block_chunk[L->meta[c].blk] = (uint32_t)c;
+    for (int64_t b = g.n_blocks - 1; b >= 0; --b)
+        if (L->block_ptr[b] == L->block_ptr[b + 1]) L->block_chunk[b] = L->block_chunk[b + 1];
     L->nnz = nnz;
     L->padding = L->entries - nnz;
     L->val_bits = vbits;

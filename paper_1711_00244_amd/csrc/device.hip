@@ -36,13 +36,22 @@ struct LayerDev {
     const uint64_t *records;
     const cl_chunk_meta *meta;
     const uint32_t *panel_chunk;
+    const uint32_t *block_chunk;
     const float *codebook;
     const lut_t *val_lut;
     const lut_t *idx_lut;
     int M, K, bh, bw, nbw;
     int val_bits, idx_bits, ncode;       // index widths of the decode tables, codebook entries
+    int table_rows;                      // 16-byte rows of the table image (tables + codebook)
     uint32_t n_chunks;
 };
+
+// Bytes of the table image: both decode tables, then the codebook, each padded to 16 bytes.
+static size_t table_image_bytes(int vbits, int ibits, int ncode)
+{
+    const size_t tb = (((size_t)1 << vbits) + ((size_t)1 << ibits)) * sizeof(lut_t);
+    return ((tb + 15) & ~(size_t)15) + (((size_t)ncode * 4 + 15) & ~(size_t)15);
+}
 
 static LayerDev make_dev(const cl_layer *L)
 {
@@ -50,6 +59,7 @@ static LayerDev make_dev(const cl_layer *L)
     d.records = L->dev.records;
     d.meta = L->dev.meta;
     d.panel_chunk = L->dev.panel_chunk;
+    d.block_chunk = L->dev.block_chunk;
     d.codebook = L->dev.codebook;
     d.val_lut = L->dev.val_lut;
     d.idx_lut = L->dev.idx_lut;
@@ -61,6 +71,7 @@ static LayerDev make_dev(const cl_layer *L)
     d.val_bits = L->val_lut_bits;
     d.idx_bits = L->idx_lut_bits;
     d.ncode = 1 << L->desc.weight_bits;
+    d.table_rows = (int)(table_image_bytes(L->val_lut_bits, L->idx_lut_bits, d.ncode) / 16);
     d.n_chunks = (uint32_t)L->n_chunks;
     return d;
 }
@@ -182,10 +193,7 @@ struct Smem {
     float *extra;
 };
 
-static size_t smem_fixed_bytes(int vbits, int ibits, int ncode)
-{
-    return (((size_t)1 << vbits) + ((size_t)1 << ibits)) * sizeof(lut_t) + (size_t)ncode * 4 + 16;
-}
+static size_t smem_fixed_bytes(int vbits, int ibits, int ncode) { return table_image_bytes(vbits, ibits, ncode); }
 
 __device__ __forceinline__ Smem carve(uint8_t *base, const LayerDev &L)
 {
@@ -200,22 +208,40 @@ __device__ __forceinline__ Smem carve(uint8_t *base, const LayerDev &L)
     s.T.cb = cb;
     s.T.vmask = (1u << L.val_bits) - 1u;
     s.T.imask = (1u << L.idx_bits) - 1u;
-    s.extra = cb + L.ncode;
+    s.extra = cb + ((L.ncode + 3) & ~3);
     return s;
 }
 
-__device__ __forceinline__ void load_tables(const Smem &s, const LayerDev &L)
+// The decode tables and the codebook sit in device memory exactly as they sit in
+// LDS (value table, index table, padding to 16 bytes, codebook, padding to 16
+// bytes), so a workgroup copies them as 16-byte rows: all loads are issued first,
+// the LDS stores follow once the rest of the prologue is under way.
+constexpr int kTableRows = 3;            // 16-byte rows per thread: 3 * 512 * 16 B covers two 12-bit tables + codebook
+
+struct TableRegs {
+    uint4 row[kTableRows];
+};
+
+__device__ __forceinline__ TableRegs fetch_tables(const LayerDev &L)
 {
-    // tables are whole numbers of dwords (at least 2 entries each)
-    const int nv = (1 << L.val_bits) / 2, ni = (1 << L.idx_bits) / 2;
-    const uint32_t *gv = (const uint32_t *)L.val_lut, *gi = (const uint32_t *)L.idx_lut;
-    uint32_t *sv = (uint32_t *)s.T.vlut, *si = (uint32_t *)s.T.ilut;
-    for (int t = threadIdx.x; t < nv + ni; t += blockDim.x) {
-        if (t < nv) sv[t] = gv[t];
-        else si[t - nv] = gi[t - nv];
+    TableRegs t;
+    const uint4 *g = (const uint4 *)L.val_lut;
+#pragma unroll
+    for (int k = 0; k < kTableRows; ++k) {
+        const int i = (int)threadIdx.x + k * kThreads;
+        t.row[k] = i < L.table_rows ? g[i] : uint4{0, 0, 0, 0};
     }
-    float *cb = (float *)s.T.cb;
-    for (int t = threadIdx.x; t < L.ncode; t += blockDim.x) cb[t] = L.codebook[t];
+    return t;
+}
+
+__device__ __forceinline__ void store_tables(const Smem &s, const LayerDev &L, const TableRegs &t)
+{
+    uint4 *d = (uint4 *)s.T.vlut;
+#pragma unroll
+    for (int k = 0; k < kTableRows; ++k) {
+        const int i = (int)threadIdx.x + k * kThreads;
+        if (i < L.table_rows) d[i] = t.row[k];
+    }
 }
 
 // ------------------------------------------------------------------------- //
@@ -235,7 +261,7 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(LayerDev L, uint8_t *v
         h = load_head(L, c);
         rec = load_record(L, h, lane);
     }
-    load_tables(s, L);
+    store_tables(s, L, fetch_tables(L));
     __syncthreads();
     if (!have) return;
     const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
@@ -267,13 +293,14 @@ __global__ void fill_kernel(float *p, size_t n, float v)
 // Workgroup j of block row p takes chunks [8 j, 8 j + 8) of that block row, one per
 // wavefront, and accumulates w * x into an LDS tile of the bh x BT outputs of the
 // block row (Algorithm 2 step 12, b[row_id : row_id + bh, :] += block * a[col_id :
-// col_id + bw, :]), then adds the tile into Y.  A lane's entries run along a row
-// of the block, so it sums w * x in registers and touches the tile only when the
-// row changes.  The activation columns of the blocks the workgroup's chunks belong
-// to are staged in LDS first when they fit xcap columns; otherwise activations are
+// col_id + bw, :]); the tile then goes to the workgroup's slot of `part`, and a
+// second kernel adds the slots of a block row up.  A lane's entries run along a
+// row of the block, so it sums w * x in registers and touches the tile only when
+// the row changes.  The activation columns of the blocks the workgroup's chunks
+// belong to are staged in LDS first when they fit xcap columns; otherwise they are
 // read from global memory.  A padding entry carries codebook value 0 and adds 0.
 template <int BT>
-__global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *Y,
+__global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *part,
                                                              int wg_per_panel, int xcap)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
@@ -292,11 +319,9 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
         h = load_head(L, c);
         rec = load_record(L, h, lane);
     }
-    const int row_id = p * L.bh;
-    const int bhp = min(L.bh, L.M - row_id);
+    const TableRegs tr = fetch_tables(L);
     float *ytile = s.extra;                  // [BT][bh]
     float *xs = ytile + (size_t)L.bh * BT;   // [BT][xcap]
-    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
     // activation columns of the blocks this workgroup's chunks belong to
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     const uint32_t c_last = min(pc1, my0 + (uint32_t)kWaves) - 1u;
@@ -309,23 +334,28 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
         for (int b = 0; b < BT; ++b)
             for (int t = threadIdx.x; t < width; t += blockDim.x) xs[b * xcap + t] = X[(size_t)b * L.K + col_a + t];
     }
-    load_tables(s, L);
+    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
+    store_tables(s, L, tr);
     __syncthreads();
     if (have) {
         const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
         const BlockGeom g = block_geom(L, h.m.blk);
         uint32_t sum = st.sum;
-        // pass B: one entry per step.  The two branches differ only in where the
-        // activations come from (LDS stays LDS: no generic pointers).
+        // pass B: one entry per step; the table lookups of the next entry are issued
+        // before the current entry's codebook value and activations are fetched.
+        // The two instantiations differ only in where the activations come from
+        // (LDS stays LDS: no generic pointers).
         auto entries = [&](auto load_x) {
             constexpr uint32_t kNoRow = 0xffffffffu;
             uint32_t cur = kNoRow;
             float acc[BT];
 #pragma unroll
             for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
+            uint32_t v = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);
+            uint32_t z = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);
             for (uint32_t jn = 0; jn < rec.n; ++jn) {
-                const uint32_t v = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);
-                const uint32_t z = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);
+                const uint32_t v1 = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);   // past the last entry these
+                const uint32_t z1 = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);   // read padding: harmless
                 sum += z + 1u;
                 uint32_t r, cc;
                 split_pos(sum - 1u, g, r, cc);
@@ -341,6 +371,8 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
                 const float w = s.T.cb[v];
 #pragma unroll
                 for (int b = 0; b < BT; ++b) acc[b] += w * load_x(b, (int)cc);
+                v = v1;
+                z = z1;
             }
             if (cur != kNoRow) {
 #pragma unroll
@@ -356,25 +388,164 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
         }
     }
     __syncthreads();
-    for (int t = threadIdx.x; t < bhp * BT; t += blockDim.x) {
-        const int b = t / bhp, r = t - b * bhp;
-        const float v = ytile[b * L.bh + r];
-        if (v != 0.0f) atomicAdd(Y + (size_t)b * L.M + row_id + r, v);
+    float *mine = part + (size_t)blockIdx.x * L.bh * BT;
+    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) mine[t] = ytile[t];
+}
+
+// Adds up the partial tiles of each block row in a fixed order, then bias and
+// activation (Eq. 1): Y[b][row] = act(sum_j part[p][j][b][r] + v[row]).
+// One workgroup per (block row, image).  The kSlices thread groups each add every
+// kSlices-th tile (several loads in flight), LDS adds the slices in order.
+constexpr int kRedThreads = 256, kSlices = 4;
+
+__global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
+                                                                const float *__restrict__ bias, float *Y, int B,
+                                                                int part_b, int wg_per_panel, int relu, int uniform_active)
+{
+    __shared__ float slice_sum[kRedThreads];
+    const int p = (int)blockIdx.x / B, b = (int)blockIdx.x - p * B;
+    const int row_id = p * L.bh;
+    const int bhp = min(L.bh, L.M - row_id);
+    // the sparse kernel fills one slot per eight chunks; the MFMA kernel fills every slot
+    const int active = uniform_active > 0 ? uniform_active
+                                          : (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kWaves - 1) / kWaves);
+    constexpr int kRows = kRedThreads / kSlices;
+    const int sl = (int)threadIdx.x / kRows, rl = (int)threadIdx.x - sl * kRows;
+    // part[p][j][image (part_b of them)][bh]
+    const float *src = part + ((size_t)p * wg_per_panel * part_b + b) * L.bh;
+    const size_t step = (size_t)part_b * L.bh;
+    for (int r0 = 0; r0 < bhp; r0 += kRows) {
+        const int r = r0 + rl;
+        float acc = 0.0f;
+        if (r < bhp) {
+            int j = sl;
+            for (; j + 3 * kSlices < active; j += 4 * kSlices) {
+                const float a0 = src[(size_t)j * step + r], a1 = src[(size_t)(j + kSlices) * step + r];
+                const float a2 = src[(size_t)(j + 2 * kSlices) * step + r], a3 = src[(size_t)(j + 3 * kSlices) * step + r];
+                acc += a0;
+                acc += a1;
+                acc += a2;
+                acc += a3;
+            }
+            for (; j < active; j += kSlices) acc += src[(size_t)j * step + r];
+        }
+        slice_sum[threadIdx.x] = acc;
+        __syncthreads();
+        if (sl == 0 && r < bhp) {
+            float t = slice_sum[rl];
+#pragma unroll
+            for (int k = 1; k < kSlices; ++k) t += slice_sum[k * kRows + rl];
+            if (bias) t += bias[row_id + r];
+            Y[(size_t)b * L.M + row_id + r] = relu ? fmaxf(t, 0.0f) : t;
+        }
+        __syncthreads();
     }
 }
 
-// Y[b][m] = bias[m] (or 0) before the partial sums are added in.
-__global__ void init_out_kernel(float *Y, const float *bias, int M, int B)
+// ------------------------------------------------------------------------- //
+// large batches: decode a block into a dense LDS tile, multiply on the fp32 MFMA
+// ------------------------------------------------------------------------- //
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTile = 128;               // block rows, block columns and images per workgroup tile
+constexpr int kWtStride = kTile + 4;     // LDS row stride of the weight tile (floats)
+
+// XT[k][b] = X[b][k], with the image axis padded to Bp (a multiple of kTile) with
+// zeros, so that a tile of activations is a plain copy of 128 rows.
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restrict__ X, float *XT, int B, int K, int Bp)
 {
-    const size_t n = (size_t)M * B;
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
-        Y[i] = bias ? bias[i % (size_t)M] : 0.0f;
+    __shared__ float t[32][33];
+    const int k0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+    for (int i = ty; i < 32; i += 8) {
+        const int b = b0 + i, k = k0 + tx;
+        t[i][tx] = (b < B && k < K) ? X[(size_t)b * K + k] : 0.0f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int k = k0 + i, b = b0 + tx;
+        if (k < K && b < Bp) XT[(size_t)k * Bp + b] = t[tx][i];
+    }
 }
 
-__global__ void relu_kernel(float *Y, size_t n)
+// Workgroup (block row p, split j, image tile nb).  For each of its blocks:
+//   1. clear the 128 x 128 weight tile in LDS, copy the block's 128 rows of XT
+//   2. decode the block's chunks (one wavefront per chunk) and write each weight at
+//      its place in the tile (Algorithm 2 steps 5-9: decode, prefix sum, codebook,
+//      "arrange as bh x bw block")
+//   3. tile x activations on the matrix cores, v_mfma_f32_32x32x2_f32 (step 12)
+// The tile is kept k-major (wt[k][r]) so that an MFMA A-fragment - 32 rows at one
+// k - is 32 consecutive floats.  Wavefront w owns rows 32 (w % 4) .. + 31 and
+// images 64 (w / 4) .. + 63 of the tile: two 32 x 32 accumulators.
+__global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
+                                                           int splits, int Bp)
 {
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
-        Y[i] = fmaxf(Y[i], 0.0f);
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    const Smem s = carve(smem_raw, L);
+    float *wt = s.extra;                                   // [kTile k][kWtStride]
+    float *xt = wt + kTile * kWtStride;                    // [kTile k][kTile b]
+    const int nbt = Bp / kTile;
+    const int nb = (int)blockIdx.x % nbt;
+    const int pj = (int)blockIdx.x / nbt;
+    const int p = pj / splits, j = pj - p * splits;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    store_tables(s, L, fetch_tables(L));
+    // this split's share of the block row's blocks
+    const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
+    floatx16 acc0 = {0}, acc1 = {0};
+    const int rb = wave & 3, ch = wave >> 2;
+    for (int bi = blk_lo; bi < blk_hi; ++bi) {
+        const uint32_t b = (uint32_t)p * (uint32_t)L.nbw + (uint32_t)bi;
+        const BlockGeom g = block_geom(L, b);
+        __syncthreads();                                   // previous tile fully consumed (and tables stored)
+        // 1. clear the weight tile, copy the activation rows (zero rows past the block's width)
+        for (int t = threadIdx.x; t < kTile * kWtStride / 4; t += kThreads) ((float4 *)wt)[t] = float4{0.f, 0.f, 0.f, 0.f};
+        for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) {
+            const int k = t / (kTile / 4), q = t - k * (kTile / 4);
+            float4 v = float4{0.f, 0.f, 0.f, 0.f};
+            if (k < g.bwp) v = *(const float4 *)(XT + (size_t)(g.col_id + k) * Bp + (size_t)nb * kTile + q * 4);
+            ((float4 *)xt)[t] = v;
+        }
+        __syncthreads();
+        // 2. decode: wavefront w takes chunks w, w + 8, ... of the block
+        const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
+        for (uint32_t c = c0 + (uint32_t)wave; c < c1; c += kWaves) {
+            const ChunkHead h = load_head(L, c);
+            LaneRecord rec = load_record(L, h, lane);
+            const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
+            uint32_t sum = st.sum;
+            for (uint32_t jn = 0; jn < rec.n; ++jn) {
+                const uint32_t v = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);
+                const uint32_t z = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);
+                sum += z + 1u;
+                uint32_t r, cc;
+                split_pos(sum - 1u, g, r, cc);
+                if (v != 0 && cc < (uint32_t)kTile) wt[cc * kWtStride + r] = s.T.cb[v];
+            }
+        }
+        __syncthreads();
+        // 3. 128 x 128 x 128 on the matrix cores
+        const float *wa = wt + (lane >> 5) * kWtStride + rb * 32 + (lane & 31);
+        const float *xb = xt + (lane >> 5) * kTile + ch * 64 + (lane & 31);
+#pragma unroll 4
+        for (int k = 0; k < kTile; k += 2) {
+            const float a = wa[k * kWtStride];
+            const float b0 = xb[k * kTile], b1 = xb[k * kTile + 32];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        }
+    }
+    // accumulator element i of lane l is row 8 (i / 4) + 4 (l / 32) + i % 4, column l % 32
+    float *mine = part + ((size_t)pj * Bp + (size_t)nb * kTile) * L.bh;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = rb * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+        if (r < L.bh) {
+            mine[(size_t)(ch * 64 + (lane & 31)) * L.bh + r] = acc0[i];
+            mine[(size_t)(ch * 64 + 32 + (lane & 31)) * L.bh + r] = acc1[i];
+        }
+    }
 }
 
 // ------------------------------------------------------------------------- //
@@ -457,14 +628,22 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
     if (L->dev.blob && L->dev.device == dev) return CL_OK;
     release_device(L);
     struct Sec { const void *src; size_t bytes; size_t off; };
-    Sec secs[7] = {
+    // decode tables + codebook, laid out as in LDS
+    const int ncode = 1 << L->desc.weight_bits;
+    std::vector<char> image(table_image_bytes(L->val_lut_bits, L->idx_lut_bits, ncode), 0);
+    {
+        const size_t vb = L->val_lut.size() * sizeof(lut_t), ib = L->idx_lut.size() * sizeof(lut_t);
+        std::memcpy(image.data(), L->val_lut.data(), vb);
+        std::memcpy(image.data() + vb, L->idx_lut.data(), ib);
+        std::memcpy(image.data() + ((vb + ib + 15) & ~(size_t)15), L->codebook.data(), L->codebook.size() * 4);
+    }
+    Sec secs[6] = {
         {L->records.data(), L->records.size() * 8, 0},
         {L->meta.data(), L->meta.size() * sizeof(cl_chunk_meta), 0},
         {L->block_ptr.data(), L->block_ptr.size() * 4, 0},
         {L->panel_chunk.data(), L->panel_chunk.size() * 4, 0},
-        {L->codebook.data(), L->codebook.size() * 4, 0},
-        {L->val_lut.data(), L->val_lut.size() * sizeof(lut_t), 0},
-        {L->idx_lut.data(), L->idx_lut.size() * sizeof(lut_t), 0},
+        {image.data(), image.size(), 0},
+        {L->block_chunk.data(), L->block_chunk.size() * 4, 0},
     };
     size_t total = 0;
     for (auto &s : secs) { s.off = total; total += (s.bytes + 255) / 256 * 256; }
@@ -485,9 +664,10 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
     L->dev.meta = (const cl_chunk_meta *)(blob + secs[1].off);
     L->dev.block_ptr = (const uint32_t *)(blob + secs[2].off);
     L->dev.panel_chunk = (const uint32_t *)(blob + secs[3].off);
-    L->dev.codebook = (const float *)(blob + secs[4].off);
-    L->dev.val_lut = (const lut_t *)(blob + secs[5].off);
-    L->dev.idx_lut = (const lut_t *)(blob + secs[6].off);
+    L->dev.block_chunk = (const uint32_t *)(blob + secs[5].off);
+    L->dev.val_lut = (const lut_t *)(blob + secs[4].off);
+    L->dev.idx_lut = L->dev.val_lut + L->val_lut.size();
+    L->dev.codebook = (const float *)(blob + secs[4].off + ((L->val_lut.size() + L->idx_lut.size()) * sizeof(lut_t) + 15) / 16 * 16);
     clear_error();
     return CL_OK;
 }
@@ -515,67 +695,108 @@ extern "C" int32_t cl_decode_layer(const cl_layer *L, uint8_t *d_val_sym, uint8_
     return CL_OK;
 }
 
+namespace {
+
+// Launch shape of the sparse forward path for one layer and batch.
+struct SparsePlan {
+    int bt_max = 1;          // batch tile of the main kernel (power of two, <= 16)
+    int wg_per_panel = 0;    // workgroups per block row (one wavefront per chunk, 8 per workgroup)
+    int xwant = 0;           // activation columns to stage in LDS per image (3 blocks wide)
+    size_t fixed = 0;        // LDS bytes of tables + codebook
+    size_t part_bytes = 0;   // partial-tile buffer in the workspace
+    int xcap_for(int bt) const { return (size_t)xwant * 4 * bt <= 32 * 1024 ? xwant : 0; }
+    size_t lds_for(const cl_layer *L, int bt) const { return fixed + ((size_t)L->desc.block_h + xcap_for(bt)) * 4 * bt; }
+};
+
+int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
+{
+    P.fixed = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
+    P.xwant = (int)std::min<int64_t>(L->desc.K, 3 * (int64_t)L->desc.block_w);
+    // largest power-of-two batch tile (<= 16) that fits; prefer to stay under 64 KiB
+    size_t budget = std::min<size_t>(max_lds, 64 * 1024);
+    if (P.lds_for(L, 1) > budget) budget = max_lds;
+    if (P.lds_for(L, 1) > budget) return fail(CL_EUNSUPPORTED, "block_h %d needs more LDS than a workgroup has", L->desc.block_h);
+    P.bt_max = 16;
+    while (P.bt_max > 1 && (P.lds_for(L, P.bt_max) > budget || P.bt_max / 2 >= batch)) P.bt_max >>= 1;
+    P.wg_per_panel = (int)((L->max_panel_chunks + kWaves - 1) / kWaves);
+    P.part_bytes = (size_t)L->n_panels * P.wg_per_panel * L->desc.block_h * P.bt_max * sizeof(float);
+    return CL_OK;
+}
+
+// Launch shape of the MFMA path.
+struct MfmaPlan {
+    int Bp = 0;              // batch rounded up to whole image tiles
+    int splits = 1;          // workgroups sharing the blocks of one block row
+    size_t lds = 0;
+    size_t xt_bytes = 0, part_bytes = 0;
+};
+
+bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->desc.block_w <= kTile; }
+
+int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan &P)
+{
+    if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the MFMA path needs blocks of at most %d x %d", kTile, kTile);
+    P.Bp = (batch + kTile - 1) / kTile * kTile;
+    const int tiles = L->n_panels * (P.Bp / kTile);
+    P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
+    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) +
+            ((size_t)kTile * kWtStride + (size_t)kTile * kTile) * sizeof(float);
+    if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the MFMA path needs %zu bytes of LDS", P.lds);
+    P.xt_bytes = ((size_t)L->desc.K * P.Bp * sizeof(float) + 255) / 256 * 256;
+    P.part_bytes = (size_t)L->n_panels * P.splits * P.Bp * L->desc.block_h * sizeof(float);
+    return CL_OK;
+}
+
+// CL_PATH_AUTO: the dense-tile path once the batch fills an image tile reasonably
+// and the blocks fit a tile; the sparse path otherwise.
+int resolve_path(const cl_layer *L, int batch, int path)
+{
+    if (path != CL_PATH_AUTO) return path;
+    return (batch >= kTile / 2 && mfma_capable(L)) ? CL_PATH_MFMA_F32 : CL_PATH_SPARSE;
+}
+
+}  // namespace
+
 extern "C" int32_t cl_fc_workspace_bytes(const cl_layer *L, int32_t batch, int32_t path, size_t *out)
 {
     if (!L || !out) return fail(CL_EINVAL, "null argument");
     if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
     if (path != CL_PATH_AUTO && path != CL_PATH_SPARSE && path != CL_PATH_MFMA_F32) return fail(CL_EINVAL, "unknown path %d", path);
-    *out = 0;
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    if (resolve_path(L, batch, path) == CL_PATH_MFMA_F32) {
+        MfmaPlan P;
+        if (int32_t rc = plan_mfma(L, batch, dl, P)) return rc;
+        *out = P.xt_bytes + P.part_bytes;
+    } else {
+        SparsePlan P;
+        if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P)) return rc;
+        *out = P.part_bytes;
+    }
     return CL_OK;
 }
 
-extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X, const float *d_bias,
-                                            float *d_Y, int32_t batch, int32_t relu, int32_t path,
-                                            void *d_workspace, size_t workspace_bytes, void *stream)
+static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, const float *d_X,
+                              const float *d_bias, float *d_Y, int batch, int relu, float *part, hipStream_t st)
 {
-    (void)d_workspace;
-    if (int32_t rc = require_device(L)) return rc;
-    if (!d_X || !d_Y) return fail(CL_EINVAL, "null activation pointer");
-    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
-    size_t need = 0;
-    if (int32_t rc = cl_fc_workspace_bytes(L, batch, path, &need)) return rc;
-    if (workspace_bytes < need) return fail(CL_EINVAL, "workspace too small: %zu < %zu", workspace_bytes, need);
-    if (path == CL_PATH_MFMA_F32) return fail(CL_EUNSUPPORTED, "MFMA path is not built yet");
-    DeviceLimits dl;
-    if (int32_t rc = device_limits(dl)) return rc;
-    hipStream_t st = (hipStream_t)stream;
-    const LayerDev D = make_dev(L);
+    SparsePlan P;
+    if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P)) return rc;
     const int M = L->desc.M, K = L->desc.K;
-    const size_t nout = (size_t)M * batch;
-
-    hipLaunchKernelGGL(init_out_kernel, dim3((unsigned)std::min<size_t>((nout + 255) / 256, 2048)), dim3(256), 0, st,
-                       d_Y, d_bias, M, batch);
-    HIP_TRY(hipGetLastError());
-    if (L->n_chunks > 0) {
-        const size_t fixed = smem_fixed_bytes(D.val_bits, D.idx_bits, D.ncode);
-        // LDS per image: a column of the output tile plus the staged activations (the
-        // columns of up to three neighbouring blocks; none when that is too much)
-        const int xwant = (int)std::min<int64_t>(K, 3 * (int64_t)L->desc.block_w);
-        auto xcap_for = [&](int bt) { return (size_t)xwant * 4 * bt <= 32 * 1024 ? xwant : 0; };
-        auto lds_for = [&](int bt) { return fixed + ((size_t)L->desc.block_h + xcap_for(bt)) * 4 * bt; };
-        // largest power-of-two batch tile (<= 16) that fits; prefer to stay under 64 KiB
-        size_t budget = std::min<size_t>(dl.max_lds, 64 * 1024);
-        if (lds_for(1) > budget) budget = dl.max_lds;
-        if (lds_for(1) > budget) return fail(CL_EUNSUPPORTED, "block_h %d needs more LDS than a workgroup has", L->desc.block_h);
-        int bt_max = 16;
-        while (bt_max > 1 && lds_for(bt_max) > budget) bt_max >>= 1;
-        // one wavefront per chunk: each block row gets enough workgroups for its chunks
-        const int wg_per_panel = (int)((L->max_panel_chunks + kWaves - 1) / kWaves);
-        const dim3 grid((unsigned)(L->n_panels * wg_per_panel));
-        timing_begin(st);
-        int launches = 0;
-        for (int b0 = 0; b0 < batch; ++launches) {
-            int bt = bt_max;
-            while (bt > batch - b0) bt >>= 1;
-            const size_t lds = lds_for(bt);
-            const int xcap = xcap_for(bt);
-            const float *x = d_X + (size_t)b0 * K;
-            float *y = d_Y + (size_t)b0 * M;
+    const dim3 grid((unsigned)(L->n_panels * P.wg_per_panel));
+    for (int b0 = 0; b0 < batch;) {
+        int bt = P.bt_max;
+        while (bt > batch - b0) bt >>= 1;
+        const float *x = d_X + (size_t)b0 * K;
+        float *y = d_Y + (size_t)b0 * M;
+        if (L->n_chunks > 0) {
+            const size_t lds = P.lds_for(L, bt);
+            const int xcap = P.xcap_for(bt);
+            if (b0 == 0) timing_begin(st);      // benchmarks time the first main-kernel launch of a call
 #define CL_LAUNCH_SPARSE(BTV)                                                                                      \
     do {                                                                                                           \
         if (lds > 64 * 1024)                                                                                       \
             HIP_TRY(hipFuncSetAttribute((const void *)fc_sparse_kernel<BTV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-        hipLaunchKernelGGL(fc_sparse_kernel<BTV>, grid, dim3(kThreads), lds, st, D, x, y, wg_per_panel, xcap);           \
+        hipLaunchKernelGGL(fc_sparse_kernel<BTV>, grid, dim3(kThreads), lds, st, D, x, part, P.wg_per_panel, xcap); \
     } while (0)
             switch (bt) {
             case 16: CL_LAUNCH_SPARSE(16); break;
@@ -586,16 +807,60 @@ extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X,
             }
 #undef CL_LAUNCH_SPARSE
             HIP_TRY(hipGetLastError());
-            b0 += bt;
+            if (b0 == 0) timing_end(st, 1);
         }
-        timing_end(st, launches);
-    }
-    if (relu) {
-        hipLaunchKernelGGL(relu_kernel, dim3((unsigned)std::min<size_t>((nout + 255) / 256, 2048)), dim3(256), 0, st, d_Y, nout);
+        hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * bt)), dim3(kRedThreads), 0, st,
+                           D, part, d_bias, y, bt, bt, P.wg_per_panel, relu, 0);
         HIP_TRY(hipGetLastError());
+        b0 += bt;
     }
-    clear_error();
     return CL_OK;
+}
+
+static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, const float *d_X,
+                            const float *d_bias, float *d_Y, int batch, int relu, char *ws, hipStream_t st)
+{
+    MfmaPlan P;
+    if (int32_t rc = plan_mfma(L, batch, dl, P)) return rc;
+    const int K = L->desc.K;
+    float *xt = (float *)ws;
+    float *part = (float *)(ws + P.xt_bytes);
+    hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)((K + 31) / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
+                       d_X, xt, batch, K, P.Bp);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
+    const dim3 grid((unsigned)(L->n_panels * P.splits * (P.Bp / kTile)));
+    timing_begin(st);
+    hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, P.Bp);
+    HIP_TRY(hipGetLastError());
+    timing_end(st, 1);
+    hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * batch)), dim3(kRedThreads), 0, st,
+                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, P.splits);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
+extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X, const float *d_bias,
+                                            float *d_Y, int32_t batch, int32_t relu, int32_t path,
+                                            void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (int32_t rc = require_device(L)) return rc;
+    if (!d_X || !d_Y) return fail(CL_EINVAL, "null activation pointer");
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    size_t need = 0;
+    if (int32_t rc = cl_fc_workspace_bytes(L, batch, path, &need)) return rc;
+    if (workspace_bytes < need || (need && !d_workspace)) return fail(CL_EINVAL, "workspace too small: %zu < %zu", workspace_bytes, need);
+    if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    const LayerDev D = make_dev(L);
+    int32_t rc;
+    if (resolve_path(L, batch, path) == CL_PATH_MFMA_F32)
+        rc = forward_mfma(L, D, dl, d_X, d_bias, d_Y, batch, relu, (char *)d_workspace, (hipStream_t)stream);
+    else
+        rc = forward_sparse(L, D, dl, d_X, d_bias, d_Y, batch, relu, (float *)d_workspace, (hipStream_t)stream);
+    if (rc == CL_OK) clear_error();
+    return rc;
 }
 
 extern "C" int32_t cl_set_kernel_timing(int32_t enable)

@@ -26,6 +26,7 @@ struct DeviceImage {
     const cl_chunk_meta *meta = nullptr;
     const uint32_t *block_ptr = nullptr;
     const uint32_t *panel_chunk = nullptr;
+    const uint32_t *block_chunk = nullptr;
     const float *codebook = nullptr;
     const lut_t *val_lut = nullptr;
     const lut_t *idx_lut = nullptr;
@@ -44,6 +45,7 @@ struct cl_layer {
     std::vector<uint8_t> val_len, idx_len;
     std::vector<uint32_t> val_code, idx_code;       // codewords, bit j = j-th bit in tree-walk order
     std::vector<uint32_t> block_ptr, panel_chunk;
+    std::vector<uint32_t> block_chunk;              // n_blocks + 1: first chunk of each block (derived)
     std::vector<cl_chunk_meta> meta;                // n_chunks + 1
     std::vector<uint64_t> records;
     std::vector<cl::lut_t> val_lut, idx_lut;        // indexed by the next val_lut_bits / idx_lut_bits stream bits

@@ -87,6 +87,69 @@ def test_fc_forward_sparse_path(M, K, bh, bw, d, r, k, B):
         assert rel_err(Y.cpu().numpy(), ref) <= TOL
 
 
+@pytest.mark.parametrize("M,K,d,r,k", [(200, 333, 0.09, 5, 4), (1000, 520, 0.25, 5, 4), (256, 1024, 0.09, 5, 4),
+                                       (128, 256, 0.0, 5, 4), (384, 300, 0.37, 8, 8), (96, 363, 0.84, 8, 8)])
+@pytest.mark.parametrize("B", [64, 100, 256])
+def test_fc_forward_mfma_path(M, K, d, r, k, B):
+    """Dense-tile path: blocks decoded into LDS tiles, fp32 MFMA.  Ragged batch,
+    ragged last block row (M = 1000) and ragged last block column (K = 520, 333)."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(M + K * 3 + B)
+    W = rand_pruned(rng, M, K, d)
+    L, m, oW = check_decode(W, r, k, 128, 128)
+    X = np.maximum(rng.standard_normal((B, K)), 0).astype(np.float32)
+    bias = rng.standard_normal(M).astype(np.float32) * 0.1
+    for use_bias, relu in [(False, False), (True, True)]:
+        ref = oracle.fc_forward(oW, X, bias if use_bias else None, relu, nthreads=8)
+        Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda() if use_bias else None,
+                                     relu=relu, path=cl.PATH_MFMA_F32)
+        torch.cuda.synchronize()
+        assert Y.shape == (B, M)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+    # the two paths agree with each other as well
+    Ys = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), path=cl.PATH_SPARSE).cpu().numpy()
+    Ym = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), path=cl.PATH_MFMA_F32).cpu().numpy()
+    assert rel_err(Ys, Ym.astype(np.float64)) <= 2 * TOL
+
+
+def test_mfma_path_is_deterministic_and_refuses_big_blocks():
+    torch = torch_cuda()
+    rng = np.random.default_rng(5)
+    W = rand_pruned(rng, 300, 400, 0.2)
+    L = cl.compress_layer(W, 5, 4, 128, 128, upload=True)
+    X = torch.from_numpy(rng.standard_normal((128, 400)).astype(np.float32)).cuda()
+    first = cl.compressed_fc_forward(L, X, path=cl.PATH_MFMA_F32).clone()
+    for _ in range(5):
+        assert torch.equal(cl.compressed_fc_forward(L, X, path=cl.PATH_MFMA_F32), first)
+    L2 = cl.compress_layer(W, 5, 4, 300, 1, upload=True)            # plain CSC columns: no dense tile
+    with pytest.raises(cl.CLError) as e:
+        cl.compressed_fc_forward(L2, X, path=cl.PATH_MFMA_F32)
+    assert e.value.code == binding.CL_EUNSUPPORTED
+    ref = oracle.fc_forward(oracle.dense_weights(oracle.compress_layer(W, 5, 4, 300, 1)), X.cpu().numpy())
+    assert rel_err(cl.compressed_fc_forward(L2, X).cpu().numpy(), ref) <= TOL      # AUTO falls back to the sparse path
+
+
+def test_config3_alexnet_fc_stack_batch256():
+    """configs[2] at full size, in the launch configuration the benchmark times:
+    fc6 -> ReLU -> fc7 -> ReLU -> fc8 at batch 256 (AUTO picks the MFMA path) and
+    at batch 4 (sparse path)."""
+    torch = torch_cuda()
+    layers, dense = [], []
+    for li in range(3):
+        spec, W = wl.layer_weights(3, li)
+        layers.append(cl.compress_layer(W, spec.r, spec.k, 128, 128, upload=True))
+        dense.append(oracle.dense_weights(oracle.compress_layer(W, spec.r, spec.k, 128, 128)))
+    for B in (256, 4):
+        X = wl.activations(3, B)
+        a_ref, a = X, torch.from_numpy(X).cuda()
+        for li in range(3):
+            ref = oracle.fc_forward(dense[li], a_ref, relu=(li < 2), nthreads=16)
+            a = cl.compressed_fc_forward(layers[li], a, relu=(li < 2))
+            assert rel_err(a.cpu().numpy(), ref) <= TOL, (B, li)
+            a_ref = ref.astype(np.float32)
+            a = torch.from_numpy(a_ref).cuda()          # each layer is fed the oracle's activations
+
+
 def test_fc_forward_repeatable_within_tolerance():
     """Atomic accumulation: the summation order may differ between runs, the
     result stays inside the tolerance and the decode stays bit-identical."""
