@@ -400,10 +400,12 @@ constexpr int kRedThreads = 256, kSlices = 4;
 
 __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
                                                                 const float *__restrict__ bias, float *Y, int B,
-                                                                int part_b, int wg_per_panel, int relu, int uniform_active)
+                                                                int part_b, int wg_per_panel, int relu, int uniform_active,
+                                                                int panel0, int conv_pq)
 {
     __shared__ float slice_sum[kRedThreads];
-    const int p = (int)blockIdx.x / B, b = (int)blockIdx.x - p * B;
+    const int pl = (int)blockIdx.x / B, b = (int)blockIdx.x - pl * B;     // pl: block row counted from panel0
+    const int p = panel0 + pl;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
     // the sparse kernel fills one slot per eight chunks; the MFMA kernel fills every slot
@@ -412,7 +414,7 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
     constexpr int kRows = kRedThreads / kSlices;
     const int sl = (int)threadIdx.x / kRows, rl = (int)threadIdx.x - sl * kRows;
     // part[p][j][image (part_b of them)][bh]
-    const float *src = part + ((size_t)p * wg_per_panel * part_b + b) * L.bh;
+    const float *src = part + ((size_t)pl * wg_per_panel * part_b + b) * L.bh;
     const size_t step = (size_t)part_b * L.bh;
     for (int r0 = 0; r0 < bhp; r0 += kRows) {
         const int r = r0 + rl;
@@ -436,7 +438,10 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
 #pragma unroll
             for (int k = 1; k < kSlices; ++k) t += slice_sum[k * kRows + rl];
             if (bias) t += bias[row_id + r];
-            Y[(size_t)b * L.M + row_id + r] = relu ? fmaxf(t, 0.0f) : t;
+            t = relu ? fmaxf(t, 0.0f) : t;
+            // FC: Y[image][row].  Convolution: column b is (image, output pixel), Y[image][row][pixel].
+            if (conv_pq == 0) Y[(size_t)b * L.M + row_id + r] = t;
+            else Y[((size_t)(b / conv_pq) * L.M + row_id + r) * conv_pq + (b % conv_pq)] = t;
         }
         __syncthreads();
     }
@@ -468,6 +473,32 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restr
     }
 }
 
+// Sec. III-A: the receptive field of every output pixel becomes a column, so that a
+// convolution is the matrix product filters x columns.  Written transposed and
+// padded like XT above: XT[(c*R + r)*S + s][n], n = image * P*Q + output pixel,
+// for the input channels of one group; zero outside the image and past n_cols.
+struct ConvGeom {
+    int C, H, W, R, S, stride, pad, Cg, P, Q;
+};
+
+__global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, int c0,
+                                                         int n_cols, int Np)
+{
+    const int k = blockIdx.y;                               // (c, r, s) of this row
+    const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
+    const int pq = cg.P * cg.Q;
+    for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < Np; n += gridDim.x * blockDim.x) {
+        float v = 0.0f;
+        if (n < n_cols) {
+            const int img = n / pq, o = n - img * pq;
+            const int y = (o / cg.Q) * cg.stride - cg.pad + r, x = (o % cg.Q) * cg.stride - cg.pad + s;
+            if (y >= 0 && y < cg.H && x >= 0 && x < cg.W)
+                v = X[(((size_t)img * cg.C + (c0 + c)) * cg.H + y) * cg.W + x];
+        }
+        XT[(size_t)k * Np + n] = v;
+    }
+}
+
 // Workgroup (block row p, split j, image tile nb).  For each of its blocks:
 //   1. clear the 128 x 128 weight tile in LDS, copy the block's 128 rows of XT
 //   2. decode the block's chunks (one wavefront per chunk) and write each weight at
@@ -478,7 +509,7 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restr
 // k - is 32 consecutive floats.  Wavefront w owns rows 32 (w % 4) .. + 31 and
 // images 64 (w / 4) .. + 63 of the tile: two 32 x 32 accumulators.
 __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
-                                                           int splits, int Bp)
+                                                           int splits, int Bp, int panel0)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
@@ -487,7 +518,7 @@ __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const flo
     const int nbt = Bp / kTile;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
-    const int p = pj / splits, j = pj - p * splits;
+    const int p = panel0 + pj / splits, j = pj % splits;     // part slots are numbered from panel0
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     store_tables(s, L, fetch_tables(L));
@@ -810,7 +841,7 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
             if (b0 == 0) timing_end(st, 1);
         }
         hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * bt)), dim3(kRedThreads), 0, st,
-                           D, part, d_bias, y, bt, bt, P.wg_per_panel, relu, 0);
+                           D, part, d_bias, y, bt, bt, P.wg_per_panel, relu, 0, 0, 0);
         HIP_TRY(hipGetLastError());
         b0 += bt;
     }
@@ -831,11 +862,11 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     const dim3 grid((unsigned)(L->n_panels * P.splits * (P.Bp / kTile)));
     timing_begin(st);
-    hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, P.Bp);
+    hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
     HIP_TRY(hipGetLastError());
     timing_end(st, 1);
     hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * batch)), dim3(kRedThreads), 0, st,
-                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, P.splits);
+                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, P.splits, 0, 0);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -884,13 +915,109 @@ extern "C" int32_t cl_last_kernel_ms(float *ms, int32_t *launches)
     return CL_OK;
 }
 
-extern "C" int32_t cl_conv_workspace_bytes(const cl_layer *, const cl_conv_desc *, int32_t, int32_t, size_t *)
+namespace {
+
+// Launch shape of the convolution path: the batch is cut into groups of images whose
+// column matrix stays under kConvXtCap bytes; each group of images and each filter
+// group is one matrix product on the MFMA path.
+constexpr size_t kConvXtCap = (size_t)256 << 20;
+
+struct ConvPlan {
+    ConvGeom cg{};
+    int OCg = 0, panels_per_group = 0, imgs = 0, Np = 0, splits = 1;
+    size_t lds = 0, xt_bytes = 0, part_bytes = 0;
+};
+
+int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const DeviceLimits &dl, ConvPlan &P)
 {
-    return fail(CL_EUNSUPPORTED, "convolution forward is not built yet");
+    if (!cv) return fail(CL_EINVAL, "null convolution descriptor");
+    if (cv->C < 1 || cv->H < 1 || cv->W < 1 || cv->R < 1 || cv->S < 1 || cv->stride < 1 || cv->pad < 0 || cv->groups < 1 ||
+        cv->out_channels < 1)
+        return fail(CL_EINVAL, "bad convolution geometry");
+    if (cv->C % cv->groups || cv->out_channels % cv->groups) return fail(CL_EINVAL, "groups must divide C and out_channels");
+    ConvGeom &g = P.cg;
+    g.C = cv->C; g.H = cv->H; g.W = cv->W; g.R = cv->R; g.S = cv->S; g.stride = cv->stride; g.pad = cv->pad;
+    g.Cg = cv->C / cv->groups;
+    g.P = (cv->H + 2 * cv->pad - cv->R) / cv->stride + 1;
+    g.Q = (cv->W + 2 * cv->pad - cv->S) / cv->stride + 1;
+    if (g.P < 1 || g.Q < 1) return fail(CL_EINVAL, "filter larger than the padded input");
+    if (L->desc.M != cv->out_channels || L->desc.K != g.Cg * g.R * g.S)
+        return fail(CL_EINVAL, "layer is %d x %d, the convolution needs %d x %d", L->desc.M, L->desc.K, cv->out_channels, g.Cg * g.R * g.S);
+    if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the convolution path needs blocks of at most %d x %d", kTile, kTile);
+    P.OCg = cv->out_channels / cv->groups;
+    if (cv->groups > 1 && P.OCg % L->desc.block_h) return fail(CL_EUNSUPPORTED, "block_h %d must divide the %d filters of a group", L->desc.block_h, P.OCg);
+    P.panels_per_group = (P.OCg + L->desc.block_h - 1) / L->desc.block_h;
+    const size_t per_image = (size_t)L->desc.K * g.P * g.Q * sizeof(float);
+    P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
+    P.Np = (P.imgs * g.P * g.Q + kTile - 1) / kTile * kTile;
+    const int tiles = P.panels_per_group * (P.Np / kTile);
+    P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
+    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) +
+            ((size_t)kTile * kWtStride + (size_t)kTile * kTile) * sizeof(float);
+    if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
+    P.xt_bytes = ((size_t)L->desc.K * P.Np * sizeof(float) + 255) / 256 * 256;
+    P.part_bytes = (size_t)P.panels_per_group * P.splits * P.Np * L->desc.block_h * sizeof(float);
+    return CL_OK;
 }
 
-extern "C" int32_t cl_compressed_conv_forward(const cl_layer *, const cl_conv_desc *, const float *, const float *,
-                                              float *, int32_t, int32_t, int32_t, void *, size_t, void *)
+}  // namespace
+
+extern "C" int32_t cl_conv_workspace_bytes(const cl_layer *L, const cl_conv_desc *cv, int32_t batch, int32_t path, size_t *out)
 {
-    return fail(CL_EUNSUPPORTED, "convolution forward is not built yet");
+    if (!L || !out) return fail(CL_EINVAL, "null argument");
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    if (path != CL_PATH_AUTO && path != CL_PATH_MFMA_F32) return fail(CL_EUNSUPPORTED, "convolution runs on the MFMA path only");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    ConvPlan P;
+    if (int32_t rc = plan_conv(L, cv, batch, dl, P)) return rc;
+    *out = P.xt_bytes + P.part_bytes;
+    return CL_OK;
+}
+
+extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_desc *cv, const float *d_X,
+                                              const float *d_bias, float *d_Y, int32_t batch, int32_t relu,
+                                              int32_t path, void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (int32_t rc = require_device(L)) return rc;
+    if (!d_X || !d_Y) return fail(CL_EINVAL, "null activation pointer");
+    size_t need = 0;
+    if (int32_t rc = cl_conv_workspace_bytes(L, cv, batch, path, &need)) return rc;
+    if (workspace_bytes < need || !d_workspace) return fail(CL_EINVAL, "workspace too small: %zu < %zu", workspace_bytes, need);
+    if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    ConvPlan P;
+    if (int32_t rc = plan_conv(L, cv, batch, dl, P)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const LayerDev D = make_dev(L);
+    const ConvGeom &g = P.cg;
+    const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
+    float *xt = (float *)d_workspace;
+    float *part = (float *)((char *)d_workspace + P.xt_bytes);
+    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
+    bool timed = false;
+    for (int b0 = 0; b0 < batch; b0 += P.imgs) {
+        const int nb = std::min(P.imgs, batch - b0);
+        const int ncols = nb * pq;
+        const int Np = (ncols + kTile - 1) / kTile * kTile;
+        const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
+        float *y = d_Y + (size_t)b0 * M * pq;
+        for (int grp = 0; grp < cv->groups; ++grp) {
+            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)K), dim3(256), 0, st,
+                               x, xt, g, grp * g.Cg, ncols, Np);
+            HIP_TRY(hipGetLastError());
+            const int panel0 = grp * P.panels_per_group;
+            const dim3 grid((unsigned)(P.panels_per_group * P.splits * (Np / kTile)));
+            if (!timed) timing_begin(st);
+            hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, Np, panel0);
+            HIP_TRY(hipGetLastError());
+            if (!timed) { timing_end(st, 1); timed = true; }
+            hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(P.panels_per_group * ncols)), dim3(kRedThreads), 0, st,
+                               D, part, d_bias, y, ncols, Np, P.splits, relu, P.splits, panel0, pq);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    clear_error();
+    return CL_OK;
 }

@@ -150,6 +150,59 @@ def test_config3_alexnet_fc_stack_batch256():
             a = torch.from_numpy(a_ref).cuda()          # each layer is fed the oracle's activations
 
 
+SMALL_CONVS = [dict(C=3, H=19, W=19, R=5, S=5, stride=4, pad=0, groups=1, OC=6),
+               dict(C=4, H=9, W=11, R=3, S=3, stride=1, pad=1, groups=2, OC=6),
+               dict(C=6, H=7, W=7, R=3, S=3, stride=2, pad=2, groups=3, OC=9),
+               dict(C=32, H=13, W=13, R=3, S=3, stride=1, pad=1, groups=2, OC=256)]
+
+
+@pytest.mark.parametrize("geom", SMALL_CONVS)
+@pytest.mark.parametrize("B", [1, 3])
+def test_conv_forward_small(geom, B):
+    """Convolution as filters x receptive-field columns on the MFMA path against
+    the oracle's direct convolution (groups, stride, padding, ragged tiles)."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(geom["OC"] + B)
+    OC, Kc = geom["OC"], geom["C"] // geom["groups"] * geom["R"] * geom["S"]
+    W = rand_pruned(rng, OC, Kc, 0.4)
+    bh = OC // geom["groups"] if OC // geom["groups"] <= 128 else 128
+    L, m, oW = check_decode(W, 8, 8, bh, 128)
+    X = rng.random((B, geom["C"], geom["H"], geom["W"]), dtype=np.float32)
+    bias = rng.standard_normal(OC).astype(np.float32) * 0.1
+    for use_bias, relu in [(False, False), (True, True)]:
+        ref = oracle.conv_forward(oW, X, geom, bias if use_bias else None, relu, nthreads=8)
+        Y = cl.compressed_conv_forward(L, geom, torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda() if use_bias else None,
+                                       relu=relu)
+        torch.cuda.synchronize()
+        assert tuple(Y.shape) == ref.shape
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+
+
+@pytest.mark.parametrize("li", range(5))
+def test_config4_alexnet_conv_layers(li):
+    """configs[3]: the five AlexNet convolutions as compressed matrices (8-bit value
+    index, 8-bit relative index), each fed its own synthetic input, batch 2."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(4, li)
+    geom = spec.conv
+    ocg = geom["OC"] // geom["groups"]
+    bh = 128 if ocg % 128 == 0 or geom["groups"] == 1 else 64
+    L, m, oW = check_decode(W, spec.r, spec.k, bh, 128)
+    X = wl.activations(4, 2, layer_index=li)
+    ref = oracle.conv_forward(oW, X, geom, relu=True, nthreads=16)
+    Y = cl.compressed_conv_forward(L, geom, torch.from_numpy(X).cuda(), relu=True)
+    assert rel_err(Y.cpu().numpy(), ref) <= TOL
+
+
+def test_conv_rejects_mismatched_layer():
+    torch = torch_cuda()
+    L = cl.compress_layer(np.ones((6, 75), np.float32), 5, 4, 6, 75, upload=True)
+    X = torch.zeros((1, 3, 19, 19), device="cuda")
+    with pytest.raises(cl.CLError) as e:
+        cl.compressed_conv_forward(L, dict(C=3, H=19, W=19, R=3, S=3, stride=1, pad=0, groups=1, OC=6), X)
+    assert e.value.code == binding.CL_EINVAL
+
+
 def test_fc_forward_repeatable_within_tolerance():
     """Atomic accumulation: the summation order may differ between runs, the
     result stays inside the tolerance and the decode stays bit-identical."""
