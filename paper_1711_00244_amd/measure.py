@@ -1,0 +1,73 @@
+"""Per-layer timings for the benchmark configurations other than the headline one
+(bench.py covers configs[2]).  Prints one JSON line per (layer, batch).
+
+    python -m paper_1711_00244_amd.measure --config 4          # AlexNet conv layers
+    python -m paper_1711_00244_amd.measure --config 2          # AlexNet fc6, batch 1 and 8
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import numpy as np
+
+from . import binding as cl
+from . import workloads as wl
+
+
+def time_ms(fn, reps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def main(argv=None):
+    import torch
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--reps", type=int, default=30)
+    ap.add_argument("--block", type=int, nargs=2, default=[128, 128])
+    args = ap.parse_args(argv)
+    cfg = wl.CONFIGS[args.config]
+    for li, spec0 in enumerate(cfg["layers"]):
+        spec, W = wl.layer_weights(args.config, li)
+        bh, bw = args.block
+        if spec.conv is not None:
+            ocg = spec.conv["OC"] // spec.conv["groups"]
+            if spec.conv["groups"] > 1 and ocg % bh:
+                bh = 64
+        L = cl.compress_layer(W, spec.r, spec.k, bh, bw, upload=True)
+        st = L.stats()
+        for B in cfg["batches"]:
+            X = torch.from_numpy(wl.activations(args.config, B, layer_index=li)).cuda()
+            if spec.conv is not None:
+                g = spec.conv
+                ws = torch.empty(max(256, cl.conv_workspace_bytes(L, g, B)), dtype=torch.uint8, device="cuda")
+                P = (g["H"] + 2 * g["pad"] - g["R"]) // g["stride"] + 1
+                out = torch.empty((B, g["OC"], P, P), device="cuda")
+                ms = time_ms(lambda: cl.compressed_conv_forward(L, g, X, relu=True, out=out, workspace=ws), args.reps, 3)
+                n_cols = B * P * P
+            else:
+                ws = torch.empty(max(256, cl.fc_workspace_bytes(L, B)), dtype=torch.uint8, device="cuda")
+                out = torch.empty((B, spec.M), device="cuda")
+                ms = time_ms(lambda: cl.compressed_fc_forward(L, X, out=out, workspace=ws), args.reps, 3)
+                n_cols = B
+            print(json.dumps(dict(config=args.config, layer=spec.name, batch=B, block=[bh, bw], ms=round(ms, 5),
+                                  images_per_s=round(B / (ms * 1e-3), 1), model_bytes=st["model_bytes"], nnz=st["nnz"],
+                                  compressed_GBps=round(st["model_bytes"] / (ms * 1e-3) / 1e9, 2),
+                                  dense_TFLOPs=round(2.0 * spec.M * spec.K * n_cols / (ms * 1e-3) / 1e12, 3),
+                                  useful_TFLOPs=round(2.0 * st["nnz"] * n_cols / (ms * 1e-3) / 1e12, 3))), flush=True)
+        L.free()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

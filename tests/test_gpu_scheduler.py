@@ -1,0 +1,79 @@
+"""Variable batch sizes and the request scheduler on the GPU (configs[4] shape,
+scaled down so that the oracle side stays quick)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1711_00244_amd as cl
+from paper_1711_00244_amd import scheduler, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vgg_stack():
+    import torch
+    assert torch.cuda.is_available()
+    layers, dense = [], []
+    K = None
+    for li in range(3):
+        spec, W = wl.layer_weights(5, li, scale=0.125)
+        if K is not None and W.shape[1] != K:           # chain the scaled shapes: inputs of layer i = outputs of layer i-1
+            W = wl.pruned_weights(W.shape[0], K, spec.density, spec.sigma, 7 + li)
+        K = W.shape[0]
+        layers.append(cl.compress_layer(W, spec.r, spec.k, 128, 128, upload=True))
+        dense.append(oracle.dense_weights(oracle.compress_layer(W, spec.r, spec.k, 128, 128)))
+    return layers, dense
+
+
+def oracle_stack(dense, X):
+    a = X
+    for li, W in enumerate(dense):
+        y = oracle.fc_forward(W, a, relu=(li + 1 < len(dense)), nthreads=8)
+        a = y.astype(np.float32)
+    return y
+
+
+def test_variable_batch_run_matches_oracle(vgg_stack):
+    import torch
+    layers, dense = vgg_stack
+    runner = scheduler.StackRunner(layers)
+    X = wl.activations(5, 48, K=layers[0].K)
+    ref = oracle_stack(dense, X)
+    Xd = torch.from_numpy(X).cuda()
+    for bpl in (None, [4, 8, 16], [1, 1, 16], [16, 16, 16], [2, 4, 4]):
+        Y = runner.run(Xd, bpl).cpu().numpy()
+        # activations pass through fp32 between layers on both sides; allow the chain a little more room
+        assert np.abs(Y - ref).max() / np.abs(ref).max() <= 3e-5, bpl
+
+
+def test_plan_and_poisson_stream(vgg_stack):
+    import torch
+    layers, dense = vgg_stack
+    runner = scheduler.StackRunner(layers)
+    batch_set = [1, 2, 4, 8, 16, 32, 64]
+    times = runner.measure_times(batch_set, reps=5, warmup=2)
+    assert times.shape == (3, len(batch_set)) and (times > 0).all()
+    budget = 64 << 20
+    plan = runner.plan(batch_set, budget, latency_cap_ms=10.0, time_ms=times)
+    assert plan is not None
+    bpl = plan.batch_per_layer
+    assert all(a <= b and b % a == 0 for a, b in zip(bpl, bpl[1:]))
+    # the plan respects the budget: activations in/out of the largest layer call plus its scratch
+    for li, L in enumerate(layers):
+        assert bpl[li] * (L.K + L.M) * 4 + plan.ws_bytes[li] <= budget
+    # an impossible budget yields no plan
+    assert runner.plan(batch_set, 1024, latency_cap_ms=10.0, time_ms=times) is None
+    # a latency cap below the fastest single image yields no plan either
+    assert runner.plan(batch_set, budget, latency_cap_ms=1e-6, time_ms=times) is None
+
+    n = 256
+    arrivals = wl.poisson_arrivals(n, 20000.0, 99)
+    X = wl.activations(5, n, K=layers[0].K)
+    Xd = torch.from_numpy(X).cuda()
+    outs, stats = scheduler.simulate(runner, plan, arrivals, [Xd[i] for i in range(n)], 10.0)
+    assert stats["requests"] == n and stats["over_cap"] == 0 and stats["max_ms"] <= 10.0
+    assert 1 <= stats["mean_batch"] <= bpl[-1]
+    Y = torch.stack(outs, 0).cpu().numpy()
+    ref = oracle_stack(dense, X)
+    assert np.abs(Y - ref).max() / np.abs(ref).max() <= 3e-5
