@@ -453,10 +453,9 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 128;               // block rows, block columns and images per workgroup tile
-constexpr int kWtStride = kTile + 4;     // LDS row stride of the weight tile (floats)
 
 // XT[k][b] = X[b][k], with the image axis padded to Bp (a multiple of kTile) with
-// zeros, so that a tile of activations is a plain copy of 128 rows.
+// zeros and one extra all-zero row K (what k-steps past a narrow block's width read).
 __global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restrict__ X, float *XT, int B, int K, int Bp)
 {
     __shared__ float t[32][33];
@@ -469,7 +468,7 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restr
     __syncthreads();
     for (int i = ty; i < 32; i += 8) {
         const int k = k0 + i, b = b0 + tx;
-        if (k < K && b < Bp) XT[(size_t)k * Bp + b] = t[tx][i];
+        if (k <= K && b < Bp) XT[(size_t)k * Bp + b] = k < K ? t[tx][i] : 0.0f;     // row K: zeros
     }
 }
 
@@ -484,12 +483,13 @@ struct ConvGeom {
 __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, int c0,
                                                          int n_cols, int Np)
 {
-    const int k = blockIdx.y;                               // (c, r, s) of this row
+    const int k = blockIdx.y;                               // (c, r, s) of this row; the last row is all zeros
     const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
     const int pq = cg.P * cg.Q;
+    const bool zero_row = c >= cg.Cg;
     for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < Np; n += gridDim.x * blockDim.x) {
         float v = 0.0f;
-        if (n < n_cols) {
+        if (n < n_cols && !zero_row) {
             const int img = n / pq, o = n - img * pq;
             const int y = (o / cg.Q) * cg.stride - cg.pad + r, x = (o % cg.Q) * cg.stride - cg.pad + s;
             if (y >= 0 && y < cg.H && x >= 0 && x < cg.W)
@@ -499,49 +499,48 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
     }
 }
 
-// Workgroup (block row p, split j, image tile nb).  For each of its blocks:
-//   1. clear the 128 x 128 weight tile in LDS, copy the block's 128 rows of XT
-//   2. decode the block's chunks (one wavefront per chunk) and write each weight at
-//      its place in the tile (Algorithm 2 steps 5-9: decode, prefix sum, codebook,
-//      "arrange as bh x bw block")
-//   3. tile x activations on the matrix cores, v_mfma_f32_32x32x2_f32 (step 12)
-// The tile is kept k-major (wt[k][r]) so that an MFMA A-fragment - 32 rows at one
-// k - is 32 consecutive floats.  Wavefront w owns rows 32 (w % 4) .. + 31 and
-// images 64 (w / 4) .. + 63 of the tile: two 32 x 32 accumulators.
+// Workgroup (block row p, split j, image tile nb) of eight wavefronts with two roles.
+//   Producers (wavefronts 4-7) decode block i + 1 - one chunk per wavefront, pass A /
+//   scan / pass B as in the sparse kernel - and write each entry's value INDEX at its
+//   place in a 128 x 128 byte tile in LDS (Algorithm 2 steps 5-9: decode, prefix sum,
+//   "arrange as bh x bw block"; the codebook look-up of step 8 moves to the consumer).
+//   Consumers (wavefronts 0-3) multiply block i on the matrix cores (step 12):
+//   wavefront w owns rows 32 w .. 32 w + 31 of the block row and all 128 images of
+//   the tile, four 32 x 32 accumulators fed by v_mfma_f32_32x32x2_f32.  The A
+//   fragment of a k-step is 32 consecutive index bytes of the tile turned into
+//   weights through the codebook in LDS; the B fragments are 32 consecutive floats of
+//   row k of XT, read from global memory a few k-steps ahead.
+// Two index tiles alternate; a consumer clears its own 32 rows of a tile when it is
+// done with it, so a tile is always clean when the producers get it back.
+constexpr int kIdxStride = kTile + 16;   // bytes per k-row of an index tile (keeps rows 16-byte aligned)
+constexpr int kIdxTileBytes = kTile * kIdxStride;
+constexpr int kBPrefetch = 8;            // k-steps of B fragments in flight (divides kTile / 2)
+
 __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
                                                            int splits, int Bp, int panel0)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    float *wt = s.extra;                                   // [kTile k][kWtStride]
-    float *xt = wt + kTile * kWtStride;                    // [kTile k][kTile b]
+    uint8_t *tiles = (uint8_t *)s.extra;                   // [2][kTile k][kIdxStride]
     const int nbt = Bp / kTile;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
     const int p = panel0 + pj / splits, j = pj % splits;     // part slots are numbered from panel0
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
+    const bool producer = wave >= 4;
     store_tables(s, L, fetch_tables(L));
+    for (int t = threadIdx.x; t < 2 * kIdxTileBytes / 16; t += kThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
     // this split's share of the block row's blocks
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
-    floatx16 acc0 = {0}, acc1 = {0};
-    const int rb = wave & 3, ch = wave >> 2;
-    for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        const uint32_t b = (uint32_t)p * (uint32_t)L.nbw + (uint32_t)bi;
+    const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
+
+    // Producer: decode block bi into an index tile (clean on entry).
+    auto produce = [&](int bi, uint8_t *tile) {
+        const uint32_t b = pb0 + (uint32_t)bi;
         const BlockGeom g = block_geom(L, b);
-        __syncthreads();                                   // previous tile fully consumed (and tables stored)
-        // 1. clear the weight tile, copy the activation rows (zero rows past the block's width)
-        for (int t = threadIdx.x; t < kTile * kWtStride / 4; t += kThreads) ((float4 *)wt)[t] = float4{0.f, 0.f, 0.f, 0.f};
-        for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) {
-            const int k = t / (kTile / 4), q = t - k * (kTile / 4);
-            float4 v = float4{0.f, 0.f, 0.f, 0.f};
-            if (k < g.bwp) v = *(const float4 *)(XT + (size_t)(g.col_id + k) * Bp + (size_t)nb * kTile + q * 4);
-            ((float4 *)xt)[t] = v;
-        }
-        __syncthreads();
-        // 2. decode: wavefront w takes chunks w, w + 8, ... of the block
         const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
-        for (uint32_t c = c0 + (uint32_t)wave; c < c1; c += kWaves) {
+        for (uint32_t c = c0 + (uint32_t)(wave - 4); c < c1; c += 4) {
             const ChunkHead h = load_head(L, c);
             LaneRecord rec = load_record(L, h, lane);
             const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
@@ -552,29 +551,80 @@ __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const flo
                 sum += z + 1u;
                 uint32_t r, cc;
                 split_pos(sum - 1u, g, r, cc);
-                if (v != 0 && cc < (uint32_t)kTile) wt[cc * kWtStride + r] = s.T.cb[v];
+                if (v != 0 && cc < (uint32_t)kTile) tile[cc * kIdxStride + r] = (uint8_t)v;
             }
         }
-        __syncthreads();
-        // 3. 128 x 128 x 128 on the matrix cores
-        const float *wa = wt + (lane >> 5) * kWtStride + rb * 32 + (lane & 31);
-        const float *xb = xt + (lane >> 5) * kTile + ch * 64 + (lane & 31);
-#pragma unroll 4
-        for (int k = 0; k < kTile; k += 2) {
-            const float a = wa[k * kWtStride];
-            const float b0 = xb[k * kTile], b1 = xb[k * kTile + 32];
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
-        }
+    };
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = floatx16{0};
+    // Consumer: the B fragments run as one stream of k-steps over all blocks of this
+    // split, t = 64 (block - blk_lo) + k-step, kept kBPrefetch steps ahead of the
+    // multiplies across block boundaries.  Lanes 0-31 take row k, lanes 32-63 row
+    // k + 1 of a k-step.  Rows past a narrow or ragged block's width, and steps past
+    // the last block, read the all-zero row that follows XT's K rows: every load has
+    // a valid address and nothing touches its result before the multiply.
+    const int kl = lane >> 5;
+    const int total = (blk_hi - blk_lo) * (kTile / 2);
+    const float *xrow = XT + (size_t)nb * kTile + (lane & 31);
+    auto load_b = [&](int t, float *dst) {
+        const int k = 2 * (t & (kTile / 2 - 1)) + kl;
+        const int col = (blk_lo + (t >> 6)) * L.bw + k;
+        const bool ok = t < total && k < L.bw && col < L.K;
+        const float *src = xrow + (size_t)(ok ? col : L.K) * Bp;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dst[q] = src[q * 32];
+    };
+    float bq[kBPrefetch][4];
+    if (!producer) {
+#pragma unroll
+        for (int i = 0; i < kBPrefetch; ++i) load_b(i, bq[i]);
     }
+    __syncthreads();                                        // tables stored, tiles clean
+    if (producer && blk_lo < blk_hi) produce(blk_lo, tiles);
+    __syncthreads();
+    for (int bi = blk_lo; bi < blk_hi; ++bi) {
+        uint8_t *cur = tiles + ((bi - blk_lo) & 1) * kIdxTileBytes;
+        if (producer) {
+            if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * kIdxTileBytes);
+        } else {
+            const int t0 = (bi - blk_lo) * (kTile / 2);
+            // A fragment of a k-step: 32 consecutive index bytes of tile row k turned into
+            // weights through the codebook; index two steps ahead, weight one step ahead
+            const uint8_t *ia = cur + kl * kIdxStride + wave * 32 + (lane & 31);
+            auto idx_at = [&](int ks) { return (uint32_t)ia[(2 * min(ks, kTile / 2 - 1)) * kIdxStride]; };
+            float a_cur = s.T.cb[idx_at(0)];
+            uint32_t i_next = idx_at(1);
+            for (int ks = 0; ks < kTile / 2; ks += kBPrefetch) {
+#pragma unroll
+                for (int i = 0; i < kBPrefetch; ++i) {
+                    const float a_next = s.T.cb[i_next];
+                    i_next = idx_at(ks + i + 2);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, bq[i][q], acc[q], 0, 0, 0);
+                    load_b(t0 + ks + i + kBPrefetch, bq[i]);
+                    a_cur = a_next;
+                }
+            }
+            // done with this tile: clear this wavefront's 32 rows of it (k = 2 lane, 2 lane + 1)
+            uint8_t *z0 = cur + (2 * lane) * kIdxStride + wave * 32;
+            ((uint4 *)z0)[0] = uint4{0, 0, 0, 0};
+            ((uint4 *)z0)[1] = uint4{0, 0, 0, 0};
+            ((uint4 *)(z0 + kIdxStride))[0] = uint4{0, 0, 0, 0};
+            ((uint4 *)(z0 + kIdxStride))[1] = uint4{0, 0, 0, 0};
+        }
+        __syncthreads();
+    }
+    if (producer) return;
     // accumulator element i of lane l is row 8 (i / 4) + 4 (l / 32) + i % 4, column l % 32
     float *mine = part + ((size_t)pj * Bp + (size_t)nb * kTile) * L.bh;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int r = rb * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+        const int r = wave * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
         if (r < L.bh) {
-            mine[(size_t)(ch * 64 + (lane & 31)) * L.bh + r] = acc0[i];
-            mine[(size_t)(ch * 64 + 32 + (lane & 31)) * L.bh + r] = acc1[i];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) mine[(size_t)(q * 32 + (lane & 31)) * L.bh + r] = acc[q][i];
         }
     }
 }
@@ -770,10 +820,9 @@ int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan
     P.Bp = (batch + kTile - 1) / kTile * kTile;
     const int tiles = L->n_panels * (P.Bp / kTile);
     P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
-    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) +
-            ((size_t)kTile * kWtStride + (size_t)kTile * kTile) * sizeof(float);
+    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kIdxTileBytes;
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the MFMA path needs %zu bytes of LDS", P.lds);
-    P.xt_bytes = ((size_t)L->desc.K * P.Bp * sizeof(float) + 255) / 256 * 256;
+    P.xt_bytes = (((size_t)L->desc.K + 1) * P.Bp * sizeof(float) + 255) / 256 * 256;
     P.part_bytes = (size_t)L->n_panels * P.splits * P.Bp * L->desc.block_h * sizeof(float);
     return CL_OK;
 }
@@ -856,10 +905,9 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     const int K = L->desc.K;
     float *xt = (float *)ws;
     float *part = (float *)(ws + P.xt_bytes);
-    hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)((K + 31) / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
+    hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(K / 32 + 1), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
                        d_X, xt, batch, K, P.Bp);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     const dim3 grid((unsigned)(L->n_panels * P.splits * (P.Bp / kTile)));
     timing_begin(st);
     hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
@@ -952,10 +1000,9 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const De
     P.Np = (P.imgs * g.P * g.Q + kTile - 1) / kTile * kTile;
     const int tiles = P.panels_per_group * (P.Np / kTile);
     P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
-    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) +
-            ((size_t)kTile * kWtStride + (size_t)kTile * kTile) * sizeof(float);
+    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kIdxTileBytes;
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
-    P.xt_bytes = ((size_t)L->desc.K * P.Np * sizeof(float) + 255) / 256 * 256;
+    P.xt_bytes = (((size_t)L->desc.K + 1) * P.Np * sizeof(float) + 255) / 256 * 256;
     P.part_bytes = (size_t)P.panels_per_group * P.splits * P.Np * L->desc.block_h * sizeof(float);
     return CL_OK;
 }
@@ -995,7 +1042,6 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
     float *xt = (float *)d_workspace;
     float *part = (float *)((char *)d_workspace + P.xt_bytes);
-    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     bool timed = false;
     for (int b0 = 0; b0 < batch; b0 += P.imgs) {
         const int nb = std::min(P.imgs, batch - b0);
@@ -1004,7 +1050,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         for (int grp = 0; grp < cv->groups; ++grp) {
-            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)K), dim3(256), 0, st,
+            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)(K + 1)), dim3(256), 0, st,
                                x, xt, g, grp * g.Cg, ncols, Np);
             HIP_TRY(hipGetLastError());
             const int panel0 = grp * P.panels_per_group;
