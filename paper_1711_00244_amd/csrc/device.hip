@@ -454,74 +454,90 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 128;               // block rows, block columns and images per workgroup tile
 
-// XT[k][b] = X[b][k], with the image axis padded to Bp (a multiple of kTile) with
-// zeros and one extra all-zero row K (what k-steps past a narrow block's width read).
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restrict__ X, float *XT, int B, int K, int Bp)
+// The activations as the dense-tile kernel reads them: XT[row][b] with the image axis
+// padded to Bp (a multiple of kTile) and the K axis laid out block by block, every block
+// column of the layer taking kTile rows: row = (k / bw) * kTile + k % bw holds X[b][k],
+// the other rows and the padded images are zero.  A wavefront's walk over the blocks
+// of a block row is then a walk over consecutive rows whatever the block width.
+// kXtTailRows more rows follow (never written; read ahead by the last steps of the last
+// block and never multiplied).
+constexpr int kBPrefetch = 8;            // k-steps of activations in flight (a multiple of 4 that divides kTile / 2)
+constexpr int kXtTailRows = kTile;       // the read-ahead stays within half a block + kBPrefetch rows
+
+__device__ __forceinline__ int xt_row_to_k(int row, int bw, int K)
+{
+    const int kk = row % kTile, k = (row / kTile) * bw + kk;
+    return (kk < bw && k < K) ? k : -1;
+}
+
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const float *__restrict__ X, float *XT, int B, int K, int Bp,
+                                                            int bw, int rows)
 {
     __shared__ float t[32][33];
-    const int k0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
+    const int r0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
     for (int i = ty; i < 32; i += 8) {
-        const int b = b0 + i, k = k0 + tx;
-        t[i][tx] = (b < B && k < K) ? X[(size_t)b * K + k] : 0.0f;
+        const int b = b0 + i, k = xt_row_to_k(r0 + tx, bw, K);
+        t[i][tx] = (b < B && k >= 0) ? X[(size_t)b * K + k] : 0.0f;
     }
     __syncthreads();
     for (int i = ty; i < 32; i += 8) {
-        const int k = k0 + i, b = b0 + tx;
-        if (k <= K && b < Bp) XT[(size_t)k * Bp + b] = k < K ? t[tx][i] : 0.0f;     // row K: zeros
+        const int r = r0 + i, b = b0 + tx;
+        if (r < rows && b < Bp) XT[(size_t)r * Bp + b] = t[tx][i];
     }
 }
 
 // Sec. III-A: the receptive field of every output pixel becomes a column, so that a
 // convolution is the matrix product filters x columns.  Written transposed and
-// padded like XT above: XT[(c*R + r)*S + s][n], n = image * P*Q + output pixel,
+// padded like XT above, row k = (c*R + r)*S + s, column n = image * P*Q + output pixel,
 // for the input channels of one group; zero outside the image and past n_cols.
 struct ConvGeom {
     int C, H, W, R, S, stride, pad, Cg, P, Q;
 };
 
 __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, int c0,
-                                                         int n_cols, int Np)
+                                                         int n_cols, int Np, int bw, int K)
 {
-    const int k = blockIdx.y;                               // (c, r, s) of this row; the last row is all zeros
+    const int k = xt_row_to_k((int)blockIdx.y, bw, K);      // (c, r, s) of this row, or a padding row
     const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
     const int pq = cg.P * cg.Q;
-    const bool zero_row = c >= cg.Cg;
     for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < Np; n += gridDim.x * blockDim.x) {
         float v = 0.0f;
-        if (n < n_cols && !zero_row) {
+        if (n < n_cols && k >= 0) {
             const int img = n / pq, o = n - img * pq;
             const int y = (o / cg.Q) * cg.stride - cg.pad + r, x = (o % cg.Q) * cg.stride - cg.pad + s;
             if (y >= 0 && y < cg.H && x >= 0 && x < cg.W)
                 v = X[(((size_t)img * cg.C + (c0 + c)) * cg.H + y) * cg.W + x];
         }
-        XT[(size_t)k * Np + n] = v;
+        XT[(size_t)blockIdx.y * Np + n] = v;
     }
 }
 
 // Workgroup (block row p, split j, image tile nb) of eight wavefronts with two roles.
 //   Producers (wavefronts 4-7) decode block i + 1 - one chunk per wavefront, pass A /
-//   scan / pass B as in the sparse kernel - and write each entry's value INDEX at its
-//   place in a 128 x 128 byte tile in LDS (Algorithm 2 steps 5-9: decode, prefix sum,
-//   "arrange as bh x bw block"; the codebook look-up of step 8 moves to the consumer).
-//   Consumers (wavefronts 0-3) multiply block i on the matrix cores (step 12):
-//   wavefront w owns rows 32 w .. 32 w + 31 of the block row and all 128 images of
-//   the tile, four 32 x 32 accumulators fed by v_mfma_f32_32x32x2_f32.  The A
-//   fragment of a k-step is 32 consecutive index bytes of the tile turned into
-//   weights through the codebook in LDS; the B fragments are 32 consecutive floats of
-//   row k of XT, read from global memory a few k-steps ahead.
-// Two index tiles alternate; a consumer clears its own 32 rows of a tile when it is
+//   scan / pass B as in the sparse kernel - and write each entry's weight at its place
+//   in a 128 x 128 fp32 tile in LDS, row by row (Algorithm 2 steps 5-9: decode, prefix
+//   sum, codebook look-up, "arrange as bh x bw block").
+//   Consumers (wavefronts 0-3) multiply block i on the matrix cores (step 12) with
+//   v_mfma_f32_32x32x2_f32, the images on the instruction's row axis and the weights on
+//   its column axis: wavefront w owns weight rows 32 w .. 32 w + 31 of the block row and
+//   all 128 images of the tile in four 32 x 32 accumulators; accumulator q holds images
+//   4 m + q (m = 0 .. 31), so that a lane's four A values are one 16-byte load.  The two
+//   k values of step s are s (lanes 0-31) and 64 + s (lanes 32-63): a lane walks
+//   consecutive columns of its weight row and reads four steps of B values with one
+//   16-byte LDS load, and its A values from consecutive rows of XT, kBPrefetch steps
+//   ahead of the multiplies.
+// Two weight tiles alternate; a consumer clears its own 32 rows of a tile when it is
 // done with it, so a tile is always clean when the producers get it back.
-constexpr int kIdxStride = kTile + 16;   // bytes per k-row of an index tile (keeps rows 16-byte aligned)
-constexpr int kIdxTileBytes = kTile * kIdxStride;
-constexpr int kBPrefetch = 8;            // k-steps of B fragments in flight (divides kTile / 2)
+constexpr int kWStride = kTile + 4;      // floats per weight row of a tile (16-byte rows, 4-bank skew)
+constexpr int kWTileBytes = kTile * kWStride * 4;
 
 __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
                                                            int splits, int Bp, int panel0)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    uint8_t *tiles = (uint8_t *)s.extra;                   // [2][kTile k][kIdxStride]
+    float *tiles = (float *)s.extra;                        // [2][kTile rows][kWStride]
     const int nbt = Bp / kTile;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
@@ -530,13 +546,13 @@ __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const flo
     const int lane = (int)(threadIdx.x & 63);
     const bool producer = wave >= 4;
     store_tables(s, L, fetch_tables(L));
-    for (int t = threadIdx.x; t < 2 * kIdxTileBytes / 16; t += kThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
+    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
     // this split's share of the block row's blocks
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
-    // Producer: decode block bi into an index tile (clean on entry).
-    auto produce = [&](int bi, uint8_t *tile) {
+    // Producer: decode block bi into a weight tile (clean on entry).
+    auto produce = [&](int bi, float *tile) {
         const uint32_t b = pb0 + (uint32_t)bi;
         const BlockGeom g = block_geom(L, b);
         const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
@@ -551,80 +567,87 @@ __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const flo
                 sum += z + 1u;
                 uint32_t r, cc;
                 split_pos(sum - 1u, g, r, cc);
-                if (v != 0 && cc < (uint32_t)kTile) tile[cc * kIdxStride + r] = (uint8_t)v;
+                if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = s.T.cb[v];
             }
         }
     };
 
+    // the decoders go first at the issue arbiter: a multiplying wavefront needs one issue
+    // slot per 64-cycle multiply, the decoder next to it on the SIMD can have the rest
+    if (producer) __builtin_amdgcn_s_setprio(3);
     floatx16 acc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[q] = floatx16{0};
-    // Consumer: the B fragments run as one stream of k-steps over all blocks of this
-    // split, t = 64 (block - blk_lo) + k-step, kept kBPrefetch steps ahead of the
-    // multiplies across block boundaries.  Lanes 0-31 take row k, lanes 32-63 row
-    // k + 1 of a k-step.  Rows past a narrow or ragged block's width, and steps past
-    // the last block, read the all-zero row that follows XT's K rows: every load has
-    // a valid address and nothing touches its result before the multiply.
-    const int kl = lane >> 5;
-    const int total = (blk_hi - blk_lo) * (kTile / 2);
-    const float *xrow = XT + (size_t)nb * kTile + (lane & 31);
-    auto load_b = [&](int t, float *dst) {
-        const int k = 2 * (t & (kTile / 2 - 1)) + kl;
-        const int col = (blk_lo + (t >> 6)) * L.bw + k;
-        const bool ok = t < total && k < L.bw && col < L.K;
-        const float *src = xrow + (size_t)(ok ? col : L.K) * Bp;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) dst[q] = src[q * 32];
-    };
-    float bq[kBPrefetch][4];
+    // Consumer: the A values run as one stream of k-steps over all blocks of this split.
+    // With XT laid out block by block, step s of block bi is rows kTile bi + s and
+    // kTile bi + 64 + s; the stream is loaded kBPrefetch steps ahead of the multiplies,
+    // across block boundaries.  The last steps read ahead into the next rows of XT (the
+    // next split's, or the tail rows): valid memory, never multiplied.
+    const int kl = lane >> 5, m = lane & 31;
+    const float4 *ap = (const float4 *)(XT + ((size_t)blk_lo * kTile + 64 * kl) * Bp + (size_t)nb * kTile + 4 * m);
+    const size_t row_stride = (size_t)Bp / 4;               // in float4
+    float4 aq[kBPrefetch];
     if (!producer) {
 #pragma unroll
-        for (int i = 0; i < kBPrefetch; ++i) load_b(i, bq[i]);
+        for (int i = 0; i < kBPrefetch; ++i) {
+            aq[i] = *ap;
+            ap += row_stride;
+        }
     }
     __syncthreads();                                        // tables stored, tiles clean
     if (producer && blk_lo < blk_hi) produce(blk_lo, tiles);
     __syncthreads();
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        uint8_t *cur = tiles + ((bi - blk_lo) & 1) * kIdxTileBytes;
+        float *cur = tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4);
         if (producer) {
-            if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * kIdxTileBytes);
+            if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
         } else {
-            const int t0 = (bi - blk_lo) * (kTile / 2);
-            // A fragment of a k-step: 32 consecutive index bytes of tile row k turned into
-            // weights through the codebook; index two steps ahead, weight one step ahead
-            const uint8_t *ia = cur + kl * kIdxStride + wave * 32 + (lane & 31);
-            auto idx_at = [&](int ks) { return (uint32_t)ia[(2 * min(ks, kTile / 2 - 1)) * kIdxStride]; };
-            float a_cur = s.T.cb[idx_at(0)];
-            uint32_t i_next = idx_at(1);
+            // B values of four steps: columns 64 kl + 4 g .. + 3 of weight row 32 wave + m
+            const float4 *wp = (const float4 *)(cur + (wave * 32 + m) * kWStride + 64 * kl);
+            float4 b_cur = wp[0];
             for (int ks = 0; ks < kTile / 2; ks += kBPrefetch) {
+                // steps are kept in program order (scheduling barriers): hoisting a group's
+                // LDS reads or sinking its loads would put their latency in front of the
+                // multiplies
 #pragma unroll
-                for (int i = 0; i < kBPrefetch; ++i) {
-                    const float a_next = s.T.cb[i_next];
-                    i_next = idx_at(ks + i + 2);
+                for (int h4 = 0; h4 < kBPrefetch / 4; ++h4) {
+                    const float4 b_next = wp[min(ks / 4 + h4 + 1, kTile / 8 - 1)];
+                    __builtin_amdgcn_sched_barrier(0);      // the LDS read goes out before these multiplies
+                    const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, bq[i][q], acc[q], 0, 0, 0);
-                    load_b(t0 + ks + i + kBPrefetch, bq[i]);
-                    a_cur = a_next;
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = 4 * h4 + u;
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].x, bv[u], acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].y, bv[u], acc[1], 0, 0, 0);
+                        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].z, bv[u], acc[2], 0, 0, 0);
+                        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].w, bv[u], acc[3], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);  // the step's A values are free again
+                        aq[i] = *ap;
+                        ap += row_stride;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    b_cur = b_next;
                 }
+                // the loads of the group after next start the next block: skip this block's other half
+                if (ks == kTile / 2 - 2 * kBPrefetch) ap += (kTile / 2) * row_stride;
             }
-            // done with this tile: clear this wavefront's 32 rows of it (k = 2 lane, 2 lane + 1)
-            uint8_t *z0 = cur + (2 * lane) * kIdxStride + wave * 32;
-            ((uint4 *)z0)[0] = uint4{0, 0, 0, 0};
-            ((uint4 *)z0)[1] = uint4{0, 0, 0, 0};
-            ((uint4 *)(z0 + kIdxStride))[0] = uint4{0, 0, 0, 0};
-            ((uint4 *)(z0 + kIdxStride))[1] = uint4{0, 0, 0, 0};
+            // done with this tile: clear this wavefront's 32 rows of it
+            uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
+            for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
         }
         __syncthreads();
     }
     if (producer) return;
-    // accumulator element i of lane l is row 8 (i / 4) + 4 (l / 32) + i % 4, column l % 32
-    float *mine = part + ((size_t)pj * Bp + (size_t)nb * kTile) * L.bh;
+    // accumulator q, element e of lane l: image 4 (8 (e / 4) + 4 (l / 32) + e % 4) + q of the
+    // tile, weight row 32 wave + l % 32; 32 lanes write 32 consecutive floats
+    const int r = wave * 32 + m;
+    if (r < L.bh) {
+        float *mine = part + ((size_t)pj * Bp + (size_t)nb * kTile) * L.bh + r;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = wave * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-        if (r < L.bh) {
+        for (int e = 0; e < 16; ++e) {
+            const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) mine[(size_t)(q * 32 + (lane & 31)) * L.bh + r] = acc[q][i];
+            for (int q = 0; q < 4; ++q) mine[(size_t)(4 * slot + q) * L.bh] = acc[q][e];
         }
     }
 }
@@ -812,6 +835,9 @@ struct MfmaPlan {
     size_t xt_bytes = 0, part_bytes = 0;
 };
 
+// rows of the block-by-block activation layout, tail included
+size_t xt_rows(const cl_layer *L) { return (size_t)L->nbw * kTile + kXtTailRows; }
+
 bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->desc.block_w <= kTile; }
 
 int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan &P)
@@ -820,9 +846,9 @@ int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan
     P.Bp = (batch + kTile - 1) / kTile * kTile;
     const int tiles = L->n_panels * (P.Bp / kTile);
     P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
-    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kIdxTileBytes;
+    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes;
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the MFMA path needs %zu bytes of LDS", P.lds);
-    P.xt_bytes = (((size_t)L->desc.K + 1) * P.Bp * sizeof(float) + 255) / 256 * 256;
+    P.xt_bytes = (xt_rows(L) * P.Bp * sizeof(float) + 255) / 256 * 256;
     P.part_bytes = (size_t)L->n_panels * P.splits * P.Bp * L->desc.block_h * sizeof(float);
     return CL_OK;
 }
@@ -905,9 +931,11 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     const int K = L->desc.K;
     float *xt = (float *)ws;
     float *part = (float *)(ws + P.xt_bytes);
-    hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(K / 32 + 1), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
-                       d_X, xt, batch, K, P.Bp);
+    const int rows = L->nbw * kTile;
+    hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
+                       d_X, xt, batch, K, P.Bp, L->desc.block_w, rows);
     HIP_TRY(hipGetLastError());
+    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     const dim3 grid((unsigned)(L->n_panels * P.splits * (P.Bp / kTile)));
     timing_begin(st);
     hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
@@ -995,14 +1023,14 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const De
     P.OCg = cv->out_channels / cv->groups;
     if (cv->groups > 1 && P.OCg % L->desc.block_h) return fail(CL_EUNSUPPORTED, "block_h %d must divide the %d filters of a group", L->desc.block_h, P.OCg);
     P.panels_per_group = (P.OCg + L->desc.block_h - 1) / L->desc.block_h;
-    const size_t per_image = (size_t)L->desc.K * g.P * g.Q * sizeof(float);
+    const size_t per_image = xt_rows(L) * g.P * g.Q * sizeof(float);
     P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
     P.Np = (P.imgs * g.P * g.Q + kTile - 1) / kTile * kTile;
     const int tiles = P.panels_per_group * (P.Np / kTile);
     P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
-    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kIdxTileBytes;
+    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes;
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
-    P.xt_bytes = (((size_t)L->desc.K + 1) * P.Np * sizeof(float) + 255) / 256 * 256;
+    P.xt_bytes = (xt_rows(L) * P.Np * sizeof(float) + 255) / 256 * 256;
     P.part_bytes = (size_t)P.panels_per_group * P.splits * P.Np * L->desc.block_h * sizeof(float);
     return CL_OK;
 }
@@ -1042,6 +1070,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
     float *xt = (float *)d_workspace;
     float *part = (float *)((char *)d_workspace + P.xt_bytes);
+    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     bool timed = false;
     for (int b0 = 0; b0 < batch; b0 += P.imgs) {
         const int nb = std::min(P.imgs, batch - b0);
@@ -1050,8 +1079,8 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         for (int grp = 0; grp < cv->groups; ++grp) {
-            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)(K + 1)), dim3(256), 0, st,
-                               x, xt, g, grp * g.Cg, ncols, Np);
+            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)(L->nbw * kTile)), dim3(256), 0, st,
+                               x, xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K);
             HIP_TRY(hipGetLastError());
             const int panel0 = grp * P.panels_per_group;
             const dim3 grid((unsigned)(P.panels_per_group * P.splits * (Np / kTile)));
