@@ -155,7 +155,7 @@ int32_t finalize_and_validate(cl_layer *L)
             int vused = 0, iused = 0;
             for (int j = 0; j < n; ++j) {
                 const lut_t ev = L->val_lut[(uint32_t)vbuf & vmask], ei = L->idx_lut[(uint32_t)ibuf & imask];
-                const int v = ev & 0xff, lv = ev >> 8, z = ei & 0xff, li = ei >> 8;
+                const int v = lut_sym(ev), lv = lut_len(ev), z = lut_sym(ei), li = lut_len(ei);
                 if (L->val_len[v] != lv || L->idx_len[z] != li) return fail(CL_ECORRUPT, "record %llu: bit pattern is not a codeword", (unsigned long long)r);
                 vbuf >>= lv;
                 ibuf >>= li;

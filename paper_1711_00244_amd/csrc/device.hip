@@ -131,11 +131,43 @@ __device__ __forceinline__ LaneRecord load_record(const LayerDev &L, const Chunk
 }
 
 // One table lookup: the symbol at the head of buf; buf moves on to the next codeword.
+// The entry itself is the shift amount (length in its low bits, the shifter ignores
+// the rest), which keeps the loop-carried chain at mask, address, read, shift.
 __device__ __forceinline__ uint32_t next_symbol(uint64_t &buf, const lut_t *lut, uint32_t mask)
 {
     const uint32_t e = lut[(uint32_t)buf & mask];
-    buf >>= (e >> 8);
-    return e & 0xffu;
+    buf >>= (e & 63u);
+    return e >> 8;
+}
+
+// A lane's record with both codeword streams decoded: eight bits per entry, entries
+// 0-7 in z[0] / v[0], entries 8-14 in z[1] / v[1].
+struct Symbols {
+    uint64_t z[2];     // relative indices
+    uint64_t v[2];     // value indices
+    uint32_t n;        // entries
+    uint32_t adv;      // sum of (z + 1): how far the record moves the position
+};
+
+// Algorithm 2 step 6 for one record: both streams are decoded in one loop - two
+// independent table chains per lane, so one lookup's latency hides behind the
+// other's - and kept in registers; positions and weights follow from them without
+// touching the tables again.
+__device__ __forceinline__ Symbols decode_record(LaneRecord rec, const Tables &T)
+{
+    Symbols y{{0, 0}, {0, 0}, rec.n, 0};
+    auto run = [&](uint64_t &zs, uint64_t &vs, uint32_t cnt) {
+        for (uint32_t j = 0; j < cnt; ++j) {
+            const uint32_t z = next_symbol(rec.ibuf, T.ilut, T.imask);
+            const uint32_t v = next_symbol(rec.vbuf, T.vlut, T.vmask);
+            zs |= (uint64_t)z << (8u * j);
+            vs |= (uint64_t)v << (8u * j);
+            y.adv += z + 1u;
+        }
+    };
+    run(y.z[0], y.v[0], min(rec.n, 8u));
+    if (rec.n > 8u) run(y.z[1], y.v[1], rec.n - 8u);
+    return y;
 }
 
 struct LaneStart {
@@ -143,20 +175,34 @@ struct LaneStart {
     uint32_t sum;      // sum of (z + 1) over the block's entries before the lane's first entry
 };
 
-// Pass A and the scan: Algorithm 2 step 6 for the relative indices of the lane's
-// record, then the prefix sum of step 7 across the wavefront.  Lane counts (<= 15,
-// 960 per chunk: 10 bits) and lane sums (<= 15 * 256) travel in one scan.
-__device__ __forceinline__ LaneStart lane_starts(const LaneRecord &rec, const Tables &T, uint32_t pos0)
+// Algorithm 2 step 7: the prefix sum across the wavefront.  Lane counts (<= 15, 960
+// per chunk: 10 bits) and lane advances (<= 15 * 256) travel in one scan.
+__device__ __forceinline__ LaneStart lane_starts(const Symbols &y, uint32_t pos0)
 {
-    uint64_t ibuf = rec.ibuf;
-    uint32_t adv = 0;
-    for (uint32_t j = 0; j < rec.n; ++j) adv += next_symbol(ibuf, T.ilut, T.imask) + 1u;
-    const uint32_t mine = rec.n | (adv << 10);
+    const uint32_t mine = y.n | (y.adv << 10);
     const uint32_t excl = wave_incl_scan(mine) - mine;
     LaneStart s;
     s.entry = excl & 1023u;
     s.sum = pos0 + (excl >> 10);
     return s;
+}
+
+// Calls f(j, v, z, position) for the record's entries in order; sum starts as the
+// lane's LaneStart::sum.
+template <class F>
+__device__ __forceinline__ void for_each_entry(const Symbols &y, uint32_t sum, F f)
+{
+    auto run = [&](uint64_t zs, uint64_t vs, uint32_t j0, uint32_t cnt) {
+        for (uint32_t j = 0; j < cnt; ++j) {
+            const uint32_t z = (uint32_t)zs & 0xffu, v = (uint32_t)vs & 0xffu;
+            zs >>= 8;
+            vs >>= 8;
+            sum += z + 1u;
+            f(j0 + j, v, z, sum - 1u);
+        }
+    };
+    run(y.z[0], y.v[0], 0u, min(y.n, 8u));
+    if (y.n > 8u) run(y.z[1], y.v[1], 8u, y.n - 8u);
 }
 
 struct BlockGeom {
@@ -264,22 +310,19 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(LayerDev L, uint8_t *v
     store_tables(s, L, fetch_tables(L));
     __syncthreads();
     if (!have) return;
-    const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
+    const Symbols y = decode_record(rec, s.T);
+    const LaneStart st = lane_starts(y, h.m.pos0);
     const BlockGeom g = block_geom(L, h.m.blk);
-    uint32_t e = h.m.sym_off + st.entry;
-    uint32_t sum = st.sum;
-    for (uint32_t j = 0; j < rec.n; ++j, ++e) {
-        const uint32_t v = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);
-        const uint32_t z = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);
-        sum += z + 1u;
-        if (val_out) val_out[e] = (uint8_t)v;
-        if (idx_out) idx_out[e] = (uint8_t)z;
-        if (dense && v != 0 && sum <= (uint32_t)g.bhp * (uint32_t)g.bwp) {
+    const uint32_t e0 = h.m.sym_off + st.entry;
+    for_each_entry(y, st.sum, [&](uint32_t j, uint32_t v, uint32_t z, uint32_t pos) {
+        if (val_out) val_out[e0 + j] = (uint8_t)v;
+        if (idx_out) idx_out[e0 + j] = (uint8_t)z;
+        if (dense && v != 0 && pos < (uint32_t)g.bhp * (uint32_t)g.bwp) {
             uint32_t r, cc;
-            split_pos(sum - 1u, g, r, cc);
+            split_pos(pos, g, r, cc);
             dense[(size_t)(g.row_id + (int)r) * L.K + (size_t)(g.col_id + (int)cc)] = s.T.cb[v];
         }
-    }
+    });
 }
 
 __global__ void fill_kernel(float *p, size_t n, float v)
@@ -338,27 +381,20 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     store_tables(s, L, tr);
     __syncthreads();
     if (have) {
-        const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
+        const Symbols y = decode_record(rec, s.T);
+        const LaneStart st = lane_starts(y, h.m.pos0);
         const BlockGeom g = block_geom(L, h.m.blk);
-        uint32_t sum = st.sum;
-        // pass B: one entry per step; the table lookups of the next entry are issued
-        // before the current entry's codebook value and activations are fetched.
-        // The two instantiations differ only in where the activations come from
-        // (LDS stays LDS: no generic pointers).
+        // The entries of the record in order.  The two instantiations differ only in
+        // where the activations come from (LDS stays LDS: no generic pointers).
         auto entries = [&](auto load_x) {
             constexpr uint32_t kNoRow = 0xffffffffu;
             uint32_t cur = kNoRow;
             float acc[BT];
 #pragma unroll
             for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
-            uint32_t v = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);
-            uint32_t z = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);
-            for (uint32_t jn = 0; jn < rec.n; ++jn) {
-                const uint32_t v1 = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);   // past the last entry these
-                const uint32_t z1 = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);   // read padding: harmless
-                sum += z + 1u;
+            for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
                 uint32_t r, cc;
-                split_pos(sum - 1u, g, r, cc);
+                split_pos(pos, g, r, cc);
                 if (r != cur) {
                     if (cur != kNoRow) {
 #pragma unroll
@@ -371,9 +407,7 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
                 const float w = s.T.cb[v];
 #pragma unroll
                 for (int b = 0; b < BT; ++b) acc[b] += w * load_x(b, (int)cc);
-                v = v1;
-                z = z1;
-            }
+            });
             if (cur != kNoRow) {
 #pragma unroll
                 for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
@@ -513,8 +547,9 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
     }
 }
 
-// Workgroup (block row p, split j, image tile nb) of eight wavefronts with two roles.
-//   Producers (wavefronts 4-7) decode block i + 1 - one chunk per wavefront, pass A /
+// Workgroup (block row p, split j, image tile nb) of twelve wavefronts with two roles.
+//   Producers (wavefronts 4-11, two next to each consumer on a SIMD: a lone decoder's
+//   dependent chains issue too slowly to keep up) decode block i + 1 - a chunk per wavefront, pass A /
 //   scan / pass B as in the sparse kernel - and write each entry's weight at its place
 //   in a 128 x 128 fp32 tile in LDS, row by row (Algorithm 2 steps 5-9: decode, prefix
 //   sum, codebook look-up, "arrange as bh x bw block").
@@ -531,8 +566,10 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
 // done with it, so a tile is always clean when the producers get it back.
 constexpr int kWStride = kTile + 4;      // floats per weight row of a tile (16-byte rows, 4-bank skew)
 constexpr int kWTileBytes = kTile * kWStride * 4;
+constexpr int kMfmaDecoders = 8;
+constexpr int kMfmaThreads = (4 + kMfmaDecoders) * 64;
 
-__global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
+__global__ __launch_bounds__(kMfmaThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
                                                            int splits, int Bp, int panel0)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
@@ -545,99 +582,144 @@ __global__ __launch_bounds__(kThreads) void fc_mfma_kernel(LayerDev L, const flo
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const bool producer = wave >= 4;
-    store_tables(s, L, fetch_tables(L));
-    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
+    if (threadIdx.x < kThreads) store_tables(s, L, fetch_tables(L));
+    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kMfmaThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
     // this split's share of the block row's blocks
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
-    // Producer: decode block bi into a weight tile (clean on entry).
-    auto produce = [&](int bi, float *tile) {
-        const uint32_t b = pb0 + (uint32_t)bi;
-        const BlockGeom g = block_geom(L, b);
-        const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
-        for (uint32_t c = c0 + (uint32_t)(wave - 4); c < c1; c += 4) {
-            const ChunkHead h = load_head(L, c);
-            LaneRecord rec = load_record(L, h, lane);
-            const LaneStart st = lane_starts(rec, s.T, h.m.pos0);
-            uint32_t sum = st.sum;
-            for (uint32_t jn = 0; jn < rec.n; ++jn) {
-                const uint32_t v = next_symbol(rec.vbuf, s.T.vlut, s.T.vmask);
-                const uint32_t z = next_symbol(rec.ibuf, s.T.ilut, s.T.imask);
-                sum += z + 1u;
-                uint32_t r, cc;
-                split_pos(sum - 1u, g, r, cc);
-                if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = s.T.cb[v];
+    if (producer) {
+        // The chunks of this split's blocks are consecutive, [c_lo, c_hi); decoder
+        // d = wave - 4 takes c_lo + d, c_lo + d + kMfmaDecoders, ... and finds a block's
+        // end at the first chunk head that names a later block.  Block -> chunk head ->
+        // record is a chain of dependent loads, so the stream runs ahead of the decoding:
+        // the heads of the next three chunks and the records of the next two are in
+        // registers or in flight.  Every load is unconditional (a position past the end
+        // re-reads the last chunk and is marked invalid; chunk heads sit in a zero-padded
+        // section, so the head after the last one is readable even for a layer without
+        // chunks) and nothing touches a loaded value before it is decoded: the loads are
+        // not waited for where they are issued.  Heads are read through an address the
+        // compiler cannot prove uniform, or they would be moved to scalar registers right
+        // behind the load.
+        struct Head {
+            uint32_t rec_off, rec_end, blk, pos0;
+            bool valid;
+        };
+        uint32_t lane_zero;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+        const uint32_t c_hi = blk_lo < blk_hi ? L.block_chunk[pb0 + (uint32_t)blk_hi] : 0u;
+        uint32_t c_tail = blk_lo < blk_hi ? L.block_chunk[pb0 + (uint32_t)blk_lo] + (uint32_t)(wave - 4) : 0u;   // next head to load
+        auto next_head = [&]() {
+            Head h;
+            h.valid = c_tail < c_hi;
+            const cl_chunk_meta *mp = L.meta + (h.valid ? c_tail : (c_hi ? c_hi - 1u : 0u)) + lane_zero;
+            h.rec_off = mp[0].rec_off;
+            h.rec_end = mp[1].rec_off;
+            h.blk = mp[0].blk;
+            h.pos0 = mp[0].pos0;
+            c_tail += (uint32_t)kMfmaDecoders;
+            return h;
+        };
+        auto word_of = [&](const Head &h) {
+            const uint32_t last = h.rec_end - h.rec_off - 1u;       // a chunk has at least one record
+            return L.records[h.rec_off + min((uint32_t)lane, last)];
+        };
+        Head h0 = next_head(), h1 = next_head(), h2 = next_head();
+        uint64_t w0 = word_of(h0), w1 = word_of(h1);
+        // decode block bi into a weight tile (clean on entry): Algorithm 2 steps 5-9
+        auto produce = [&](int bi, float *tile) {
+            const uint32_t b = pb0 + (uint32_t)bi;
+            const BlockGeom g = block_geom(L, b);
+            while (h0.valid && (uint32_t)__builtin_amdgcn_readfirstlane((int)h0.blk) == b) {
+                LaneRecord rec;
+                rec.n = (uint32_t)lane < h0.rec_end - h0.rec_off ? (uint32_t)w0 & 15u : 0u;
+                rec.vbuf = w0 >> kCountBits;
+                rec.ibuf = __builtin_bitreverse64(w0);
+                const uint32_t pos0 = h0.pos0;
+                // move the stream on; the record load issued here uses a head that arrived
+                // a chunk ago
+                h0 = h1; w0 = w1;
+                h1 = h2; w1 = word_of(h1);
+                h2 = next_head();
+                const Symbols y = decode_record(rec, s.T);
+                const LaneStart st = lane_starts(y, pos0);
+                for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                    uint32_t r, cc;
+                    split_pos(pos, g, r, cc);
+                    if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = s.T.cb[v];
+                });
             }
+        };
+        // the decoders go first at the issue arbiter: a multiplying wavefront needs one
+        // issue slot per 64-cycle multiply, the decoders next to it on the SIMD can have
+        // the rest
+        __builtin_amdgcn_s_setprio(3);
+        __syncthreads();                                    // tables stored, tiles clean
+        if (blk_lo < blk_hi) produce(blk_lo, tiles);
+        __syncthreads();
+        for (int bi = blk_lo; bi < blk_hi; ++bi) {
+            if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
+            __syncthreads();
         }
-    };
+        return;
+    }
 
-    // the decoders go first at the issue arbiter: a multiplying wavefront needs one issue
-    // slot per 64-cycle multiply, the decoder next to it on the SIMD can have the rest
-    if (producer) __builtin_amdgcn_s_setprio(3);
-    floatx16 acc[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = floatx16{0};
     // Consumer: the A values run as one stream of k-steps over all blocks of this split.
     // With XT laid out block by block, step s of block bi is rows kTile bi + s and
     // kTile bi + 64 + s; the stream is loaded kBPrefetch steps ahead of the multiplies,
     // across block boundaries.  The last steps read ahead into the next rows of XT (the
-    // next split's, or the tail rows): valid memory, never multiplied.
+    // next split's, or the tail rows): valid memory, never multiplied.  The barriers
+    // below pair with the decoders' above, one for one.
+    floatx16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = floatx16{0};
     const int kl = lane >> 5, m = lane & 31;
     const float4 *ap = (const float4 *)(XT + ((size_t)blk_lo * kTile + 64 * kl) * Bp + (size_t)nb * kTile + 4 * m);
     const size_t row_stride = (size_t)Bp / 4;               // in float4
     float4 aq[kBPrefetch];
-    if (!producer) {
 #pragma unroll
-        for (int i = 0; i < kBPrefetch; ++i) {
-            aq[i] = *ap;
-            ap += row_stride;
-        }
+    for (int i = 0; i < kBPrefetch; ++i) {
+        aq[i] = *ap;
+        ap += row_stride;
     }
     __syncthreads();                                        // tables stored, tiles clean
-    if (producer && blk_lo < blk_hi) produce(blk_lo, tiles);
-    __syncthreads();
+    __syncthreads();                                        // first block decoded
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
         float *cur = tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4);
-        if (producer) {
-            if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
-        } else {
-            // B values of four steps: columns 64 kl + 4 g .. + 3 of weight row 32 wave + m
-            const float4 *wp = (const float4 *)(cur + (wave * 32 + m) * kWStride + 64 * kl);
-            float4 b_cur = wp[0];
-            for (int ks = 0; ks < kTile / 2; ks += kBPrefetch) {
-                // steps are kept in program order (scheduling barriers): hoisting a group's
-                // LDS reads or sinking its loads would put their latency in front of the
-                // multiplies
+        // B values of four steps: columns 64 kl + 4 g .. + 3 of weight row 32 wave + m
+        const float4 *wp = (const float4 *)(cur + (wave * 32 + m) * kWStride + 64 * kl);
+        float4 b_cur = wp[0];
+        for (int ks = 0; ks < kTile / 2; ks += kBPrefetch) {
+            // steps are kept in program order (scheduling barriers): hoisting a group's
+            // LDS reads or sinking its loads would put their latency in front of the
+            // multiplies
 #pragma unroll
-                for (int h4 = 0; h4 < kBPrefetch / 4; ++h4) {
-                    const float4 b_next = wp[min(ks / 4 + h4 + 1, kTile / 8 - 1)];
-                    __builtin_amdgcn_sched_barrier(0);      // the LDS read goes out before these multiplies
-                    const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
+            for (int h4 = 0; h4 < kBPrefetch / 4; ++h4) {
+                const float4 b_next = wp[min(ks / 4 + h4 + 1, kTile / 8 - 1)];
+                __builtin_amdgcn_sched_barrier(0);          // the LDS read goes out before these multiplies
+                const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = 4 * h4 + u;
-                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].x, bv[u], acc[0], 0, 0, 0);
-                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].y, bv[u], acc[1], 0, 0, 0);
-                        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].z, bv[u], acc[2], 0, 0, 0);
-                        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].w, bv[u], acc[3], 0, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);  // the step's A values are free again
-                        aq[i] = *ap;
-                        ap += row_stride;
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    b_cur = b_next;
+                for (int u = 0; u < 4; ++u) {
+                    const int i = 4 * h4 + u;
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].x, bv[u], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].y, bv[u], acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].z, bv[u], acc[2], 0, 0, 0);
+                    acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].w, bv[u], acc[3], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);      // the step's A values are free again
+                    aq[i] = *ap;
+                    ap += row_stride;
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                // the loads of the group after next start the next block: skip this block's other half
-                if (ks == kTile / 2 - 2 * kBPrefetch) ap += (kTile / 2) * row_stride;
+                b_cur = b_next;
             }
-            // done with this tile: clear this wavefront's 32 rows of it
-            uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
-            for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
+            // the loads of the group after next start the next block: skip this block's other half
+            if (ks == kTile / 2 - 2 * kBPrefetch) ap += (kTile / 2) * row_stride;
         }
+        // done with this tile: clear this wavefront's 32 rows of it
+        uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
+        for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
         __syncthreads();
     }
-    if (producer) return;
     // accumulator q, element e of lane l: image 4 (8 (e / 4) + 4 (l / 32) + e % 4) + q of the
     // tile, weight row 32 wave + l % 32; 32 lanes write 32 consecutive floats
     const int r = wave * 32 + m;
@@ -938,7 +1020,7 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     const dim3 grid((unsigned)(L->n_panels * P.splits * (P.Bp / kTile)));
     timing_begin(st);
-    hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
+    hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kMfmaThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
     HIP_TRY(hipGetLastError());
     timing_end(st, 1);
     hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * batch)), dim3(kRedThreads), 0, st,
@@ -1085,7 +1167,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             const int panel0 = grp * P.panels_per_group;
             const dim3 grid((unsigned)(P.panels_per_group * P.splits * (Np / kTile)));
             if (!timed) timing_begin(st);
-            hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kThreads), P.lds, st, D, xt, part, P.splits, Np, panel0);
+            hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kMfmaThreads), P.lds, st, D, xt, part, P.splits, Np, panel0);
             HIP_TRY(hipGetLastError());
             if (!timed) { timing_end(st, 1); timed = true; }
             hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(P.panels_per_group * ncols)), dim3(kRedThreads), 0, st,

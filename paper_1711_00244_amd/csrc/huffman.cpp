@@ -120,12 +120,12 @@ void build_lut(const std::vector<uint8_t> &len, const std::vector<uint32_t> &cod
     const int bits = std::max(1, max_len);
     // Slots no codeword reaches (incomplete codes) still advance by one bit, so a
     // decoder loop always terminates.
-    lut.assign((size_t)1 << bits, (lut_t)(1u << 8));
+    lut.assign((size_t)1 << bits, (lut_t)1u);
     for (int s = 0; s < (int)len.size(); ++s) {
         const int l = len[s];
         if (!l) continue;
         for (uint32_t hi = 0; hi < (1u << (bits - l)); ++hi)
-            lut[(hi << l) | code[s]] = (lut_t)((l << 8) | s);
+            lut[(hi << l) | code[s]] = (lut_t)((s << 8) | l);
     }
 }
 

@@ -15,7 +15,11 @@ constexpr int kCountBits = 4;                       // width of a record's entry
 int32_t fail(int32_t code, const char *fmt, ...);
 void clear_error();
 
-// Entry of a decode table: low byte = symbol, next byte = codeword length (>= 1).
+// Entry of a decode table: low byte = codeword length (>= 1, <= CL_MAX_CODE_LEN, so
+// the entry can feed a 64-bit shift, which looks at the low six bits only), next byte
+// = symbol.
+constexpr int lut_len(uint16_t e) { return e & 0xff; }
+constexpr int lut_sym(uint16_t e) { return e >> 8; }
 using lut_t = uint16_t;
 
 struct DeviceImage {
