@@ -90,11 +90,15 @@ CONFIGS: dict[int, dict] = {
 }
 
 
-def layer_weights(cfg: int, layer_index: int, scale: float = 1.0) -> tuple[LayerSpec, np.ndarray]:
+def layer_weights(cfg: int, layer_index: int, scale: float = 1.0,
+                  density: float | None = None) -> tuple[LayerSpec, np.ndarray]:
     """Weights of one layer of a configuration.  scale < 1 shrinks both
     dimensions (rounded to a multiple of 8, at least 8) for quick tests; conv
-    layers are not scaled."""
+    layers are not scaled.  density overrides the configuration's fraction of
+    non-zeros (the uniform 70/80/90 % pruning levels of Sec. VI)."""
     spec = CONFIGS[cfg]["layers"][layer_index]
+    if density is not None:
+        spec = LayerSpec(spec.name, spec.M, spec.K, density, spec.sigma, spec.r, spec.k, spec.conv)
     M, K = spec.M, spec.K
     if scale != 1.0 and spec.conv is None:
         M = max(8, int(M * scale) // 8 * 8)
