@@ -245,6 +245,48 @@ def test_config2_alexnet_fc6_full_size():
         assert rel_err(Y.cpu().numpy(), ref) <= TOL
 
 
+def test_config5_vgg_fc_layers_full_size():
+    """configs[4]: the VGG-16 FC shapes at full size (fc6 is 4096 x 25088 at 4 %),
+    decoded bit-exactly and multiplied on both paths: 3 images on the sparse path,
+    130 images (two image tiles, the second ragged) on the MFMA path, the latter on
+    sampled output rows that the oracle computes one by one from its own decode."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(5)
+    for li in range(3):
+        spec, W = wl.layer_weights(5, li)
+        L, m, oW = check_decode(W, spec.r, spec.k, 128, 128)
+        X = wl.activations(5, 3, K=spec.K)
+        ref = oracle.fc_forward(oW, X, nthreads=8)
+        Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), path=cl.PATH_SPARSE)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+        X = wl.activations(5, 130, K=spec.K)
+        Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), path=cl.PATH_MFMA_F32).cpu().numpy()
+        rows = np.sort(rng.choice(spec.M, size=48, replace=False))
+        ref = oracle.fc_forward(np.ascontiguousarray(oW[rows]), X, nthreads=8)
+        assert rel_err(Y[:, rows], ref) <= TOL
+        L.free()
+        del oW, W
+
+
+def test_auto_path_on_both_sides_of_the_crossover():
+    """CL_PATH_AUTO picks the sparse kernel for 8 images and the MFMA kernel for 9:
+    both results must match the oracle, and each must equal the result of naming
+    the path."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(11)
+    W = rand_pruned(rng, 300, 520, 0.09)
+    L, m, oW = check_decode(W, 5, 4, 128, 128)
+    for B, named in ((8, cl.PATH_SPARSE), (9, cl.PATH_MFMA_F32)):
+        X = np.maximum(rng.standard_normal((B, 520)), 0).astype(np.float32)
+        ref = oracle.fc_forward(oW, X)
+        Xd = torch.from_numpy(X).cuda()
+        Y = cl.compressed_fc_forward(L, Xd)
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+        if named == cl.PATH_MFMA_F32:       # the MFMA path is run-to-run deterministic
+            assert torch.equal(Y, cl.compressed_fc_forward(L, Xd, path=named))
+        assert cl.fc_workspace_bytes(L, B) == cl.fc_workspace_bytes(L, B, named)
+
+
 def test_forward_rejects_bad_arguments():
     torch = torch_cuda()
     L = cl.compress_layer(np.eye(8, dtype=np.float32), 5, 4, 8, 8)
