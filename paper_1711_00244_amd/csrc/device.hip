@@ -734,6 +734,56 @@ __global__ __launch_bounds__(kMfmaThreads) void fc_mfma_kernel(LayerDev L, const
     }
 }
 
+// Finishes the dense-tile path: Y = act(sum over the splits of a block row, in a fixed
+// order, + bias) (Eq. 1).  A workgroup takes a block row and ct <= kColTile consecutive
+// columns (images, or image x output pixel for a convolution): for each split that
+// is one contiguous run of ct x bh floats of the partial buffer.  The host picks ct
+// so that the launch still has a few workgroups per CU.  FC output
+// rows are contiguous in Y[image][row]; a convolution's output is contiguous along
+// the pixels, Y[image][row][pixel], so its tile is turned in LDS first.
+constexpr int kColTile = 32;
+
+__global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const float *__restrict__ part,
+                                                          const float *__restrict__ bias, float *Y, int ncols, int part_b,
+                                                          int splits, int relu, int panel0, int conv_pq, int ct)
+{
+    __shared__ float tile[kColTile][kTile + 1];
+    const int ntile = (ncols + ct - 1) / ct;
+    const int pl = (int)blockIdx.x / ntile, c0 = ((int)blockIdx.x - pl * ntile) * ct;
+    const int p = panel0 + pl;
+    const int row_id = p * L.bh;
+    const int bhp = min(L.bh, L.M - row_id);
+    const size_t split_stride = (size_t)part_b * L.bh;
+    for (int e = threadIdx.x; e < ct * L.bh; e += blockDim.x) {
+        const int ci = e / L.bh, r = e - ci * L.bh;
+        const int c = c0 + ci;
+        if (c >= ncols || r >= bhp) continue;
+        const float *src = part + ((size_t)pl * splits * part_b + c) * L.bh + r;
+        float t = 0.0f;
+        int j = 0;
+        for (; j + 3 < splits; j += 4) {                    // four loads in flight, added in order
+            const float a0 = src[(size_t)j * split_stride], a1 = src[(size_t)(j + 1) * split_stride];
+            const float a2 = src[(size_t)(j + 2) * split_stride], a3 = src[(size_t)(j + 3) * split_stride];
+            t += a0;
+            t += a1;
+            t += a2;
+            t += a3;
+        }
+        for (; j < splits; ++j) t += src[(size_t)j * split_stride];
+        if (bias) t += bias[row_id + r];
+        t = relu ? fmaxf(t, 0.0f) : t;
+        if (conv_pq == 0) Y[(size_t)c * L.M + row_id + r] = t;
+        else tile[ci][r] = t;
+    }
+    if (conv_pq == 0) return;
+    __syncthreads();
+    for (int e = threadIdx.x; e < ct * bhp; e += blockDim.x) {
+        const int r = e / ct, ci = e - r * ct;
+        const int c = c0 + ci;
+        if (c < ncols) Y[((size_t)(c / conv_pq) * L.M + row_id + r) * conv_pq + (c % conv_pq)] = tile[ci][r];
+    }
+}
+
 // ------------------------------------------------------------------------- //
 // host side
 // ------------------------------------------------------------------------- //
@@ -917,6 +967,14 @@ struct MfmaPlan {
     size_t xt_bytes = 0, part_bytes = 0;
 };
 
+// columns per workgroup of the finishing kernel: as many as leave 1024 workgroups
+int reduce_col_tile(int panels, int ncols)
+{
+    int ct = kColTile;
+    while (ct > 1 && (int64_t)panels * ((ncols + ct - 1) / ct) < 1024) ct >>= 1;
+    return ct;
+}
+
 // rows of the block-by-block activation layout, tail included
 size_t xt_rows(const cl_layer *L) { return (size_t)L->nbw * kTile + kXtTailRows; }
 
@@ -1027,8 +1085,9 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kMfmaThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
     HIP_TRY(hipGetLastError());
     timing_end(st, 1);
-    hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * batch)), dim3(kRedThreads), 0, st,
-                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, P.splits, 0, 0);
+    const int ct = reduce_col_tile(L->n_panels, batch);
+    hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((batch + ct - 1) / ct))), dim3(256), 0, st,
+                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, 0, 0, ct);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -1174,8 +1233,9 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kMfmaThreads), P.lds, st, D, xt, part, P.splits, Np, panel0);
             HIP_TRY(hipGetLastError());
             if (!timed) { timing_end(st, 1); timed = true; }
-            hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(P.panels_per_group * ncols)), dim3(kRedThreads), 0, st,
-                               D, part, d_bias, y, ncols, Np, P.splits, relu, P.splits, panel0, pq);
+            const int ct = reduce_col_tile(P.panels_per_group, ncols);
+            hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(P.panels_per_group * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
+                               D, part, d_bias, y, ncols, Np, P.splits, relu, panel0, pq, ct);
             HIP_TRY(hipGetLastError());
         }
     }
