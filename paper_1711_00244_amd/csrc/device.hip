@@ -566,16 +566,28 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
 // done with it, so a tile is always clean when the producers get it back.
 constexpr int kWStride = kTile + 4;      // floats per weight row of a tile (16-byte rows, 4-bank skew)
 constexpr int kWTileBytes = kTile * kWStride * 4;
-constexpr int kMfmaDecoders = 8;
-constexpr int kMfmaThreads = (4 + kMfmaDecoders) * 64;
+// NH = 128-image halves per workgroup tile.  With two halves a decoded block feeds twice
+// the multiplies (eight accumulators per multiplying wavefront, which leaves room for four
+// decoder wavefronts and four steps of load-ahead).
+template <int NH> struct MfmaShape {
+    static constexpr int kDecoders = NH == 1 ? 8 : 4;
+    static constexpr int kThreads = (4 + kDecoders) * 64;
+    static constexpr int kAhead = NH == 1 ? kBPrefetch : kBPrefetch / 2;     // k-steps of activations in flight
+    static constexpr int kImages = NH * kTile;
+};
 
-__global__ __launch_bounds__(kMfmaThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
-                                                           int splits, int Bp, int panel0)
+template <int NH>
+__global__ __launch_bounds__(MfmaShape<NH>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
+                                                                         int splits, int Bp, int panel0)
 {
+    constexpr int kMfmaDecoders = MfmaShape<NH>::kDecoders;
+    constexpr int kMfmaThreads = MfmaShape<NH>::kThreads;
+    constexpr int kAhead = MfmaShape<NH>::kAhead;
+    constexpr int kImages = MfmaShape<NH>::kImages;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
     float *tiles = (float *)s.extra;                        // [2][kTile rows][kWStride]
-    const int nbt = Bp / kTile;
+    const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
     const int p = panel0 + pj / splits, j = pj % splits;     // part slots are numbered from panel0
@@ -670,16 +682,17 @@ __global__ __launch_bounds__(kMfmaThreads) void fc_mfma_kernel(LayerDev L, const
     // across block boundaries.  The last steps read ahead into the next rows of XT (the
     // next split's, or the tail rows): valid memory, never multiplied.  The barriers
     // below pair with the decoders' above, one for one.
-    floatx16 acc[4];
+    floatx16 acc[4 * NH];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = floatx16{0};
+    for (int q = 0; q < 4 * NH; ++q) acc[q] = floatx16{0};
     const int kl = lane >> 5, m = lane & 31;
-    const float4 *ap = (const float4 *)(XT + ((size_t)blk_lo * kTile + 64 * kl) * Bp + (size_t)nb * kTile + 4 * m);
+    const float4 *ap = (const float4 *)(XT + ((size_t)blk_lo * kTile + 64 * kl) * Bp + (size_t)nb * kImages + 4 * m);
     const size_t row_stride = (size_t)Bp / 4;               // in float4
-    float4 aq[kBPrefetch];
+    float4 aq[kAhead][NH];
 #pragma unroll
-    for (int i = 0; i < kBPrefetch; ++i) {
-        aq[i] = *ap;
+    for (int i = 0; i < kAhead; ++i) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) aq[i][h] = ap[h * (kTile / 4)];
         ap += row_stride;
     }
     __syncthreads();                                        // tables stored, tiles clean
@@ -689,47 +702,54 @@ __global__ __launch_bounds__(kMfmaThreads) void fc_mfma_kernel(LayerDev L, const
         // B values of four steps: columns 64 kl + 4 g .. + 3 of weight row 32 wave + m
         const float4 *wp = (const float4 *)(cur + (wave * 32 + m) * kWStride + 64 * kl);
         float4 b_cur = wp[0];
-        for (int ks = 0; ks < kTile / 2; ks += kBPrefetch) {
+        for (int ks = 0; ks < kTile / 2; ks += kAhead) {
             // steps are kept in program order (scheduling barriers): hoisting a group's
             // LDS reads or sinking its loads would put their latency in front of the
             // multiplies
 #pragma unroll
-            for (int h4 = 0; h4 < kBPrefetch / 4; ++h4) {
+            for (int h4 = 0; h4 < kAhead / 4; ++h4) {
                 const float4 b_next = wp[min(ks / 4 + h4 + 1, kTile / 8 - 1)];
                 __builtin_amdgcn_sched_barrier(0);          // the LDS read goes out before these multiplies
                 const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int i = 4 * h4 + u;
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].x, bv[u], acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].y, bv[u], acc[1], 0, 0, 0);
-                    acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].z, bv[u], acc[2], 0, 0, 0);
-                    acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i].w, bv[u], acc[3], 0, 0, 0);
+#pragma unroll
+                    for (int h = 0; h < NH; ++h) {
+                        acc[4 * h + 0] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].x, bv[u], acc[4 * h + 0], 0, 0, 0);
+                        acc[4 * h + 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].y, bv[u], acc[4 * h + 1], 0, 0, 0);
+                        acc[4 * h + 2] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].z, bv[u], acc[4 * h + 2], 0, 0, 0);
+                        acc[4 * h + 3] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].w, bv[u], acc[4 * h + 3], 0, 0, 0);
+                    }
                     __builtin_amdgcn_sched_barrier(0);      // the step's A values are free again
-                    aq[i] = *ap;
+#pragma unroll
+                    for (int h = 0; h < NH; ++h) aq[i][h] = ap[h * (kTile / 4)];
                     ap += row_stride;
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 b_cur = b_next;
             }
             // the loads of the group after next start the next block: skip this block's other half
-            if (ks == kTile / 2 - 2 * kBPrefetch) ap += (kTile / 2) * row_stride;
+            if (ks == kTile / 2 - 2 * kAhead) ap += (kTile / 2) * row_stride;
         }
         // done with this tile: clear this wavefront's 32 rows of it
         uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
         for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
         __syncthreads();
     }
-    // accumulator q, element e of lane l: image 4 (8 (e / 4) + 4 (l / 32) + e % 4) + q of the
-    // tile, weight row 32 wave + l % 32; 32 lanes write 32 consecutive floats
+    // accumulator 4 h + q, element e of lane l: image 128 h + 4 (8 (e / 4) + 4 (l / 32) + e % 4) + q
+    // of the tile, weight row 32 wave + l % 32; 32 lanes write 32 consecutive floats
     const int r = wave * 32 + m;
     if (r < L.bh) {
-        float *mine = part + ((size_t)pj * Bp + (size_t)nb * kTile) * L.bh + r;
+        float *mine = part + ((size_t)pj * Bp + (size_t)nb * kImages) * L.bh + r;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
+        for (int h = 0; h < NH; ++h) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) mine[(size_t)(4 * slot + q) * L.bh] = acc[q][e];
+            for (int e = 0; e < 16; ++e) {
+                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) mine[(size_t)(kTile * h + 4 * slot + q) * L.bh] = acc[4 * h + q][e];
+            }
         }
     }
 }
@@ -961,6 +981,7 @@ int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
 
 // Launch shape of the MFMA path.
 struct MfmaPlan {
+    int nh = 1;              // 128-image halves per workgroup tile
     int Bp = 0;              // batch rounded up to whole image tiles
     int splits = 1;          // workgroups sharing the blocks of one block row
     size_t lds = 0;
@@ -980,16 +1001,60 @@ size_t xt_rows(const cl_layer *L) { return (size_t)L->nbw * kTile + kXtTailRows;
 
 bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->desc.block_w <= kTile; }
 
+// Image tile, padded column count and split of the block rows for `ncols` columns and
+// `panels` block rows.  A 256-column tile decodes each block once for twice the
+// multiplies; which tile is faster follows from a small model of the kernel with
+// measured constants (cycles per workgroup: 12 k to start, 21 k per block at 128
+// columns, 39 k at 256; workgroups run in rounds of one per CU).
+void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, int &nh, int &np, int &splits)
+{
+    cus = std::max(1, cus);
+    auto shape = [&](int h, int &cols, int &sp) {
+        cols = (ncols + h * kTile - 1) / (h * kTile) * (h * kTile);
+        const int64_t tiles = (int64_t)panels * (cols / (h * kTile));
+        sp = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (cus + tiles - 1) / tiles));
+        const int64_t rounds = (tiles * sp + cus - 1) / cus;
+        const int64_t blocks = (L->nbw + sp - 1) / sp;
+        return rounds * (12000 + blocks * (h == 1 ? 21000 : 39000));
+    };
+    int c1, s1, c2, s2;
+    const int64_t t1 = shape(1, c1, s1), t2 = shape(2, c2, s2);
+    const bool wide = t2 + t2 / 8 < t1;                    // the model is coarse: the wide tile must win clearly
+    nh = wide ? 2 : 1;
+    np = wide ? c2 : c1;
+    splits = wide ? s2 : s1;
+}
+
+size_t mfma_lds_bytes(const cl_layer *L)
+{
+    return table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes;
+}
+
 int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan &P)
 {
     if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the MFMA path needs blocks of at most %d x %d", kTile, kTile);
-    P.Bp = (batch + kTile - 1) / kTile * kTile;
-    const int tiles = L->n_panels * (P.Bp / kTile);
-    P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
-    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes;
+    mfma_shape(L, L->n_panels, batch, dl.cus, P.nh, P.Bp, P.splits);
+    P.lds = mfma_lds_bytes(L);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the MFMA path needs %zu bytes of LDS", P.lds);
     P.xt_bytes = (xt_rows(L) * P.Bp * sizeof(float) + 255) / 256 * 256;
     P.part_bytes = (size_t)L->n_panels * P.splits * P.Bp * L->desc.block_h * sizeof(float);
+    return CL_OK;
+}
+
+// Launches the dense-tile kernel for `panels` block rows from panel0 over np padded columns.
+int32_t launch_mfma(const LayerDev &D, int nh, int panels, int splits, int np, int panel0, size_t lds, const float *xt,
+                    float *part, hipStream_t st)
+{
+    if (nh == 2) {
+        HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(fc_mfma_kernel<2>, dim3((unsigned)(panels * splits * (np / MfmaShape<2>::kImages))),
+                           dim3(MfmaShape<2>::kThreads), lds, st, D, xt, part, splits, np, panel0);
+    } else {
+        HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(fc_mfma_kernel<1>, dim3((unsigned)(panels * splits * (np / MfmaShape<1>::kImages))),
+                           dim3(MfmaShape<1>::kThreads), lds, st, D, xt, part, splits, np, panel0);
+    }
+    HIP_TRY(hipGetLastError());
     return CL_OK;
 }
 
@@ -1079,11 +1144,8 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
                        d_X, xt, batch, K, P.Bp, L->desc.block_w, rows);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
-    const dim3 grid((unsigned)(L->n_panels * P.splits * (P.Bp / kTile)));
     timing_begin(st);
-    hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kMfmaThreads), P.lds, st, D, xt, part, P.splits, P.Bp, 0);
-    HIP_TRY(hipGetLastError());
+    if (int32_t rc = launch_mfma(D, P.nh, L->n_panels, P.splits, P.Bp, 0, P.lds, xt, part, st)) return rc;
     timing_end(st, 1);
     const int ct = reduce_col_tile(L->n_panels, batch);
     hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((batch + ct - 1) / ct))), dim3(256), 0, st,
@@ -1145,7 +1207,7 @@ constexpr size_t kConvXtCap = (size_t)256 << 20;
 
 struct ConvPlan {
     ConvGeom cg{};
-    int OCg = 0, panels_per_group = 0, imgs = 0, Np = 0, splits = 1;
+    int OCg = 0, panels_per_group = 0, imgs = 0;
     size_t lds = 0, xt_bytes = 0, part_bytes = 0;
 };
 
@@ -1170,13 +1232,17 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const De
     P.panels_per_group = (P.OCg + L->desc.block_h - 1) / L->desc.block_h;
     const size_t per_image = xt_rows(L) * g.P * g.Q * sizeof(float);
     P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
-    P.Np = (P.imgs * g.P * g.Q + kTile - 1) / kTile * kTile;
-    const int tiles = P.panels_per_group * (P.Np / kTile);
-    P.splits = std::max(1, std::min(L->nbw, (std::max(1, dl.cus) + tiles - 1) / tiles));
-    P.lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes;
+    P.lds = mfma_lds_bytes(L);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
-    P.xt_bytes = (xt_rows(L) * P.Np * sizeof(float) + 255) / 256 * 256;
-    P.part_bytes = (size_t)P.panels_per_group * P.splits * P.Np * L->desc.block_h * sizeof(float);
+    // workspace for the larger of a full image group and the last, smaller one
+    P.xt_bytes = P.part_bytes = 0;
+    for (int imgs : {P.imgs, batch % P.imgs}) {
+        if (imgs == 0) continue;
+        int nh, np, splits;
+        mfma_shape(L, P.panels_per_group, imgs * g.P * g.Q, dl.cus, nh, np, splits);
+        P.xt_bytes = std::max(P.xt_bytes, (xt_rows(L) * np * sizeof(float) + 255) / 256 * 256);
+        P.part_bytes = std::max(P.part_bytes, (size_t)P.panels_per_group * splits * np * L->desc.block_h * sizeof(float));
+    }
     return CL_OK;
 }
 
@@ -1215,12 +1281,12 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
     float *xt = (float *)d_workspace;
     float *part = (float *)((char *)d_workspace + P.xt_bytes);
-    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds));
     bool timed = false;
     for (int b0 = 0; b0 < batch; b0 += P.imgs) {
         const int nb = std::min(P.imgs, batch - b0);
         const int ncols = nb * pq;
-        const int Np = (ncols + kTile - 1) / kTile * kTile;
+        int nh, Np, splits;
+        mfma_shape(L, P.panels_per_group, ncols, dl.cus, nh, Np, splits);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         for (int grp = 0; grp < cv->groups; ++grp) {
@@ -1228,14 +1294,12 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
                                x, xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K);
             HIP_TRY(hipGetLastError());
             const int panel0 = grp * P.panels_per_group;
-            const dim3 grid((unsigned)(P.panels_per_group * P.splits * (Np / kTile)));
             if (!timed) timing_begin(st);
-            hipLaunchKernelGGL(fc_mfma_kernel, grid, dim3(kMfmaThreads), P.lds, st, D, xt, part, P.splits, Np, panel0);
-            HIP_TRY(hipGetLastError());
+            if (int32_t rc = launch_mfma(D, nh, P.panels_per_group, splits, Np, panel0, P.lds, xt, part, st)) return rc;
             if (!timed) { timing_end(st, 1); timed = true; }
             const int ct = reduce_col_tile(P.panels_per_group, ncols);
             hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(P.panels_per_group * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
-                               D, part, d_bias, y, ncols, Np, P.splits, relu, panel0, pq, ct);
+                               D, part, d_bias, y, ncols, Np, splits, relu, panel0, pq, ct);
             HIP_TRY(hipGetLastError());
         }
     }
