@@ -137,7 +137,7 @@ def main():
         return float(np.mean(ts))
 
     def uses_mfma(B):
-        return path == cl.PATH_MFMA_F32 or (path == cl.PATH_AUTO and B > 8)
+        return path == cl.PATH_MFMA_F32 or (path == cl.PATH_AUTO and B > 4)
 
     # HBM bytes (read + written) of the fc6 launch from the FETCH_SIZE / WRITE_SIZE counter runs
     # summarised under profiles/ (scaled by the reference copy's reading); they hold for the

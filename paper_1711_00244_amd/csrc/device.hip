@@ -566,24 +566,41 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
 // done with it, so a tile is always clean when the producers get it back.
 constexpr int kWStride = kTile + 4;      // floats per weight row of a tile (16-byte rows, 4-bank skew)
 constexpr int kWTileBytes = kTile * kWStride * 4;
-// NH = 128-image halves per workgroup tile.  With two halves a decoded block feeds twice
-// the multiplies (eight accumulators per multiplying wavefront, which leaves room for four
-// decoder wavefronts and four steps of load-ahead).
-template <int NH> struct MfmaShape {
-    static constexpr int kDecoders = NH == 1 ? 8 : 4;
+// NQ = 32 x 32 accumulators per multiplying wavefront = 32-column groups of the
+// workgroup's image tile (1, 2, 4 or 8: 32 to 256 images).  A wider tile feeds more
+// multiplies from each decoded block; a narrower one wastes fewer padded columns on a
+// small batch.  Up to four accumulators a lane's activation values of a k-step are one
+// load of NQ floats (accumulator q holds images NQ m + q); with eight they are two
+// 16-byte loads, 128 images apart, which leaves registers for four decoder wavefronts
+// and four steps of load-ahead.
+template <int NQ> struct MfmaShape {
+    static constexpr int kDecoders = NQ <= 4 ? 8 : 4;
     static constexpr int kThreads = (4 + kDecoders) * 64;
-    static constexpr int kAhead = NH == 1 ? kBPrefetch : kBPrefetch / 2;     // k-steps of activations in flight
-    static constexpr int kImages = NH * kTile;
+    static constexpr int kAhead = NQ <= 4 ? kBPrefetch : kBPrefetch / 2;     // k-steps of activations in flight
+    static constexpr int kImages = 32 * NQ;
+    static constexpr int kVecW = NQ < 4 ? NQ : 4;                             // floats per load
+    static constexpr int kVecs = NQ / kVecW;                                  // loads per k-step
 };
 
-template <int NH>
-__global__ __launch_bounds__(MfmaShape<NH>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
+template <int W> __device__ __forceinline__ void load_floats(const float *p, float *dst)
+{
+    typedef float vec_t __attribute__((ext_vector_type(W)));
+    const vec_t v = *(const vec_t *)p;
+#pragma unroll
+    for (int i = 0; i < W; ++i) dst[i] = v[i];
+}
+
+template <> __device__ __forceinline__ void load_floats<1>(const float *p, float *dst) { dst[0] = *p; }
+
+template <int NQ>
+__global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
                                                                          int splits, int Bp, int panel0)
 {
-    constexpr int kMfmaDecoders = MfmaShape<NH>::kDecoders;
-    constexpr int kMfmaThreads = MfmaShape<NH>::kThreads;
-    constexpr int kAhead = MfmaShape<NH>::kAhead;
-    constexpr int kImages = MfmaShape<NH>::kImages;
+    constexpr int kMfmaDecoders = MfmaShape<NQ>::kDecoders;
+    constexpr int kMfmaThreads = MfmaShape<NQ>::kThreads;
+    constexpr int kAhead = MfmaShape<NQ>::kAhead;
+    constexpr int kImages = MfmaShape<NQ>::kImages;
+    constexpr int kVecW = MfmaShape<NQ>::kVecW, kVecs = MfmaShape<NQ>::kVecs;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
     float *tiles = (float *)s.extra;                        // [2][kTile rows][kWStride]
@@ -682,17 +699,17 @@ __global__ __launch_bounds__(MfmaShape<NH>::kThreads) void fc_mfma_kernel(LayerD
     // across block boundaries.  The last steps read ahead into the next rows of XT (the
     // next split's, or the tail rows): valid memory, never multiplied.  The barriers
     // below pair with the decoders' above, one for one.
-    floatx16 acc[4 * NH];
+    floatx16 acc[NQ];
 #pragma unroll
-    for (int q = 0; q < 4 * NH; ++q) acc[q] = floatx16{0};
+    for (int q = 0; q < NQ; ++q) acc[q] = floatx16{0};
     const int kl = lane >> 5, m = lane & 31;
-    const float4 *ap = (const float4 *)(XT + ((size_t)blk_lo * kTile + 64 * kl) * Bp + (size_t)nb * kImages + 4 * m);
-    const size_t row_stride = (size_t)Bp / 4;               // in float4
-    float4 aq[kAhead][NH];
+    const float *ap = XT + ((size_t)blk_lo * kTile + 64 * kl) * Bp + (size_t)nb * kImages + kVecW * m;
+    const size_t row_stride = (size_t)Bp;
+    float aq[kAhead][NQ];
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) {
 #pragma unroll
-        for (int h = 0; h < NH; ++h) aq[i][h] = ap[h * (kTile / 4)];
+        for (int v = 0; v < kVecs; ++v) load_floats<kVecW>(ap + v * kTile, &aq[i][4 * v]);
         ap += row_stride;
     }
     __syncthreads();                                        // tables stored, tiles clean
@@ -715,15 +732,10 @@ __global__ __launch_bounds__(MfmaShape<NH>::kThreads) void fc_mfma_kernel(LayerD
                 for (int u = 0; u < 4; ++u) {
                     const int i = 4 * h4 + u;
 #pragma unroll
-                    for (int h = 0; h < NH; ++h) {
-                        acc[4 * h + 0] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].x, bv[u], acc[4 * h + 0], 0, 0, 0);
-                        acc[4 * h + 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].y, bv[u], acc[4 * h + 1], 0, 0, 0);
-                        acc[4 * h + 2] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].z, bv[u], acc[4 * h + 2], 0, 0, 0);
-                        acc[4 * h + 3] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][h].w, bv[u], acc[4 * h + 3], 0, 0, 0);
-                    }
+                    for (int q = 0; q < NQ; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[i][q], bv[u], acc[q], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);      // the step's A values are free again
 #pragma unroll
-                    for (int h = 0; h < NH; ++h) aq[i][h] = ap[h * (kTile / 4)];
+                    for (int v = 0; v < kVecs; ++v) load_floats<kVecW>(ap + v * kTile, &aq[i][4 * v]);
                     ap += row_stride;
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -737,18 +749,18 @@ __global__ __launch_bounds__(MfmaShape<NH>::kThreads) void fc_mfma_kernel(LayerD
         for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
         __syncthreads();
     }
-    // accumulator 4 h + q, element e of lane l: image 128 h + 4 (8 (e / 4) + 4 (l / 32) + e % 4) + q
+    // accumulator 4 v + q, element e of lane l: image 128 v + kVecW (8 (e / 4) + 4 (l / 32) + e % 4) + q
     // of the tile, weight row 32 wave + l % 32; 32 lanes write 32 consecutive floats
     const int r = wave * 32 + m;
     if (r < L.bh) {
         float *mine = part + ((size_t)pj * Bp + (size_t)nb * kImages) * L.bh + r;
 #pragma unroll
-        for (int h = 0; h < NH; ++h) {
+        for (int v = 0; v < kVecs; ++v) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) mine[(size_t)(kTile * h + 4 * slot + q) * L.bh] = acc[4 * h + q][e];
+                for (int q = 0; q < kVecW; ++q) mine[(size_t)(kTile * v + kVecW * slot + q) * L.bh] = acc[4 * v + q][e];
             }
         }
     }
@@ -981,7 +993,7 @@ int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
 
 // Launch shape of the MFMA path.
 struct MfmaPlan {
-    int nh = 1;              // 128-image halves per workgroup tile
+    int nq = 4;              // 32-image groups per workgroup tile
     int Bp = 0;              // batch rounded up to whole image tiles
     int splits = 1;          // workgroups sharing the blocks of one block row
     size_t lds = 0;
@@ -1002,27 +1014,34 @@ size_t xt_rows(const cl_layer *L) { return (size_t)L->nbw * kTile + kXtTailRows;
 bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->desc.block_w <= kTile; }
 
 // Image tile, padded column count and split of the block rows for `ncols` columns and
-// `panels` block rows.  A 256-column tile decodes each block once for twice the
-// multiplies; which tile is faster follows from a small model of the kernel with
-// measured constants (cycles per workgroup: 12 k to start, 21 k per block at 128
-// columns, 39 k at 256; workgroups run in rounds of one per CU).
-void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, int &nh, int &np, int &splits)
+// `panels` block rows, from a small model of the kernel with measured constants
+// (cycles per workgroup: 12 k to start; per block 5 k of decoding and bookkeeping plus
+// 4.1 k of multiplies per 32 columns of the tile; workgroups run in rounds of one per
+// CU).  The model is coarse, so a candidate must win by a sixteenth to replace a
+// narrower one.
+void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, int &nq, int &np, int &splits)
 {
     cus = std::max(1, cus);
-    auto shape = [&](int h, int &cols, int &sp) {
-        cols = (ncols + h * kTile - 1) / (h * kTile) * (h * kTile);
-        const int64_t tiles = (int64_t)panels * (cols / (h * kTile));
-        sp = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (cus + tiles - 1) / tiles));
-        const int64_t rounds = (tiles * sp + cus - 1) / cus;
-        const int64_t blocks = (L->nbw + sp - 1) / sp;
-        return rounds * (12000 + blocks * (h == 1 ? 21000 : 39000));
-    };
-    int c1, s1, c2, s2;
-    const int64_t t1 = shape(1, c1, s1), t2 = shape(2, c2, s2);
-    const bool wide = t2 + t2 / 8 < t1;                    // the model is coarse: the wide tile must win clearly
-    nh = wide ? 2 : 1;
-    np = wide ? c2 : c1;
-    splits = wide ? s2 : s1;
+    nq = 0;
+    int64_t best = -1;
+    for (int q : {1, 2, 4, 8}) {
+        const int w = 32 * q;
+        const int cols = (ncols + w - 1) / w * w;
+        const int64_t tiles = (int64_t)panels * (cols / w);
+        // the split that fills the CUs, or any smaller one that needs fewer rounds
+        const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (cus + tiles - 1) / tiles));
+        for (int sp = 1; sp <= sp_max; ++sp) {
+            const int64_t rounds = (tiles * sp + cus - 1) / cus;
+            const int64_t blocks = (L->nbw + sp - 1) / sp;
+            const int64_t t = rounds * (12000 + blocks * (5000 + 4100 * q));
+            if (best < 0 || (q == nq ? t < best : t + t / 16 < best)) {
+                best = t;
+                nq = q;
+                np = cols;
+                splits = sp;
+            }
+        }
+    }
 }
 
 size_t mfma_lds_bytes(const cl_layer *L)
@@ -1033,7 +1052,7 @@ size_t mfma_lds_bytes(const cl_layer *L)
 int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan &P)
 {
     if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the MFMA path needs blocks of at most %d x %d", kTile, kTile);
-    mfma_shape(L, L->n_panels, batch, dl.cus, P.nh, P.Bp, P.splits);
+    mfma_shape(L, L->n_panels, batch, dl.cus, P.nq, P.Bp, P.splits);
     P.lds = mfma_lds_bytes(L);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the MFMA path needs %zu bytes of LDS", P.lds);
     P.xt_bytes = (xt_rows(L) * P.Bp * sizeof(float) + 255) / 256 * 256;
@@ -1042,27 +1061,34 @@ int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan
 }
 
 // Launches the dense-tile kernel for `panels` block rows from panel0 over np padded columns.
-int32_t launch_mfma(const LayerDev &D, int nh, int panels, int splits, int np, int panel0, size_t lds, const float *xt,
-                    float *part, hipStream_t st)
+template <int NQ>
+int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int panel0, size_t lds, const float *xt, float *part,
+                       hipStream_t st)
 {
-    if (nh == 2) {
-        HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(fc_mfma_kernel<2>, dim3((unsigned)(panels * splits * (np / MfmaShape<2>::kImages))),
-                           dim3(MfmaShape<2>::kThreads), lds, st, D, xt, part, splits, np, panel0);
-    } else {
-        HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(fc_mfma_kernel<1>, dim3((unsigned)(panels * splits * (np / MfmaShape<1>::kImages))),
-                           dim3(MfmaShape<1>::kThreads), lds, st, D, xt, part, splits, np, panel0);
-    }
+    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel<NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(fc_mfma_kernel<NQ>, dim3((unsigned)(panels * splits * (np / MfmaShape<NQ>::kImages))),
+                       dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panel0);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
 
+int32_t launch_mfma(const LayerDev &D, int nq, int panels, int splits, int np, int panel0, size_t lds, const float *xt,
+                    float *part, hipStream_t st)
+{
+    switch (nq) {
+    case 1: return launch_mfma_as<1>(D, panels, splits, np, panel0, lds, xt, part, st);
+    case 2: return launch_mfma_as<2>(D, panels, splits, np, panel0, lds, xt, part, st);
+    case 4: return launch_mfma_as<4>(D, panels, splits, np, panel0, lds, xt, part, st);
+    case 8: return launch_mfma_as<8>(D, panels, splits, np, panel0, lds, xt, part, st);
+    }
+    return fail(CL_EINVAL, "internal: no dense-tile kernel for %d accumulators", nq);
+}
+
 // CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images, the dense-tile path
-// above when the blocks fit a tile.  Measured on the AlexNet-shaped stack: the dense
-// path costs the same for any batch up to one image tile (fc6 0.10 ms), the sparse path
-// 0.061 ms at 8 images and 0.110 ms at 9-16 (its batch tile is a power of two).
-constexpr int kAutoSparseBatch = 8;
+// above when the blocks fit a tile.  Measured on the AlexNet-shaped stack (fc6 / fc7 /
+// fc8, ms): sparse 0.037 / 0.024 / 0.019 at 4 images and 0.061 / 0.038 / 0.028 at 5-8
+// (its batch tile is a power of two); dense tiles of 32 images 0.048 / 0.028 / 0.021.
+constexpr int kAutoSparseBatch = 4;
 
 int resolve_path(const cl_layer *L, int batch, int path)
 {
@@ -1145,7 +1171,7 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
                        d_X, xt, batch, K, P.Bp, L->desc.block_w, rows);
     HIP_TRY(hipGetLastError());
     timing_begin(st);
-    if (int32_t rc = launch_mfma(D, P.nh, L->n_panels, P.splits, P.Bp, 0, P.lds, xt, part, st)) return rc;
+    if (int32_t rc = launch_mfma(D, P.nq, L->n_panels, P.splits, P.Bp, 0, P.lds, xt, part, st)) return rc;
     timing_end(st, 1);
     const int ct = reduce_col_tile(L->n_panels, batch);
     hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((batch + ct - 1) / ct))), dim3(256), 0, st,
@@ -1238,8 +1264,8 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const De
     P.xt_bytes = P.part_bytes = 0;
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
-        int nh, np, splits;
-        mfma_shape(L, P.panels_per_group, imgs * g.P * g.Q, dl.cus, nh, np, splits);
+        int nq, np, splits;
+        mfma_shape(L, P.panels_per_group, imgs * g.P * g.Q, dl.cus, nq, np, splits);
         P.xt_bytes = std::max(P.xt_bytes, (xt_rows(L) * np * sizeof(float) + 255) / 256 * 256);
         P.part_bytes = std::max(P.part_bytes, (size_t)P.panels_per_group * splits * np * L->desc.block_h * sizeof(float));
     }
@@ -1285,8 +1311,8 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     for (int b0 = 0; b0 < batch; b0 += P.imgs) {
         const int nb = std::min(P.imgs, batch - b0);
         const int ncols = nb * pq;
-        int nh, Np, splits;
-        mfma_shape(L, P.panels_per_group, ncols, dl.cus, nh, Np, splits);
+        int nq, Np, splits;
+        mfma_shape(L, P.panels_per_group, ncols, dl.cus, nq, Np, splits);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         for (int grp = 0; grp < cv->groups; ++grp) {
@@ -1295,7 +1321,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             HIP_TRY(hipGetLastError());
             const int panel0 = grp * P.panels_per_group;
             if (!timed) timing_begin(st);
-            if (int32_t rc = launch_mfma(D, nh, P.panels_per_group, splits, Np, panel0, P.lds, xt, part, st)) return rc;
+            if (int32_t rc = launch_mfma(D, nq, P.panels_per_group, splits, Np, panel0, P.lds, xt, part, st)) return rc;
             if (!timed) { timing_end(st, 1); timed = true; }
             const int ct = reduce_col_tile(P.panels_per_group, ncols);
             hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(P.panels_per_group * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
