@@ -112,6 +112,24 @@ def test_fc_forward_mfma_path(M, K, d, r, k, B):
     assert rel_err(Ys, Ym.astype(np.float64)) <= 2 * TOL
 
 
+@pytest.mark.parametrize("bh,bw", [(128, 128), (64, 48), (32, 128), (128, 20)])
+@pytest.mark.parametrize("B", [5, 33, 70, 129, 300])
+def test_fc_forward_mfma_tile_widths(bh, bw, B):
+    """The dense-tile kernel's image tiles (32 to 256 images, picked from the batch)
+    with ragged batches, and blocks narrower or lower than a tile: rows past a
+    block's width read zero rows of the transposed activations."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(1000 * bh + 10 * bw + B)
+    M, K = 300, 437
+    W = rand_pruned(rng, M, K, 0.12)
+    L, m, oW = check_decode(W, 5, 4, bh, bw)
+    X = np.maximum(rng.standard_normal((B, K)), 0).astype(np.float32)
+    bias = rng.standard_normal(M).astype(np.float32) * 0.1
+    ref = oracle.fc_forward(oW, X, bias, True, nthreads=8)
+    Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda(), relu=True, path=cl.PATH_MFMA_F32)
+    assert rel_err(Y.cpu().numpy(), ref) <= TOL
+
+
 def test_mfma_path_is_deterministic_and_refuses_big_blocks():
     torch = torch_cuda()
     rng = np.random.default_rng(5)
