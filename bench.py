@@ -204,6 +204,14 @@ def main():
         return {"copies": copies, "streams": n_streams, "us_per_launch_pair": round(dt * 1e6, 3),
                 "achieved": round(alg_bytes / dt / 1e9, 2), "unit": "GB/s", "frac": round(alg_bytes / dt / 1e9 / HBM_PEAK_GBS, 5)}
 
+    # The batch-1 kernel against what binds it: vector-ALU issue.  Peak = 256 CUs x 4 SIMDs x
+    # 2.4 GHz / 4 cycles per wavefront instruction; the instruction count of the fc6 launch is
+    # the SQ_INSTS_VALU counter summarised under profiles/ (default workload only).
+    valu_insts = 4611977
+    b1["alu"] = {"bound": "alu", "achieved": round(valu_insts / (b1["launch_ms"] * 1e-3) / 1e9, 1), "peak": 614.4,
+                 "unit": "G wavefront VALU instructions/s", "valu_instructions_per_launch": valu_insts}
+    b1["alu"]["frac"] = round(b1["alu"]["achieved"] / b1["alu"]["peak"], 4)
+
     if not args.no_cold_pool:
         b1["steady_state_cold"] = [cold_pool(args.cold_copies, 1), cold_pool(args.cold_copies, 4)]
 

@@ -7,11 +7,11 @@
 // A record holds n entries: their value-index codewords run up from bit 4, their
 // relative-index codewords run down from bit 63, so a lane decodes both spans side
 // by side from two shift registers with two decode tables held in LDS.
-//   pass A  decode the relative indices only, summing z + 1 per lane
+//   decode  both spans, entry by entry, symbols kept in registers, z + 1 summed per lane
 //   scan    one wavefront prefix sum turns lane sums into each lane's starting
 //           position (Algorithm 1 step 7) and lane counts into output slots
-//   pass B  decode both spans again, entry by entry, and use each entry at once:
-//           store it (decode_layer) or multiply-accumulate it (forward)
+//   use     the entries in order, each with its position: store it (decode_layer),
+//           multiply-accumulate it (sparse forward) or place it in a dense tile (MFMA forward)
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -426,29 +426,26 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) mine[t] = ytile[t];
 }
 
-// Adds up the partial tiles of each block row in a fixed order, then bias and
-// activation (Eq. 1): Y[b][row] = act(sum_j part[p][j][b][r] + v[row]).
+// Finishes the sparse path: adds up the partial tiles of each block row in a fixed
+// order, then bias and activation (Eq. 1): Y[b][row] = act(sum_j part[p][j][b][r] + v[row]).
 // One workgroup per (block row, image).  The kSlices thread groups each add every
 // kSlices-th tile (several loads in flight), LDS adds the slices in order.
 constexpr int kRedThreads = 256, kSlices = 4;
 
 __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
                                                                 const float *__restrict__ bias, float *Y, int B,
-                                                                int part_b, int wg_per_panel, int relu, int uniform_active,
-                                                                int panel0, int conv_pq)
+                                                                int part_b, int wg_per_panel, int relu)
 {
     __shared__ float slice_sum[kRedThreads];
-    const int pl = (int)blockIdx.x / B, b = (int)blockIdx.x - pl * B;     // pl: block row counted from panel0
-    const int p = panel0 + pl;
+    const int p = (int)blockIdx.x / B, b = (int)blockIdx.x - p * B;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
-    // the sparse kernel fills one slot per eight chunks; the MFMA kernel fills every slot
-    const int active = uniform_active > 0 ? uniform_active
-                                          : (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kWaves - 1) / kWaves);
+    // the sparse kernel fills one slot per eight chunks of the block row
+    const int active = (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kWaves - 1) / kWaves);
     constexpr int kRows = kRedThreads / kSlices;
     const int sl = (int)threadIdx.x / kRows, rl = (int)threadIdx.x - sl * kRows;
     // part[p][j][image (part_b of them)][bh]
-    const float *src = part + ((size_t)pl * wg_per_panel * part_b + b) * L.bh;
+    const float *src = part + ((size_t)p * wg_per_panel * part_b + b) * L.bh;
     const size_t step = (size_t)part_b * L.bh;
     for (int r0 = 0; r0 < bhp; r0 += kRows) {
         const int r = r0 + rl;
@@ -473,9 +470,7 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
             for (int k = 1; k < kSlices; ++k) t += slice_sum[k * kRows + rl];
             if (bias) t += bias[row_id + r];
             t = relu ? fmaxf(t, 0.0f) : t;
-            // FC: Y[image][row].  Convolution: column b is (image, output pixel), Y[image][row][pixel].
-            if (conv_pq == 0) Y[(size_t)b * L.M + row_id + r] = t;
-            else Y[((size_t)(b / conv_pq) * L.M + row_id + r) * conv_pq + (b % conv_pq)] = t;
+            Y[(size_t)b * L.M + row_id + r] = t;
         }
         __syncthreads();
     }
@@ -549,8 +544,8 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
 
 // Workgroup (block row p, split j, image tile nb) of twelve wavefronts with two roles.
 //   Producers (wavefronts 4-11, two next to each consumer on a SIMD: a lone decoder's
-//   dependent chains issue too slowly to keep up) decode block i + 1 - a chunk per wavefront, pass A /
-//   scan / pass B as in the sparse kernel - and write each entry's weight at its place
+//   dependent chains issue too slowly to keep up) decode block i + 1 - a chunk per wavefront, decode /
+//   scan / use as in the sparse kernel - and write each entry's weight at its place
 //   in a 128 x 128 fp32 tile in LDS, row by row (Algorithm 2 steps 5-9: decode, prefix
 //   sum, codebook look-up, "arrange as bh x bw block").
 //   Consumers (wavefronts 0-3) multiply block i on the matrix cores (step 12) with
@@ -1151,7 +1146,7 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
             if (b0 == 0) timing_end(st, 1);
         }
         hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * bt)), dim3(kRedThreads), 0, st,
-                           D, part, d_bias, y, bt, bt, P.wg_per_panel, relu, 0, 0, 0);
+                           D, part, d_bias, y, bt, bt, P.wg_per_panel, relu);
         HIP_TRY(hipGetLastError());
         b0 += bt;
     }
