@@ -56,6 +56,8 @@ def lib():
         _lib.orc_reconstruct.argtypes = [p, p, p, p, i32, i32, i32, i32, i32, i32, p, p]
         _lib.orc_fc_forward.argtypes = [p, p, p, i32, i32, i32, i32, i32, p]
         _lib.orc_conv_forward.argtypes = [p, p, p] + [i32] * 12 + [p]
+        _lib.orc_maxpool_forward.argtypes = [p] + [i32] * 6 + [p]
+        _lib.orc_lrn_forward.argtypes = [p] + [i32] * 5 + [C.c_double] * 3 + [p]
     return _lib
 
 
@@ -202,6 +204,28 @@ def conv_forward(W, X, geom, bias=None, relu=False, nthreads=1) -> np.ndarray:
     Y = np.zeros((B, g["OC"], P, Q), np.float64)
     _chk(lib().orc_conv_forward(_ptr(W), _ptr(X), _ptr(b), B, g["C"], g["H"], g["W"], g["OC"], g["R"], g["S"],
                                 g["stride"], g["pad"], g["groups"], int(relu), nthreads, _ptr(Y)), "conv_forward")
+    return Y
+
+
+def maxpool_forward(X, size: int, stride: int) -> np.ndarray:
+    """X: B x C x H x W fp32 -> B x C x P x Q fp64, P = (H - size) // stride + 1
+    (the pooling layers of the AlexNet runs, Table IV)."""
+    X = _c(X, np.float32)
+    B, Cc, H, W = X.shape
+    P, Q = (H - size) // stride + 1, (W - size) // stride + 1
+    Y = np.zeros((B, Cc, P, Q), np.float64)
+    _chk(lib().orc_maxpool_forward(_ptr(X), B, Cc, H, W, size, stride, _ptr(Y)), "maxpool_forward")
+    return Y
+
+
+def lrn_forward(X, n: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float = 1.0) -> np.ndarray:
+    """Across-channel local response normalisation (the norm layers of Table IV):
+    y[c] = x[c] / (k + alpha / n * sum of x[c']^2 over the n channels around c)^beta."""
+    X = _c(X, np.float32)
+    B, Cc, H, W = X.shape
+    Y = np.zeros(X.shape, np.float64)
+    _chk(lib().orc_lrn_forward(_ptr(X), B, Cc, H, W, n, float(alpha), float(beta), float(k), _ptr(Y)),
+         "lrn_forward")
     return Y
 
 

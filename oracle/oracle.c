@@ -474,3 +474,51 @@ int orc_conv_forward(const float *W, const float *X, const float *bias,
     }
     return ORC_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* The fixed-function layers between the convolutions of the paper's AlexNet  */
+/* runs (Table IV lists norm1/2 and pool1/2/5; Sec. II: "the RELU/POOL layers */
+/* implement fixed functions").  The paper does not define them; READING: the */
+/* layers of the AlexNet it evaluates - max pooling over size x size windows  */
+/* with a stride, no padding, windows fully inside the image; and local        */
+/* response normalisation across channels,                                     */
+/*   y[c] = x[c] / (k + alpha / n * sum_{c' in window(c)} x[c']^2)^beta,       */
+/* the window being the n channels centred on c and clipped to [0, C).         */
+/* X: B x C x H x W fp32 (NCHW); Y fp64.                                       */
+/* ------------------------------------------------------------------------- */
+int orc_maxpool_forward(const float *X, int B, int C, int H, int Wd, int size, int stride, double *Y)
+{
+    if (!X || !Y || B < 0 || C < 1 || H < size || Wd < size || size < 1 || stride < 1) return ORC_EINVAL;
+    int P = (H - size) / stride + 1, Q = (Wd - size) / stride + 1;
+    for (int64_t bc = 0; bc < (int64_t)B * C; ++bc)
+        for (int p = 0; p < P; ++p)
+            for (int q = 0; q < Q; ++q) {
+                double m = -INFINITY;
+                for (int r = 0; r < size; ++r)
+                    for (int s = 0; s < size; ++s) {
+                        double v = (double)X[(bc * H + (p * stride + r)) * Wd + (q * stride + s)];
+                        if (v > m) m = v;
+                    }
+                Y[(bc * P + p) * Q + q] = m;
+            }
+    return ORC_OK;
+}
+
+int orc_lrn_forward(const float *X, int B, int C, int H, int Wd, int n, double alpha, double beta, double k, double *Y)
+{
+    if (!X || !Y || B < 0 || C < 1 || H < 1 || Wd < 1 || n < 1 || !(n & 1)) return ORC_EINVAL;
+    int64_t hw = (int64_t)H * Wd;
+    for (int b = 0; b < B; ++b)
+        for (int c = 0; c < C; ++c)
+            for (int64_t i = 0; i < hw; ++i) {
+                double ss = 0.0;
+                for (int d = -(n / 2); d <= n / 2; ++d) {
+                    int cc = c + d;
+                    if (cc < 0 || cc >= C) continue;
+                    double v = (double)X[((int64_t)b * C + cc) * hw + i];
+                    ss += v * v;
+                }
+                Y[((int64_t)b * C + c) * hw + i] = (double)X[((int64_t)b * C + c) * hw + i] / pow(k + alpha / n * ss, beta);
+            }
+    return ORC_OK;
+}

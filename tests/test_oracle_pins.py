@@ -515,3 +515,49 @@ def test_dp_beats_fixed_batch_when_early_layers_are_memory_hungry():
     fb, B = odp.fixed_batch_baseline(time_ms, bs, inb, outb, ws, tot, None)
     got, plan = odp.plan_batches(time_ms, bs, inb, outb, ws, tot, 100_000, None)
     assert B == 4 and plan[0] <= 4 and plan[1] > 4 and got < fb
+
+
+# --------------------------------------------------------------------------- #
+# the fixed-function layers of the whole-network runs (Table IV: norm, pool)
+# --------------------------------------------------------------------------- #
+def test_maxpool_against_window_enumeration_and_closed_forms():
+    rng = np.random.default_rng(41)
+    X = rng.standard_normal((2, 5, 11, 9)).astype(np.float32)
+    for size, stride in [(3, 2), (2, 2), (1, 1), (3, 1), (11 if False else 5, 3)]:
+        Y = oracle.maxpool_forward(X, size, stride)
+        P, Q = (11 - size) // stride + 1, (9 - size) // stride + 1
+        assert Y.shape == (2, 5, P, Q)
+        for p in range(P):
+            for q in range(Q):
+                win = X[:, :, p * stride:p * stride + size, q * stride:q * stride + size]
+                assert np.array_equal(Y[:, :, p, q], win.reshape(2, 5, -1).max(-1).astype(np.float64))
+    assert np.array_equal(oracle.maxpool_forward(X, 1, 1), X.astype(np.float64))        # 1 x 1 windows: identity
+    ramp = np.arange(7 * 7, dtype=np.float32).reshape(1, 1, 7, 7)                       # increasing along both axes:
+    Y = oracle.maxpool_forward(ramp, 3, 2)                                              # the maximum is the window's last corner
+    assert np.array_equal(Y[0, 0], ramp[0, 0, 2::2, 2::2].astype(np.float64))
+    assert np.array_equal(oracle.maxpool_forward(-np.ones((1, 2, 4, 4), np.float32), 2, 2), -np.ones((1, 2, 2, 2)))   # negatives survive
+
+
+def test_lrn_closed_forms():
+    rng = np.random.default_rng(42)
+    X = rng.standard_normal((2, 9, 3, 4)).astype(np.float32)
+    x64 = X.astype(np.float64)
+    # a window of one channel: y = x / (k + alpha x^2)^beta
+    assert np.allclose(oracle.lrn_forward(X, 1, 0.3, 0.75, 2.0), x64 / (2.0 + 0.3 * x64 ** 2) ** 0.75, rtol=1e-14, atol=0)
+    # alpha = 0: y = x / k^beta
+    assert np.allclose(oracle.lrn_forward(X, 5, 0.0, 0.75, 2.0), x64 / 2.0 ** 0.75, rtol=1e-14, atol=0)
+    # constant input: interior channels see n terms, the outermost ones (n + 1) / 2
+    c = np.full((1, 9, 2, 2), 3.0, np.float32)
+    Y = oracle.lrn_forward(c, 5, 0.5, 0.75, 1.0)
+    assert np.allclose(Y[0, 4], 3.0 / (1.0 + 0.5 / 5 * 5 * 9.0) ** 0.75, rtol=1e-14)
+    assert np.allclose(Y[0, 0], 3.0 / (1.0 + 0.5 / 5 * 3 * 9.0) ** 0.75, rtol=1e-14)
+    assert np.allclose(Y[0, 1], 3.0 / (1.0 + 0.5 / 5 * 4 * 9.0) ** 0.75, rtol=1e-14)
+    # channel windows by enumeration, n = 3 and 5
+    for n in (3, 5):
+        Y = oracle.lrn_forward(X, n, 1e-1, 0.75, 1.0)
+        for ch in range(9):
+            lo, hi = max(0, ch - n // 2), min(9, ch + n // 2 + 1)
+            ss = (x64[:, lo:hi] ** 2).sum(1)
+            assert np.allclose(Y[:, ch], x64[:, ch] / (1.0 + 0.1 / n * ss) ** 0.75, rtol=1e-13, atol=0)
+    with pytest.raises(oracle.OracleError):
+        oracle.lrn_forward(X, 4)                                                         # even windows have no centre
