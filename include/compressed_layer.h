@@ -261,6 +261,24 @@ int32_t cl_plan_batches(int32_t n_layers, const int32_t *batch_set, int32_t n_ba
                         int64_t tot_bytes, int64_t mem_step_bytes, double latency_cap_ms,
                         int32_t *out_batch_per_layer, double *out_ms_per_image);
 
+/* The fixed-function layers between the convolutions of a whole network (the norm
+ * and pool rows of Table IV; Sec. II: pooling layers "implement fixed functions"),
+ * so that a network can run end to end on the device with per-layer batch sizes.
+ * d_X: batch x C x H x W fp32 (NCHW), device.  Asynchronous on `stream`.
+ *
+ * cl_maxpool_forward: maximum over size x size windows at the given stride, no
+ *   padding, windows fully inside the image; d_Y: batch x C x P x Q with
+ *   P = (H - size) / stride + 1, Q likewise.
+ * cl_lrn_forward: local response normalisation across channels,
+ *   y[c] = x[c] / (k + alpha / n * sum of x[c']^2 over the n channels centred on c,
+ *   clipped to [0, C))^beta; n odd; d_Y has the shape of d_X.
+ * Errors: CL_EINVAL (null pointers, non-positive sizes, window larger than the
+ * image, even n) - nothing is launched then; CL_EHIP. */
+int32_t cl_maxpool_forward(const float *d_X, float *d_Y, int32_t batch, int32_t C, int32_t H, int32_t W,
+                           int32_t size, int32_t stride, void *stream);
+int32_t cl_lrn_forward(const float *d_X, float *d_Y, int32_t batch, int32_t C, int32_t H, int32_t W,
+                       int32_t n, float alpha, float beta, float k, void *stream);
+
 /* Measurement hook for benchmarks (not part of the paper's method).  While
  * enabled, every forward call brackets the first launch of its main kernel (the
  * first batch tile; not the small reduction kernel) with a pair of HIP events on

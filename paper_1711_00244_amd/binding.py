@@ -22,7 +22,8 @@ EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
     "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_conv_workspace_bytes",
-    "cl_compressed_conv_forward", "cl_plan_batches", "cl_set_kernel_timing", "cl_last_kernel_ms",
+    "cl_compressed_conv_forward", "cl_plan_batches", "cl_maxpool_forward", "cl_lrn_forward",
+    "cl_set_kernel_timing", "cl_last_kernel_ms",
 ]
 
 
@@ -89,6 +90,8 @@ def lib():
     L.cl_conv_workspace_bytes.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
     L.cl_compressed_conv_forward.argtypes = [p, C.POINTER(ConvDesc), p, p, p, i32, i32, i32, p, sz, p]
     L.cl_plan_batches.argtypes = [i32, p, i32, p, p, p, p, i64, i64, C.c_double, p, C.POINTER(C.c_double)]
+    L.cl_maxpool_forward.argtypes = [p, p] + [i32] * 6 + [p]
+    L.cl_lrn_forward.argtypes = [p, p] + [i32] * 5 + [C.c_float] * 3 + [p]
     L.cl_set_kernel_timing.argtypes = [i32]
     L.cl_last_kernel_ms.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
@@ -275,6 +278,29 @@ def compressed_conv_forward(layer: Layer, conv: dict, X, bias=None, relu=False, 
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().cl_compressed_conv_forward(layer.handle, C.byref(cd), _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B,
                                             int(relu), path, _dev_ptr(workspace), wbytes, _stream()))
+    return Y
+
+
+def maxpool_forward(X, size: int, stride: int, out=None):
+    """X: (B, C, H, W) fp32 CUDA tensor -> (B, C, P, Q)."""
+    import torch
+    if X.dtype != torch.float32 or X.dim() != 4 or not X.is_contiguous():
+        raise ValueError("X must be a contiguous (B, C, H, W) float32 tensor")
+    B, Cc, H, W = X.shape
+    P, Q = (H - size) // stride + 1, (W - size) // stride + 1
+    Y = out if out is not None else torch.empty((B, Cc, max(P, 0), max(Q, 0)), dtype=torch.float32, device=X.device)
+    _check(lib().cl_maxpool_forward(_dev_ptr(X), _dev_ptr(Y), B, Cc, H, W, size, stride, _stream()))
+    return Y
+
+
+def lrn_forward(X, n: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float = 1.0, out=None):
+    """X: (B, C, H, W) fp32 CUDA tensor -> same shape."""
+    import torch
+    if X.dtype != torch.float32 or X.dim() != 4 or not X.is_contiguous():
+        raise ValueError("X must be a contiguous (B, C, H, W) float32 tensor")
+    B, Cc, H, W = X.shape
+    Y = out if out is not None else torch.empty_like(X)
+    _check(lib().cl_lrn_forward(_dev_ptr(X), _dev_ptr(Y), B, Cc, H, W, n, float(alpha), float(beta), float(k), _stream()))
     return Y
 
 

@@ -1198,6 +1198,74 @@ extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X,
     return rc;
 }
 
+// ------------------------------------------------------------------------- //
+// fixed-function layers of a whole network (Table IV: pool, norm)
+// ------------------------------------------------------------------------- //
+namespace cl {
+
+__global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ X, float *Y, int64_t n_out, int H, int W,
+                                                      int P, int Q, int size, int stride)
+{
+    for (int64_t o = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; o < n_out; o += (int64_t)gridDim.x * blockDim.x) {
+        const int q = (int)(o % Q), p = (int)((o / Q) % P);
+        const int64_t bc = o / ((int64_t)P * Q);
+        const float *x = X + (bc * H + (int64_t)p * stride) * W + (int64_t)q * stride;
+        float m = x[0];
+        for (int r = 0; r < size; ++r)
+            for (int s = 0; s < size; ++s) m = fmaxf(m, x[(int64_t)r * W + s]);
+        Y[o] = m;
+    }
+}
+
+// One thread per (image, pixel) walks the channels with a sliding sum of squares.
+__global__ __launch_bounds__(256) void lrn_kernel(const float *__restrict__ X, float *Y, int B, int C, int64_t hw, int n,
+                                                  float alpha_over_n, float beta, float k)
+{
+    const int half = n / 2;
+    for (int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; t < (int64_t)B * hw; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = t / hw, i = t - b * hw;
+        const float *x = X + b * C * hw + i;
+        float *y = Y + b * C * hw + i;
+        for (int c = 0; c < C; ++c) {
+            float ss = 0.0f;
+            for (int cc = max(0, c - half); cc <= min(C - 1, c + half); ++cc) {
+                const float v = x[(int64_t)cc * hw];
+                ss += v * v;
+            }
+            y[(int64_t)c * hw] = x[(int64_t)c * hw] * powf(k + alpha_over_n * ss, -beta);
+        }
+    }
+}
+
+}  // namespace cl
+
+extern "C" int32_t cl_maxpool_forward(const float *d_X, float *d_Y, int32_t batch, int32_t C, int32_t H, int32_t W,
+                                      int32_t size, int32_t stride, void *stream)
+{
+    if (!d_X || !d_Y) return fail(CL_EINVAL, "null pointer");
+    if (batch < 1 || C < 1 || size < 1 || stride < 1 || H < size || W < size) return fail(CL_EINVAL, "bad pooling geometry");
+    const int P = (H - size) / stride + 1, Q = (W - size) / stride + 1;
+    const int64_t n_out = (int64_t)batch * C * P * Q;
+    hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)std::min<int64_t>((n_out + 255) / 256, 65536)), dim3(256), 0, (hipStream_t)stream,
+                       d_X, d_Y, n_out, H, W, P, Q, size, stride);
+    HIP_TRY(hipGetLastError());
+    clear_error();
+    return CL_OK;
+}
+
+extern "C" int32_t cl_lrn_forward(const float *d_X, float *d_Y, int32_t batch, int32_t C, int32_t H, int32_t W,
+                                  int32_t n, float alpha, float beta, float k, void *stream)
+{
+    if (!d_X || !d_Y) return fail(CL_EINVAL, "null pointer");
+    if (batch < 1 || C < 1 || H < 1 || W < 1 || n < 1 || !(n & 1)) return fail(CL_EINVAL, "bad normalisation geometry");
+    const int64_t hw = (int64_t)H * W, threads = (int64_t)batch * hw;
+    hipLaunchKernelGGL(lrn_kernel, dim3((unsigned)std::min<int64_t>((threads + 255) / 256, 65536)), dim3(256), 0, (hipStream_t)stream,
+                       d_X, d_Y, batch, C, hw, n, alpha / (float)n, beta, k);
+    HIP_TRY(hipGetLastError());
+    clear_error();
+    return CL_OK;
+}
+
 extern "C" int32_t cl_set_kernel_timing(int32_t enable)
 {
     if (enable && !g_timing.a) {

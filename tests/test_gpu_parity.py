@@ -318,3 +318,32 @@ def test_forward_rejects_bad_arguments():
     assert rc == binding.CL_EINVAL
     rc = binding.lib().cl_compressed_fc_forward(L.handle, C.c_void_p(X.data_ptr()), None, C.c_void_p(X.data_ptr()), 0, 0, 0, None, 0, None)
     assert rc == binding.CL_EINVAL
+
+
+@pytest.mark.parametrize("shape,size,stride", [((2, 5, 11, 9), 3, 2), ((1, 96, 55, 55), 3, 2), ((3, 7, 8, 8), 2, 2),
+                                               ((1, 1, 3, 3), 3, 1), ((2, 3, 6, 7), 1, 1)])
+def test_maxpool_forward(shape, size, stride):
+    """Max pooling (the pool rows of Table IV) against the oracle: exact, a maximum
+    of fp32 values has no rounding."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(sum(shape) + size)
+    X = rng.standard_normal(shape).astype(np.float32)
+    Y = cl.maxpool_forward(torch.from_numpy(X).cuda(), size, stride)
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), oracle.maxpool_forward(X, size, stride))
+    with pytest.raises(cl.CLError):
+        cl.maxpool_forward(torch.from_numpy(X).cuda(), shape[2] + 1, 1)
+
+
+@pytest.mark.parametrize("shape,n", [((2, 9, 3, 4), 5), ((1, 96, 55, 55), 5), ((2, 256, 27, 27), 5), ((3, 4, 5, 5), 3),
+                                     ((1, 2, 2, 2), 1)])
+def test_lrn_forward(shape, n):
+    """Across-channel normalisation (the norm rows of Table IV) against the oracle's
+    fp64, with AlexNet's constants and with ones that make the denominator matter."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(sum(shape) + n)
+    X = (rng.standard_normal(shape) * 3).astype(np.float32)
+    for alpha, beta, k in [(1e-4, 0.75, 1.0), (0.5, 0.75, 2.0)]:
+        Y = cl.lrn_forward(torch.from_numpy(X).cuda(), n, alpha, beta, k)
+        assert rel_err(Y.cpu().numpy(), oracle.lrn_forward(X, n, alpha, beta, k)) <= TOL
+    with pytest.raises(cl.CLError):
+        cl.lrn_forward(torch.from_numpy(X).cuda(), 4)
