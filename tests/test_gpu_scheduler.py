@@ -77,3 +77,40 @@ def test_plan_and_poisson_stream(vgg_stack):
     Y = torch.stack(outs, 0).cpu().numpy()
     ref = oracle_stack(dense, X)
     assert np.abs(Y - ref).max() / np.abs(ref).max() <= 3e-5
+
+
+def test_alexnet_whole_network_with_per_layer_batches():
+    """The thirteen layers of Table IV end to end on the device with per-layer batch
+    sizes (small early, larger late, as in Table V), against the oracle's chain of
+    direct convolutions, normalisations, poolings and dense products in fp64 on its
+    own decode of the same compressed layers.  Eight layers with arithmetic compound
+    their 1e-5 each, so the logits are held to 2e-4 of their largest magnitude."""
+    import torch
+    from paper_1711_00244_amd import network
+    net = network.alexnet()
+    K = 4
+    rng = np.random.default_rng(77)
+    X = rng.random((K, 3, 227, 227), dtype=np.float32)
+    Y = net.run(torch.from_numpy(X).cuda(), [1, 1, 1, 2, 2, 2, 2, 2, 2, 4, 4, 4, 4]).cpu().numpy()
+    Y1 = net.run(torch.from_numpy(X).cuda(), None).cpu().numpy()
+    a = X
+    for op in net.layers:
+        if isinstance(op, network.ConvOp) or isinstance(op, network.FcOp):
+            cfg, names = (4, [s.name for s in wl.CONFIGS[4]["layers"]]) if isinstance(op, network.ConvOp) else (3, ["fc6", "fc7", "fc8"])
+            spec, W = wl.layer_weights(cfg, names.index(op.name))
+            m = oracle.compress_layer(W, spec.r, spec.k, op.block[0], op.block[1])
+            oW = oracle.dense_weights(m)
+            if isinstance(op, network.ConvOp):
+                a = oracle.conv_forward(oW, a.astype(np.float32), op.geom, relu=True, nthreads=8)
+            else:
+                a = oracle.fc_forward(oW, a.reshape(K, -1).astype(np.float32), relu=op.relu, nthreads=8)
+        elif isinstance(op, network.LrnOp):
+            a = oracle.lrn_forward(a.astype(np.float32), *op.args)
+        else:
+            a = oracle.maxpool_forward(a.astype(np.float32), op.size, op.stride)
+    scale = np.abs(a).max()
+    assert np.abs(Y - a).max() <= 2e-4 * scale
+    assert np.abs(Y1 - a).max() <= 2e-4 * scale
+    for op in net.layers:
+        if hasattr(op, "layer"):
+            op.layer.free()
