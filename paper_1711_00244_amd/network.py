@@ -158,13 +158,14 @@ class NetworkRunner(StackRunner):
         return best
 
 
-def alexnet(block=(128, 128)):
+def alexnet(block=(128, 128), density=None):
     """The AlexNet of Table IV with synthetic compressed layers: configs[3]'s
-    convolutions and configs[2]'s FC stack."""
+    convolutions and configs[2]'s FC stack.  density overrides every layer's fraction
+    of non-zeros (the uniformly pruned models of Sec. VI-B: 0.3, 0.2, 0.1)."""
     ops = []
 
     def conv(li):
-        spec, W = wl.layer_weights(4, li)
+        spec, W = wl.layer_weights(4, li, density=density)
         g = spec.conv
         bh = block[0]
         if g["groups"] > 1 and (g["OC"] // g["groups"]) % bh:
@@ -172,7 +173,7 @@ def alexnet(block=(128, 128)):
         return ConvOp(spec.name, cl.compress_layer(W, spec.r, spec.k, bh, block[1], upload=True), g, (bh, block[1]))
 
     def fc(li, relu):
-        spec, W = wl.layer_weights(3, li)
+        spec, W = wl.layer_weights(3, li, density=density)
         return FcOp(spec.name, cl.compress_layer(W, spec.r, spec.k, block[0], block[1], upload=True), relu, block)
 
     ops += [conv(0), LrnOp("norm1"), PoolOp("pool1"), conv(1), LrnOp("norm2"), PoolOp("pool2"),
@@ -187,8 +188,9 @@ def main(argv=None):
     ap.add_argument("--budgets", type=float, nargs="+", default=[1.5, 2.0, 2.5, 8.0, 32.0],
                     help="memory besides the model, in multiples of the compressed model size")
     ap.add_argument("--check", action="store_true", help="run the plan for K images and compare with one-batch execution")
+    ap.add_argument("--density", type=float, default=None, help="uniform fraction of non-zeros for all layers")
     args = ap.parse_args(argv)
-    net = alexnet()
+    net = alexnet(density=args.density)
     model_bytes = sum(op.layer.stats()["model_bytes"] for op in net.layers if hasattr(op, "layer"))
     for K in args.images:
         batch_set = [b for b in range(1, K + 1) if K % b == 0]
@@ -197,7 +199,7 @@ def main(argv=None):
             tot = int(mult * model_bytes)
             plan = net.plan(batch_set, tot, time_ms=time_ms)
             fixed = net.fixed_batch(batch_set, tot, time_ms)
-            rec = dict(images=K, budget_x_model=mult, budget_bytes=tot, model_bytes=model_bytes,
+            rec = dict(images=K, density=args.density, budget_x_model=mult, budget_bytes=tot, model_bytes=model_bytes,
                        layers=[op.name for op in net.layers])
             if plan is None or fixed is None:
                 rec["infeasible"] = True
