@@ -6,6 +6,7 @@ Prints one JSON line per (layer, block, density, path, batch).
 
     python -m paper_1711_00244_amd.measure --config 4          # AlexNet conv layers
     python -m paper_1711_00244_amd.measure --config 2          # AlexNet fc6, batch 1 and 8
+    python -m paper_1711_00244_amd.measure --config 6          # VGG-16 convolutions
     python -m paper_1711_00244_amd.measure --config 2 --batches 16 256 \
         --blocks 16x16 32x32 64x64 128x128 256x256 512x512 1024x1024 4096x9216
     python -m paper_1711_00244_amd.measure --config 2 --batches 1 16 64 256 \
@@ -39,7 +40,7 @@ def time_ms(fn, reps, warmup):
 def main(argv=None):
     import torch
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, required=True, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--reps", type=int, default=30)
     ap.add_argument("--block", type=int, nargs=2, default=[128, 128])
     ap.add_argument("--blocks", nargs="+", default=None, help="block sizes to sweep, as HxW")

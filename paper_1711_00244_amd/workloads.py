@@ -90,6 +90,22 @@ CONFIGS: dict[int, dict] = {
 }
 
 
+def _vgg16_conv_layers():
+    """The thirteen 3 x 3 convolutions of VGG-16 on 224 x 224 inputs with the
+    densities of Table I(b) (100 % minus the pruning percentage), 8-bit codebooks
+    and the 5-bit relative index the paper uses for VGG-16 (Sec. VI)."""
+    plan = [("conv1_1", 3, 224, 64, 0.58), ("conv1_2", 64, 224, 64, 0.22), ("conv2_1", 64, 112, 128, 0.34),
+            ("conv2_2", 128, 112, 128, 0.36), ("conv3_1", 128, 56, 256, 0.53), ("conv3_2", 256, 56, 256, 0.24),
+            ("conv3_3", 256, 56, 256, 0.42), ("conv4_1", 256, 28, 512, 0.32), ("conv4_2", 512, 28, 512, 0.27),
+            ("conv4_3", 512, 28, 512, 0.34), ("conv5_1", 512, 14, 512, 0.35), ("conv5_2", 512, 14, 512, 0.29),
+            ("conv5_3", 512, 14, 512, 0.36)]
+    return [LayerSpec(n, oc, c * 9, d, 0.01, 8, 5, _conv(c, hw, hw, 3, 3, 1, 1, 1, oc)) for n, c, hw, oc, d in plan]
+
+
+# beyond the five benchmark configurations: the VGG-16 convolutions (a "next" row)
+CONFIGS[6] = dict(layers=_vgg16_conv_layers(), batches=[1, 8], act="uniform")
+
+
 def layer_weights(cfg: int, layer_index: int, scale: float = 1.0,
                   density: float | None = None) -> tuple[LayerSpec, np.ndarray]:
     """Weights of one layer of a configuration.  scale < 1 shrinks both

@@ -212,6 +212,24 @@ def test_config4_alexnet_conv_layers(li):
     assert rel_err(Y.cpu().numpy(), ref) <= TOL
 
 
+@pytest.mark.parametrize("li", range(13))
+def test_vgg16_conv_layers_full_size(li):
+    """The VGG-16 convolutions at full size (224 x 224 input, densities of Table I(b),
+    8-bit codebook, 5-bit relative index), one image: decode bit-exact, outputs of
+    sampled filters against the oracle's direct convolution with those filters."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(6, li)
+    g = spec.conv
+    L, m, oW = check_decode(W, spec.r, spec.k, 128, 128)
+    X = wl.activations(6, 1, layer_index=li)
+    Y = cl.compressed_conv_forward(L, g, torch.from_numpy(X).cuda(), relu=True).cpu().numpy()
+    rows = np.sort(np.random.default_rng(li).choice(g["OC"], size=4, replace=False))
+    sub = dict(g, OC=len(rows))
+    ref = oracle.conv_forward(np.ascontiguousarray(oW[rows]), X, sub, relu=True, nthreads=8)
+    assert rel_err(Y[:, rows], ref) <= TOL
+    L.free()
+
+
 def test_conv_rejects_mismatched_layer():
     torch = torch_cuda()
     L = cl.compress_layer(np.ones((6, 75), np.float32), 5, 4, 6, 75, upload=True)
