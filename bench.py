@@ -33,7 +33,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=256, help="headline batch size")
-    ap.add_argument("--path", choices=["auto", "sparse", "mfma"], default="auto")
+    ap.add_argument("--path", choices=["auto", "sparse", "mfma", "bf16"], default="auto")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep 1,4,16,64,256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cold-pool", action="store_true", help="skip the batch-1 steady-state run over separately uploaded copies")
@@ -61,7 +61,7 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    path = {"auto": cl.PATH_AUTO, "sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32}[args.path]
+    path = {"auto": cl.PATH_AUTO, "sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32, "bf16": cl.PATH_MFMA_BF16}[args.path]
 
     # ---- the workload: configs[2], synthetic AlexNet fc6/fc7/fc8 -------------
     cfg = 3

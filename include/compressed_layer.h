@@ -56,8 +56,12 @@ enum {
 enum {
     CL_PATH_AUTO = 0,     /* library picks from batch size and layer density        */
     CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
-    CL_PATH_MFMA_F32 = 2  /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
+    CL_PATH_MFMA_F32 = 2, /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
                           /*   of at most 128 x 128, else CL_EUNSUPPORTED            */
+    CL_PATH_MFMA_BF16 = 3 /* the same on the bf16 matrix cores: weights and activations */
+                          /*   split into two bf16 terms each, three products per    */
+                          /*   fp32 product, fp32 accumulation; error below 3 * 2^-18 */
+                          /*   of sum |w x| per output; never picked by CL_PATH_AUTO  */
 };
 
 /* How a weight matrix is compressed.

@@ -15,7 +15,7 @@ import numpy as np
 from . import build as _build
 
 CL_OK, CL_EINVAL, CL_ENOMEM, CL_ECORRUPT, CL_EUNSUPPORTED, CL_EHIP = 0, -1, -2, -3, -4, -5
-PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32 = 0, 1, 2
+PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32, PATH_MFMA_BF16 = 0, 1, 2, 3
 CHUNK_BITS, RECORD_BITS, RECORDS_PER_CHUNK, MAX_RECORD_ENTRIES, MAX_CODE_LEN = 4096, 64, 64, 15, 12
 
 EXPORTS = [

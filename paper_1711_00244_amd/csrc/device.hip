@@ -561,6 +561,92 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
 // done with it, so a tile is always clean when the producers get it back.
 constexpr int kWStride = kTile + 4;      // floats per weight row of a tile (16-byte rows, 4-bank skew)
 constexpr int kWTileBytes = kTile * kWStride * 4;
+// The decoder wavefronts' side of the dense-tile kernels: decode the blocks blk_lo ..
+// blk_hi - 1 of block row pb0 / nbw into the two alternating 128 x kWStride tiles of
+// 32-bit words, one block ahead of the multipliers, meeting them at one barrier per
+// block.  weight_of(v) is the word stored for value index v (the codebook entry, or
+// its split into two bf16 halves).  With CLEAR_BARRIER the multipliers clear a used tile
+// between two barriers (their rows are shared), else right after their last read of
+// their own rows.  Called by wavefronts 4 .. 4 + DEC - 1.
+template <int DEC, bool CLEAR_BARRIER, class WeightOf>
+__device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, float *tiles, int blk_lo, int blk_hi, uint32_t pb0,
+                                             int wave, int lane, WeightOf weight_of)
+{
+    // The chunks of this split's blocks are consecutive, [c_lo, c_hi); decoder
+    // d = wave - 4 takes c_lo + d, c_lo + d + DEC, ... and finds a block's
+    // end at the first chunk head that names a later block.  Block -> chunk head ->
+    // record is a chain of dependent loads, so the stream runs ahead of the decoding:
+    // the heads of the next three chunks and the records of the next two are in
+    // registers or in flight.  Every load is unconditional (a position past the end
+    // re-reads the last chunk and is marked invalid; chunk heads sit in a zero-padded
+    // section, so the head after the last one is readable even for a layer without
+    // chunks) and nothing touches a loaded value before it is decoded: the loads are
+    // not waited for where they are issued.  Heads are read through an address the
+    // compiler cannot prove uniform, or they would be moved to scalar registers right
+    // behind the load.
+    struct Head {
+        uint32_t rec_off, rec_end, blk, pos0;
+        bool valid;
+    };
+    uint32_t lane_zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+    const uint32_t c_hi = blk_lo < blk_hi ? L.block_chunk[pb0 + (uint32_t)blk_hi] : 0u;
+    uint32_t c_tail = blk_lo < blk_hi ? L.block_chunk[pb0 + (uint32_t)blk_lo] + (uint32_t)(wave - 4) : 0u;   // next head to load
+    auto next_head = [&]() {
+        Head h;
+        h.valid = c_tail < c_hi;
+        const cl_chunk_meta *mp = L.meta + (h.valid ? c_tail : (c_hi ? c_hi - 1u : 0u)) + lane_zero;
+        h.rec_off = mp[0].rec_off;
+        h.rec_end = mp[1].rec_off;
+        h.blk = mp[0].blk;
+        h.pos0 = mp[0].pos0;
+        c_tail += (uint32_t)DEC;
+        return h;
+    };
+    auto word_of = [&](const Head &h) {
+        const uint32_t last = h.rec_end - h.rec_off - 1u;       // a chunk has at least one record
+        return L.records[h.rec_off + min((uint32_t)lane, last)];
+    };
+    Head h0 = next_head(), h1 = next_head(), h2 = next_head();
+    uint64_t w0 = word_of(h0), w1 = word_of(h1);
+    // decode block bi into a weight tile (clean on entry): Algorithm 2 steps 5-9
+    auto produce = [&](int bi, float *tile) {
+        const uint32_t b = pb0 + (uint32_t)bi;
+        const BlockGeom g = block_geom(L, b);
+        while (h0.valid && (uint32_t)__builtin_amdgcn_readfirstlane((int)h0.blk) == b) {
+            LaneRecord rec;
+            rec.n = (uint32_t)lane < h0.rec_end - h0.rec_off ? (uint32_t)w0 & 15u : 0u;
+            rec.vbuf = w0 >> kCountBits;
+            rec.ibuf = __builtin_bitreverse64(w0);
+            const uint32_t pos0 = h0.pos0;
+            // move the stream on; the record load issued here uses a head that arrived
+            // a chunk ago
+            h0 = h1; w0 = w1;
+            h1 = h2; w1 = word_of(h1);
+            h2 = next_head();
+            const Symbols y = decode_record(rec, s.T);
+            const LaneStart st = lane_starts(y, pos0);
+            for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                uint32_t r, cc;
+                split_pos(pos, g, r, cc);
+                if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = weight_of(v);
+            });
+        }
+    };
+    // the decoders go first at the issue arbiter: a multiplying wavefront needs one
+    // issue slot per 64-cycle multiply, the decoders next to it on the SIMD can have
+    // the rest
+    __builtin_amdgcn_s_setprio(3);
+    __syncthreads();                                    // tables stored, tiles clean
+    if (blk_lo < blk_hi) produce(blk_lo, tiles);
+    __syncthreads();
+    for (int bi = blk_lo; bi < blk_hi; ++bi) {
+        if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
+        __syncthreads();
+        if (CLEAR_BARRIER) __syncthreads();
+    }
+}
+
 // NQ = 32 x 32 accumulators per multiplying wavefront = 32-column groups of the
 // workgroup's image tile (1, 2, 4 or 8: 32 to 256 images).  A wider tile feeds more
 // multiplies from each decoded block; a narrower one wastes fewer padded columns on a
@@ -613,78 +699,7 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
     if (producer) {
-        // The chunks of this split's blocks are consecutive, [c_lo, c_hi); decoder
-        // d = wave - 4 takes c_lo + d, c_lo + d + kMfmaDecoders, ... and finds a block's
-        // end at the first chunk head that names a later block.  Block -> chunk head ->
-        // record is a chain of dependent loads, so the stream runs ahead of the decoding:
-        // the heads of the next three chunks and the records of the next two are in
-        // registers or in flight.  Every load is unconditional (a position past the end
-        // re-reads the last chunk and is marked invalid; chunk heads sit in a zero-padded
-        // section, so the head after the last one is readable even for a layer without
-        // chunks) and nothing touches a loaded value before it is decoded: the loads are
-        // not waited for where they are issued.  Heads are read through an address the
-        // compiler cannot prove uniform, or they would be moved to scalar registers right
-        // behind the load.
-        struct Head {
-            uint32_t rec_off, rec_end, blk, pos0;
-            bool valid;
-        };
-        uint32_t lane_zero;
-        asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
-        const uint32_t c_hi = blk_lo < blk_hi ? L.block_chunk[pb0 + (uint32_t)blk_hi] : 0u;
-        uint32_t c_tail = blk_lo < blk_hi ? L.block_chunk[pb0 + (uint32_t)blk_lo] + (uint32_t)(wave - 4) : 0u;   // next head to load
-        auto next_head = [&]() {
-            Head h;
-            h.valid = c_tail < c_hi;
-            const cl_chunk_meta *mp = L.meta + (h.valid ? c_tail : (c_hi ? c_hi - 1u : 0u)) + lane_zero;
-            h.rec_off = mp[0].rec_off;
-            h.rec_end = mp[1].rec_off;
-            h.blk = mp[0].blk;
-            h.pos0 = mp[0].pos0;
-            c_tail += (uint32_t)kMfmaDecoders;
-            return h;
-        };
-        auto word_of = [&](const Head &h) {
-            const uint32_t last = h.rec_end - h.rec_off - 1u;       // a chunk has at least one record
-            return L.records[h.rec_off + min((uint32_t)lane, last)];
-        };
-        Head h0 = next_head(), h1 = next_head(), h2 = next_head();
-        uint64_t w0 = word_of(h0), w1 = word_of(h1);
-        // decode block bi into a weight tile (clean on entry): Algorithm 2 steps 5-9
-        auto produce = [&](int bi, float *tile) {
-            const uint32_t b = pb0 + (uint32_t)bi;
-            const BlockGeom g = block_geom(L, b);
-            while (h0.valid && (uint32_t)__builtin_amdgcn_readfirstlane((int)h0.blk) == b) {
-                LaneRecord rec;
-                rec.n = (uint32_t)lane < h0.rec_end - h0.rec_off ? (uint32_t)w0 & 15u : 0u;
-                rec.vbuf = w0 >> kCountBits;
-                rec.ibuf = __builtin_bitreverse64(w0);
-                const uint32_t pos0 = h0.pos0;
-                // move the stream on; the record load issued here uses a head that arrived
-                // a chunk ago
-                h0 = h1; w0 = w1;
-                h1 = h2; w1 = word_of(h1);
-                h2 = next_head();
-                const Symbols y = decode_record(rec, s.T);
-                const LaneStart st = lane_starts(y, pos0);
-                for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-                    uint32_t r, cc;
-                    split_pos(pos, g, r, cc);
-                    if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = s.T.cb[v];
-                });
-            }
-        };
-        // the decoders go first at the issue arbiter: a multiplying wavefront needs one
-        // issue slot per 64-cycle multiply, the decoders next to it on the SIMD can have
-        // the rest
-        __builtin_amdgcn_s_setprio(3);
-        __syncthreads();                                    // tables stored, tiles clean
-        if (blk_lo < blk_hi) produce(blk_lo, tiles);
-        __syncthreads();
-        for (int bi = blk_lo; bi < blk_hi; ++bi) {
-            if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
-            __syncthreads();
-        }
+        decoder_role<kMfmaDecoders, false>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane, [&](uint32_t v) { return s.T.cb[v]; });
         return;
     }
 
@@ -756,6 +771,218 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
                 const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
 #pragma unroll
                 for (int q = 0; q < kVecW; ++q) mine[(size_t)(kTile * v + kVecW * slot + q) * L.bh] = acc[4 * v + q][e];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------- //
+// dense tiles on the bf16 matrix cores, three products per fp32 product
+// ------------------------------------------------------------------------- //
+// A weight w and an activation x are each split into two bf16 terms, w = wh + wl,
+// x = xh + xl (round to nearest even; the residual of each is below 2^-18 of the value),
+// and w x is taken as xh wh + xh wl + xl wh with fp32 accumulation in
+// v_mfma_f32_32x32x16_bf16: three multiplies at sixteen times the fp32 rate.  What is
+// dropped (xl wl and the two residuals) is below 3 * 2^-18 of |w x|.
+__device__ __forceinline__ uint32_t bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// hi half in the upper 16 bits, lo half in the lower
+__device__ __forceinline__ uint32_t bf16_split(float f)
+{
+    const uint32_t hi = bf16_bits(f);
+    const uint32_t lo = bf16_bits(f - __uint_as_float(hi << 16));
+    return (hi << 16) | lo;
+}
+
+// The activations as the bf16 kernel reads them: two planes (hi, lo) of
+// XB[g][column][16] bf16, g = 8 * (block column) + (k % bw) / 16 counting groups of
+// sixteen k of the block-ordered K axis (zero beyond a narrow or ragged block and
+// beyond the batch), so that the 32 columns of an accumulator are one contiguous
+// kilobyte per group.  Each plane has kXbTailGroups more groups (read ahead, never
+// multiplied).
+constexpr int kXbTailGroups = 4;
+
+__device__ __forceinline__ void store_split4(uint16_t *XB, size_t plane_elems, size_t at, const float v[4])
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = bf16_split(v[j]);
+    *(uint2 *)(XB + at) = uint2{(w[0] >> 16) | (w[1] & 0xffff0000u), (w[2] >> 16) | (w[3] & 0xffff0000u)};
+    *(uint2 *)(XB + plane_elems + at) = uint2{(w[0] & 0xffffu) | (w[1] << 16), (w[2] & 0xffffu) | (w[3] << 16)};
+}
+
+// grid: (groups, ceil(Bp / 64)); thread t: column 64 blockIdx.y + t / 4, k quad t % 4
+__global__ __launch_bounds__(256) void split_pad_kernel(const float *__restrict__ X, uint16_t *XB, int B, int K, int Bp, int bw,
+                                                        size_t plane_elems)
+{
+    const int g = blockIdx.x, col = blockIdx.y * 64 + (int)(threadIdx.x >> 2), kq = (int)(threadIdx.x & 3);
+    if (col >= Bp) return;
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int k = xt_row_to_k((g >> 3) * kTile + (g & 7) * 16 + 4 * kq + j, bw, K);
+        v[j] = (k >= 0 && col < B) ? X[(size_t)col * K + k] : 0.0f;
+    }
+    store_split4(XB, plane_elems, ((size_t)g * Bp + col) * 16 + 4 * kq, v);
+}
+
+// the same for a convolution: column = image * P*Q + output pixel, k = (c*R + r)*S + s
+__global__ __launch_bounds__(256) void im2col_split_kernel(const float *__restrict__ X, uint16_t *XB, ConvGeom cg, int c0,
+                                                           int n_cols, int Np, int bw, int K, size_t plane_elems)
+{
+    const int g = blockIdx.y, kq = (int)(threadIdx.x & 3);
+    const int pq = cg.P * cg.Q;
+    for (int col = blockIdx.x * 64 + (int)(threadIdx.x >> 2); col < Np; col += gridDim.x * 64) {
+        float v[4];
+        const int img = col / pq, o = col - img * pq;
+        const int y0 = (o / cg.Q) * cg.stride - cg.pad, x0 = (o % cg.Q) * cg.stride - cg.pad;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = xt_row_to_k((g >> 3) * kTile + (g & 7) * 16 + 4 * kq + j, bw, K);
+            v[j] = 0.0f;
+            if (k >= 0 && col < n_cols) {
+                const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
+                const int y = y0 + r, x = x0 + s;
+                if (y >= 0 && y < cg.H && x >= 0 && x < cg.W) v[j] = X[(((size_t)img * cg.C + (c0 + c)) * cg.H + y) * cg.W + x];
+            }
+        }
+        store_split4(XB, plane_elems, ((size_t)g * Np + col) * 16 + 4 * kq, v);
+    }
+}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Image tile of 32 NQ columns (NQ = 1, 2, 4, 8).  Unlike the fp32 kernel, whose four
+// multiplying wavefronts each take 32 weight rows and all columns, here a wavefront takes
+// 32 (64 for NQ = 8) columns and as many of the 128 weight rows as it takes to share the
+// tile among four wavefronts: the multiplies are sixteen times faster, and columns read
+// once per workgroup instead of four times keep the activation loads off the critical
+// path (weights come from LDS).
+template <int NQ> struct Bf16Shape {
+    static constexpr int kDecoders = 4;
+    static constexpr int kThreads = (4 + kDecoders) * 64;
+    static constexpr int kAhead = 4;                           // groups of sixteen k in flight
+    static constexpr int kImages = 32 * NQ;
+    static constexpr int kIT = NQ == 8 ? 2 : 1;                // 32-column groups per wavefront
+    static constexpr int kWavesPerCols = NQ >= 4 ? 1 : 4 / NQ; // wavefronts sharing the same columns
+    static constexpr int kRT = 4 / kWavesPerCols;              // 32-row tiles per wavefront
+};
+
+// Same workgroup roles, barriers, split of the block row and partial-tile layout as
+// fc_mfma_kernel.  The decoders store each weight as its two bf16 halves in one word;
+// a multiplying wavefront reads the eight words of a row for a group of sixteen k
+// (lanes 0-31 the first eight k, lanes 32-63 the other eight), separates the halves
+// with two byte permutes per word pair, and feeds three multiplies per accumulator.
+template <int NQ>
+__global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(LayerDev L, const uint16_t *__restrict__ XB,
+                                                                             float *part, int splits, int Bp, int panel0,
+                                                                             size_t plane_elems)
+{
+    using S = Bf16Shape<NQ>;
+    constexpr int kDec = S::kDecoders, kNThreads = S::kThreads, kAhead = S::kAhead, kImages = S::kImages;
+    constexpr int kIT = S::kIT, kRT = S::kRT;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    const Smem s = carve(smem_raw, L);
+    float *tiles = (float *)s.extra;                        // [2][kTile rows][kWStride] words
+    uint32_t *cbp = (uint32_t *)(tiles + 2 * (kWTileBytes / 4));   // split codebook
+    const int nbt = Bp / kImages;
+    const int nb = (int)blockIdx.x % nbt;
+    const int pj = (int)blockIdx.x / nbt;
+    const int p = panel0 + pj / splits, j = pj % splits;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    store_tables(s, L, fetch_tables(L));
+    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kNThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
+    for (int t = threadIdx.x; t < L.ncode; t += kNThreads) cbp[t] = bf16_split(L.codebook[t]);
+    const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
+    const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
+    if (wave >= 4) {
+        decoder_role<kDec, true>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane, [&](uint32_t v) { return __uint_as_float(cbp[v]); });
+        return;
+    }
+
+    floatx16 acc[kIT][kRT];
+#pragma unroll
+    for (int it = 0; it < kIT; ++it)
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) acc[it][rt] = floatx16{0};
+    const int kl = lane >> 5, m = lane & 31;
+    const int col0 = (wave / S::kWavesPerCols) * kIT * 32;  // this wavefront's first column of the tile
+    const int row0 = (wave % S::kWavesPerCols) * kRT * 32;  // and its first weight row
+    // group g, column c: 32 bytes at (g Bp + c) * 32, this lane's eight k at + 16 kl
+    const uint4 *ap = (const uint4 *)XB + ((size_t)blk_lo * 8 * Bp + (size_t)nb * kImages + col0 + m) * 2 + kl;
+    const size_t group_stride = (size_t)Bp * 2, plane_stride = plane_elems / 8;      // in 16-byte units
+    uint4 ah[kAhead][kIT], al[kAhead][kIT];
+    auto load_group = [&](int slot) {
+#pragma unroll
+        for (int it = 0; it < kIT; ++it) {
+            ah[slot][it] = ap[it * 64];
+            al[slot][it] = ap[plane_stride + it * 64];
+        }
+        ap += group_stride;
+    };
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) load_group(i);
+    __syncthreads();                                        // tables stored, tiles clean
+    __syncthreads();                                        // first block decoded
+    for (int bi = blk_lo; bi < blk_hi; ++bi) {
+        const uint32_t *cur = (const uint32_t *)(tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4));
+        // the eight words of row row0 + 32 rt + m for group g: two 16-byte reads
+        const uint4 *wp = (const uint4 *)(cur + (row0 + m) * kWStride + 8 * kl);
+        auto words_at = [&](int idx, uint4 &w0, uint4 &w1) {            // idx = g * kRT + rt
+            const int g = idx / kRT, rt = idx % kRT;
+            w0 = wp[rt * (32 * kWStride / 4) + 4 * g];
+            w1 = wp[rt * (32 * kWStride / 4) + 4 * g + 1];
+        };
+        uint4 w0, w1;
+        words_at(0, w0, w1);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            constexpr int kSlotMask = kAhead - 1;
+            const int slot = g & kSlotMask;
+#pragma unroll
+            for (int rt = 0; rt < kRT; ++rt) {
+                // byte permutes: upper halves of two words / lower halves of two words
+                const uint4 bh = {__builtin_amdgcn_perm(w0.y, w0.x, 0x07060302u), __builtin_amdgcn_perm(w0.w, w0.z, 0x07060302u),
+                                  __builtin_amdgcn_perm(w1.y, w1.x, 0x07060302u), __builtin_amdgcn_perm(w1.w, w1.z, 0x07060302u)};
+                const uint4 bl = {__builtin_amdgcn_perm(w0.y, w0.x, 0x05040100u), __builtin_amdgcn_perm(w0.w, w0.z, 0x05040100u),
+                                  __builtin_amdgcn_perm(w1.y, w1.x, 0x05040100u), __builtin_amdgcn_perm(w1.w, w1.z, 0x05040100u)};
+                if (g * kRT + rt + 1 < 8 * kRT) words_at(g * kRT + rt + 1, w0, w1);
+                const bf16x8 vbh = __builtin_bit_cast(bf16x8, bh), vbl = __builtin_bit_cast(bf16x8, bl);
+#pragma unroll
+                for (int it = 0; it < kIT; ++it) {
+                    const bf16x8 vah = __builtin_bit_cast(bf16x8, ah[slot][it]), val = __builtin_bit_cast(bf16x8, al[slot][it]);
+                    acc[it][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vah, vbh, acc[it][rt], 0, 0, 0);
+                    acc[it][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vah, vbl, acc[it][rt], 0, 0, 0);
+                    acc[it][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(val, vbh, acc[it][rt], 0, 0, 0);
+                }
+            }
+            load_group(slot);
+        }
+        // every multiplier reads rows that others read too: all done, then each clears 32 rows
+        __syncthreads();
+        uint4 *z = (uint4 *)(tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4) + wave * 32 * kWStride);
+        for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
+        __syncthreads();
+    }
+    // accumulator (it, rt), element e of lane l: column col0 + 32 it + 8 (e / 4) + 4 (l / 32) + e % 4
+    // of the tile, weight row row0 + 32 rt + l % 32; 32 lanes write 32 consecutive floats
+    float *mine = part + ((size_t)pj * Bp + (size_t)nb * kImages + col0) * L.bh;
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) {
+        const int r = row0 + 32 * rt + m;
+        if (r >= L.bh) continue;
+#pragma unroll
+        for (int it = 0; it < kIT; ++it) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
+                mine[(size_t)(32 * it + slot) * L.bh + r] = acc[it][rt][e];
             }
         }
     }
@@ -989,6 +1216,7 @@ int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
 // Launch shape of the MFMA path.
 struct MfmaPlan {
     int nq = 4;              // 32-image groups per workgroup tile
+    bool bf16 = false;       // three bf16 products instead of one fp32 product
     int Bp = 0;              // batch rounded up to whole image tiles
     int splits = 1;          // workgroups sharing the blocks of one block row
     size_t lds = 0;
@@ -1014,7 +1242,7 @@ bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->des
 // 4.1 k of multiplies per 32 columns of the tile; workgroups run in rounds of one per
 // CU).  The model is coarse, so a candidate must win by a sixteenth to replace a
 // narrower one.
-void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, int &nq, int &np, int &splits)
+void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits)
 {
     cus = std::max(1, cus);
     nq = 0;
@@ -1028,7 +1256,7 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, int &nq, int 
         for (int sp = 1; sp <= sp_max; ++sp) {
             const int64_t rounds = (tiles * sp + cus - 1) / cus;
             const int64_t blocks = (L->nbw + sp - 1) / sp;
-            const int64_t t = rounds * (12000 + blocks * (5000 + 4100 * q));
+            const int64_t t = rounds * (12000 + blocks * (5000 + (bf16 ? 900 : 4100) * q));
             if (best < 0 || (q == nq ? t < best : t + t / 16 < best)) {
                 best = t;
                 nq = q;
@@ -1039,18 +1267,30 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, int &nq, int 
     }
 }
 
-size_t mfma_lds_bytes(const cl_layer *L)
+size_t mfma_lds_bytes(const cl_layer *L, bool bf16)
 {
-    return table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes;
+    return table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes +
+           (bf16 ? ((size_t)4 << L->desc.weight_bits) : 0);
 }
 
-int32_t plan_mfma(const cl_layer *L, int batch, const DeviceLimits &dl, MfmaPlan &P)
+// bf16 elements of one plane of the split activations, read-ahead tail included
+size_t xb_plane_elems(const cl_layer *L, int np) { return ((size_t)L->nbw * 8 + kXbTailGroups) * np * 16; }
+
+// bytes of the activations as the dense-tile kernel of the given precision reads them
+size_t xt_bytes_for(const cl_layer *L, int np, bool bf16)
+{
+    const size_t raw = bf16 ? 2 * xb_plane_elems(L, np) * sizeof(uint16_t) : xt_rows(L) * np * sizeof(float);
+    return (raw + 255) / 256 * 256;
+}
+
+int32_t plan_mfma(const cl_layer *L, int batch, bool bf16, const DeviceLimits &dl, MfmaPlan &P)
 {
     if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the MFMA path needs blocks of at most %d x %d", kTile, kTile);
-    mfma_shape(L, L->n_panels, batch, dl.cus, P.nq, P.Bp, P.splits);
-    P.lds = mfma_lds_bytes(L);
+    P.bf16 = bf16;
+    mfma_shape(L, L->n_panels, batch, dl.cus, bf16, P.nq, P.Bp, P.splits);
+    P.lds = mfma_lds_bytes(L, bf16);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the MFMA path needs %zu bytes of LDS", P.lds);
-    P.xt_bytes = (xt_rows(L) * P.Bp * sizeof(float) + 255) / 256 * 256;
+    P.xt_bytes = xt_bytes_for(L, P.Bp, bf16);
     P.part_bytes = (size_t)L->n_panels * P.splits * P.Bp * L->desc.block_h * sizeof(float);
     return CL_OK;
 }
@@ -1067,14 +1307,35 @@ int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int pa
     return CL_OK;
 }
 
-int32_t launch_mfma(const LayerDev &D, int nq, int panels, int splits, int np, int panel0, size_t lds, const float *xt,
-                    float *part, hipStream_t st)
+template <int NQ>
+int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int panel0, size_t lds, const uint16_t *xb,
+                       size_t plane_elems, float *part, hipStream_t st)
 {
-    switch (nq) {
-    case 1: return launch_mfma_as<1>(D, panels, splits, np, panel0, lds, xt, part, st);
-    case 2: return launch_mfma_as<2>(D, panels, splits, np, panel0, lds, xt, part, st);
-    case 4: return launch_mfma_as<4>(D, panels, splits, np, panel0, lds, xt, part, st);
-    case 8: return launch_mfma_as<8>(D, panels, splits, np, panel0, lds, xt, part, st);
+    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_bf16_kernel<NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(fc_mfma_bf16_kernel<NQ>, dim3((unsigned)(panels * splits * (np / Bf16Shape<NQ>::kImages))),
+                       dim3(Bf16Shape<NQ>::kThreads), lds, st, D, xb, part, splits, np, panel0, plane_elems);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
+int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int panels, int splits, int np, int panel0, size_t lds,
+                    const void *xt, float *part, hipStream_t st)
+{
+    if (bf16) {
+        const size_t pe = xb_plane_elems(L, np);
+        switch (nq) {
+        case 1: return launch_bf16_as<1>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
+        case 2: return launch_bf16_as<2>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
+        case 4: return launch_bf16_as<4>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
+        case 8: return launch_bf16_as<8>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
+        }
+    } else {
+        switch (nq) {
+        case 1: return launch_mfma_as<1>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
+        case 2: return launch_mfma_as<2>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
+        case 4: return launch_mfma_as<4>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
+        case 8: return launch_mfma_as<8>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
+        }
     }
     return fail(CL_EINVAL, "internal: no dense-tile kernel for %d accumulators", nq);
 }
@@ -1091,18 +1352,21 @@ int resolve_path(const cl_layer *L, int batch, int path)
     return (batch > kAutoSparseBatch && mfma_capable(L)) ? CL_PATH_MFMA_F32 : CL_PATH_SPARSE;
 }
 
+bool is_mfma(int path) { return path == CL_PATH_MFMA_F32 || path == CL_PATH_MFMA_BF16; }
+
 }  // namespace
 
 extern "C" int32_t cl_fc_workspace_bytes(const cl_layer *L, int32_t batch, int32_t path, size_t *out)
 {
     if (!L || !out) return fail(CL_EINVAL, "null argument");
     if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
-    if (path != CL_PATH_AUTO && path != CL_PATH_SPARSE && path != CL_PATH_MFMA_F32) return fail(CL_EINVAL, "unknown path %d", path);
+    if (path < CL_PATH_AUTO || path > CL_PATH_MFMA_BF16) return fail(CL_EINVAL, "unknown path %d", path);
     DeviceLimits dl;
     if (int32_t rc = device_limits(dl)) return rc;
-    if (resolve_path(L, batch, path) == CL_PATH_MFMA_F32) {
+    const int chosen = resolve_path(L, batch, path);
+    if (is_mfma(chosen)) {
         MfmaPlan P;
-        if (int32_t rc = plan_mfma(L, batch, dl, P)) return rc;
+        if (int32_t rc = plan_mfma(L, batch, chosen == CL_PATH_MFMA_BF16, dl, P)) return rc;
         *out = P.xt_bytes + P.part_bytes;
     } else {
         SparsePlan P;
@@ -1153,20 +1417,24 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
     return CL_OK;
 }
 
-static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, const float *d_X,
+static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, bool bf16, const float *d_X,
                             const float *d_bias, float *d_Y, int batch, int relu, char *ws, hipStream_t st)
 {
     MfmaPlan P;
-    if (int32_t rc = plan_mfma(L, batch, dl, P)) return rc;
+    if (int32_t rc = plan_mfma(L, batch, bf16, dl, P)) return rc;
     const int K = L->desc.K;
-    float *xt = (float *)ws;
     float *part = (float *)(ws + P.xt_bytes);
-    const int rows = L->nbw * kTile;
-    hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
-                       d_X, xt, batch, K, P.Bp, L->desc.block_w, rows);
+    if (bf16) {
+        hipLaunchKernelGGL(split_pad_kernel, dim3((unsigned)(L->nbw * 8), (unsigned)((P.Bp + 63) / 64)), dim3(256), 0, st,
+                           d_X, (uint16_t *)ws, batch, K, P.Bp, L->desc.block_w, xb_plane_elems(L, P.Bp));
+    } else {
+        const int rows = L->nbw * kTile;
+        hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
+                           d_X, (float *)ws, batch, K, P.Bp, L->desc.block_w, rows);
+    }
     HIP_TRY(hipGetLastError());
     timing_begin(st);
-    if (int32_t rc = launch_mfma(D, P.nq, L->n_panels, P.splits, P.Bp, 0, P.lds, xt, part, st)) return rc;
+    if (int32_t rc = launch_mfma(L, D, bf16, P.nq, L->n_panels, P.splits, P.Bp, 0, P.lds, ws, part, st)) return rc;
     timing_end(st, 1);
     const int ct = reduce_col_tile(L->n_panels, batch);
     hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((batch + ct - 1) / ct))), dim3(256), 0, st,
@@ -1190,8 +1458,9 @@ extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X,
     if (int32_t rc = device_limits(dl)) return rc;
     const LayerDev D = make_dev(L);
     int32_t rc;
-    if (resolve_path(L, batch, path) == CL_PATH_MFMA_F32)
-        rc = forward_mfma(L, D, dl, d_X, d_bias, d_Y, batch, relu, (char *)d_workspace, (hipStream_t)stream);
+    const int chosen = resolve_path(L, batch, path);
+    if (is_mfma(chosen))
+        rc = forward_mfma(L, D, dl, chosen == CL_PATH_MFMA_BF16, d_X, d_bias, d_Y, batch, relu, (char *)d_workspace, (hipStream_t)stream);
     else
         rc = forward_sparse(L, D, dl, d_X, d_bias, d_Y, batch, relu, (float *)d_workspace, (hipStream_t)stream);
     if (rc == CL_OK) clear_error();
@@ -1300,7 +1569,7 @@ struct ConvPlan {
     size_t lds = 0, xt_bytes = 0, part_bytes = 0;
 };
 
-int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const DeviceLimits &dl, ConvPlan &P)
+int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf16, const DeviceLimits &dl, ConvPlan &P)
 {
     if (!cv) return fail(CL_EINVAL, "null convolution descriptor");
     if (cv->C < 1 || cv->H < 1 || cv->W < 1 || cv->R < 1 || cv->S < 1 || cv->stride < 1 || cv->pad < 0 || cv->groups < 1 ||
@@ -1321,15 +1590,15 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, const De
     P.panels_per_group = (P.OCg + L->desc.block_h - 1) / L->desc.block_h;
     const size_t per_image = xt_rows(L) * g.P * g.Q * sizeof(float);
     P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
-    P.lds = mfma_lds_bytes(L);
+    P.lds = mfma_lds_bytes(L, bf16);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
     // workspace for the larger of a full image group and the last, smaller one
     P.xt_bytes = P.part_bytes = 0;
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
         int nq, np, splits;
-        mfma_shape(L, P.panels_per_group, imgs * g.P * g.Q, dl.cus, nq, np, splits);
-        P.xt_bytes = std::max(P.xt_bytes, (xt_rows(L) * np * sizeof(float) + 255) / 256 * 256);
+        mfma_shape(L, P.panels_per_group, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits);
+        P.xt_bytes = std::max(P.xt_bytes, xt_bytes_for(L, np, bf16));
         P.part_bytes = std::max(P.part_bytes, (size_t)P.panels_per_group * splits * np * L->desc.block_h * sizeof(float));
     }
     return CL_OK;
@@ -1341,11 +1610,11 @@ extern "C" int32_t cl_conv_workspace_bytes(const cl_layer *L, const cl_conv_desc
 {
     if (!L || !out) return fail(CL_EINVAL, "null argument");
     if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
-    if (path != CL_PATH_AUTO && path != CL_PATH_MFMA_F32) return fail(CL_EUNSUPPORTED, "convolution runs on the MFMA path only");
+    if (path != CL_PATH_AUTO && !is_mfma(path)) return fail(CL_EUNSUPPORTED, "convolution runs on the MFMA paths only");
     DeviceLimits dl;
     if (int32_t rc = device_limits(dl)) return rc;
     ConvPlan P;
-    if (int32_t rc = plan_conv(L, cv, batch, dl, P)) return rc;
+    if (int32_t rc = plan_conv(L, cv, batch, path == CL_PATH_MFMA_BF16, dl, P)) return rc;
     *out = P.xt_bytes + P.part_bytes;
     return CL_OK;
 }
@@ -1362,29 +1631,34 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
     DeviceLimits dl;
     if (int32_t rc = device_limits(dl)) return rc;
+    const bool bf16 = path == CL_PATH_MFMA_BF16;
     ConvPlan P;
-    if (int32_t rc = plan_conv(L, cv, batch, dl, P)) return rc;
+    if (int32_t rc = plan_conv(L, cv, batch, bf16, dl, P)) return rc;
     hipStream_t st = (hipStream_t)stream;
     const LayerDev D = make_dev(L);
     const ConvGeom &g = P.cg;
     const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
-    float *xt = (float *)d_workspace;
+    void *xt = d_workspace;
     float *part = (float *)((char *)d_workspace + P.xt_bytes);
     bool timed = false;
     for (int b0 = 0; b0 < batch; b0 += P.imgs) {
         const int nb = std::min(P.imgs, batch - b0);
         const int ncols = nb * pq;
         int nq, Np, splits;
-        mfma_shape(L, P.panels_per_group, ncols, dl.cus, nq, Np, splits);
+        mfma_shape(L, P.panels_per_group, ncols, dl.cus, bf16, nq, Np, splits);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         for (int grp = 0; grp < cv->groups; ++grp) {
-            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)(L->nbw * kTile)), dim3(256), 0, st,
-                               x, xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K);
+            if (bf16)
+                hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8)), dim3(256), 0, st,
+                                   x, (uint16_t *)xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np));
+            else
+                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)(L->nbw * kTile)), dim3(256), 0, st,
+                                   x, (float *)xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K);
             HIP_TRY(hipGetLastError());
             const int panel0 = grp * P.panels_per_group;
             if (!timed) timing_begin(st);
-            if (int32_t rc = launch_mfma(D, nq, P.panels_per_group, splits, Np, panel0, P.lds, xt, part, st)) return rc;
+            if (int32_t rc = launch_mfma(L, D, bf16, nq, P.panels_per_group, splits, Np, panel0, P.lds, xt, part, st)) return rc;
             if (!timed) { timing_end(st, 1); timed = true; }
             const int ct = reduce_col_tile(P.panels_per_group, ncols);
             hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(P.panels_per_group * ((ncols + ct - 1) / ct))), dim3(256), 0, st,

@@ -46,11 +46,11 @@ def main(argv=None):
     ap.add_argument("--blocks", nargs="+", default=None, help="block sizes to sweep, as HxW")
     ap.add_argument("--batches", type=int, nargs="+", default=None, help="override the configuration's batch sizes")
     ap.add_argument("--densities", type=float, nargs="+", default=[None], help="override the fraction of non-zeros")
-    ap.add_argument("--paths", nargs="+", default=["auto"], choices=["auto", "sparse", "mfma"])
+    ap.add_argument("--paths", nargs="+", default=["auto"], choices=["auto", "sparse", "mfma", "bf16"])
     ap.add_argument("--layers", type=int, nargs="+", default=None, help="layer indices (default: all)")
     args = ap.parse_args(argv)
     cfg = wl.CONFIGS[args.config]
-    paths = {"auto": cl.PATH_AUTO, "sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32}
+    paths = {"auto": cl.PATH_AUTO, "sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32, "bf16": cl.PATH_MFMA_BF16}
     blocks = [tuple(int(t) for t in b.lower().split("x")) for b in args.blocks] if args.blocks else [tuple(args.block)]
     for li, spec0 in enumerate(cfg["layers"]):
         if args.layers is not None and li not in args.layers:
@@ -71,10 +71,10 @@ def main(argv=None):
                         try:
                             if spec.conv is not None:
                                 g = spec.conv
-                                ws = torch.empty(max(256, cl.conv_workspace_bytes(L, g, B)), dtype=torch.uint8, device="cuda")
+                                ws = torch.empty(max(256, cl.conv_workspace_bytes(L, g, B, path)), dtype=torch.uint8, device="cuda")
                                 P = (g["H"] + 2 * g["pad"] - g["R"]) // g["stride"] + 1
                                 out = torch.empty((B, g["OC"], P, P), device="cuda")
-                                ms = time_ms(lambda: cl.compressed_conv_forward(L, g, X, relu=True, out=out, workspace=ws), args.reps, 3)
+                                ms = time_ms(lambda: cl.compressed_conv_forward(L, g, X, relu=True, path=path, out=out, workspace=ws), args.reps, 3)
                                 n_cols = B * P * P
                             else:
                                 ws = torch.empty(max(256, cl.fc_workspace_bytes(L, B, path)), dtype=torch.uint8, device="cuda")

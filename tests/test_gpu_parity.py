@@ -130,6 +130,51 @@ def test_fc_forward_mfma_tile_widths(bh, bw, B):
     assert rel_err(Y.cpu().numpy(), ref) <= TOL
 
 
+def bf16x3_bound(abs_products, ref):
+    """Error bound of the three-product bf16 split, relative to the largest output:
+    each product w x is off by at most 3 * 2^-18 |w x| (the dropped lo x lo term and
+    the two split residuals), fp32 accumulation adds the usual 1e-5."""
+    return 3.0 * 2.0 ** -18 * float(np.abs(abs_products).max()) / max(float(np.abs(ref).max()), 1e-300) + TOL
+
+
+@pytest.mark.parametrize("M,K,bh,bw,d,r,k", [(300, 437, 128, 128, 0.12, 5, 4), (1000, 520, 128, 128, 0.25, 5, 4),
+                                             (384, 300, 64, 48, 0.37, 8, 8), (128, 256, 128, 128, 0.0, 5, 4)])
+@pytest.mark.parametrize("B", [5, 33, 100, 256])
+def test_fc_forward_bf16_path(M, K, bh, bw, d, r, k, B):
+    """Dense tiles on the bf16 matrix cores (three products per fp32 product): within
+    the split's own error bound of the oracle, far inside the 2e-3 allowed for bf16
+    tiles, and run-to-run identical."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(M + 7 * K + B)
+    W = rand_pruned(rng, M, K, d)
+    L, m, oW = check_decode(W, r, k, bh, bw)
+    X = np.maximum(rng.standard_normal((B, K)), 0).astype(np.float32)
+    bias = rng.standard_normal(M).astype(np.float32) * 0.1
+    ref = oracle.fc_forward(oW, X, bias, True, nthreads=8)
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
+    Y = cl.compressed_fc_forward(L, Xd, bd, relu=True, path=cl.PATH_MFMA_BF16)
+    err = rel_err(Y.cpu().numpy(), ref)
+    assert err <= bf16x3_bound(oracle.fc_forward(np.abs(oW), np.abs(X), nthreads=8), ref)
+    assert err <= 2e-3
+    assert torch.equal(Y, cl.compressed_fc_forward(L, Xd, bd, relu=True, path=cl.PATH_MFMA_BF16))
+
+
+@pytest.mark.parametrize("li", [0, 1, 2, 4])
+def test_conv_forward_bf16_path(li):
+    """AlexNet convolutions of configs[3] on the bf16 path, two images."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(4, li)
+    g = spec.conv
+    bh = 128 if g["groups"] == 1 or (g["OC"] // g["groups"]) % 128 == 0 else 64
+    L, m, oW = check_decode(W, spec.r, spec.k, bh, 128)
+    X = wl.activations(4, 2, layer_index=li)
+    ref = oracle.conv_forward(oW, X, g, relu=True, nthreads=8)
+    Y = cl.compressed_conv_forward(L, g, torch.from_numpy(X).cuda(), relu=True, path=cl.PATH_MFMA_BF16).cpu().numpy()
+    err = rel_err(Y, ref)
+    assert err <= bf16x3_bound(oracle.conv_forward(np.abs(oW), np.abs(X), g, nthreads=8), ref)
+    assert err <= 2e-3
+
+
 def test_mfma_path_is_deterministic_and_refuses_big_blocks():
     torch = torch_cuda()
     rng = np.random.default_rng(5)
