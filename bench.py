@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--path", choices=["auto", "sparse", "mfma", "bf16"], default="auto")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep 1,4,16,64,256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bf16", action="store_true", help="skip the extra run on the bf16-tile path")
     ap.add_argument("--no-cold-pool", action="store_true", help="skip the batch-1 steady-state run over separately uploaded copies")
     ap.add_argument("--cold-copies", type=int, default=128)
     ap.add_argument("--cpu-batch", type=int, default=256, help="batch of the CPU-oracle sample")
@@ -204,6 +205,48 @@ def main():
         return {"copies": copies, "streams": n_streams, "us_per_launch_pair": round(dt * 1e6, 3),
                 "achieved": round(alg_bytes / dt / 1e9, 2), "unit": "GB/s", "frac": round(alg_bytes / dt / 1e9 / HBM_PEAK_GBS, 5)}
 
+    # ---- the same step on the bf16-tile path (three bf16 products per fp32 product) ----
+    def bf16_tiles(B):
+        pb = cl.PATH_MFMA_BF16
+        X, ys, _ = bufs[B]
+        ysb = [torch.empty_like(y) for y in ys]
+        wsb = [torch.empty(max(1, cl.fc_workspace_bytes(L, B, pb)), dtype=torch.uint8, device="cuda") for L in layers]
+
+        def stepb():
+            a = X
+            for li, L in enumerate(layers):
+                a = cl.compressed_fc_forward(L, a, relu=(li < 2), path=pb, out=ysb[li], workspace=wsb[li])
+            return a
+        for _ in range(args.warmup):
+            stepb()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            stepb()
+        torch.cuda.synchronize()
+        msb = (time.perf_counter() - t0) * 1e3 / args.steps
+        step(B)
+        torch.cuda.synchronize()
+        diff = float((ysb[2] - ys[2]).abs().max() / ys[2].abs().max())
+        binding.set_kernel_timing(True)
+        ts = []
+        for i in range(30):
+            cl.compressed_fc_forward(layers[0], X, relu=True, path=pb, out=ysb[0], workspace=wsb[0])
+            t, n = binding.last_kernel_ms()
+            if i >= 5:
+                ts.append(t / n)
+        binding.set_kernel_timing(False)
+        kms = float(np.mean(ts))
+        Bp = -(-B // 32) * 32
+        executed = 3 * 2.0 * specs[0].M * specs[0].K * Bp         # three bf16 tile products per fp32 one
+        return {"value": round(B / (msb * 1e-3), 1), "unit": "images/s", "ms_per_step": round(msb, 5), "batch": B, "dtype": "bf16 x3, f32 accumulate",
+                "max_abs_diff_vs_f32_path_over_max_abs": diff,
+                "roofline": {"bound": "mfma", "kernel": "fc_mfma_bf16_kernel", "layer": "fc6", "launch_ms": round(kms, 5),
+                             "achieved": round(executed / (kms * 1e-3) / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                             "frac": round(executed / (kms * 1e-3) / 1e12 / 2500.0, 4),
+                             "flops_counted": "executed bf16 tile flops 3*2*M*K*B",
+                             "fp32_equivalent_TFLOPs": round(executed / 3 / (kms * 1e-3) / 1e12, 1)}}
+
     # The batch-1 kernel against what binds it: vector-ALU issue.  Peak = 256 CUs x 4 SIMDs x
     # 2.4 GHz / 4 cycles per wavefront instruction; the instruction count of the fc6 launch is
     # the SQ_INSTS_VALU counter summarised under profiles/ (default workload only).
@@ -237,6 +280,8 @@ def main():
         "roofline": headline,
         "roofline_batch1": b1,
     }
+    if not args.no_bf16 and args.path == "auto":
+        out["bf16_tiles"] = bf16_tiles(args.batch)
 
     # ---- the CPU oracle on the host cores, same workload, bounded sample -----
     if not args.no_cpu_baseline:

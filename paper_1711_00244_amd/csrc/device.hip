@@ -1239,8 +1239,8 @@ bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->des
 // Image tile, padded column count and split of the block rows for `ncols` columns and
 // `panels` block rows, from a small model of the kernel with measured constants
 // (cycles per workgroup: 12 k to start; per block 5 k of decoding and bookkeeping plus
-// 4.1 k of multiplies per 32 columns of the tile; workgroups run in rounds of one per
-// CU).  The model is coarse, so a candidate must win by a sixteenth to replace a
+// 4.1 k of multiplies per 32 columns of the tile - 1.5 k on the bf16 matrix cores;
+// workgroups run in rounds of one per CU).  The model is coarse, so a candidate must win by a sixteenth to replace a
 // narrower one.
 void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits)
 {
@@ -1256,7 +1256,7 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
         for (int sp = 1; sp <= sp_max; ++sp) {
             const int64_t rounds = (tiles * sp + cus - 1) / cus;
             const int64_t blocks = (L->nbw + sp - 1) / sp;
-            const int64_t t = rounds * (12000 + blocks * (5000 + (bf16 ? 900 : 4100) * q));
+            const int64_t t = rounds * (12000 + blocks * (5000 + (bf16 ? 1500 : 4100) * q));
             if (best < 0 || (q == nq ? t < best : t + t / 16 < best)) {
                 best = t;
                 nq = q;
