@@ -54,7 +54,8 @@ enum {
 
 /* Kernel selection for the forward entry points. */
 enum {
-    CL_PATH_AUTO = 0,     /* library picks from batch size and layer density        */
+    CL_PATH_AUTO = 0,     /* CL_PATH_SPARSE for up to 4 images, CL_PATH_MFMA_F32 above */
+                          /*   when the blocks fit a tile (else CL_PATH_SPARSE)       */
     CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
     CL_PATH_MFMA_F32 = 2, /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
                           /*   of at most 128 x 128, else CL_EUNSUPPORTED            */
@@ -207,7 +208,9 @@ int32_t cl_decode_layer(const cl_layer *layer, uint8_t *d_val_sym, uint8_t *d_id
                         uint32_t *d_block_ptr, float *d_dense, void *stream);
 
 /* Device scratch a forward call needs for (batch, path): the partial output tiles
- * of the workgroups of each block row.  Needs a HIP device (CL_EHIP otherwise). */
+ * of the workgroups of each block row and, on the MFMA paths, the activations in
+ * the layout the kernel reads (transposed, K laid out block by block; two bf16
+ * planes for CL_PATH_MFMA_BF16).  Needs a HIP device (CL_EHIP otherwise). */
 int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path, size_t *out);
 
 /* Y = act(X W^T + v) straight from the compressed layer (Eq. 1-2 with the
@@ -217,7 +220,8 @@ int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path
  *  relu    non-zero applies max(0, .)
  *  path    CL_PATH_*.  CL_PATH_SPARSE adds lane sums into an LDS tile with
  *          floating-point atomics, so the last bits of Y can differ between runs;
- *          the tiles of a block row are then added up in a fixed order
+ *          the tiles of a block row are then added up in a fixed order.  The MFMA
+ *          paths are run-to-run identical.
  *  d_workspace / workspace_bytes   at least cl_fc_workspace_bytes(); may be NULL
  *          when that is 0
  * Errors: CL_EINVAL (null pointers, batch < 1, workspace too small, layer not
@@ -242,7 +246,12 @@ int32_t cl_conv_workspace_bytes(const cl_layer *layer, const cl_conv_desc *conv,
                                 int32_t path, size_t *out);
 
 /* d_X: batch x C x H x W fp32 (NCHW); d_Y: batch x out_channels x P x Q fp32 with
- * P = (H + 2 pad - R) / stride + 1, Q likewise. */
+ * P = (H + 2 pad - R) / stride + 1, Q likewise.  The receptive fields are written
+ * out as columns (Sec. III-A) in the workspace, at most 256 MiB of them at a time,
+ * and multiplied on an MFMA path: path is CL_PATH_AUTO (= CL_PATH_MFMA_F32),
+ * CL_PATH_MFMA_F32 or CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are
+ * blocks above 128 x 128 and, with groups > 1, a block_h that does not divide
+ * out_channels / groups. */
 int32_t cl_compressed_conv_forward(const cl_layer *layer, const cl_conv_desc *conv, const float *d_X,
                                    const float *d_bias_or_null, float *d_Y, int32_t batch, int32_t relu,
                                    int32_t path, void *d_workspace, size_t workspace_bytes, void *stream);
