@@ -28,7 +28,9 @@ namespace cl {
         if (e_ != hipSuccess) return fail(CL_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
 
-constexpr int kWaves = 8;                 // wavefronts (= chunks) per workgroup
+constexpr int kWaves = 8;                 // wavefronts per workgroup
+constexpr int kSparseChunksPerWave = 1;   // chunks a wavefront of the sparse kernel decodes, one after the other
+                                          // (2 amortises the table copy but measured 18 % slower at batch 1)
 constexpr int kThreads = kWaves * 64;
 
 // Everything a kernel needs to read a layer, passed by value.
@@ -350,24 +352,32 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     const Smem s = carve(smem_raw, L);
     const int p = (int)(blockIdx.x / (uint32_t)wg_per_panel), j = (int)(blockIdx.x % (uint32_t)wg_per_panel);
     const uint32_t pc1 = L.panel_chunk[p + 1];
-    const uint32_t my0 = L.panel_chunk[p] + (uint32_t)j * kWaves;
+    const uint32_t my0 = L.panel_chunk[p] + (uint32_t)j * (kWaves * kSparseChunksPerWave);
     if (my0 >= pc1) return;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    const uint32_t c = my0 + (uint32_t)wave;
-    const bool have = c < pc1;
-    ChunkHead h{};
-    LaneRecord rec{};
-    if (have) {
-        h = load_head(L, c);
-        rec = load_record(L, h, lane);
+    // wavefront w takes chunks my0 + w, my0 + 8 + w, ...: all their records are requested
+    // before the tables are copied
+    bool have[kSparseChunksPerWave];
+    ChunkHead h[kSparseChunksPerWave];
+    LaneRecord rec[kSparseChunksPerWave];
+#pragma unroll
+    for (int i = 0; i < kSparseChunksPerWave; ++i) {
+        const uint32_t c = my0 + (uint32_t)(i * kWaves + wave);
+        have[i] = c < pc1;
+        h[i] = ChunkHead{};
+        rec[i] = LaneRecord{};
+        if (have[i]) {
+            h[i] = load_head(L, c);
+            rec[i] = load_record(L, h[i], lane);
+        }
     }
     const TableRegs tr = fetch_tables(L);
     float *ytile = s.extra;                  // [BT][bh]
     float *xs = ytile + (size_t)L.bh * BT;   // [BT][xcap]
     // activation columns of the blocks this workgroup's chunks belong to
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
-    const uint32_t c_last = min(pc1, my0 + (uint32_t)kWaves) - 1u;
+    const uint32_t c_last = min(pc1, my0 + (uint32_t)(kWaves * kSparseChunksPerWave)) - 1u;
     const int col_a = (int)(L.meta[my0].blk - pb0) * L.bw;
     const int col_b = min(L.K, (int)(L.meta[c_last].blk - pb0 + 1u) * L.bw);
     const int width = col_b - col_a;
@@ -380,10 +390,12 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
     store_tables(s, L, tr);
     __syncthreads();
-    if (have) {
-        const Symbols y = decode_record(rec, s.T);
-        const LaneStart st = lane_starts(y, h.m.pos0);
-        const BlockGeom g = block_geom(L, h.m.blk);
+#pragma unroll
+    for (int i = 0; i < kSparseChunksPerWave; ++i) {
+        if (!have[i]) continue;
+        const Symbols y = decode_record(rec[i], s.T);
+        const LaneStart st = lane_starts(y, h[i].m.pos0);
+        const BlockGeom g = block_geom(L, h[i].m.blk);
         // The entries of the record in order.  The two instantiations differ only in
         // where the activations come from (LDS stays LDS: no generic pointers).
         auto entries = [&](auto load_x) {
@@ -440,8 +452,9 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
     const int p = (int)blockIdx.x / B, b = (int)blockIdx.x - p * B;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
-    // the sparse kernel fills one slot per eight chunks of the block row
-    const int active = (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kWaves - 1) / kWaves);
+    // the sparse kernel fills one slot per workgroup's worth of chunks of the block row
+    constexpr uint32_t kPerWg = kWaves * kSparseChunksPerWave;
+    const int active = (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kPerWg - 1) / kPerWg);
     constexpr int kRows = kRedThreads / kSlices;
     const int sl = (int)threadIdx.x / kRows, rl = (int)threadIdx.x - sl * kRows;
     // part[p][j][image (part_b of them)][bh]
@@ -1190,7 +1203,7 @@ namespace {
 // Launch shape of the sparse forward path for one layer and batch.
 struct SparsePlan {
     int bt_max = 1;          // batch tile of the main kernel (power of two, <= 16)
-    int wg_per_panel = 0;    // workgroups per block row (one wavefront per chunk, 8 per workgroup)
+    int wg_per_panel = 0;    // workgroups per block row (8 wavefronts of kSparseChunksPerWave chunks each)
     int xwant = 0;           // activation columns to stage in LDS per image (3 blocks wide)
     size_t fixed = 0;        // LDS bytes of tables + codebook
     size_t part_bytes = 0;   // partial-tile buffer in the workspace
@@ -1201,14 +1214,14 @@ struct SparsePlan {
 int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
 {
     P.fixed = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
-    P.xwant = (int)std::min<int64_t>(L->desc.K, 3 * (int64_t)L->desc.block_w);
+    P.xwant = (int)std::min<int64_t>(L->desc.K, (1 + 2 * kSparseChunksPerWave) * (int64_t)L->desc.block_w);
     // largest power-of-two batch tile (<= 16) that fits; prefer to stay under 64 KiB
     size_t budget = std::min<size_t>(max_lds, 64 * 1024);
     if (P.lds_for(L, 1) > budget) budget = max_lds;
     if (P.lds_for(L, 1) > budget) return fail(CL_EUNSUPPORTED, "block_h %d needs more LDS than a workgroup has", L->desc.block_h);
     P.bt_max = 16;
     while (P.bt_max > 1 && (P.lds_for(L, P.bt_max) > budget || P.bt_max / 2 >= batch)) P.bt_max >>= 1;
-    P.wg_per_panel = (int)((L->max_panel_chunks + kWaves - 1) / kWaves);
+    P.wg_per_panel = (int)((L->max_panel_chunks + kWaves * kSparseChunksPerWave - 1) / (kWaves * kSparseChunksPerWave));
     P.part_bytes = (size_t)L->n_panels * P.wg_per_panel * L->desc.block_h * P.bt_max * sizeof(float);
     return CL_OK;
 }
