@@ -577,13 +577,13 @@ constexpr int kWTileBytes = kTile * kWStride * 4;
 // The decoder wavefronts' side of the dense-tile kernels: decode the blocks blk_lo ..
 // blk_hi - 1 of block row pb0 / nbw into the two alternating 128 x kWStride tiles of
 // 32-bit words, one block ahead of the multipliers, meeting them at one barrier per
-// block.  weight_of(v) is the word stored for value index v (the codebook entry, or
-// its split into two bf16 halves).  With CLEAR_BARRIER the multipliers clear a used tile
+// block.  The two buffers are BUF_FLOATS floats apart; store(buffer, row, column, v)
+// places value index v (the codebook entry, or its two bf16 halves in two half tiles).  With CLEAR_BARRIER the multipliers clear a used tile
 // between two barriers (their rows are shared), else right after their last read of
 // their own rows.  Called by wavefronts 4 .. 4 + DEC - 1.
-template <int DEC, bool CLEAR_BARRIER, class WeightOf>
+template <int DEC, bool CLEAR_BARRIER, int BUF_FLOATS, class Store>
 __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, float *tiles, int blk_lo, int blk_hi, uint32_t pb0,
-                                             int wave, int lane, WeightOf weight_of)
+                                             int wave, int lane, Store store)
 {
     // The chunks of this split's blocks are consecutive, [c_lo, c_hi); decoder
     // d = wave - 4 takes c_lo + d, c_lo + d + DEC, ... and finds a block's
@@ -642,7 +642,7 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
             for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
                 uint32_t r, cc;
                 split_pos(pos, g, r, cc);
-                if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = weight_of(v);
+                if (v != 0 && cc < (uint32_t)kTile) store(tile, r, cc, v);
             });
         }
     };
@@ -654,7 +654,7 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
     if (blk_lo < blk_hi) produce(blk_lo, tiles);
     __syncthreads();
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
+        if (bi + 1 < blk_hi) produce(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * BUF_FLOATS);
         __syncthreads();
         if (CLEAR_BARRIER) __syncthreads();
     }
@@ -712,7 +712,8 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
     if (producer) {
-        decoder_role<kMfmaDecoders, false>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane, [&](uint32_t v) { return s.T.cb[v]; });
+        decoder_role<kMfmaDecoders, false, kWTileBytes / 4>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
+                                                             [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) { tile[r * kWStride + cc] = s.T.cb[v]; });
         return;
     }
 
@@ -887,10 +888,12 @@ template <int NQ> struct Bf16Shape {
 };
 
 // Same workgroup roles, barriers, split of the block row and partial-tile layout as
-// fc_mfma_kernel.  The decoders store each weight as its two bf16 halves in one word;
-// a multiplying wavefront reads the eight words of a row for a group of sixteen k
-// (lanes 0-31 the first eight k, lanes 32-63 the other eight), separates the halves
-// with two byte permutes per word pair, and feeds three multiplies per accumulator.
+// fc_mfma_kernel.  The decoders store the two bf16 halves of each weight in two half
+// tiles; a multiplying wavefront reads the eight hi halves and the eight lo halves of a
+// row for a group of sixteen k with one 16-byte LDS read each (lanes 0-31 the first
+// eight k, lanes 32-63 the other eight) and feeds three multiplies per accumulator.
+constexpr int kHStride = kTile + 8;                       // bf16 per row of a half tile (16-byte rows, 4-bank skew)
+constexpr int kBf16BufFloats = 2 * kTile * kHStride / 2;  // floats per buffer: hi tile + lo tile
 template <int NQ>
 __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(LayerDev L, const uint16_t *__restrict__ XB,
                                                                              float *part, int splits, int Bp, int panel0,
@@ -901,8 +904,10 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
     constexpr int kIT = S::kIT, kRT = S::kRT;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    float *tiles = (float *)s.extra;                        // [2][kTile rows][kWStride] words
-    uint32_t *cbp = (uint32_t *)(tiles + 2 * (kWTileBytes / 4));   // split codebook
+    // two buffers, each a tile of the hi halves and a tile of the lo halves:
+    // [2][2][kTile rows][kHStride] bf16
+    float *tiles = (float *)s.extra;
+    uint32_t *cbp = (uint32_t *)(tiles + 2 * kBf16BufFloats);       // split codebook
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
@@ -910,12 +915,18 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     store_tables(s, L, fetch_tables(L));
-    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kNThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
+    for (int t = threadIdx.x; t < 2 * kBf16BufFloats / 4; t += kNThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
     for (int t = threadIdx.x; t < L.ncode; t += kNThreads) cbp[t] = bf16_split(L.codebook[t]);
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     if (wave >= 4) {
-        decoder_role<kDec, true>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane, [&](uint32_t v) { return __uint_as_float(cbp[v]); });
+        decoder_role<kDec, true, kBf16BufFloats>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
+                                                 [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) {
+                                                     const uint32_t w = cbp[v];
+                                                     uint16_t *t16 = (uint16_t *)tile + r * kHStride + cc;
+                                                     t16[0] = (uint16_t)(w >> 16);
+                                                     t16[kTile * kHStride] = (uint16_t)w;
+                                                 });
         return;
     }
 
@@ -944,29 +955,24 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
     __syncthreads();                                        // tables stored, tiles clean
     __syncthreads();                                        // first block decoded
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        const uint32_t *cur = (const uint32_t *)(tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4));
-        // the eight words of row row0 + 32 rt + m for group g: two 16-byte reads
-        const uint4 *wp = (const uint4 *)(cur + (row0 + m) * kWStride + 8 * kl);
-        auto words_at = [&](int idx, uint4 &w0, uint4 &w1) {            // idx = g * kRT + rt
+        float *buf = tiles + ((bi - blk_lo) & 1) * kBf16BufFloats;
+        // the eight hi (lo) halves of row row0 + 32 rt + m for group g: one 16-byte read each
+        const uint4 *wp = (const uint4 *)((const uint16_t *)buf + (row0 + m) * kHStride + 8 * kl);
+        auto halves_at = [&](int idx, uint4 &h, uint4 &l) {             // idx = g * kRT + rt
             const int g = idx / kRT, rt = idx % kRT;
-            w0 = wp[rt * (32 * kWStride / 4) + 4 * g];
-            w1 = wp[rt * (32 * kWStride / 4) + 4 * g + 1];
+            h = wp[rt * (32 * kHStride / 8) + 2 * g];
+            l = wp[kTile * kHStride / 8 + rt * (32 * kHStride / 8) + 2 * g];
         };
-        uint4 w0, w1;
-        words_at(0, w0, w1);
+        uint4 bh, bl;
+        halves_at(0, bh, bl);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             constexpr int kSlotMask = kAhead - 1;
             const int slot = g & kSlotMask;
 #pragma unroll
             for (int rt = 0; rt < kRT; ++rt) {
-                // byte permutes: upper halves of two words / lower halves of two words
-                const uint4 bh = {__builtin_amdgcn_perm(w0.y, w0.x, 0x07060302u), __builtin_amdgcn_perm(w0.w, w0.z, 0x07060302u),
-                                  __builtin_amdgcn_perm(w1.y, w1.x, 0x07060302u), __builtin_amdgcn_perm(w1.w, w1.z, 0x07060302u)};
-                const uint4 bl = {__builtin_amdgcn_perm(w0.y, w0.x, 0x05040100u), __builtin_amdgcn_perm(w0.w, w0.z, 0x05040100u),
-                                  __builtin_amdgcn_perm(w1.y, w1.x, 0x05040100u), __builtin_amdgcn_perm(w1.w, w1.z, 0x05040100u)};
-                if (g * kRT + rt + 1 < 8 * kRT) words_at(g * kRT + rt + 1, w0, w1);
                 const bf16x8 vbh = __builtin_bit_cast(bf16x8, bh), vbl = __builtin_bit_cast(bf16x8, bl);
+                if (g * kRT + rt + 1 < 8 * kRT) halves_at(g * kRT + rt + 1, bh, bl);
 #pragma unroll
                 for (int it = 0; it < kIT; ++it) {
                     const bf16x8 vah = __builtin_bit_cast(bf16x8, ah[slot][it]), val = __builtin_bit_cast(bf16x8, al[slot][it]);
@@ -977,10 +983,10 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
             }
             load_group(slot);
         }
-        // every multiplier reads rows that others read too: all done, then each clears 32 rows
+        // every multiplier reads rows that others read too: all done, then each clears a quarter
         __syncthreads();
-        uint4 *z = (uint4 *)(tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4) + wave * 32 * kWStride);
-        for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
+        uint4 *z = (uint4 *)buf + wave * (kBf16BufFloats / 16);
+        for (int t = lane; t < kBf16BufFloats / 16; t += 64) z[t] = uint4{0, 0, 0, 0};
         __syncthreads();
     }
     // accumulator (it, rt), element e of lane l: column col0 + 32 it + 8 (e / 4) + 4 (l / 32) + e % 4
@@ -1282,8 +1288,8 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
 
 size_t mfma_lds_bytes(const cl_layer *L, bool bf16)
 {
-    return table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + 2 * (size_t)kWTileBytes +
-           (bf16 ? ((size_t)4 << L->desc.weight_bits) : 0);
+    const size_t tables = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
+    return bf16 ? tables + 2 * (size_t)kBf16BufFloats * 4 + ((size_t)4 << L->desc.weight_bits) : tables + 2 * (size_t)kWTileBytes;
 }
 
 // bf16 elements of one plane of the split activations, read-ahead tail included
