@@ -639,11 +639,21 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
             h2 = next_head();
             const Symbols y = decode_record(rec, s.T);
             const LaneStart st = lane_starts(y, pos0);
-            for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-                uint32_t r, cc;
-                split_pos(pos, g, r, cc);
-                if (v != 0 && cc < (uint32_t)kTile) store(tile, r, cc, v);
-            });
+            if (g.shift >= 0) {
+                // a power-of-two block width (every full block): row and column are a
+                // shift and a mask, the column cannot leave the tile, and a padding
+                // entry may store its zero (codebook entry 0) like any other
+                const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u, rmax = (uint32_t)g.bhp - 1u;
+                for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                    store(tile, min(pos >> sh, rmax), pos & cmask, v);
+                });
+            } else {
+                for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                    uint32_t r, cc;
+                    split_pos(pos, g, r, cc);
+                    if (v != 0 && cc < (uint32_t)kTile) store(tile, r, cc, v);
+                });
+            }
         }
     };
     // the decoders go first at the issue arbiter: a multiplying wavefront needs one
@@ -713,7 +723,7 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
 
     if (producer) {
         decoder_role<kMfmaDecoders, false, kWTileBytes / 4>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
-                                                             [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) { tile[r * kWStride + cc] = s.T.cb[v]; });
+                                                             [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) { tile[__umul24(r, (uint32_t)kWStride) + cc] = s.T.cb[v]; });
         return;
     }
 
@@ -923,7 +933,7 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
         decoder_role<kDec, true, kBf16BufFloats>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
                                                  [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) {
                                                      const uint32_t w = cbp[v];
-                                                     uint16_t *t16 = (uint16_t *)tile + r * kHStride + cc;
+                                                     uint16_t *t16 = (uint16_t *)tile + __umul24(r, (uint32_t)kHStride) + cc;
                                                      t16[0] = (uint16_t)(w >> 16);
                                                      t16[kTile * kHStride] = (uint16_t)w;
                                                  });
