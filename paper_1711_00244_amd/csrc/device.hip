@@ -13,6 +13,7 @@
 //   use     the entries in order, each with its position: store it (decode_layer),
 //           multiply-accumulate it (sparse forward) or place it in a dense tile (MFMA forward)
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include <algorithm>
 #include <cstdio>
@@ -94,6 +95,19 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
     return v;
 }
 
+// Largest value over the 64 lanes (all lanes must be active), the same in every lane
+// and known to be uniform.
+__device__ __forceinline__ uint32_t wave_max(uint32_t v)
+{
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false));
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // Decode tables and codebook in LDS.
 struct Tables {
     const lut_t *vlut;
@@ -132,43 +146,76 @@ __device__ __forceinline__ LaneRecord load_record(const LayerDev &L, const Chunk
     return r;
 }
 
-// One table lookup: the symbol at the head of buf; buf moves on to the next codeword.
-// The entry itself is the shift amount (length in its low bits, the shifter ignores
-// the rest), which keeps the loop-carried chain at mask, address, read, shift.
-__device__ __forceinline__ uint32_t next_symbol(uint64_t &buf, const lut_t *lut, uint32_t mask)
+// One table lookup: the entry for the codeword at the head of buf (symbol in its second
+// byte); buf moves on to the next codeword.  The entry itself is the shift amount
+// (length in its low bits, the shifter ignores the rest), which keeps the loop-carried
+// chain at mask, address, read, shift.
+__device__ __forceinline__ uint32_t next_entry(uint64_t &buf, const lut_t *lut, uint32_t mask)
 {
     const uint32_t e = lut[(uint32_t)buf & mask];
     buf >>= (e & 63u);
-    return e >> 8;
+    return e;
 }
 
-// A lane's record with both codeword streams decoded: eight bits per entry, entries
-// 0-7 in z[0] / v[0], entries 8-14 in z[1] / v[1].
+constexpr int kMaxEntries = 15;        // a record's count field is four bits
+
+// A lane's record with both codeword streams decoded: eight bits per entry, entry j in
+// byte j % 4 of word j / 4; the bytes of entries the record does not have are zero.
 struct Symbols {
-    uint64_t z[2];     // relative indices
-    uint64_t v[2];     // value indices
+    uint32_t z[4];     // relative indices
+    uint32_t v[4];     // value indices
     uint32_t n;        // entries
+    uint32_t nmax;     // largest n of the wavefront (uniform)
     uint32_t adv;      // sum of (z + 1): how far the record moves the position
 };
 
-// Algorithm 2 step 6 for one record: both streams are decoded in one loop - two
+// One step of the decoding pass: entry J of both streams.  Every lane looks up (the
+// masked table index is always inside the table) and stores the symbol, also a lane
+// that has no entry J: what it stored is cleared after the pass, so the pass has no
+// divergent branch and no per-lane test.
+template <int J>
+__device__ __forceinline__ void decode_from(LaneRecord &rec, const Tables &T, Symbols &y)
+{
+    if constexpr (J < kMaxEntries) {
+        if ((uint32_t)J >= y.nmax) return;                                  // uniform
+        constexpr int at = J % 4;
+        // identity selector with 5 at byte `at`: the symbol byte of the table entry goes there
+        constexpr uint32_t put = (0x03020100u & ~(0xffu << (8 * at))) | (5u << (8 * at));
+        const uint32_t ez = next_entry(rec.ibuf, T.ilut, T.imask);
+        const uint32_t ev = next_entry(rec.vbuf, T.vlut, T.vmask);
+        y.z[J / 4] = __builtin_amdgcn_perm(ez, y.z[J / 4], put);
+        y.v[J / 4] = __builtin_amdgcn_perm(ev, y.v[J / 4], put);
+        decode_from<J + 1>(rec, T, y);
+    }
+}
+
+// Algorithm 2 step 6 for one record: both streams are decoded in one pass - two
 // independent table chains per lane, so one lookup's latency hides behind the
 // other's - and kept in registers; positions and weights follow from them without
-// touching the tables again.
+// touching the tables again.  The pass is written out for the fifteen possible entries
+// (it ends after the wavefront's longest record), so every byte position is a constant.
+// All lanes of the wavefront must be active.
 __device__ __forceinline__ Symbols decode_record(LaneRecord rec, const Tables &T)
 {
-    Symbols y{{0, 0}, {0, 0}, rec.n, 0};
-    auto run = [&](uint64_t &zs, uint64_t &vs, uint32_t cnt) {
-        for (uint32_t j = 0; j < cnt; ++j) {
-            const uint32_t z = next_symbol(rec.ibuf, T.ilut, T.imask);
-            const uint32_t v = next_symbol(rec.vbuf, T.vlut, T.vmask);
-            zs |= (uint64_t)z << (8u * j);
-            vs |= (uint64_t)v << (8u * j);
-            y.adv += z + 1u;
-        }
-    };
-    run(y.z[0], y.v[0], min(rec.n, 8u));
-    if (rec.n > 8u) run(y.z[1], y.v[1], rec.n - 8u);
+    Symbols y{{0, 0, 0, 0}, {0, 0, 0, 0}, rec.n, wave_max(rec.n), 0};
+    decode_from<0>(rec, T, y);
+    // clear the bytes of entries a lane does not have: word w keeps its first
+    // clamp(n - 4 w, 0, 4) bytes (the shift by 8 bits per byte is done in two halves,
+    // so that four bytes shift everything out)
+    const uint32_t n4 = 4u * y.n;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if ((uint32_t)(4 * w) >= y.nmax) break;                             // uniform
+        const uint32_t half = (uint32_t)min(max((int)n4 - 16 * w, 0), 16);
+        const uint32_t drop = (0xffffffffu << half) << half;
+        y.z[w] &= ~drop;
+        y.v[w] &= ~drop;
+    }
+    // absent entries are zero bytes: the byte sums of the four words are the sum of z
+    uint32_t adv = y.n;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) adv = __builtin_amdgcn_sad_u8(y.z[w], 0u, adv);
+    y.adv = adv;
     return y;
 }
 
@@ -190,21 +237,27 @@ __device__ __forceinline__ LaneStart lane_starts(const Symbols &y, uint32_t pos0
 }
 
 // Calls f(j, v, z, position) for the record's entries in order; sum starts as the
-// lane's LaneStart::sum.
-template <class F>
+// lane's LaneStart::sum.  Written out like the decoding pass.  With ALL the call is
+// made in every lane up to the wavefront's longest record: a lane past its own last
+// entry sees v = 0, z = 0 and a position that moves on by one per call (for callers
+// to whom a zero weight at such a position does no harm); without, only for the
+// lane's own entries.
+template <bool ALL, int J, class F>
+__device__ __forceinline__ void entries_from(const Symbols &y, uint32_t pos, F &f)
+{
+    if constexpr (J < kMaxEntries) {
+        if ((uint32_t)J >= y.nmax) return;                                  // uniform
+        const uint32_t z = (y.z[J / 4] >> (8 * (J % 4))) & 0xffu, v = (y.v[J / 4] >> (8 * (J % 4))) & 0xffu;
+        pos += z + 1u;
+        if (ALL || (uint32_t)J < y.n) f((uint32_t)J, v, z, pos);
+        entries_from<ALL, J + 1>(y, pos, f);
+    }
+}
+
+template <bool ALL = false, class F>
 __device__ __forceinline__ void for_each_entry(const Symbols &y, uint32_t sum, F f)
 {
-    auto run = [&](uint64_t zs, uint64_t vs, uint32_t j0, uint32_t cnt) {
-        for (uint32_t j = 0; j < cnt; ++j) {
-            const uint32_t z = (uint32_t)zs & 0xffu, v = (uint32_t)vs & 0xffu;
-            zs >>= 8;
-            vs >>= 8;
-            sum += z + 1u;
-            f(j0 + j, v, z, sum - 1u);
-        }
-    };
-    run(y.z[0], y.v[0], 0u, min(y.n, 8u));
-    if (y.n > 8u) run(y.z[1], y.v[1], 8u, y.n - 8u);
+    entries_from<ALL, 0>(y, sum - 1u, f);
 }
 
 struct BlockGeom {
@@ -396,41 +449,48 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
         const Symbols y = decode_record(rec[i], s.T);
         const LaneStart st = lane_starts(y, h[i].m.pos0);
         const BlockGeom g = block_geom(L, h[i].m.blk);
-        // The entries of the record in order.  The two instantiations differ only in
-        // where the activations come from (LDS stays LDS: no generic pointers).
-        auto entries = [&](auto load_x) {
-            constexpr uint32_t kNoRow = 0xffffffffu;
-            uint32_t cur = kNoRow;
+        // The entries of the record in order, in every lane up to the wavefront's longest
+        // record: a lane past its own entries multiplies codebook entry 0 with a column
+        // of the block.  The instantiations differ in where the activations come from
+        // (LDS stays LDS: no generic pointers) and in how a position splits into row and
+        // column (shift and mask for a power-of-two block width).
+        auto entries = [&](auto load_x, auto split) {
+            uint32_t cur = 0;
             float acc[BT];
 #pragma unroll
             for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
-            for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+            for_each_entry<true>(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
                 uint32_t r, cc;
-                split_pos(pos, g, r, cc);
+                split(pos, r, cc);
                 if (r != cur) {
-                    if (cur != kNoRow) {
 #pragma unroll
-                        for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
+                    for (int b = 0; b < BT; ++b) {
+                        atomicAdd(ytile + b * L.bh + cur, acc[b]);
+                        acc[b] = 0.0f;
                     }
-#pragma unroll
-                    for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
                     cur = r;
                 }
                 const float w = s.T.cb[v];
 #pragma unroll
                 for (int b = 0; b < BT; ++b) acc[b] += w * load_x(b, (int)cc);
             });
-            if (cur != kNoRow) {
 #pragma unroll
-                for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
+            for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
+        };
+        auto with_split = [&](auto load_x) {
+            if (g.shift >= 0) {
+                const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u, rmax = (uint32_t)g.bhp - 1u;
+                entries(load_x, [&](uint32_t pos, uint32_t &r, uint32_t &cc) { r = min(pos >> sh, rmax); cc = pos & cmask; });
+            } else {
+                entries(load_x, [&](uint32_t pos, uint32_t &r, uint32_t &cc) { split_pos(pos, g, r, cc); });
             }
         };
         if (slab) {
             const int xoff = g.col_id - col_a;
-            entries([&](int b, int cc) { return xs[b * xcap + (xoff + cc)]; });
+            with_split([&](int b, int cc) { return xs[b * xcap + (xoff + cc)]; });
         } else {
             const float *xg = X + g.col_id;
-            entries([&](int b, int cc) { return xg[(size_t)b * L.K + cc]; });
+            with_split([&](int b, int cc) { return xg[(size_t)b * L.K + cc]; });
         }
     }
     __syncthreads();
