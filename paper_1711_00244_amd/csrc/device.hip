@@ -603,15 +603,30 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
     const int k = xt_row_to_k((int)blockIdx.y, bw, K);      // (c, r, s) of this row, or a padding row
     const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
     const int pq = cg.P * cg.Q;
-    for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < Np; n += gridDim.x * blockDim.x) {
-        float v = 0.0f;
-        if (n < n_cols && k >= 0) {
-            const int img = n / pq, o = n - img * pq;
-            const int y = (o / cg.Q) * cg.stride - cg.pad + r, x = (o % cg.Q) * cg.stride - cg.pad + s;
-            if (y >= 0 && y < cg.H && x >= 0 && x < cg.W)
-                v = X[(((size_t)img * cg.C + (c0 + c)) * cg.H + y) * cg.W + x];
+    const size_t plane = (size_t)cg.H * cg.W;
+    const float *xc = X + (size_t)(c0 + c) * plane;         // the row's channel in image 0
+    float4 *row = (float4 *)(XT + (size_t)blockIdx.y * Np);
+    // a thread writes four consecutive columns (Np is a multiple of the 32-column
+    // accumulator): output pixel and image are divided out once and stepped from there
+    for (int n4 = blockIdx.x * blockDim.x + threadIdx.x; n4 < Np / 4; n4 += gridDim.x * blockDim.x) {
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        const int n = 4 * n4;
+        if (k >= 0 && n < n_cols) {
+            int img = n / pq;
+            const int o = n - img * pq;
+            int oy = o / cg.Q, ox = o - oy * cg.Q;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int y = oy * cg.stride - cg.pad + r, x = ox * cg.stride - cg.pad + s;
+                if (n + i < n_cols && y >= 0 && y < cg.H && x >= 0 && x < cg.W)
+                    v[i] = xc[(size_t)img * cg.C * plane + (size_t)y * cg.W + x];
+                if (++ox == cg.Q) {
+                    ox = 0;
+                    if (++oy == cg.P) { oy = 0; ++img; }
+                }
+            }
         }
-        XT[(size_t)blockIdx.y * Np + n] = v;
+        row[n4] = make_float4(v[0], v[1], v[2], v[3]);
     }
 }
 
@@ -1742,7 +1757,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
                 hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8)), dim3(256), 0, st,
                                    x, (uint16_t *)xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np));
             else
-                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np + 255) / 256, 1024), (unsigned)(L->nbw * kTile)), dim3(256), 0, st,
+                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np / 4 + 255) / 256, 1024), (unsigned)(L->nbw * kTile)), dim3(256), 0, st,
                                    x, (float *)xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K);
             HIP_TRY(hipGetLastError());
             const int panel0 = grp * P.panels_per_group;
