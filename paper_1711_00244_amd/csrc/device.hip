@@ -16,6 +16,7 @@
 #include <type_traits>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 
@@ -1400,11 +1401,29 @@ int32_t plan_mfma(const cl_layer *L, int batch, bool bf16, const DeviceLimits &d
 }
 
 // Launches the dense-tile kernel for `panels` block rows from panel0 over np padded columns.
+// Raises a kernel's dynamic LDS limit when a launch needs more than any before it on
+// this device (the attribute sticks; asking again for every launch costs a runtime
+// call each time).  `seen` belongs to one kernel instantiation.
+constexpr int kMaxDevices = 64;
+struct LdsLimit { std::atomic<size_t> bytes[kMaxDevices]; };
+
+static int32_t ensure_lds(const void *kernel, size_t lds, LdsLimit &seen)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (tracked && seen.bytes[dev].load(std::memory_order_relaxed) >= lds) return CL_OK;
+    HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (tracked) seen.bytes[dev].store(lds, std::memory_order_relaxed);
+    return CL_OK;
+}
+
 template <int NQ>
 int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int panel0, size_t lds, const float *xt, float *part,
                        hipStream_t st)
 {
-    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_kernel<NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    static LdsLimit seen;
+    if (int32_t rc = ensure_lds((const void *)fc_mfma_kernel<NQ>, lds, seen)) return rc;
     hipLaunchKernelGGL(fc_mfma_kernel<NQ>, dim3((unsigned)(panels * splits * (np / MfmaShape<NQ>::kImages))),
                        dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panel0);
     HIP_TRY(hipGetLastError());
@@ -1415,7 +1434,8 @@ template <int NQ>
 int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int panel0, size_t lds, const uint16_t *xb,
                        size_t plane_elems, float *part, hipStream_t st)
 {
-    HIP_TRY(hipFuncSetAttribute((const void *)fc_mfma_bf16_kernel<NQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    static LdsLimit seen;
+    if (int32_t rc = ensure_lds((const void *)fc_mfma_bf16_kernel<NQ>, lds, seen)) return rc;
     hipLaunchKernelGGL(fc_mfma_bf16_kernel<NQ>, dim3((unsigned)(panels * splits * (np / Bf16Shape<NQ>::kImages))),
                        dim3(Bf16Shape<NQ>::kThreads), lds, st, D, xb, part, splits, np, panel0, plane_elems);
     HIP_TRY(hipGetLastError());
