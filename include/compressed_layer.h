@@ -247,8 +247,9 @@ int32_t cl_conv_workspace_bytes(const cl_layer *layer, const cl_conv_desc *conv,
 
 /* d_X: batch x C x H x W fp32 (NCHW); d_Y: batch x out_channels x P x Q fp32 with
  * P = (H + 2 pad - R) / stride + 1, Q likewise.  The receptive fields are written
- * out as columns (Sec. III-A) in the workspace, at most 256 MiB of them at a time,
- * and multiplied on an MFMA path: path is CL_PATH_AUTO (= CL_PATH_MFMA_F32),
+ * out as columns (Sec. III-A) in the workspace, one matrix per filter group and at
+ * most 1 GiB of them at a time (the batch is cut into image groups accordingly),
+ * and multiplied on an MFMA path, all filter groups in one launch: path is CL_PATH_AUTO (= CL_PATH_MFMA_F32),
  * CL_PATH_MFMA_F32 or CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are
  * blocks above 128 x 128 and, with groups > 1, a block_h that does not divide
  * out_channels / groups. */

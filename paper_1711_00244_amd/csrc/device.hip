@@ -598,9 +598,11 @@ struct ConvGeom {
     int C, H, W, R, S, stride, pad, Cg, P, Q;
 };
 
-__global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, int c0,
+__global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, size_t x_stride,
                                                          int n_cols, int Np, int bw, int K)
 {
+    const int c0 = (int)blockIdx.z * cg.Cg;                 // filter group blockIdx.z: its input channels, its matrix
+    XT += (size_t)blockIdx.z * x_stride;
     const int k = xt_row_to_k((int)blockIdx.y, bw, K);      // (c, r, s) of this row, or a padding row
     const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
     const int pq = cg.P * cg.Q;
@@ -774,7 +776,7 @@ template <> __device__ __forceinline__ void load_floats<1>(const float *p, float
 
 template <int NQ>
 __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
-                                                                         int splits, int Bp, int panel0)
+                                                                         int splits, int Bp, int panels_per_x, size_t x_stride)
 {
     constexpr int kMfmaDecoders = MfmaShape<NQ>::kDecoders;
     constexpr int kMfmaThreads = MfmaShape<NQ>::kThreads;
@@ -787,7 +789,10 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
-    const int p = panel0 + pj / splits, j = pj % splits;     // part slots are numbered from panel0
+    const int p = pj / splits, j = pj % splits;
+    // every panels_per_x block rows have an activation matrix of their own, x_stride
+    // elements after the one before (the filter groups of a convolution)
+    XT += (size_t)(p / panels_per_x) * x_stride;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const bool producer = wave >= 4;
@@ -932,9 +937,11 @@ __global__ __launch_bounds__(256) void split_pad_kernel(const float *__restrict_
 }
 
 // the same for a convolution: column = image * P*Q + output pixel, k = (c*R + r)*S + s
-__global__ __launch_bounds__(256) void im2col_split_kernel(const float *__restrict__ X, uint16_t *XB, ConvGeom cg, int c0,
+__global__ __launch_bounds__(256) void im2col_split_kernel(const float *__restrict__ X, uint16_t *XB, ConvGeom cg, size_t x_stride,
                                                            int n_cols, int Np, int bw, int K, size_t plane_elems)
 {
+    const int c0 = (int)blockIdx.z * cg.Cg;
+    XB += (size_t)blockIdx.z * x_stride;
     const int g = blockIdx.y, kq = (int)(threadIdx.x & 3);
     const int pq = cg.P * cg.Q;
     for (int col = blockIdx.x * 64 + (int)(threadIdx.x >> 2); col < Np; col += gridDim.x * 64) {
@@ -982,8 +989,8 @@ constexpr int kHStride = kTile + 8;                       // bf16 per row of a h
 constexpr int kBf16BufFloats = 2 * kTile * kHStride / 2;  // floats per buffer: hi tile + lo tile
 template <int NQ>
 __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(LayerDev L, const uint16_t *__restrict__ XB,
-                                                                             float *part, int splits, int Bp, int panel0,
-                                                                             size_t plane_elems)
+                                                                             float *part, int splits, int Bp, size_t plane_elems,
+                                                                             int panels_per_x, size_t x_stride)
 {
     using S = Bf16Shape<NQ>;
     constexpr int kDec = S::kDecoders, kNThreads = S::kThreads, kAhead = S::kAhead, kImages = S::kImages;
@@ -997,7 +1004,8 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
-    const int p = panel0 + pj / splits, j = pj % splits;
+    const int p = pj / splits, j = pj % splits;
+    XB += (size_t)(p / panels_per_x) * x_stride;            // one pair of planes per filter group
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     store_tables(s, L, fetch_tables(L));
@@ -1104,12 +1112,11 @@ constexpr int kColTile = 32;
 
 __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const float *__restrict__ part,
                                                           const float *__restrict__ bias, float *Y, int ncols, int part_b,
-                                                          int splits, int relu, int panel0, int conv_pq, int ct)
+                                                          int splits, int relu, int conv_pq, int ct)
 {
     __shared__ float tile[kColTile][kTile + 1];
     const int ntile = (ncols + ct - 1) / ct;
-    const int pl = (int)blockIdx.x / ntile, c0 = ((int)blockIdx.x - pl * ntile) * ct;
-    const int p = panel0 + pl;
+    const int p = (int)blockIdx.x / ntile, c0 = ((int)blockIdx.x - p * ntile) * ct;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
     const size_t split_stride = (size_t)part_b * L.bh;
@@ -1117,7 +1124,7 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
         const int ci = e / L.bh, r = e - ci * L.bh;
         const int c = c0 + ci;
         if (c >= ncols || r >= bhp) continue;
-        const float *src = part + ((size_t)pl * splits * part_b + c) * L.bh + r;
+        const float *src = part + ((size_t)p * splits * part_b + c) * L.bh + r;
         float t = 0.0f;
         int j = 0;
         for (; j + 3 < splits; j += 4) {                    // four loads in flight, added in order
@@ -1400,7 +1407,6 @@ int32_t plan_mfma(const cl_layer *L, int batch, bool bf16, const DeviceLimits &d
     return CL_OK;
 }
 
-// Launches the dense-tile kernel for `panels` block rows from panel0 over np padded columns.
 // Raises a kernel's dynamic LDS limit when a launch needs more than any before it on
 // this device (the attribute sticks; asking again for every launch costs a runtime
 // call each time).  `seen` belongs to one kernel instantiation.
@@ -1419,46 +1425,49 @@ static int32_t ensure_lds(const void *kernel, size_t lds, LdsLimit &seen)
 }
 
 template <int NQ>
-int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int panel0, size_t lds, const float *xt, float *part,
-                       hipStream_t st)
+int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int panels_per_x, size_t x_stride, size_t lds,
+                       const float *xt, float *part, hipStream_t st)
 {
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)fc_mfma_kernel<NQ>, lds, seen)) return rc;
     hipLaunchKernelGGL(fc_mfma_kernel<NQ>, dim3((unsigned)(panels * splits * (np / MfmaShape<NQ>::kImages))),
-                       dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panel0);
+                       dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
 
 template <int NQ>
-int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int panel0, size_t lds, const uint16_t *xb,
-                       size_t plane_elems, float *part, hipStream_t st)
+int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int panels_per_x, size_t x_stride, size_t lds,
+                       const uint16_t *xb, size_t plane_elems, float *part, hipStream_t st)
 {
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)fc_mfma_bf16_kernel<NQ>, lds, seen)) return rc;
     hipLaunchKernelGGL(fc_mfma_bf16_kernel<NQ>, dim3((unsigned)(panels * splits * (np / Bf16Shape<NQ>::kImages))),
-                       dim3(Bf16Shape<NQ>::kThreads), lds, st, D, xb, part, splits, np, panel0, plane_elems);
+                       dim3(Bf16Shape<NQ>::kThreads), lds, st, D, xb, part, splits, np, plane_elems, panels_per_x, x_stride);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
 
-int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int panels, int splits, int np, int panel0, size_t lds,
-                    const void *xt, float *part, hipStream_t st)
+// panels block rows in one launch; each run of panels_per_x of them multiplies an
+// activation matrix of its own, x_bytes after the one before
+int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int panels, int splits, int np, int panels_per_x,
+                    size_t x_bytes, size_t lds, const void *xt, float *part, hipStream_t st)
 {
+    const size_t x_stride = x_bytes / (bf16 ? sizeof(uint16_t) : sizeof(float));
     if (bf16) {
         const size_t pe = xb_plane_elems(L, np);
         switch (nq) {
-        case 1: return launch_bf16_as<1>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
-        case 2: return launch_bf16_as<2>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
-        case 4: return launch_bf16_as<4>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
-        case 8: return launch_bf16_as<8>(D, panels, splits, np, panel0, lds, (const uint16_t *)xt, pe, part, st);
+        case 1: return launch_bf16_as<1>(D, panels, splits, np, panels_per_x, x_stride, lds, (const uint16_t *)xt, pe, part, st);
+        case 2: return launch_bf16_as<2>(D, panels, splits, np, panels_per_x, x_stride, lds, (const uint16_t *)xt, pe, part, st);
+        case 4: return launch_bf16_as<4>(D, panels, splits, np, panels_per_x, x_stride, lds, (const uint16_t *)xt, pe, part, st);
+        case 8: return launch_bf16_as<8>(D, panels, splits, np, panels_per_x, x_stride, lds, (const uint16_t *)xt, pe, part, st);
         }
     } else {
         switch (nq) {
-        case 1: return launch_mfma_as<1>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
-        case 2: return launch_mfma_as<2>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
-        case 4: return launch_mfma_as<4>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
-        case 8: return launch_mfma_as<8>(D, panels, splits, np, panel0, lds, (const float *)xt, part, st);
+        case 1: return launch_mfma_as<1>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, st);
+        case 2: return launch_mfma_as<2>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, st);
+        case 4: return launch_mfma_as<4>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, st);
+        case 8: return launch_mfma_as<8>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, st);
         }
     }
     return fail(CL_EINVAL, "internal: no dense-tile kernel for %d accumulators", nq);
@@ -1558,11 +1567,11 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     }
     HIP_TRY(hipGetLastError());
     timing_begin(st);
-    if (int32_t rc = launch_mfma(L, D, bf16, P.nq, L->n_panels, P.splits, P.Bp, 0, P.lds, ws, part, st)) return rc;
+    if (int32_t rc = launch_mfma(L, D, bf16, P.nq, L->n_panels, P.splits, P.Bp, L->n_panels, 0, P.lds, ws, part, st)) return rc;
     timing_end(st, 1);
     const int ct = reduce_col_tile(L->n_panels, batch);
     hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((batch + ct - 1) / ct))), dim3(256), 0, st,
-                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, 0, 0, ct);
+                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, 0, ct);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -1683,9 +1692,9 @@ extern "C" int32_t cl_last_kernel_ms(float *ms, int32_t *launches)
 namespace {
 
 // Launch shape of the convolution path: the batch is cut into groups of images whose
-// column matrix stays under kConvXtCap bytes; each group of images and each filter
-// group is one matrix product on the MFMA path.
-constexpr size_t kConvXtCap = (size_t)256 << 20;
+// column matrices (one per filter group) stay under kConvXtCap bytes; each group of
+// images is one launch of the MFMA path over the block rows of all filter groups.
+constexpr size_t kConvXtCap = (size_t)1024 << 20;
 
 struct ConvPlan {
     ConvGeom cg{};
@@ -1712,7 +1721,7 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     P.OCg = cv->out_channels / cv->groups;
     if (cv->groups > 1 && P.OCg % L->desc.block_h) return fail(CL_EUNSUPPORTED, "block_h %d must divide the %d filters of a group", L->desc.block_h, P.OCg);
     P.panels_per_group = (P.OCg + L->desc.block_h - 1) / L->desc.block_h;
-    const size_t per_image = xt_rows(L) * g.P * g.Q * sizeof(float);
+    const size_t per_image = (size_t)cv->groups * xt_rows(L) * g.P * g.Q * sizeof(float);
     P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
     P.lds = mfma_lds_bytes(L, bf16);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
@@ -1721,9 +1730,9 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
         int nq, np, splits;
-        mfma_shape(L, P.panels_per_group, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits);
-        P.xt_bytes = std::max(P.xt_bytes, xt_bytes_for(L, np, bf16));
-        P.part_bytes = std::max(P.part_bytes, (size_t)P.panels_per_group * splits * np * L->desc.block_h * sizeof(float));
+        mfma_shape(L, L->n_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits);
+        P.xt_bytes = std::max(P.xt_bytes, (size_t)cv->groups * xt_bytes_for(L, np, bf16));
+        P.part_bytes = std::max(P.part_bytes, (size_t)L->n_panels * splits * np * L->desc.block_h * sizeof(float));
     }
     return CL_OK;
 }
@@ -1769,26 +1778,27 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const int nb = std::min(P.imgs, batch - b0);
         const int ncols = nb * pq;
         int nq, Np, splits;
-        mfma_shape(L, P.panels_per_group, ncols, dl.cus, bf16, nq, Np, splits);
+        mfma_shape(L, L->n_panels, ncols, dl.cus, bf16, nq, Np, splits);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
-        for (int grp = 0; grp < cv->groups; ++grp) {
-            if (bf16)
-                hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8)), dim3(256), 0, st,
-                                   x, (uint16_t *)xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np));
-            else
-                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np / 4 + 255) / 256, 1024), (unsigned)(L->nbw * kTile)), dim3(256), 0, st,
-                                   x, (float *)xt, g, grp * g.Cg, ncols, Np, L->desc.block_w, K);
-            HIP_TRY(hipGetLastError());
-            const int panel0 = grp * P.panels_per_group;
-            if (!timed) timing_begin(st);
-            if (int32_t rc = launch_mfma(L, D, bf16, nq, P.panels_per_group, splits, Np, panel0, P.lds, xt, part, st)) return rc;
-            if (!timed) { timing_end(st, 1); timed = true; }
-            const int ct = reduce_col_tile(P.panels_per_group, ncols);
-            hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(P.panels_per_group * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
-                               D, part, d_bias, y, ncols, Np, splits, relu, panel0, pq, ct);
-            HIP_TRY(hipGetLastError());
-        }
+        // all filter groups in one launch of each kernel: group grp has its column matrix
+        // at xt + grp * x_bytes and multiplies block rows grp * panels_per_group onwards
+        const size_t x_bytes = xt_bytes_for(L, Np, bf16);
+        const unsigned groups = (unsigned)cv->groups;
+        if (bf16)
+            hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8), groups), dim3(256), 0, st,
+                               x, (uint16_t *)xt, g, x_bytes / sizeof(uint16_t), ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np));
+        else
+            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np / 4 + 255) / 256, 1024), (unsigned)(L->nbw * kTile), groups), dim3(256), 0, st,
+                               x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K);
+        HIP_TRY(hipGetLastError());
+        if (!timed) timing_begin(st);
+        if (int32_t rc = launch_mfma(L, D, bf16, nq, L->n_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st)) return rc;
+        if (!timed) { timing_end(st, 1); timed = true; }
+        const int ct = reduce_col_tile(L->n_panels, ncols);
+        hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
+                           D, part, d_bias, y, ncols, Np, splits, relu, pq, ct);
+        HIP_TRY(hipGetLastError());
     }
     clear_error();
     return CL_OK;

@@ -275,6 +275,24 @@ def test_vgg16_conv_layers_full_size(li):
     L.free()
 
 
+def test_conv_batch_cut_into_image_groups():
+    """A batch whose column matrices exceed the library's limit (1 GiB) runs as
+    several image groups, the last one smaller: VGG-16 conv1_2 (128 MB of columns per
+    image) with 9 images; outputs of sampled filters and images against the oracle."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(6, 1)
+    g = spec.conv
+    L, m, oW = check_decode(W, spec.r, spec.k, 128, 128)
+    B = 9
+    X = wl.activations(6, B, layer_index=1)
+    Y = cl.compressed_conv_forward(L, g, torch.from_numpy(X).cuda(), relu=True).cpu().numpy()
+    rows = np.array([3, 40])
+    imgs = [0, 7, 8]                                   # first group, its last image, the second group
+    ref = oracle.conv_forward(np.ascontiguousarray(oW[rows]), np.ascontiguousarray(X[imgs]), dict(g, OC=len(rows)), relu=True, nthreads=8)
+    assert rel_err(Y[imgs][:, rows], ref) <= TOL
+    L.free()
+
+
 def test_conv_rejects_mismatched_layer():
     torch = torch_cuda()
     L = cl.compress_layer(np.ones((6, 75), np.float32), 5, 4, 6, 75, upload=True)
