@@ -558,7 +558,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kTile = 128;               // block rows, block columns and images per workgroup tile
 
 // The activations as the dense-tile kernel reads them: XT[row][b] with the image axis
-// padded to Bp (a multiple of kTile) and the K axis laid out block by block, every block
+// padded to Bp (whole image tiles of the kernel) and the K axis laid out block by block, every block
 // column of the layer taking kTile rows: row = (k / bw) * kTile + k % bw holds X[b][k],
 // the other rows and the padded images are zero.  A wavefront's walk over the blocks
 // of a block row is then a walk over consecutive rows whatever the block width.
@@ -633,32 +633,26 @@ __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict
     }
 }
 
-// Workgroup (block row p, split j, image tile nb) of twelve wavefronts with two roles.
-//   Producers (wavefronts 4-11, two next to each consumer on a SIMD: a lone decoder's
-//   dependent chains issue too slowly to keep up) decode block i + 1 - a chunk per wavefront, decode /
-//   scan / use as in the sparse kernel - and write each entry's weight at its place
-//   in a 128 x 128 fp32 tile in LDS, row by row (Algorithm 2 steps 5-9: decode, prefix
-//   sum, codebook look-up, "arrange as bh x bw block").
-//   Consumers (wavefronts 0-3) multiply block i on the matrix cores (step 12) with
-//   v_mfma_f32_32x32x2_f32, the images on the instruction's row axis and the weights on
-//   its column axis: wavefront w owns weight rows 32 w .. 32 w + 31 of the block row and
-//   all 128 images of the tile in four 32 x 32 accumulators; accumulator q holds images
-//   4 m + q (m = 0 .. 31), so that a lane's four A values are one 16-byte load.  The two
-//   k values of step s are s (lanes 0-31) and 64 + s (lanes 32-63): a lane walks
-//   consecutive columns of its weight row and reads four steps of B values with one
-//   16-byte LDS load, and its A values from consecutive rows of XT, kBPrefetch steps
-//   ahead of the multiplies.
-// Two weight tiles alternate; a consumer clears its own 32 rows of a tile when it is
-// done with it, so a tile is always clean when the producers get it back.
+// Workgroup (block row p, split j of its blocks, image tile nb) of wavefronts in two roles.
+//   Decoders (wavefronts 4 and up, one or two next to each multiplier on a SIMD) decode
+//   block i + 1 - a chunk per wavefront, decode / scan / use as in the sparse kernel -
+//   and write each entry's weight at its place in a 128 x 128 tile in LDS, row by row
+//   (Algorithm 2 steps 5-9: decode, prefix sum, codebook look-up, "arrange as bh x bw
+//   block").
+//   Multipliers (wavefronts 0-3) multiply block i on the matrix cores (step 12); how
+//   the tile and the images are divided among them is the kernel's own business.
+// Two weight tiles alternate; a used tile is cleared by the multipliers, so a tile
+// is always clean when the decoders get it back.
 constexpr int kWStride = kTile + 4;      // floats per weight row of a tile (16-byte rows, 4-bank skew)
 constexpr int kWTileBytes = kTile * kWStride * 4;
 // The decoder wavefronts' side of the dense-tile kernels: decode the blocks blk_lo ..
 // blk_hi - 1 of block row pb0 / nbw into the two alternating 128 x kWStride tiles of
 // 32-bit words, one block ahead of the multipliers, meeting them at one barrier per
 // block.  The two buffers are BUF_FLOATS floats apart; store(buffer, row, column, v)
-// places value index v (the codebook entry, or its two bf16 halves in two half tiles).  With CLEAR_BARRIER the multipliers clear a used tile
-// between two barriers (their rows are shared), else right after their last read of
-// their own rows.  Called by wavefronts 4 .. 4 + DEC - 1.
+// places value index v (the codebook entry, or its two bf16 halves in two half
+// tiles).  With CLEAR_BARRIER the multipliers clear a used tile between two barriers
+// (their rows are shared), else right after their last read of their own rows.
+// Called by wavefronts 4 .. 4 + DEC - 1.
 template <int DEC, bool CLEAR_BARRIER, int BUF_FLOATS, class Store>
 __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, float *tiles, int blk_lo, int blk_hi, uint32_t pb0,
                                              int wave, int lane, Store store)
