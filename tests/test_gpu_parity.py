@@ -275,6 +275,38 @@ def test_vgg16_conv_layers_full_size(li):
     L.free()
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_random_layers_all_paths(seed):
+    """Seeded random layers - shape, block size (also 1-wide and non-power-of-two),
+    density 0 to 1, code widths 1 to 8 - decoded bit-exact and multiplied on every
+    path that takes them, three batch sizes each, against the oracle."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(8):
+        M, K = int(rng.integers(1, 700)), int(rng.integers(1, 900))
+        bh = int(rng.choice([1, 7, 16, 32, 64, 100, 128]))
+        bw = int(rng.choice([1, 5, 16, 48, 64, 128]))
+        d = float(rng.choice([0.0, 0.01, 0.05, 0.1, 0.3, 0.7, 1.0]))
+        r, k = int(rng.choice([1, 3, 5, 8])), int(rng.choice([1, 2, 4, 5, 8]))
+        case = dict(M=M, K=K, bh=bh, bw=bw, d=d, r=r, k=k)
+        L, m, oW = check_decode(rand_pruned(rng, M, K, d), r, k, bh, bw)
+        for B in rng.choice([1, 2, 3, 4, 5, 8, 17, 33, 64, 100, 129, 257], size=3, replace=False):
+            B = int(B)
+            X = np.maximum(rng.standard_normal((B, K)), 0).astype(np.float32)
+            bias = rng.standard_normal(M).astype(np.float32) * 0.1
+            ref = oracle.fc_forward(oW, X, bias, True, nthreads=8)
+            Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
+            for path in (cl.PATH_AUTO, cl.PATH_SPARSE, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16):
+                if path == cl.PATH_SPARSE and B > 64:
+                    continue
+                tol = TOL
+                if path == cl.PATH_MFMA_BF16:
+                    tol = bf16x3_bound(oracle.fc_forward(np.abs(oW), np.abs(X), nthreads=8), ref)
+                Y = cl.compressed_fc_forward(L, Xd, bd, relu=True, path=path)
+                assert rel_err(Y.cpu().numpy(), ref) <= tol, (case, B, path)
+        L.free()
+
+
 def test_conv_batch_cut_into_image_groups():
     """A batch whose column matrices exceed the library's limit (1 GiB) runs as
     several image groups, the last one smaller: VGG-16 conv1_2 (128 MB of columns per
