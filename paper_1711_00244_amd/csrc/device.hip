@@ -109,6 +109,17 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// W consecutive floats (W * 4-byte aligned) with one load.
+template <int W> __device__ __forceinline__ void load_floats(const float *p, float *dst)
+{
+    typedef float vec_t __attribute__((ext_vector_type(W)));
+    const vec_t v = *(const vec_t *)p;
+#pragma unroll
+    for (int i = 0; i < W; ++i) dst[i] = v[i];
+}
+
+template <> __device__ __forceinline__ void load_floats<1>(const float *p, float *dst) { dst[0] = *p; }
+
 // Decode tables and codebook in LDS.
 struct Tables {
     const lut_t *vlut;
@@ -428,7 +439,7 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     }
     const TableRegs tr = fetch_tables(L);
     float *ytile = s.extra;                  // [BT][bh]
-    float *xs = ytile + (size_t)L.bh * BT;   // [BT][xcap]
+    float *xs = ytile + (size_t)L.bh * BT;   // [xcap][BT]: a column's BT images side by side, one LDS read per entry
     // activation columns of the blocks this workgroup's chunks belong to
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     const uint32_t c_last = min(pc1, my0 + (uint32_t)(kWaves * kSparseChunksPerWave)) - 1u;
@@ -439,7 +450,7 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     if (slab) {
 #pragma unroll
         for (int b = 0; b < BT; ++b)
-            for (int t = threadIdx.x; t < width; t += blockDim.x) xs[b * xcap + t] = X[(size_t)b * L.K + col_a + t];
+            for (int t = threadIdx.x; t < width; t += blockDim.x) xs[t * BT + b] = X[(size_t)b * L.K + col_a + t];
     }
     for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
     store_tables(s, L, tr);
@@ -472,8 +483,10 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
                     cur = r;
                 }
                 const float w = s.T.cb[v];
+                float x[BT];
+                load_x((int)cc, x);
 #pragma unroll
-                for (int b = 0; b < BT; ++b) acc[b] += w * load_x(b, (int)cc);
+                for (int b = 0; b < BT; ++b) acc[b] += w * x[b];
             });
 #pragma unroll
             for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
@@ -488,10 +501,17 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
         };
         if (slab) {
             const int xoff = g.col_id - col_a;
-            with_split([&](int b, int cc) { return xs[b * xcap + (xoff + cc)]; });
+            with_split([&](int cc, float (&x)[BT]) {
+                constexpr int kW = BT < 4 ? BT : 4;
+#pragma unroll
+                for (int q = 0; q < BT / kW; ++q) load_floats<kW>(xs + (xoff + cc) * BT + q * kW, x + q * kW);
+            });
         } else {
             const float *xg = X + g.col_id;
-            with_split([&](int b, int cc) { return xg[(size_t)b * L.K + cc]; });
+            with_split([&](int cc, float (&x)[BT]) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) x[b] = xg[(size_t)b * L.K + cc];
+            });
         }
     }
     __syncthreads();
@@ -757,16 +777,6 @@ template <int NQ> struct MfmaShape {
     static constexpr int kVecW = NQ < 4 ? NQ : 4;                             // floats per load
     static constexpr int kVecs = NQ / kVecW;                                  // loads per k-step
 };
-
-template <int W> __device__ __forceinline__ void load_floats(const float *p, float *dst)
-{
-    typedef float vec_t __attribute__((ext_vector_type(W)));
-    const vec_t v = *(const vec_t *)p;
-#pragma unroll
-    for (int i = 0; i < W; ++i) dst[i] = v[i];
-}
-
-template <> __device__ __forceinline__ void load_floats<1>(const float *p, float *dst) { dst[0] = *p; }
 
 template <int NQ>
 __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
