@@ -521,9 +521,11 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
 
 // Finishes the sparse path: adds up the partial tiles of each block row in a fixed
 // order, then bias and activation (Eq. 1): Y[b][row] = act(sum_j part[p][j][b][r] + v[row]).
-// One workgroup per (block row, image).  The kSlices thread groups each add every
-// kSlices-th tile (several loads in flight), LDS adds the slices in order.
-constexpr int kRedThreads = 256, kSlices = 4;
+// One workgroup per (block row, image).  The kernel is a chain of memory latencies and
+// nothing else, so it is laid out to have few links: the threads form as many groups
+// (slices) as fit next to one pass over the rows, slice s adds slots s, s + slices, ...
+// with twelve loads in flight, LDS adds the slices in order.
+constexpr int kRedThreads = 512;
 
 __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
                                                                 const float *__restrict__ bias, float *Y, int B,
@@ -536,37 +538,41 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
     // the sparse kernel fills one slot per workgroup's worth of chunks of the block row
     constexpr uint32_t kPerWg = kWaves * kSparseChunksPerWave;
     const int active = (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kPerWg - 1) / kPerWg);
-    constexpr int kRows = kRedThreads / kSlices;
-    const int sl = (int)threadIdx.x / kRows, rl = (int)threadIdx.x - sl * kRows;
+    const int rows = min(kRedThreads, (bhp + 63) / 64 * 64);        // rows per pass: whole wavefronts
+    const int slices = kRedThreads / rows;
+    const int sl = (int)threadIdx.x / rows, rl = (int)threadIdx.x - sl * rows;
     // part[p][j][image (part_b of them)][bh]
     const float *src = part + ((size_t)p * wg_per_panel * part_b + b) * L.bh;
     const size_t step = (size_t)part_b * L.bh;
-    for (int r0 = 0; r0 < bhp; r0 += kRows) {
+    for (int r0 = 0; r0 < bhp; r0 += rows) {
         const int r = r0 + rl;
         float acc = 0.0f;
-        if (r < bhp) {
-            int j = sl;
-            for (; j + 3 * kSlices < active; j += 4 * kSlices) {
-                const float a0 = src[(size_t)j * step + r], a1 = src[(size_t)(j + kSlices) * step + r];
-                const float a2 = src[(size_t)(j + 2 * kSlices) * step + r], a3 = src[(size_t)(j + 3 * kSlices) * step + r];
-                acc += a0;
-                acc += a1;
-                acc += a2;
-                acc += a3;
-            }
-            for (; j < active; j += kSlices) acc += src[(size_t)j * step + r];
-        }
-        slice_sum[threadIdx.x] = acc;
-        __syncthreads();
-        if (sl == 0 && r < bhp) {
-            float t = slice_sum[rl];
+        if (r < bhp && sl < slices) {
+            // twelve slots per round, all loads issued before the first add (a slot past
+            // the last one reads slot sl again and is not added)
+            for (int j = sl; j < active; j += 12 * slices) {
+                float a[12];
 #pragma unroll
-            for (int k = 1; k < kSlices; ++k) t += slice_sum[k * kRows + rl];
-            if (bias) t += bias[row_id + r];
-            t = relu ? fmaxf(t, 0.0f) : t;
-            Y[(size_t)b * L.M + row_id + r] = t;
+                for (int u = 0; u < 12; ++u) {
+                    const int jj = j + u * slices;
+                    a[u] = src[(size_t)(jj < active ? jj : sl) * step + r];
+                }
+#pragma unroll
+                for (int u = 0; u < 12; ++u)
+                    if (j + u * slices < active) acc += a[u];
+            }
         }
-        __syncthreads();
+        if (slices > 1) {
+            slice_sum[threadIdx.x] = acc;
+            __syncthreads();
+            if (sl == 0 && r < bhp)
+                for (int k = 1; k < slices; ++k) acc += slice_sum[k * rows + rl];
+            __syncthreads();
+        }
+        if (sl == 0 && r < bhp) {
+            if (bias) acc += bias[row_id + r];
+            Y[(size_t)b * L.M + row_id + r] = relu ? fmaxf(acc, 0.0f) : acc;
+        }
     }
 }
 
