@@ -1136,16 +1136,14 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
         if (c >= ncols || r >= bhp) continue;
         const float *src = part + ((size_t)p * splits * part_b + c) * L.bh + r;
         float t = 0.0f;
-        int j = 0;
-        for (; j + 3 < splits; j += 4) {                    // four loads in flight, added in order
-            const float a0 = src[(size_t)j * split_stride], a1 = src[(size_t)(j + 1) * split_stride];
-            const float a2 = src[(size_t)(j + 2) * split_stride], a3 = src[(size_t)(j + 3) * split_stride];
-            t += a0;
-            t += a1;
-            t += a2;
-            t += a3;
+        for (int j = 0; j < splits; j += 8) {               // eight loads in flight, added in order
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = src[(size_t)(j + u < splits ? j + u : 0) * split_stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (j + u < splits) t += a[u];
         }
-        for (; j < splits; ++j) t += src[(size_t)j * split_stride];
         if (bias) t += bias[row_id + r];
         t = relu ? fmaxf(t, 0.0f) : t;
         if (conv_pq == 0) Y[(size_t)c * L.M + row_id + r] = t;
