@@ -1,0 +1,38 @@
+// Fixed-function layers of a whole network (Table IV: pool, norm).
+// Part of the device translation unit: included by device.hip inside namespace cl,
+// in the order given there.
+#pragma once
+
+__global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ X, float *Y, int64_t n_out, int H, int W,
+                                                      int P, int Q, int size, int stride)
+{
+    for (int64_t o = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; o < n_out; o += (int64_t)gridDim.x * blockDim.x) {
+        const int q = (int)(o % Q), p = (int)((o / Q) % P);
+        const int64_t bc = o / ((int64_t)P * Q);
+        const float *x = X + (bc * H + (int64_t)p * stride) * W + (int64_t)q * stride;
+        float m = x[0];
+        for (int r = 0; r < size; ++r)
+            for (int s = 0; s < size; ++s) m = fmaxf(m, x[(int64_t)r * W + s]);
+        Y[o] = m;
+    }
+}
+
+// One thread per (image, pixel) walks the channels with a sliding sum of squares.
+__global__ __launch_bounds__(256) void lrn_kernel(const float *__restrict__ X, float *Y, int B, int C, int64_t hw, int n,
+                                                  float alpha_over_n, float beta, float k)
+{
+    const int half = n / 2;
+    for (int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; t < (int64_t)B * hw; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t b = t / hw, i = t - b * hw;
+        const float *x = X + b * C * hw + i;
+        float *y = Y + b * C * hw + i;
+        for (int c = 0; c < C; ++c) {
+            float ss = 0.0f;
+            for (int cc = max(0, c - half); cc <= min(C - 1, c + half); ++cc) {
+                const float v = x[(int64_t)cc * hw];
+                ss += v * v;
+            }
+            y[(int64_t)c * hw] = x[(int64_t)c * hw] * powf(k + alpha_over_n * ss, -beta);
+        }
+    }
+}

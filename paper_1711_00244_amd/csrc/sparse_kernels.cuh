@@ -1,0 +1,223 @@
+// decode_layer kernel and the small-batch path: fused decode + sparse multiply, and its finishing kernel.
+// Part of the device translation unit: included by device.hip inside namespace cl,
+// in the order given there.
+#pragma once
+
+// ------------------------------------------------------------------------- //
+// decode_layer: symbols and (optionally) the dense matrix
+// ------------------------------------------------------------------------- //
+__global__ __launch_bounds__(kThreads) void decode_kernel(LayerDev L, uint8_t *val_out, uint8_t *idx_out, float *dense)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    const Smem s = carve(smem_raw, L);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const uint32_t c = blockIdx.x * kWaves + (uint32_t)wave;
+    const bool have = c < L.n_chunks;
+    ChunkHead h{};
+    LaneRecord rec{};
+    if (have) {
+        h = load_head(L, c);
+        rec = load_record(L, h, lane);
+    }
+    store_tables(s, L, fetch_tables(L));
+    __syncthreads();
+    if (!have) return;
+    const Symbols y = decode_record(rec, s.T);
+    const LaneStart st = lane_starts(y, h.m.pos0);
+    const BlockGeom g = block_geom(L, h.m.blk);
+    const uint32_t e0 = h.m.sym_off + st.entry;
+    for_each_entry(y, st.sum, [&](uint32_t j, uint32_t v, uint32_t z, uint32_t pos) {
+        if (val_out) val_out[e0 + j] = (uint8_t)v;
+        if (idx_out) idx_out[e0 + j] = (uint8_t)z;
+        if (dense && v != 0 && pos < (uint32_t)g.bhp * (uint32_t)g.bwp) {
+            uint32_t r, cc;
+            split_pos(pos, g, r, cc);
+            dense[(size_t)(g.row_id + (int)r) * L.K + (size_t)(g.col_id + (int)cc)] = s.T.cb[v];
+        }
+    });
+}
+
+__global__ void fill_kernel(float *p, size_t n, float v)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// ------------------------------------------------------------------------- //
+// fused decode + sparse multiply (small batches)
+// ------------------------------------------------------------------------- //
+// Workgroup j of block row p takes chunks [8 j, 8 j + 8) of that block row, one per
+// wavefront, and accumulates w * x into an LDS tile of the bh x BT outputs of the
+// block row (Algorithm 2 step 12, b[row_id : row_id + bh, :] += block * a[col_id :
+// col_id + bw, :]); the tile then goes to the workgroup's slot of `part`, and a
+// second kernel adds the slots of a block row up.  A lane's entries run along a
+// row of the block, so it sums w * x in registers and touches the tile only when
+// the row changes.  The activation columns of the blocks the workgroup's chunks
+// belong to are staged in LDS first when they fit xcap columns; otherwise they are
+// read from global memory.  A padding entry carries codebook value 0 and adds 0.
+template <int BT>
+__global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *part,
+                                                             int wg_per_panel, int xcap)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    const Smem s = carve(smem_raw, L);
+    const int p = (int)(blockIdx.x / (uint32_t)wg_per_panel), j = (int)(blockIdx.x % (uint32_t)wg_per_panel);
+    const uint32_t pc1 = L.panel_chunk[p + 1];
+    const uint32_t my0 = L.panel_chunk[p] + (uint32_t)j * (kWaves * kSparseChunksPerWave);
+    if (my0 >= pc1) return;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    // wavefront w takes chunks my0 + w, my0 + 8 + w, ...: all their records are requested
+    // before the tables are copied
+    bool have[kSparseChunksPerWave];
+    ChunkHead h[kSparseChunksPerWave];
+    LaneRecord rec[kSparseChunksPerWave];
+#pragma unroll
+    for (int i = 0; i < kSparseChunksPerWave; ++i) {
+        const uint32_t c = my0 + (uint32_t)(i * kWaves + wave);
+        have[i] = c < pc1;
+        h[i] = ChunkHead{};
+        rec[i] = LaneRecord{};
+        if (have[i]) {
+            h[i] = load_head(L, c);
+            rec[i] = load_record(L, h[i], lane);
+        }
+    }
+    const TableRegs tr = fetch_tables(L);
+    float *ytile = s.extra;                  // [BT][bh]
+    float *xs = ytile + (size_t)L.bh * BT;   // [xcap][BT]: a column's BT images side by side, one LDS read per entry
+    // activation columns of the blocks this workgroup's chunks belong to
+    const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
+    const uint32_t c_last = min(pc1, my0 + (uint32_t)(kWaves * kSparseChunksPerWave)) - 1u;
+    const int col_a = (int)(L.meta[my0].blk - pb0) * L.bw;
+    const int col_b = min(L.K, (int)(L.meta[c_last].blk - pb0 + 1u) * L.bw);
+    const int width = col_b - col_a;
+    const bool slab = width <= xcap;
+    if (slab) {
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+            for (int t = threadIdx.x; t < width; t += blockDim.x) xs[t * BT + b] = X[(size_t)b * L.K + col_a + t];
+    }
+    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
+    store_tables(s, L, tr);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSparseChunksPerWave; ++i) {
+        if (!have[i]) continue;
+        const Symbols y = decode_record(rec[i], s.T);
+        const LaneStart st = lane_starts(y, h[i].m.pos0);
+        const BlockGeom g = block_geom(L, h[i].m.blk);
+        // The entries of the record in order, in every lane up to the wavefront's longest
+        // record: a lane past its own entries multiplies codebook entry 0 with a column
+        // of the block.  The instantiations differ in where the activations come from
+        // (LDS stays LDS: no generic pointers) and in how a position splits into row and
+        // column (shift and mask for a power-of-two block width).
+        auto entries = [&](auto load_x, auto split) {
+            uint32_t cur = 0;
+            float acc[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
+            for_each_entry<true>(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                uint32_t r, cc;
+                split(pos, r, cc);
+                if (r != cur) {
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        atomicAdd(ytile + b * L.bh + cur, acc[b]);
+                        acc[b] = 0.0f;
+                    }
+                    cur = r;
+                }
+                const float w = s.T.cb[v];
+                float x[BT];
+                load_x((int)cc, x);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) acc[b] += w * x[b];
+            });
+#pragma unroll
+            for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
+        };
+        auto with_split = [&](auto load_x) {
+            if (g.shift >= 0) {
+                const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u, rmax = (uint32_t)g.bhp - 1u;
+                entries(load_x, [&](uint32_t pos, uint32_t &r, uint32_t &cc) { r = min(pos >> sh, rmax); cc = pos & cmask; });
+            } else {
+                entries(load_x, [&](uint32_t pos, uint32_t &r, uint32_t &cc) { split_pos(pos, g, r, cc); });
+            }
+        };
+        if (slab) {
+            const int xoff = g.col_id - col_a;
+            with_split([&](int cc, float (&x)[BT]) {
+                constexpr int kW = BT < 4 ? BT : 4;
+#pragma unroll
+                for (int q = 0; q < BT / kW; ++q) load_floats<kW>(xs + (xoff + cc) * BT + q * kW, x + q * kW);
+            });
+        } else {
+            const float *xg = X + g.col_id;
+            with_split([&](int cc, float (&x)[BT]) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) x[b] = xg[(size_t)b * L.K + cc];
+            });
+        }
+    }
+    __syncthreads();
+    float *mine = part + (size_t)blockIdx.x * L.bh * BT;
+    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) mine[t] = ytile[t];
+}
+
+// Finishes the sparse path: adds up the partial tiles of each block row in a fixed
+// order, then bias and activation (Eq. 1): Y[b][row] = act(sum_j part[p][j][b][r] + v[row]).
+// One workgroup per (block row, image).  The kernel is a chain of memory latencies and
+// nothing else, so it is laid out to have few links: the threads form as many groups
+// (slices) as fit next to one pass over the rows, slice s adds slots s, s + slices, ...
+// with twelve loads in flight, LDS adds the slices in order.
+constexpr int kRedThreads = 512;
+
+__global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
+                                                                const float *__restrict__ bias, float *Y, int B,
+                                                                int part_b, int wg_per_panel, int relu)
+{
+    __shared__ float slice_sum[kRedThreads];
+    const int p = (int)blockIdx.x / B, b = (int)blockIdx.x - p * B;
+    const int row_id = p * L.bh;
+    const int bhp = min(L.bh, L.M - row_id);
+    // the sparse kernel fills one slot per workgroup's worth of chunks of the block row
+    constexpr uint32_t kPerWg = kWaves * kSparseChunksPerWave;
+    const int active = (int)((L.panel_chunk[p + 1] - L.panel_chunk[p] + kPerWg - 1) / kPerWg);
+    const int rows = min(kRedThreads, (bhp + 63) / 64 * 64);        // rows per pass: whole wavefronts
+    const int slices = kRedThreads / rows;
+    const int sl = (int)threadIdx.x / rows, rl = (int)threadIdx.x - sl * rows;
+    // part[p][j][image (part_b of them)][bh]
+    const float *src = part + ((size_t)p * wg_per_panel * part_b + b) * L.bh;
+    const size_t step = (size_t)part_b * L.bh;
+    for (int r0 = 0; r0 < bhp; r0 += rows) {
+        const int r = r0 + rl;
+        float acc = 0.0f;
+        if (r < bhp && sl < slices) {
+            // twelve slots per round, all loads issued before the first add (a slot past
+            // the last one reads slot sl again and is not added)
+            for (int j = sl; j < active; j += 12 * slices) {
+                float a[12];
+#pragma unroll
+                for (int u = 0; u < 12; ++u) {
+                    const int jj = j + u * slices;
+                    a[u] = src[(size_t)(jj < active ? jj : sl) * step + r];
+                }
+#pragma unroll
+                for (int u = 0; u < 12; ++u)
+                    if (j + u * slices < active) acc += a[u];
+            }
+        }
+        if (slices > 1) {
+            slice_sum[threadIdx.x] = acc;
+            __syncthreads();
+            if (sl == 0 && r < bhp)
+                for (int k = 1; k < slices; ++k) acc += slice_sum[k * rows + rl];
+            __syncthreads();
+        }
+        if (sl == 0 && r < bhp) {
+            if (bias) acc += bias[row_id + r];
+            Y[(size_t)b * L.M + row_id + r] = relu ? fmaxf(acc, 0.0f) : acc;
+        }
+    }
+}
