@@ -305,8 +305,9 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
         const int w = 32 * q;
         const int cols = (ncols + w - 1) / w * w;
         const int64_t tiles = (int64_t)panels * (cols / w);
-        // the split that fills the CUs, or any smaller one that needs fewer rounds
-        const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (cus + tiles - 1) / tiles));
+        // any split up to three rounds of workgroups: more, shorter workgroups can beat
+        // one round that leaves CUs idle
+        const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
         for (int sp = 1; sp <= sp_max; ++sp) {
             const int64_t rounds = (tiles * sp + cus - 1) / cus;
             const int64_t blocks = (L->nbw + sp - 1) / sp;
