@@ -193,6 +193,16 @@ class Layer:
         return buf.raw[:n.value]
 
 
+def conv_block_h(out_channels: int, groups: int, block_h: int = 128) -> int:
+    """Block height for a convolution layer: with filter groups the library wants
+    block_h to divide the filters of a group, so the largest such divisor up to
+    block_h (AlexNet conv4, 192 filters per group: 96)."""
+    per_group = out_channels // groups
+    if groups == 1 or per_group % block_h == 0:
+        return block_h
+    return max(d for d in range(1, min(block_h, per_group) + 1) if per_group % d == 0)
+
+
 def compress_layer(W, weight_bits, index_bits, block_h, block_w, codebook=None, max_code_len=0, upload=False) -> Layer:
     W = np.ascontiguousarray(W, np.float32)
     if W.ndim != 2:

@@ -59,9 +59,7 @@ def main(argv=None):
             spec, W = wl.layer_weights(args.config, li, density=density)
             for bh, bw in blocks:
                 if spec.conv is not None:
-                    ocg = spec.conv["OC"] // spec.conv["groups"]
-                    if spec.conv["groups"] > 1 and ocg % bh:
-                        bh = 64
+                    bh = cl.conv_block_h(spec.conv["OC"], spec.conv["groups"], bh)
                 L = cl.compress_layer(W, spec.r, spec.k, bh, bw, upload=True)
                 st = L.stats()
                 for B in (args.batches or cfg["batches"]):

@@ -167,9 +167,7 @@ def alexnet(block=(128, 128), density=None):
     def conv(li):
         spec, W = wl.layer_weights(4, li, density=density)
         g = spec.conv
-        bh = block[0]
-        if g["groups"] > 1 and (g["OC"] // g["groups"]) % bh:
-            bh = 64
+        bh = cl.conv_block_h(g["OC"], g["groups"], block[0])
         return ConvOp(spec.name, cl.compress_layer(W, spec.r, spec.k, bh, block[1], upload=True), g, (bh, block[1]))
 
     def fc(li, relu):

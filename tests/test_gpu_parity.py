@@ -165,7 +165,7 @@ def test_conv_forward_bf16_path(li):
     torch = torch_cuda()
     spec, W = wl.layer_weights(4, li)
     g = spec.conv
-    bh = 128 if g["groups"] == 1 or (g["OC"] // g["groups"]) % 128 == 0 else 64
+    bh = cl.conv_block_h(g["OC"], g["groups"])
     L, m, oW = check_decode(W, spec.r, spec.k, bh, 128)
     X = wl.activations(4, 2, layer_index=li)
     ref = oracle.conv_forward(oW, X, g, relu=True, nthreads=8)
@@ -248,8 +248,7 @@ def test_config4_alexnet_conv_layers(li):
     torch = torch_cuda()
     spec, W = wl.layer_weights(4, li)
     geom = spec.conv
-    ocg = geom["OC"] // geom["groups"]
-    bh = 128 if ocg % 128 == 0 or geom["groups"] == 1 else 64
+    bh = cl.conv_block_h(geom["OC"], geom["groups"])          # conv4: 96
     L, m, oW = check_decode(W, spec.r, spec.k, bh, 128)
     X = wl.activations(4, 2, layer_index=li)
     ref = oracle.conv_forward(oW, X, geom, relu=True, nthreads=16)
