@@ -292,3 +292,16 @@ def test_planner_rejects_bad_arguments():
     with pytest.raises(cl.CLError):
         cl.plan_batches([[1.0, float("nan")]], [1, 2], [1], [1], [0], 100, 1)
     assert cl.plan_batches([[1.0, 2.0]], [1, 2], [1000], [1000], [0], 100, 1) == (float("inf"), None)
+
+
+def test_conv_block_h_divides_a_groups_filters():
+    """The binding's choice of block height for grouped convolutions: the largest
+    divisor of the filters per group that fits the requested height."""
+    assert cl.conv_block_h(96, 1) == 128            # no groups: as asked
+    assert cl.conv_block_h(256, 2) == 128           # AlexNet conv2 / conv5: 128 filters per group
+    assert cl.conv_block_h(384, 2) == 96            # AlexNet conv4: 192 per group
+    assert cl.conv_block_h(384, 2, 64) == 64
+    assert cl.conv_block_h(14, 2) == 7
+    for oc, g, bh in [(384, 2, 128), (60, 3, 16), (26, 2, 128)]:
+        h = cl.conv_block_h(oc, g, bh)
+        assert (oc // g) % h == 0 and h <= bh
