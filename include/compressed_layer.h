@@ -230,6 +230,31 @@ int32_t cl_compressed_fc_forward(const cl_layer *layer, const float *d_X, const 
                                  float *d_Y, int32_t batch, int32_t relu, int32_t path,
                                  void *d_workspace, size_t workspace_bytes, void *stream);
 
+/* A stack of fully connected layers, layer i + 1 reading what layer i writes
+ * (Eq. 1 applied layer after layer; the FC6-8 stack of Table IV): the same kernels
+ * as cl_compressed_fc_forward, layer by layer on the given stream, with the
+ * intermediate activations kept in the workspace.  Between two layers on the
+ * dense-tile paths the finishing kernel writes the next layer's activations in the
+ * layout its multiply kernel reads (when that layer has 128-column blocks and K a
+ * multiple of 128), which saves the separate transposition; the results are the
+ * same bit for bit as those of per-layer calls.
+ *  layers          n_layers uploaded layers, layers[i]->K == layers[i-1]->M
+ *  d_X             batch x layers[0]->K fp32
+ *  d_bias_or_null  NULL, or n_layers device pointers (each M_i fp32 or NULL)
+ *  d_Y             batch x layers[n_layers-1]->M fp32, overwritten
+ *  relu_hidden     non-zero applies max(0, .) after every layer but the last
+ *  relu_last       the same for the last layer
+ *  path            CL_PATH_*, resolved per layer as in cl_compressed_fc_forward
+ *  d_workspace     at least cl_fc_stack_workspace_bytes(), 256-byte aligned
+ * Errors: CL_EINVAL (null pointers, n_layers < 1, layer sizes that do not chain,
+ * workspace too small, a layer not uploaded) - nothing is launched then. */
+int32_t cl_fc_stack_workspace_bytes(const cl_layer *const *layers, int32_t n_layers, int32_t batch, int32_t path,
+                                    size_t *out);
+int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers, int32_t n_layers, const float *d_X,
+                                       const float *const *d_bias_or_null, float *d_Y, int32_t batch,
+                                       int32_t relu_hidden, int32_t relu_last, int32_t path, void *d_workspace,
+                                       size_t workspace_bytes, void *stream);
+
 /* Convolution geometry.  The layer's matrix has M = out_channels rows and
  * K = (C / groups) * R * S columns, row oc being filter oc flattened as
  * ((c * R + r) * S + s) (Sec. III-A: filters become rows, receptive fields

@@ -21,7 +21,8 @@ CHUNK_BITS, RECORD_BITS, RECORDS_PER_CHUNK, MAX_RECORD_ENTRIES, MAX_CODE_LEN = 4
 EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
-    "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_conv_workspace_bytes",
+    "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_fc_stack_workspace_bytes",
+    "cl_compressed_fc_stack_forward", "cl_conv_workspace_bytes",
     "cl_compressed_conv_forward", "cl_plan_batches", "cl_maxpool_forward", "cl_lrn_forward",
     "cl_set_kernel_timing", "cl_last_kernel_ms",
 ]
@@ -87,6 +88,8 @@ def lib():
     L.cl_decode_layer.argtypes = [p, p, p, p, p, p]
     L.cl_fc_workspace_bytes.argtypes = [p, i32, i32, C.POINTER(sz)]
     L.cl_compressed_fc_forward.argtypes = [p, p, p, p, i32, i32, i32, p, sz, p]
+    L.cl_fc_stack_workspace_bytes.argtypes = [p, i32, i32, i32, C.POINTER(sz)]
+    L.cl_compressed_fc_stack_forward.argtypes = [p, i32, p, p, p, i32, i32, i32, i32, p, sz, p]
     L.cl_conv_workspace_bytes.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
     L.cl_compressed_conv_forward.argtypes = [p, C.POINTER(ConvDesc), p, p, p, i32, i32, i32, p, sz, p]
     L.cl_plan_batches.argtypes = [i32, p, i32, p, p, p, p, i64, i64, C.c_double, p, C.POINTER(C.c_double)]
@@ -264,6 +267,36 @@ def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().cl_compressed_fc_forward(layer.handle, _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B, int(relu), path,
                                           _dev_ptr(workspace), wbytes, _stream()))
+    return Y
+
+
+def _handles(layers):
+    return (C.c_void_p * len(layers))(*[l.handle for l in layers])
+
+
+def fc_stack_workspace_bytes(layers, batch: int, path: int = PATH_AUTO) -> int:
+    n = C.c_size_t(0)
+    _check(lib().cl_fc_stack_workspace_bytes(_handles(layers), len(layers), batch, path, C.byref(n)))
+    return n.value
+
+
+def compressed_fc_stack_forward(layers, X, biases=None, relu_hidden=True, relu_last=False, path=PATH_AUTO, out=None,
+                                workspace=None):
+    """A stack of FC layers in one call: X (B, K_0) fp32 CUDA tensor -> (B, M_last)."""
+    import torch
+    layers = list(layers)
+    if X.dtype != torch.float32 or X.dim() != 2 or X.shape[1] != layers[0].K:
+        raise ValueError(f"X must be (B, {layers[0].K}) float32")
+    B = X.shape[0]
+    Y = out if out is not None else torch.empty((B, layers[-1].M), dtype=torch.float32, device=X.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, fc_stack_workspace_bytes(layers, B, path)), dtype=torch.uint8, device=X.device)
+    bias_ptrs = None
+    if biases is not None:
+        bias_ptrs = (C.c_void_p * len(layers))(*[None if b is None else _dev_ptr(b).value for b in biases])
+    _check(lib().cl_compressed_fc_stack_forward(_handles(layers), len(layers), _dev_ptr(X), bias_ptrs, _dev_ptr(Y), B,
+                                                int(relu_hidden), int(relu_last), path, _dev_ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream()))
     return Y
 
 

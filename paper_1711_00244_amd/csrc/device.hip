@@ -24,6 +24,7 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "layer.hpp"
 
@@ -493,30 +494,43 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
     return CL_OK;
 }
 
+// One layer on a dense-tile path with launch shape P.  The input is d_X (batch x K, laid
+// out for the kernel into xt first) or, when d_X is null, already sits in xt.  The
+// output goes to d_Y as batch x M, or, with next_bp > 0, as the transposed activations
+// of a following 128-column-block layer whose image axis is padded to next_bp
+// (Y[row][next_bp], padded images zero).
+static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPlan &P, const float *d_X, void *xt, float *part,
+                              const float *d_bias, float *d_Y, int next_bp, int batch, int relu, hipStream_t st)
+{
+    const int K = L->desc.K;
+    if (d_X) {
+        if (P.bf16) {
+            hipLaunchKernelGGL(split_pad_kernel, dim3((unsigned)(L->nbw * 8), (unsigned)((P.Bp + 63) / 64)), dim3(256), 0, st,
+                               d_X, (uint16_t *)xt, batch, K, P.Bp, L->desc.block_w, xb_plane_elems(L, P.Bp));
+        } else {
+            const int rows = L->nbw * kTile;
+            hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
+                               d_X, (float *)xt, batch, K, P.Bp, L->desc.block_w, rows);
+        }
+        HIP_TRY(hipGetLastError());
+    }
+    timing_begin(st);
+    if (int32_t rc = launch_mfma(L, D, P.bf16, P.nq, L->n_panels, P.splits, P.Bp, L->n_panels, 0, P.lds, xt, part, st)) return rc;
+    timing_end(st, 1);
+    const int cols = std::max(batch, next_bp);
+    const int ct = reduce_col_tile(L->n_panels, cols);
+    hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((cols + ct - 1) / ct))), dim3(256), 0, st,
+                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, next_bp, ct, next_bp);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
 static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, bool bf16, const float *d_X,
                             const float *d_bias, float *d_Y, int batch, int relu, char *ws, hipStream_t st)
 {
     MfmaPlan P;
     if (int32_t rc = plan_mfma(L, batch, bf16, dl, P)) return rc;
-    const int K = L->desc.K;
-    float *part = (float *)(ws + P.xt_bytes);
-    if (bf16) {
-        hipLaunchKernelGGL(split_pad_kernel, dim3((unsigned)(L->nbw * 8), (unsigned)((P.Bp + 63) / 64)), dim3(256), 0, st,
-                           d_X, (uint16_t *)ws, batch, K, P.Bp, L->desc.block_w, xb_plane_elems(L, P.Bp));
-    } else {
-        const int rows = L->nbw * kTile;
-        hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
-                           d_X, (float *)ws, batch, K, P.Bp, L->desc.block_w, rows);
-    }
-    HIP_TRY(hipGetLastError());
-    timing_begin(st);
-    if (int32_t rc = launch_mfma(L, D, bf16, P.nq, L->n_panels, P.splits, P.Bp, L->n_panels, 0, P.lds, ws, part, st)) return rc;
-    timing_end(st, 1);
-    const int ct = reduce_col_tile(L->n_panels, batch);
-    hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((batch + ct - 1) / ct))), dim3(256), 0, st,
-                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, 0, ct);
-    HIP_TRY(hipGetLastError());
-    return CL_OK;
+    return run_mfma_layer(L, D, P, d_X, ws, (float *)(ws + P.xt_bytes), d_bias, d_Y, 0, batch, relu, st);
 }
 
 extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X, const float *d_bias,
@@ -541,6 +555,112 @@ extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X,
         rc = forward_sparse(L, D, dl, d_X, d_bias, d_Y, batch, relu, (float *)d_workspace, (hipStream_t)stream);
     if (rc == CL_OK) clear_error();
     return rc;
+}
+
+// ------------------------------------------------------------------------- //
+// a stack of fully connected layers (Eq. 1 layer after layer)
+// ------------------------------------------------------------------------- //
+namespace {
+
+struct StackPlan {
+    std::vector<int> path;            // per layer: the path it runs on
+    std::vector<MfmaPlan> mfma;       // per layer on a dense-tile path
+    std::vector<SparsePlan> sparse;   // per layer on the sparse path
+    std::vector<char> xt_in;          // layer reads its transposed activations straight from the layer before
+    size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0;
+    size_t total() const { return 2 * xt_bytes + part_bytes + 2 * act_bytes; }
+};
+
+size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, const DeviceLimits &dl, StackPlan &P)
+{
+    if (!layers || n < 1) return fail(CL_EINVAL, "a stack needs at least one layer");
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    if (path < CL_PATH_AUTO || path > CL_PATH_MFMA_BF16) return fail(CL_EINVAL, "unknown path %d", path);
+    P.path.assign(n, 0);
+    P.mfma.assign(n, MfmaPlan{});
+    P.sparse.assign(n, SparsePlan{});
+    P.xt_in.assign(n, 0);
+    for (int i = 0; i < n; ++i) {
+        const cl_layer *L = layers[i];
+        if (!L) return fail(CL_EINVAL, "layer %d is null", i);
+        if (i > 0 && L->desc.K != layers[i - 1]->desc.M)
+            return fail(CL_EINVAL, "layer %d takes %d inputs, layer %d gives %d outputs", i, L->desc.K, i - 1, layers[i - 1]->desc.M);
+        P.path[i] = resolve_path(L, batch, path);
+        if (is_mfma(P.path[i])) {
+            if (int32_t rc = plan_mfma(L, batch, P.path[i] == CL_PATH_MFMA_BF16, dl, P.mfma[i])) return rc;
+            P.xt_bytes = std::max(P.xt_bytes, P.mfma[i].xt_bytes);
+            P.part_bytes = std::max(P.part_bytes, round256(P.mfma[i].part_bytes));
+            // the finishing kernel of the layer before can write this layer's transposed
+            // activations itself when their row order is the plain one (128-column blocks,
+            // no ragged last block)
+            P.xt_in[i] = i > 0 && is_mfma(P.path[i - 1]) && P.path[i] == CL_PATH_MFMA_F32 && L->desc.block_w == kTile &&
+                         L->desc.K % kTile == 0;
+        } else {
+            if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P.sparse[i])) return rc;
+            P.part_bytes = std::max(P.part_bytes, round256(P.sparse[i].part_bytes));
+        }
+        if (i + 1 < n) P.act_bytes = std::max(P.act_bytes, round256((size_t)batch * L->desc.M * sizeof(float)));
+    }
+    return CL_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t cl_fc_stack_workspace_bytes(const cl_layer *const *layers, int32_t n_layers, int32_t batch, int32_t path,
+                                               size_t *out)
+{
+    if (!out) return fail(CL_EINVAL, "null argument");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    StackPlan P;
+    if (int32_t rc = plan_stack(layers, n_layers, batch, path, dl, P)) return rc;
+    *out = P.total();
+    return CL_OK;
+}
+
+extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers, int32_t n_layers, const float *d_X,
+                                                  const float *const *d_bias_or_null, float *d_Y, int32_t batch,
+                                                  int32_t relu_hidden, int32_t relu_last, int32_t path, void *d_workspace,
+                                                  size_t workspace_bytes, void *stream)
+{
+    if (!d_X || !d_Y) return fail(CL_EINVAL, "null activation pointer");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    StackPlan P;
+    if (int32_t rc = plan_stack(layers, n_layers, batch, path, dl, P)) return rc;
+    for (int i = 0; i < n_layers; ++i)
+        if (int32_t rc = require_device(layers[i])) return rc;
+    if (workspace_bytes < P.total() || (P.total() && !d_workspace))
+        return fail(CL_EINVAL, "workspace too small: %zu < %zu", workspace_bytes, P.total());
+    if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)d_workspace;
+    char *xt[2] = {ws, ws + P.xt_bytes};
+    float *part = (float *)(ws + 2 * P.xt_bytes);
+    float *act[2] = {(float *)(ws + 2 * P.xt_bytes + P.part_bytes), (float *)(ws + 2 * P.xt_bytes + P.part_bytes + P.act_bytes)};
+    const float *in = d_X;              // the layer's input as batch x K, or null when it sits in xt[i & 1]
+    for (int i = 0; i < n_layers; ++i) {
+        const cl_layer *L = layers[i];
+        const LayerDev D = make_dev(L);
+        const bool last = i + 1 == n_layers;
+        const float *bias = d_bias_or_null ? d_bias_or_null[i] : nullptr;
+        const int relu = last ? relu_last : relu_hidden;
+        float *out = last ? d_Y : act[i & 1];
+        if (is_mfma(P.path[i])) {
+            const bool to_xt = !last && P.xt_in[i + 1];
+            float *dst = to_xt ? (float *)xt[(i + 1) & 1] : out;
+            if (int32_t rc = run_mfma_layer(L, D, P.mfma[i], in, xt[i & 1], part, bias, dst, to_xt ? P.mfma[i + 1].Bp : 0, batch, relu, st))
+                return rc;
+            in = to_xt ? nullptr : out;
+        } else {
+            if (int32_t rc = forward_sparse(L, D, dl, in, bias, out, batch, relu, part, st)) return rc;
+            in = out;
+        }
+    }
+    clear_error();
+    return CL_OK;
 }
 
 // ------------------------------------------------------------------------- //
@@ -703,7 +823,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         if (!timed) { timing_end(st, 1); timed = true; }
         const int ct = reduce_col_tile(L->n_panels, ncols);
         hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
-                           D, part, d_bias, y, ncols, Np, splits, relu, pq, ct);
+                           D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0);
         HIP_TRY(hipGetLastError());
     }
     clear_error();

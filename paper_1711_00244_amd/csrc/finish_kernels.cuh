@@ -9,15 +9,18 @@
 // is one contiguous run of ct x bh floats of the partial buffer.  The host picks ct
 // so that the launch still has a few workgroups per CU.  FC output
 // rows are contiguous in Y[image][row]; a convolution's output is contiguous along
-// the pixels, Y[image][row][pixel], so its tile is turned in LDS first.
+// the pixels, Y[image][row][pixel], so its tile is turned in LDS first.  The same
+// turned form with conv_pq = the padded image count of a following layer writes the
+// output as that layer's transposed activations, XT[row][image]; columns from ncols up
+// to zero_to are then written as zeros (the padded images of that layout).
 constexpr int kColTile = 32;
 
 __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const float *__restrict__ part,
                                                           const float *__restrict__ bias, float *Y, int ncols, int part_b,
-                                                          int splits, int relu, int conv_pq, int ct)
+                                                          int splits, int relu, int conv_pq, int ct, int zero_to)
 {
     __shared__ float tile[kColTile][kTile + 1];
-    const int ntile = (ncols + ct - 1) / ct;
+    const int ntile = (max(ncols, zero_to) + ct - 1) / ct;
     const int p = (int)blockIdx.x / ntile, c0 = ((int)blockIdx.x - p * ntile) * ct;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
@@ -25,7 +28,11 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
     for (int e = threadIdx.x; e < ct * L.bh; e += blockDim.x) {
         const int ci = e / L.bh, r = e - ci * L.bh;
         const int c = c0 + ci;
-        if (c >= ncols || r >= bhp) continue;
+        if (r >= bhp) continue;
+        if (c >= ncols) {
+            if (conv_pq != 0) tile[ci][r] = 0.0f;
+            continue;
+        }
         const float *src = part + ((size_t)p * splits * part_b + c) * L.bh + r;
         float t = 0.0f;
         for (int j = 0; j < splits; j += 8) {               // eight loads in flight, added in order
@@ -46,6 +53,6 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
     for (int e = threadIdx.x; e < ct * bhp; e += blockDim.x) {
         const int r = e / ct, ci = e - r * ct;
         const int c = c0 + ci;
-        if (c < ncols) Y[((size_t)(c / conv_pq) * L.M + row_id + r) * conv_pq + (c % conv_pq)] = tile[ci][r];
+        if (c < max(ncols, zero_to)) Y[((size_t)(c / conv_pq) * L.M + row_id + r) * conv_pq + (c % conv_pq)] = tile[ci][r];
     }
 }

@@ -213,6 +213,78 @@ def test_config3_alexnet_fc_stack_batch256():
             a = torch.from_numpy(a_ref).cuda()          # each layer is fed the oracle's activations
 
 
+def _stack(dims, blocks, rng, density=0.12):
+    layers, dense = [], []
+    for (K, M), (bh, bw) in zip(zip(dims[:-1], dims[1:]), blocks):
+        L, m, oW = check_decode(rand_pruned(rng, M, K, density), 5, 4, bh, bw)
+        layers.append(L)
+        dense.append(oW)
+    return layers, dense
+
+
+@pytest.mark.parametrize("dims,blocks", [((640, 384, 256, 100), [(128, 128)] * 3),          # every hand-over in the multiply layout
+                                         ((300, 437, 200, 64), [(128, 128), (64, 48), (128, 128)]),   # none: ragged K, narrow blocks
+                                         ((256, 256), [(128, 128)])])
+@pytest.mark.parametrize("B", [1, 4, 5, 33, 256])
+def test_fc_stack_forward(dims, blocks, B):
+    """A stack of layers in one call (bias and ReLU between the layers, none after the
+    last): on the dense-tile paths bit for bit what per-layer calls give, and on every
+    path within tolerance of the oracle's chain."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(sum(dims) + B)
+    layers, dense = _stack(dims, blocks, rng)
+    n = len(layers)
+    X = np.maximum(rng.standard_normal((B, dims[0])), 0).astype(np.float32)
+    biases = [rng.standard_normal(L.M).astype(np.float32) * 0.1 for L in layers]
+    ref = X
+    for li in range(n):
+        ref = oracle.fc_forward(dense[li], ref.astype(np.float32), biases[li], li < n - 1, nthreads=8)
+    Xd, bd = torch.from_numpy(X).cuda(), [torch.from_numpy(b).cuda() for b in biases]
+    for path in (cl.PATH_AUTO, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16, cl.PATH_SPARSE):
+        Y = cl.compressed_fc_stack_forward(layers, Xd, bd, relu_hidden=True, relu_last=False, path=path)
+        a = Xd
+        for li in range(n):
+            a = cl.compressed_fc_forward(layers[li], a, bd[li], relu=li < n - 1, path=path)
+        sparse = path == cl.PATH_SPARSE or (path == cl.PATH_AUTO and B <= 4)
+        if sparse:
+            assert rel_err(Y.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= TOL, path
+        else:
+            assert torch.equal(Y, a), path
+        assert rel_err(Y.cpu().numpy(), ref) <= (2e-3 if path == cl.PATH_MFMA_BF16 else 4 * TOL), path
+    # no bias pointers at all, ReLU after the last layer too
+    Y = cl.compressed_fc_stack_forward(layers, Xd, None, relu_hidden=True, relu_last=True)
+    a = Xd
+    for li in range(n):
+        a = cl.compressed_fc_forward(layers[li], a, relu=True)
+    assert rel_err(Y.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= TOL
+    for L in layers:
+        L.free()
+
+
+def test_fc_stack_alexnet_batch256_and_errors():
+    """configs[2] at full size through the stack entry point, batch 256 and 16: the same
+    bits as per-layer calls (which the test above this one checks against the oracle);
+    layers that do not chain and a short workspace are refused."""
+    torch = torch_cuda()
+    layers = []
+    for li in range(3):
+        spec, W = wl.layer_weights(3, li)
+        layers.append(cl.compress_layer(W, spec.r, spec.k, 128, 128, upload=True))
+    for B in (256, 16):
+        Xd = torch.from_numpy(wl.activations(3, B)).cuda()
+        Y = cl.compressed_fc_stack_forward(layers, Xd)
+        a = Xd
+        for li in range(3):
+            a = cl.compressed_fc_forward(layers[li], a, relu=li < 2)
+        assert torch.equal(Y, a)
+    with pytest.raises(cl.CLError):
+        cl.compressed_fc_stack_forward([layers[2], layers[0]], torch.zeros((2, layers[2].K), device="cuda"))
+    with pytest.raises(cl.CLError):
+        cl.compressed_fc_stack_forward(layers, Xd, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    for L in layers:
+        L.free()
+
+
 SMALL_CONVS = [dict(C=3, H=19, W=19, R=5, S=5, stride=4, pad=0, groups=1, OC=6),
                dict(C=4, H=9, W=11, R=3, S=3, stride=1, pad=1, groups=2, OC=6),
                dict(C=6, H=7, W=7, R=3, S=3, stride=2, pad=2, groups=3, OC=9),
