@@ -85,13 +85,14 @@ def main():
         ys = [torch.empty((B, s.M), dtype=torch.float32, device="cuda") for s in specs]
         ws = [torch.empty(max(1, cl.fc_workspace_bytes(L, B, path)), dtype=torch.uint8, device="cuda") for L in layers]
         bufs[B] = (X, ys, ws)
+    stack_ws = {B: torch.empty(max(256, cl.fc_stack_workspace_bytes(layers, B, path)), dtype=torch.uint8, device="cuda")
+                for B in batches}
 
     def step(B):
+        # the whole stack through the library's stack entry point: fc6 -> ReLU -> fc7 -> ReLU -> fc8
         X, ys, ws = bufs[B]
-        a = X
-        for li, L in enumerate(layers):
-            a = cl.compressed_fc_forward(L, a, relu=(li < 2), path=path, out=ys[li], workspace=ws[li])
-        return a
+        return cl.compressed_fc_stack_forward(layers, X, relu_hidden=True, relu_last=False, path=path, out=ys[-1],
+                                              workspace=stack_ws[B])
 
     def timed(B, steps, warmup):
         for _ in range(warmup):
@@ -212,11 +213,10 @@ def main():
         ysb = [torch.empty_like(y) for y in ys]
         wsb = [torch.empty(max(1, cl.fc_workspace_bytes(L, B, pb)), dtype=torch.uint8, device="cuda") for L in layers]
 
+        wss = torch.empty(max(256, cl.fc_stack_workspace_bytes(layers, B, pb)), dtype=torch.uint8, device="cuda")
+
         def stepb():
-            a = X
-            for li, L in enumerate(layers):
-                a = cl.compressed_fc_forward(L, a, relu=(li < 2), path=pb, out=ysb[li], workspace=wsb[li])
-            return a
+            return cl.compressed_fc_stack_forward(layers, X, relu_hidden=True, relu_last=False, path=pb, out=ysb[2], workspace=wss)
         for _ in range(args.warmup):
             stepb()
         torch.cuda.synchronize()

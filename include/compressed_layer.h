@@ -237,7 +237,9 @@ int32_t cl_compressed_fc_forward(const cl_layer *layer, const float *d_X, const 
  * dense-tile paths the finishing kernel writes the next layer's activations in the
  * layout its multiply kernel reads (when that layer has 128-column blocks and K a
  * multiple of 128), which saves the separate transposition; the results are the
- * same bit for bit as those of per-layer calls.
+ * same bit for bit as those of per-layer calls.  The workspace holds up to four
+ * copies of each scratch buffer, used in rotation (a kernel that writes where
+ * another has just read runs slower on this chip).
  *  layers          n_layers uploaded layers, layers[i]->K == layers[i-1]->M
  *  d_X             batch x layers[0]->K fp32
  *  d_bias_or_null  NULL, or n_layers device pointers (each M_i fp32 or NULL)

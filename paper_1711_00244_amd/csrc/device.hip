@@ -518,9 +518,17 @@ static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPl
     if (int32_t rc = launch_mfma(L, D, P.bf16, P.nq, L->n_panels, P.splits, P.Bp, L->n_panels, 0, P.lds, xt, part, st)) return rc;
     timing_end(st, 1);
     const int cols = std::max(batch, next_bp);
-    const int ct = reduce_col_tile(L->n_panels, cols);
-    hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((cols + ct - 1) / ct))), dim3(256), 0, st,
-                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, next_bp, ct, next_bp);
+    // towards a following layer the output runs along the images: full 32-column tiles
+    // (128-byte runs), and the rows of a block row shared out to keep the launch wide
+    int ct = reduce_col_tile(L->n_panels, cols), rt = L->desc.block_h;
+    if (next_bp > 0) {
+        ct = kColTile;
+        rt = kTile;
+        while (rt > 32 && (int64_t)L->n_panels * ((cols + ct - 1) / ct) * ((L->desc.block_h + rt - 1) / rt) < 1024) rt >>= 1;
+    }
+    const int nrt = (L->desc.block_h + rt - 1) / rt;
+    hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((cols + ct - 1) / ct) * nrt)), dim3(256), 0, st,
+                       D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, next_bp, ct, next_bp, rt);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -568,10 +576,13 @@ struct StackPlan {
     std::vector<SparsePlan> sparse;   // per layer on the sparse path
     std::vector<char> xt_in;          // layer reads its transposed activations straight from the layer before
     size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0;
-    size_t total() const { return 2 * xt_bytes + part_bytes + 2 * act_bytes; }
+    int regions = 1;                  // copies of each buffer, used in rotation
+    size_t total() const { return (size_t)regions * (xt_bytes + part_bytes + act_bytes); }
 };
 
 size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+constexpr int kStackRegions = 4;
 
 int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, const DeviceLimits &dl, StackPlan &P)
 {
@@ -594,7 +605,7 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
             P.part_bytes = std::max(P.part_bytes, round256(P.mfma[i].part_bytes));
             // the finishing kernel of the layer before can write this layer's transposed
             // activations itself when their row order is the plain one (128-column blocks,
-            // no ragged last block)
+            // no ragged last block): 2-3 % of a step on the AlexNet-shaped stack
             P.xt_in[i] = i > 0 && is_mfma(P.path[i - 1]) && P.path[i] == CL_PATH_MFMA_F32 && L->desc.block_w == kTile &&
                          L->desc.K % kTile == 0;
         } else {
@@ -603,6 +614,7 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
         }
         if (i + 1 < n) P.act_bytes = std::max(P.act_bytes, round256((size_t)batch * L->desc.M * sizeof(float)));
     }
+    P.regions = std::min(n, kStackRegions);
     return CL_OK;
 }
 
@@ -637,25 +649,30 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
     if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)d_workspace;
-    char *xt[2] = {ws, ws + P.xt_bytes};
-    float *part = (float *)(ws + 2 * P.xt_bytes);
-    float *act[2] = {(float *)(ws + 2 * P.xt_bytes + P.part_bytes), (float *)(ws + 2 * P.xt_bytes + P.part_bytes + P.act_bytes)};
-    const float *in = d_X;              // the layer's input as batch x K, or null when it sits in xt[i & 1]
+    // Up to four of everything, used in rotation.  Two would do for the data's lifetime;
+    // more are a matter of speed: a kernel that writes where a kernel shortly before has
+    // read (the partial tiles above all) runs slower, the lines being still held by the
+    // other dies' caches - 3 % of a step at batch 256 with one buffer of partial tiles,
+    // 5 % at batch 64 with two.
+    const int R = P.regions;
+    auto region = [&](size_t base, size_t bytes, int i) { return ws + base + (size_t)(i % R) * bytes; };
+    const size_t xt0 = 0, part0 = (size_t)R * P.xt_bytes, act0 = part0 + (size_t)R * P.part_bytes;
+    const float *in = d_X;              // the layer's input as batch x K, or null when it sits in its xt region
     for (int i = 0; i < n_layers; ++i) {
         const cl_layer *L = layers[i];
         const LayerDev D = make_dev(L);
         const bool last = i + 1 == n_layers;
         const float *bias = d_bias_or_null ? d_bias_or_null[i] : nullptr;
         const int relu = last ? relu_last : relu_hidden;
-        float *out = last ? d_Y : act[i & 1];
+        float *out = last ? d_Y : (float *)region(act0, P.act_bytes, i);
         if (is_mfma(P.path[i])) {
             const bool to_xt = !last && P.xt_in[i + 1];
-            float *dst = to_xt ? (float *)xt[(i + 1) & 1] : out;
-            if (int32_t rc = run_mfma_layer(L, D, P.mfma[i], in, xt[i & 1], part, bias, dst, to_xt ? P.mfma[i + 1].Bp : 0, batch, relu, st))
+            float *dst = to_xt ? (float *)region(xt0, P.xt_bytes, i + 1) : out;
+            if (int32_t rc = run_mfma_layer(L, D, P.mfma[i], in, region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i), bias, dst, to_xt ? P.mfma[i + 1].Bp : 0, batch, relu, st))
                 return rc;
             in = to_xt ? nullptr : out;
         } else {
-            if (int32_t rc = forward_sparse(L, D, dl, in, bias, out, batch, relu, part, st)) return rc;
+            if (int32_t rc = forward_sparse(L, D, dl, in, bias, out, batch, relu, (float *)region(part0, P.part_bytes, i), st)) return rc;
             in = out;
         }
     }
@@ -823,7 +840,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         if (!timed) { timing_end(st, 1); timed = true; }
         const int ct = reduce_col_tile(L->n_panels, ncols);
         hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
-                           D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0);
+                           D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
         HIP_TRY(hipGetLastError());
     }
     clear_error();

@@ -12,23 +12,27 @@
 // the pixels, Y[image][row][pixel], so its tile is turned in LDS first.  The same
 // turned form with conv_pq = the padded image count of a following layer writes the
 // output as that layer's transposed activations, XT[row][image]; columns from ncols up
-// to zero_to are then written as zeros (the padded images of that layout).
+// to zero_to are then written as zeros (the padded images of that layout).  The rows of
+// a block row can be shared out among workgroups, rt to each (the host's choice, as ct).
 constexpr int kColTile = 32;
 
 __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const float *__restrict__ part,
                                                           const float *__restrict__ bias, float *Y, int ncols, int part_b,
-                                                          int splits, int relu, int conv_pq, int ct, int zero_to)
+                                                          int splits, int relu, int conv_pq, int ct, int zero_to, int rt)
 {
     __shared__ float tile[kColTile][kTile + 1];
-    const int ntile = (max(ncols, zero_to) + ct - 1) / ct;
-    const int p = (int)blockIdx.x / ntile, c0 = ((int)blockIdx.x - p * ntile) * ct;
+    // workgroup -> (block row, column tile, row tile of rt rows)
+    const int ntile = (max(ncols, zero_to) + ct - 1) / ct, nrt = (L.bh + rt - 1) / rt;
+    const int p = (int)blockIdx.x / (ntile * nrt), rem = (int)blockIdx.x - p * ntile * nrt;
+    const int c0 = (rem / nrt) * ct, r0 = (rem % nrt) * rt;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
+    const int r1 = min(r0 + rt, bhp);                       // this workgroup's rows are r0 .. r1 - 1
     const size_t split_stride = (size_t)part_b * L.bh;
-    for (int e = threadIdx.x; e < ct * L.bh; e += blockDim.x) {
-        const int ci = e / L.bh, r = e - ci * L.bh;
+    for (int e = threadIdx.x; e < ct * rt; e += blockDim.x) {
+        const int ci = e / rt, r = r0 + (e - ci * rt);
         const int c = c0 + ci;
-        if (r >= bhp) continue;
+        if (r >= r1) continue;
         if (c >= ncols) {
             if (conv_pq != 0) tile[ci][r] = 0.0f;
             continue;
@@ -50,8 +54,8 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
     }
     if (conv_pq == 0) return;
     __syncthreads();
-    for (int e = threadIdx.x; e < ct * bhp; e += blockDim.x) {
-        const int r = e / ct, ci = e - r * ct;
+    for (int e = threadIdx.x; e < ct * (r1 - r0); e += blockDim.x) {
+        const int r = r0 + e / ct, ci = e % ct;
         const int c = c0 + ci;
         if (c < max(ncols, zero_to)) Y[((size_t)(c / conv_pq) * L.M + row_id + r) * conv_pq + (c % conv_pq)] = tile[ci][r];
     }
