@@ -261,6 +261,27 @@ def test_fc_stack_forward(dims, blocks, B):
         L.free()
 
 
+def test_fc_stack_mixed_paths():
+    """A stack whose middle layer has 256-wide blocks: CL_PATH_AUTO runs it on the sparse
+    path between two dense-tile layers (batch 33), all three on the sparse path at
+    batch 3; against the oracle's chain."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(77)
+    dims, blocks = (384, 512, 256, 130), [(128, 128), (256, 256), (128, 128)]
+    layers, dense = _stack(dims, blocks, rng)
+    for B in (33, 3):
+        X = np.maximum(rng.standard_normal((B, dims[0])), 0).astype(np.float32)
+        ref = X
+        for li in range(3):
+            ref = oracle.fc_forward(dense[li], ref.astype(np.float32), None, li < 2, nthreads=8)
+        Y = cl.compressed_fc_stack_forward(layers, torch.from_numpy(X).cuda())
+        assert rel_err(Y.cpu().numpy(), ref) <= 4 * TOL, B
+    with pytest.raises(cl.CLError):
+        cl.compressed_fc_stack_forward(layers, torch.from_numpy(X).cuda(), path=cl.PATH_MFMA_F32)
+    for L in layers:
+        L.free()
+
+
 def test_fc_stack_alexnet_batch256_and_errors():
     """configs[2] at full size through the stack entry point, batch 256 and 16: the same
     bits as per-layer calls (which the test above this one checks against the oracle);
