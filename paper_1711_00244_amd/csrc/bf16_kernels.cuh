@@ -137,8 +137,8 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     if (wave >= 4) {
         decoder_role<kDec, true, kBf16BufFloats>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
-                                                 [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) {
-                                                     const uint32_t w = cbp[v];
+                                                 [&](uint32_t v) { return cbp[v]; },
+                                                 [&](float *tile, uint32_t r, uint32_t cc, uint32_t w) {
                                                      uint16_t *t16 = (uint16_t *)tile + __umul24(r, (uint32_t)kHStride) + cc;
                                                      t16[0] = (uint16_t)(w >> 16);
                                                      t16[kTile * kHStride] = (uint16_t)w;

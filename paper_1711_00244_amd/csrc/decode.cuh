@@ -195,6 +195,38 @@ __device__ __forceinline__ void for_each_entry(const Symbols &y, uint32_t sum, F
     entries_from<ALL, 0>(y, sum - 1u, f);
 }
 
+// The same walk over a record's entries for callers that look a value up per entry and
+// then store it: the entries are taken four at a time, the four look-ups (made in every
+// lane, value index 0 for entries a lane does not have) go out together and are waited
+// for once, then put(position, looked-up value) is called for the lane's own entries.
+template <int J, class Look, class Put>
+__device__ __forceinline__ void place_from(const Symbols &y, uint32_t pos, Look &look, Put &put)
+{
+    if constexpr (J < kMaxEntries) {
+        if ((uint32_t)J >= y.nmax) return;                                  // uniform, once per four entries
+        constexpr int G = kMaxEntries - J < 4 ? kMaxEntries - J : 4;
+        uint32_t at[G];
+        decltype(look(0u)) w[G];
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+            const uint32_t z = (y.z[J / 4] >> (8 * u)) & 0xffu, v = (y.v[J / 4] >> (8 * u)) & 0xffu;
+            pos += z + 1u;
+            at[u] = pos;
+            w[u] = look(v);
+        }
+#pragma unroll
+        for (int u = 0; u < G; ++u)
+            if ((uint32_t)(J + u) < y.n) put(at[u], w[u]);
+        place_from<J + G>(y, pos, look, put);
+    }
+}
+
+template <class Look, class Put>
+__device__ __forceinline__ void place_entries(const Symbols &y, uint32_t sum, Look look, Put put)
+{
+    place_from<0>(y, sum - 1u, look, put);
+}
+
 struct BlockGeom {
     int row_id, col_id, bhp, bwp;
     int shift;        // log2(bwp) when bwp is a power of two, else -1

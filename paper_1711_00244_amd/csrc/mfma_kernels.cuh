@@ -101,14 +101,14 @@ constexpr int kWTileBytes = kTile * kWStride * 4;
 // The decoder wavefronts' side of the dense-tile kernels: decode the blocks blk_lo ..
 // blk_hi - 1 of block row pb0 / nbw into the two alternating 128 x kWStride tiles of
 // 32-bit words, one block ahead of the multipliers, meeting them at one barrier per
-// block.  The two buffers are BUF_FLOATS floats apart; store(buffer, row, column, v)
-// places value index v (the codebook entry, or its two bf16 halves in two half
-// tiles).  With CLEAR_BARRIER the multipliers clear a used tile between two barriers
+// block.  The two buffers are BUF_FLOATS floats apart; look(v) reads what stands for
+// value index v (the codebook entry, or its two bf16 halves) and put(buffer, row,
+// column, that) places it (in the tile, or in two half tiles).  With CLEAR_BARRIER the multipliers clear a used tile between two barriers
 // (their rows are shared), else right after their last read of their own rows.
 // Called by wavefronts 4 .. 4 + DEC - 1.
-template <int DEC, bool CLEAR_BARRIER, int BUF_FLOATS, class Store>
+template <int DEC, bool CLEAR_BARRIER, int BUF_FLOATS, class Look, class Put>
 __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, float *tiles, int blk_lo, int blk_hi, uint32_t pb0,
-                                             int wave, int lane, Store store)
+                                             int wave, int lane, Look look, Put put)
 {
     // The chunks of this split's blocks are consecutive, [c_lo, c_hi); decoder
     // d = wave - 4 takes c_lo + d, c_lo + d + DEC, ... and finds a block's
@@ -169,14 +169,13 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
                 // shift and a mask, the column cannot leave the tile, and a padding
                 // entry may store its zero (codebook entry 0) like any other
                 const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u, rmax = (uint32_t)g.bhp - 1u;
-                for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-                    store(tile, min(pos >> sh, rmax), pos & cmask, v);
-                });
+                place_entries(y, st.sum, look,
+                              [&](uint32_t pos, auto w) { put(tile, min(pos >> sh, rmax), pos & cmask, w); });
             } else {
                 for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
                     uint32_t r, cc;
                     split_pos(pos, g, r, cc);
-                    if (v != 0 && cc < (uint32_t)kTile) store(tile, r, cc, v);
+                    if (v != 0 && cc < (uint32_t)kTile) put(tile, r, cc, look(v));
                 });
             }
         }
@@ -241,7 +240,8 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
 
     if (producer) {
         decoder_role<kMfmaDecoders, false, kWTileBytes / 4>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
-                                                             [&](float *tile, uint32_t r, uint32_t cc, uint32_t v) { tile[__umul24(r, (uint32_t)kWStride) + cc] = s.T.cb[v]; });
+                                                             [&](uint32_t v) { return s.T.cb[v]; },
+                                                             [&](float *tile, uint32_t r, uint32_t cc, float w) { tile[__umul24(r, (uint32_t)kWStride) + cc] = w; });
         return;
     }
 
