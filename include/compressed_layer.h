@@ -276,7 +276,11 @@ int32_t cl_conv_workspace_bytes(const cl_layer *layer, const cl_conv_desc *conv,
  * P = (H + 2 pad - R) / stride + 1, Q likewise.  The receptive fields are written
  * out as columns (Sec. III-A) in the workspace, one matrix per filter group and at
  * most 1 GiB of them at a time (the batch is cut into image groups accordingly),
- * and multiplied on an MFMA path, all filter groups in one launch: path is CL_PATH_AUTO (= CL_PATH_MFMA_F32),
+ * and multiplied on an MFMA path, all filter groups in one launch.  From 4096
+ * columns (images x output pixels) on, CL_PATH_MFMA_F32 first decodes every block
+ * of the layer once into a dense 128 x 128 tile in the workspace (64 KiB per block)
+ * and multiplies from those, instead of decoding the blocks again for every tile
+ * of columns; the results are the same bit for bit.  path: path is CL_PATH_AUTO (= CL_PATH_MFMA_F32),
  * CL_PATH_MFMA_F32 or CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are
  * blocks above 128 x 128 and, with groups > 1, a block_h that does not divide
  * out_channels / groups. */

@@ -194,6 +194,66 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
     }
 }
 
+// Every block of the layer decoded once into a dense 128 x 128 fp32 tile in device
+// memory (Algorithm 2 steps 5-9 for all blocks; rows and columns a block does not have
+// are zero): tiles_out[block][row][column].  One workgroup per block, a chunk per
+// wavefront at a time, the tile built in LDS and written out in one piece.  For layers
+// whose blocks would otherwise be decoded over and over - a convolution, where hundreds
+// of column tiles multiply the same few blocks.
+__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    const Smem s = carve(smem_raw, L);
+    float *tile = s.extra;                                  // [kTile][kTile]
+    const uint32_t b = blockIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
+    const TableRegs tr = fetch_tables(L);
+    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) ((uint4 *)tile)[t] = uint4{0, 0, 0, 0};
+    store_tables(s, L, tr);
+    __syncthreads();
+    const BlockGeom g = block_geom(L, b);
+    for (uint32_t c = c0 + (uint32_t)wave; c < c1; c += kWaves) {       // uniform per wavefront
+        const ChunkHead h = load_head(L, c);
+        const Symbols y = decode_record(load_record(L, h, lane), s.T);
+        const LaneStart st = lane_starts(y, h.m.pos0);
+        for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+            uint32_t r, cc;
+            split_pos(pos, g, r, cc);
+            if (v != 0 && cc < (uint32_t)kTile) tile[r * kTile + cc] = s.T.cb[v];
+        });
+    }
+    __syncthreads();
+    uint4 *dst = (uint4 *)(tiles_out + (size_t)b * kTile * kTile);
+    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) dst[t] = ((const uint4 *)tile)[t];
+}
+
+// The loader wavefronts' side of the dense-tile kernel when the blocks have been decoded
+// beforehand (decode_tiles_kernel): copy tile after tile from device memory into the
+// two alternating LDS tiles, one block ahead of the multipliers, meeting them at one
+// barrier per block like the decoders.  A copied tile overwrites all of the LDS tile,
+// so nothing has to be cleared.  Called by wavefronts 4 .. 4 + DEC - 1.
+template <int DEC>
+__device__ __forceinline__ void loader_role(const float *__restrict__ wt, float *tiles, int blk_lo, int blk_hi, uint32_t pb0,
+                                            int wave, int lane)
+{
+    auto fill = [&](int bi, float *tile) {
+        const float4 *src = (const float4 *)(wt + (size_t)(pb0 + (uint32_t)bi) * kTile * kTile);
+        float4 *dst = (float4 *)tile;
+#pragma unroll 8
+        for (int t = (wave - 4) * 64 + lane; t < kTile * kTile / 4; t += DEC * 64)
+            dst[(t >> 5) * (kWStride / 4) + (t & 31)] = src[t];
+    };
+    __syncthreads();
+    if (blk_lo < blk_hi) fill(blk_lo, tiles);
+    __syncthreads();
+    for (int bi = blk_lo; bi < blk_hi; ++bi) {
+        if (bi + 1 < blk_hi) fill(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
+        __syncthreads();
+    }
+}
+
 // NQ = 32 x 32 accumulators per multiplying wavefront = 32-column groups of the
 // workgroup's image tile (1, 2, 4 or 8: 32 to 256 images).  A wider tile feeds more
 // multiplies from each decoded block; a narrower one wastes fewer padded columns on a
@@ -210,9 +270,12 @@ template <int NQ> struct MfmaShape {
     static constexpr int kVecs = NQ / kVecW;                                  // loads per k-step
 };
 
-template <int NQ>
+// With DENSE the blocks come decoded from device memory (wt, written by
+// decode_tiles_kernel) and the wavefronts 4 and up only copy them into LDS.
+template <int NQ, bool DENSE>
 __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
-                                                                         int splits, int Bp, int panels_per_x, size_t x_stride)
+                                                                         int splits, int Bp, int panels_per_x, size_t x_stride,
+                                                                         const float *__restrict__ wt)
 {
     constexpr int kMfmaDecoders = MfmaShape<NQ>::kDecoders;
     constexpr int kMfmaThreads = MfmaShape<NQ>::kThreads;
@@ -221,7 +284,7 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     constexpr int kVecW = MfmaShape<NQ>::kVecW, kVecs = MfmaShape<NQ>::kVecs;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    float *tiles = (float *)s.extra;                        // [2][kTile rows][kWStride]
+    float *tiles = DENSE ? (float *)smem_raw : (float *)s.extra;      // [2][kTile rows][kWStride]; no decode tables with DENSE
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
@@ -232,13 +295,19 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const bool producer = wave >= 4;
-    if (threadIdx.x < kThreads) store_tables(s, L, fetch_tables(L));
-    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kMfmaThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
+    if (!DENSE) {
+        if (threadIdx.x < kThreads) store_tables(s, L, fetch_tables(L));
+        for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kMfmaThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
+    }
     // this split's share of the block row's blocks
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
     if (producer) {
+        if (DENSE) {
+            loader_role<kMfmaDecoders>(wt, tiles, blk_lo, blk_hi, pb0, wave, lane);
+            return;
+        }
         decoder_role<kMfmaDecoders, false, kWTileBytes / 4>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
                                                              [&](uint32_t v) { return s.T.cb[v]; },
                                                              [&](float *tile, uint32_t r, uint32_t cc, float w) { tile[__umul24(r, (uint32_t)kWStride) + cc] = w; });
@@ -296,9 +365,12 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
             // the loads of the group after next start the next block: skip this block's other half
             if (ks == kTile / 2 - 2 * kAhead) ap += (kTile / 2) * row_stride;
         }
-        // done with this tile: clear this wavefront's 32 rows of it
-        uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
-        for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
+        // done with this tile: clear this wavefront's 32 rows of it (a decoded tile must be
+        // clean for the decoders; a copied one is overwritten whole)
+        if (!DENSE) {
+            uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
+            for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
+        }
         __syncthreads();
     }
     // accumulator 4 v + q, element e of lane l: image 128 v + kVecW (8 (e / 4) + 4 (l / 32) + e % 4) + q
