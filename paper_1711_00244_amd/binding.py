@@ -22,7 +22,7 @@ EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
     "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_fc_stack_workspace_bytes",
-    "cl_compressed_fc_stack_forward", "cl_conv_workspace_bytes",
+    "cl_compressed_fc_stack_forward", "cl_conv_workspace_bytes", "cl_conv_workspace_bytes_min",
     "cl_compressed_conv_forward", "cl_plan_batches", "cl_maxpool_forward", "cl_lrn_forward",
     "cl_set_kernel_timing", "cl_last_kernel_ms",
 ]
@@ -91,6 +91,7 @@ def lib():
     L.cl_fc_stack_workspace_bytes.argtypes = [p, i32, i32, i32, C.POINTER(sz)]
     L.cl_compressed_fc_stack_forward.argtypes = [p, i32, p, p, p, i32, i32, i32, i32, p, sz, p]
     L.cl_conv_workspace_bytes.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
+    L.cl_conv_workspace_bytes_min.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
     L.cl_compressed_conv_forward.argtypes = [p, C.POINTER(ConvDesc), p, p, p, i32, i32, i32, p, sz, p]
     L.cl_plan_batches.argtypes = [i32, p, i32, p, p, p, p, i64, i64, C.c_double, p, C.POINTER(C.c_double)]
     L.cl_maxpool_forward.argtypes = [p, p] + [i32] * 6 + [p]
@@ -300,10 +301,12 @@ def compressed_fc_stack_forward(layers, X, biases=None, relu_hidden=True, relu_l
     return Y
 
 
-def conv_workspace_bytes(layer: Layer, conv: dict, batch: int, path: int = PATH_AUTO) -> int:
+def conv_workspace_bytes(layer: Layer, conv: dict, batch: int, path: int = PATH_AUTO, compact: bool = False) -> int:
+    """Scratch for the fast form of the call, or (compact) the least it works with."""
     cd = ConvDesc(conv["C"], conv["H"], conv["W"], conv["R"], conv["S"], conv["stride"], conv["pad"], conv["groups"], conv["OC"])
     n = C.c_size_t(0)
-    _check(lib().cl_conv_workspace_bytes(layer.handle, C.byref(cd), batch, path, C.byref(n)))
+    fn = lib().cl_conv_workspace_bytes_min if compact else lib().cl_conv_workspace_bytes
+    _check(fn(layer.handle, C.byref(cd), batch, path, C.byref(n)))
     return n.value
 
 

@@ -60,9 +60,9 @@ __global__ __launch_bounds__(256) void split_pad_kernel(const float *__restrict_
 
 // the same for a convolution: column = image * P*Q + output pixel, k = (c*R + r)*S + s
 __global__ __launch_bounds__(256) void im2col_split_kernel(const float *__restrict__ X, uint16_t *XB, ConvGeom cg, size_t x_stride,
-                                                           int n_cols, int Np, int bw, int K, size_t plane_elems)
+                                                           int n_cols, int Np, int bw, int K, size_t plane_elems, int grp0)
 {
-    const int c0 = (int)blockIdx.z * cg.Cg;
+    const int c0 = (grp0 + (int)blockIdx.z) * cg.Cg;
     XB += (size_t)blockIdx.z * x_stride;
     const int g = blockIdx.y, kq = (int)(threadIdx.x & 3);
     const int pq = cg.P * cg.Q;
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(Bf16Shape<NQ>::kThreads) void fc_mfma_bf16_kernel(L
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
-    const int p = pj / splits, j = pj % splits;
-    XB += (size_t)(p / panels_per_x) * x_stride;            // one pair of planes per filter group
+    const int p = L.panel0 + pj / splits, j = pj % splits;
+    XB += (size_t)((pj / splits) / panels_per_x) * x_stride;            // one pair of planes per filter group
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     store_tables(s, L, fetch_tables(L));

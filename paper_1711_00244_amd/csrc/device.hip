@@ -54,6 +54,7 @@ struct LayerDev {
     int val_bits, idx_bits, ncode;       // index widths of the decode tables, codebook entries
     int table_rows;                      // 16-byte rows of the table image (tables + codebook)
     uint32_t n_chunks;
+    int panel0;                          // first block row of a launch that covers only some (a filter group); else 0
 };
 
 // Bytes of the table image: both decode tables, then the codebook, each padded to 16 bytes.
@@ -83,6 +84,7 @@ static LayerDev make_dev(const cl_layer *L)
     d.ncode = 1 << L->desc.weight_bits;
     d.table_rows = (int)(table_image_bytes(L->val_lut_bits, L->idx_lut_bits, d.ncode) / 16);
     d.n_chunks = (uint32_t)L->n_chunks;
+    d.panel0 = 0;
     return d;
 }
 
@@ -753,7 +755,9 @@ struct ConvPlan {
     ConvGeom cg{};
     int OCg = 0, panels_per_group = 0, imgs = 0;
     bool dense = false;        // decode every block once into a dense tile, then multiply from those
+    int groups_at_once = 1;    // filter groups per launch: all of them, or one (the compact form)
     size_t lds = 0, xt_bytes = 0, part_bytes = 0, wt_bytes = 0;
+    size_t total() const { return xt_bytes + part_bytes + wt_bytes; }
 };
 
 // From this many columns on (image x output pixel) a convolution decodes its blocks
@@ -763,7 +767,10 @@ struct ConvPlan {
 // repeated decoding).
 constexpr int64_t kConvDenseColumns = 4096;
 
-int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf16, const DeviceLimits &dl, ConvPlan &P)
+// compact: the form that needs the least scratch - filter groups one after the other
+// through the same buffers, blocks decoded inside the multiply kernel.
+int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf16, const DeviceLimits &dl, ConvPlan &P,
+                  bool compact = false)
 {
     if (!cv) return fail(CL_EINVAL, "null convolution descriptor");
     if (cv->C < 1 || cv->H < 1 || cv->W < 1 || cv->R < 1 || cv->S < 1 || cv->stride < 1 || cv->pad < 0 || cv->groups < 1 ||
@@ -782,20 +789,22 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     P.OCg = cv->out_channels / cv->groups;
     if (cv->groups > 1 && P.OCg % L->desc.block_h) return fail(CL_EUNSUPPORTED, "block_h %d must divide the %d filters of a group", L->desc.block_h, P.OCg);
     P.panels_per_group = (P.OCg + L->desc.block_h - 1) / L->desc.block_h;
-    const size_t per_image = (size_t)cv->groups * xt_rows(L) * g.P * g.Q * sizeof(float);
+    P.groups_at_once = compact ? 1 : cv->groups;
+    const int launch_panels = P.panels_per_group * P.groups_at_once;
+    const size_t per_image = (size_t)P.groups_at_once * xt_rows(L) * g.P * g.Q * sizeof(float);
     P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
     P.lds = mfma_lds_bytes(L, bf16);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
-    P.dense = !bf16 && (int64_t)std::min(P.imgs, batch) * g.P * g.Q >= kConvDenseColumns;
+    P.dense = !compact && !bf16 && (int64_t)std::min(P.imgs, batch) * g.P * g.Q >= kConvDenseColumns;
     P.wt_bytes = P.dense ? (size_t)L->n_blocks * kTile * kTile * sizeof(float) : 0;
     // workspace for the larger of a full image group and the last, smaller one
     P.xt_bytes = P.part_bytes = 0;
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
         int nq, np, splits;
-        mfma_shape(L, L->n_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense);
-        P.xt_bytes = std::max(P.xt_bytes, (size_t)cv->groups * xt_bytes_for(L, np, bf16));
-        P.part_bytes = std::max(P.part_bytes, (size_t)L->n_panels * splits * np * L->desc.block_h * sizeof(float));
+        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense);
+        P.xt_bytes = std::max(P.xt_bytes, (size_t)P.groups_at_once * xt_bytes_for(L, np, bf16));
+        P.part_bytes = std::max(P.part_bytes, (size_t)launch_panels * splits * np * L->desc.block_h * sizeof(float));
     }
     return CL_OK;
 }
@@ -811,7 +820,21 @@ extern "C" int32_t cl_conv_workspace_bytes(const cl_layer *L, const cl_conv_desc
     if (int32_t rc = device_limits(dl)) return rc;
     ConvPlan P;
     if (int32_t rc = plan_conv(L, cv, batch, path == CL_PATH_MFMA_BF16, dl, P)) return rc;
-    *out = P.xt_bytes + P.part_bytes + P.wt_bytes;
+    *out = P.total();
+    return CL_OK;
+}
+
+extern "C" int32_t cl_conv_workspace_bytes_min(const cl_layer *L, const cl_conv_desc *cv, int32_t batch, int32_t path, size_t *out)
+{
+    if (!L || !out) return fail(CL_EINVAL, "null argument");
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    if (path != CL_PATH_AUTO && !is_mfma(path)) return fail(CL_EUNSUPPORTED, "convolution runs on the MFMA paths only");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    ConvPlan P, F;
+    if (int32_t rc = plan_conv(L, cv, batch, path == CL_PATH_MFMA_BF16, dl, P, true)) return rc;
+    if (int32_t rc = plan_conv(L, cv, batch, path == CL_PATH_MFMA_BF16, dl, F)) return rc;
+    *out = std::min(P.total(), F.total());      // the fast form's launch shape can happen to need less
     return CL_OK;
 }
 
@@ -821,17 +844,24 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
 {
     if (int32_t rc = require_device(L)) return rc;
     if (!d_X || !d_Y) return fail(CL_EINVAL, "null activation pointer");
-    size_t need = 0;
-    if (int32_t rc = cl_conv_workspace_bytes(L, cv, batch, path, &need)) return rc;
-    if (workspace_bytes < need || !d_workspace) return fail(CL_EINVAL, "workspace too small: %zu < %zu", workspace_bytes, need);
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    if (path != CL_PATH_AUTO && !is_mfma(path)) return fail(CL_EUNSUPPORTED, "convolution runs on the MFMA paths only");
     if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
     DeviceLimits dl;
     if (int32_t rc = device_limits(dl)) return rc;
     const bool bf16 = path == CL_PATH_MFMA_BF16;
+    // the fast form if the workspace holds it, else the compact one
     ConvPlan P;
     if (int32_t rc = plan_conv(L, cv, batch, bf16, dl, P)) return rc;
+    if (workspace_bytes < P.total() || !d_workspace) {
+        const size_t fast = P.total();
+        P = ConvPlan{};
+        if (int32_t rc = plan_conv(L, cv, batch, bf16, dl, P, true)) return rc;
+        if (workspace_bytes < P.total() || !d_workspace)
+            return fail(CL_EINVAL, "workspace too small: %zu < %zu (%zu for the fast form)", workspace_bytes, P.total(), fast);
+    }
     hipStream_t st = (hipStream_t)stream;
-    const LayerDev D = make_dev(L);
+    LayerDev D = make_dev(L);
     const ConvGeom &g = P.cg;
     const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
     void *xt = d_workspace;
@@ -849,27 +879,31 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const int nb = std::min(P.imgs, batch - b0);
         const int ncols = nb * pq;
         int nq, Np, splits;
-        mfma_shape(L, L->n_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense);
+        const int launch_panels = P.panels_per_group * P.groups_at_once;
+        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
-        // all filter groups in one launch of each kernel: group grp has its column matrix
-        // at xt + grp * x_bytes and multiplies block rows grp * panels_per_group onwards
+        // groups_at_once filter groups per launch of each kernel: group grp of a launch has
+        // its column matrix at xt + grp * x_bytes and multiplies its own block rows
         const size_t x_bytes = xt_bytes_for(L, Np, bf16);
-        const unsigned groups = (unsigned)cv->groups;
-        if (bf16)
-            hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8), groups), dim3(256), 0, st,
-                               x, (uint16_t *)xt, g, x_bytes / sizeof(uint16_t), ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np));
-        else
-            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np / 4 + 255) / 256, 1024), (unsigned)(L->nbw * kTile), groups), dim3(256), 0, st,
-                               x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K);
-        HIP_TRY(hipGetLastError());
-        if (!timed) timing_begin(st);
-        if (int32_t rc = launch_mfma(L, D, bf16, nq, L->n_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, wt)) return rc;
-        if (!timed) { timing_end(st, 1); timed = true; }
-        const int ct = reduce_col_tile(L->n_panels, ncols);
-        hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
-                           D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
-        HIP_TRY(hipGetLastError());
+        for (int grp0 = 0; grp0 < cv->groups; grp0 += P.groups_at_once) {
+            const unsigned groups = (unsigned)P.groups_at_once;
+            D.panel0 = grp0 * P.panels_per_group;
+            if (bf16)
+                hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8), groups), dim3(256), 0, st,
+                                   x, (uint16_t *)xt, g, x_bytes / sizeof(uint16_t), ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np), grp0);
+            else
+                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np / 4 + 255) / 256, 1024), (unsigned)(L->nbw * kTile), groups), dim3(256), 0, st,
+                                   x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K, grp0);
+            HIP_TRY(hipGetLastError());
+            if (!timed) timing_begin(st);
+            if (int32_t rc = launch_mfma(L, D, bf16, nq, launch_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, wt)) return rc;
+            if (!timed) { timing_end(st, 1); timed = true; }
+            const int ct = reduce_col_tile(launch_panels, ncols);
+            hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(launch_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
+                               D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
+            HIP_TRY(hipGetLastError());
+        }
     }
     clear_error();
     return CL_OK;

@@ -23,7 +23,8 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
     __shared__ float tile[kColTile][kTile + 1];
     // workgroup -> (block row, column tile, row tile of rt rows)
     const int ntile = (max(ncols, zero_to) + ct - 1) / ct, nrt = (L.bh + rt - 1) / rt;
-    const int p = (int)blockIdx.x / (ntile * nrt), rem = (int)blockIdx.x - p * ntile * nrt;
+    const int pl = (int)blockIdx.x / (ntile * nrt), rem = (int)blockIdx.x - pl * ntile * nrt;
+    const int p = L.panel0 + pl;                            // part slots are numbered from the launch's first block row
     const int c0 = (rem / nrt) * ct, r0 = (rem % nrt) * rt;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(256) void mfma_reduce_kernel(LayerDev L, const floa
             if (conv_pq != 0) tile[ci][r] = 0.0f;
             continue;
         }
-        const float *src = part + ((size_t)p * splits * part_b + c) * L.bh + r;
+        const float *src = part + ((size_t)pl * splits * part_b + c) * L.bh + r;
         float t = 0.0f;
         for (int j = 0; j < splits; j += 8) {               // eight loads in flight, added in order
             float a[8];

@@ -52,9 +52,9 @@ struct ConvGeom {
 };
 
 __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, size_t x_stride,
-                                                         int n_cols, int Np, int bw, int K)
+                                                         int n_cols, int Np, int bw, int K, int grp0)
 {
-    const int c0 = (int)blockIdx.z * cg.Cg;                 // filter group blockIdx.z: its input channels, its matrix
+    const int c0 = (grp0 + (int)blockIdx.z) * cg.Cg;        // filter group grp0 + blockIdx.z: its input channels, matrix blockIdx.z
     XT += (size_t)blockIdx.z * x_stride;
     const int k = xt_row_to_k((int)blockIdx.y, bw, K);      // (c, r, s) of this row, or a padding row
     const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
@@ -288,10 +288,10 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
-    const int p = pj / splits, j = pj % splits;
+    const int p = L.panel0 + pj / splits, j = pj % splits;    // part slots are numbered from the launch's first block row
     // every panels_per_x block rows have an activation matrix of their own, x_stride
     // elements after the one before (the filter groups of a convolution)
-    XT += (size_t)(p / panels_per_x) * x_stride;
+    XT += (size_t)((pj / splits) / panels_per_x) * x_stride;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const bool producer = wave >= 4;

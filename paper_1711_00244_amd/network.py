@@ -44,8 +44,12 @@ class FcOp:
 
 
 class ConvOp:
-    def __init__(self, name, layer, geom, block, relu=True):
+    """compact: run with the least scratch the library works with (filter groups one
+    after the other, blocks decoded inside the multiply kernel) instead of the fast form."""
+
+    def __init__(self, name, layer, geom, block, relu=True, compact=False):
         self.name, self.layer, self.geom, self.relu, self.block = name, layer, geom, relu, tuple(block)
+        self.compact = compact
         self._ws = {}
 
     def out_shape(self, in_shape):
@@ -55,13 +59,13 @@ class ConvOp:
         return (g["OC"], P, Q)
 
     def ws_bytes(self, B, in_shape):
-        return cl.conv_workspace_bytes(self.layer, self.geom, B)
+        return cl.conv_workspace_bytes(self.layer, self.geom, B, compact=self.compact)
 
     def forward(self, X, out=None):
         import torch
         B = X.shape[0]
         if B not in self._ws:
-            self._ws[B] = torch.empty(max(256, cl.conv_workspace_bytes(self.layer, self.geom, B)), dtype=torch.uint8, device="cuda")
+            self._ws[B] = torch.empty(max(256, self.ws_bytes(B, None)), dtype=torch.uint8, device="cuda")
         return cl.compressed_conv_forward(self.layer, self.geom, X, relu=self.relu, out=out, workspace=self._ws[B])
 
 
@@ -158,6 +162,12 @@ class NetworkRunner(StackRunner):
         return best
 
 
+def compact_copy(net):
+    """The same network (the same compressed layers) with its convolutions in the compact form."""
+    ops = [ConvOp(op.name, op.layer, op.geom, op.block, op.relu, compact=True) if isinstance(op, ConvOp) else op for op in net.layers]
+    return NetworkRunner(ops, net.in_shape)
+
+
 def alexnet(block=(128, 128), density=None):
     """The AlexNet of Table IV with synthetic compressed layers: configs[3]'s
     convolutions and configs[2]'s FC stack.  density overrides every layer's fraction
@@ -188,22 +198,30 @@ def main(argv=None):
     ap.add_argument("--check", action="store_true", help="run the plan for K images and compare with one-batch execution")
     ap.add_argument("--density", type=float, default=None, help="uniform fraction of non-zeros for all layers")
     args = ap.parse_args(argv)
-    net = alexnet(density=args.density)
-    model_bytes = sum(op.layer.stats()["model_bytes"] for op in net.layers if hasattr(op, "layer"))
+    fast = alexnet(density=args.density)
+    nets = {"fast": fast, "compact": compact_copy(fast)}
+    model_bytes = sum(op.layer.stats()["model_bytes"] for op in fast.layers if hasattr(op, "layer"))
     for K in args.images:
         batch_set = [b for b in range(1, K + 1) if K % b == 0]
-        time_ms = net.measure_times(batch_set)
+        times = {name: n.measure_times(batch_set) for name, n in nets.items()}
         for mult in args.budgets:
             tot = int(mult * model_bytes)
-            plan = net.plan(batch_set, tot, time_ms=time_ms)
-            fixed = net.fixed_batch(batch_set, tot, time_ms)
+            # the convolutions' scratch is part of the budget: both forms of the network are
+            # planned, the faster feasible plan (and the faster feasible fixed batch) is reported
+            plans = {name: n.plan(batch_set, tot, time_ms=times[name]) for name, n in nets.items()}
+            fixeds = {name: n.fixed_batch(batch_set, tot, times[name]) for name, n in nets.items()}
+            form = min((nm for nm in nets if plans[nm] is not None), key=lambda nm: plans[nm].ms_per_image, default=None)
+            fform = min((nm for nm in nets if fixeds[nm] is not None), key=lambda nm: fixeds[nm][0], default=None)
+            plan = plans[form] if form else None
+            fixed = fixeds[fform] + (fform,) if fform else None
+            net = nets[form] if form else fast
             rec = dict(images=K, density=args.density, budget_x_model=mult, budget_bytes=tot, model_bytes=model_bytes,
-                       layers=[op.name for op in net.layers])
+                       layers=[op.name for op in net.layers], conv_form=form)
             if plan is None or fixed is None:
                 rec["infeasible"] = True
             else:
                 rec.update(plan=plan.batch_per_layer, plan_ms_total=round(plan.ms_per_image * K, 4),
-                           fixed_batch=fixed[1], fixed_ms_total=round(fixed[0] * K, 4),
+                           fixed_batch=fixed[1], fixed_ms_total=round(fixed[0] * K, 4), fixed_conv_form=fixed[2],
                            gain_percent=round(100.0 * (fixed[0] / plan.ms_per_image - 1.0), 1))
                 if args.check:
                     X = torch.rand((K, 3, 227, 227), device="cuda")

@@ -417,6 +417,30 @@ def test_conv_batch_cut_into_image_groups():
     L.free()
 
 
+@pytest.mark.parametrize("li,B", [(1, 2), (3, 1), (0, 2)])
+def test_conv_compact_form(li, B):
+    """Given only cl_conv_workspace_bytes_min() of scratch the call runs the filter groups
+    one after the other and decodes inside the multiply kernel: less memory for a
+    grouped layer, the oracle's result within tolerance, and a smaller workspace still
+    is refused."""
+    torch = torch_cuda()
+    spec, W = wl.layer_weights(4, li)
+    g = spec.conv
+    L, m, oW = check_decode(W, spec.r, spec.k, cl.conv_block_h(g["OC"], g["groups"]), 128)
+    X = wl.activations(4, B, layer_index=li)
+    ref = oracle.conv_forward(oW, X, g, relu=True, nthreads=16)
+    fast, small = cl.conv_workspace_bytes(L, g, B), cl.conv_workspace_bytes(L, g, B, compact=True)
+    assert small <= fast and (g["groups"] == 1 or small < 0.7 * fast)
+    Xd = torch.from_numpy(X).cuda()
+    ws = torch.empty(small, dtype=torch.uint8, device="cuda")
+    Y = cl.compressed_conv_forward(L, g, Xd, relu=True, workspace=ws)
+    assert rel_err(Y.cpu().numpy(), ref) <= TOL
+    assert rel_err(cl.compressed_conv_forward(L, g, Xd, relu=True).cpu().numpy(), ref) <= TOL
+    with pytest.raises(cl.CLError):
+        cl.compressed_conv_forward(L, g, Xd, relu=True, workspace=torch.empty(small - 256, dtype=torch.uint8, device="cuda"))
+    L.free()
+
+
 def test_conv_rejects_mismatched_layer():
     torch = torch_cuda()
     L = cl.compress_layer(np.ones((6, 75), np.float32), 5, 4, 6, 75, upload=True)
