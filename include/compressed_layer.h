@@ -287,9 +287,13 @@ int32_t cl_conv_workspace_bytes_min(const cl_layer *layer, const cl_conv_desc *c
  * columns (images x output pixels) on, CL_PATH_MFMA_F32 first decodes every block
  * of the layer once into a dense 128 x 128 tile in the workspace (64 KiB per block)
  * and multiplies from those, instead of decoding the blocks again for every tile
- * of columns; the results are the same bit for bit.  path: path is CL_PATH_AUTO (= CL_PATH_MFMA_F32),
- * CL_PATH_MFMA_F32 or CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are
- * blocks above 128 x 128 and, with groups > 1, a block_h that does not divide
+ * of columns; the results are the same bit for bit.  All this is the form of the
+ * call that cl_conv_workspace_bytes() sizes the workspace for; with a workspace
+ * between cl_conv_workspace_bytes_min() and that, the compact form described there
+ * runs instead, and below the minimum the call fails with CL_EINVAL.
+ * path is CL_PATH_AUTO (= CL_PATH_MFMA_F32), CL_PATH_MFMA_F32 or
+ * CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are blocks above
+ * 128 x 128 and, with groups > 1, a block_h that does not divide
  * out_channels / groups. */
 int32_t cl_compressed_conv_forward(const cl_layer *layer, const cl_conv_desc *conv, const float *d_X,
                                    const float *d_bias_or_null, float *d_Y, int32_t batch, int32_t relu,
