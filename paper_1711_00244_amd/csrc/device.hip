@@ -374,12 +374,12 @@ static int32_t ensure_lds(const void *kernel, size_t lds, LdsLimit &seen)
 
 template <int NQ, bool DENSE>
 int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int panels_per_x, size_t x_stride, size_t lds,
-                       const float *xt, float *part, const float *wt, hipStream_t st)
+                       const float *xt, float *part, const float *wt, const DirectOut &out, hipStream_t st)
 {
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)fc_mfma_kernel<NQ, DENSE>, lds, seen)) return rc;
     hipLaunchKernelGGL((fc_mfma_kernel<NQ, DENSE>), dim3((unsigned)(panels * splits * (np / MfmaShape<NQ>::kImages))),
-                       dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride, wt);
+                       dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride, wt, out);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -400,7 +400,8 @@ int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int pa
 // activation matrix of its own, x_bytes after the one before
 // wt: the layer's blocks as dense tiles (decode_tiles_kernel), or null to decode them in the kernel
 int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int panels, int splits, int np, int panels_per_x,
-                    size_t x_bytes, size_t lds, const void *xt, float *part, hipStream_t st, const float *wt = nullptr)
+                    size_t x_bytes, size_t lds, const void *xt, float *part, hipStream_t st, const float *wt = nullptr,
+                    const DirectOut &out = DirectOut{nullptr, nullptr, 0, 1, 0})
 {
     const size_t x_stride = x_bytes / (bf16 ? sizeof(uint16_t) : sizeof(float));
     if (bf16) {
@@ -413,17 +414,17 @@ int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int
         }
     } else if (wt) {
         switch (nq) {
-        case 1: return launch_mfma_as<1, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, st);
-        case 2: return launch_mfma_as<2, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, st);
-        case 4: return launch_mfma_as<4, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, st);
-        case 8: return launch_mfma_as<8, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, st);
+        case 1: return launch_mfma_as<1, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
+        case 2: return launch_mfma_as<2, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
+        case 4: return launch_mfma_as<4, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
+        case 8: return launch_mfma_as<8, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
         }
     } else {
         switch (nq) {
-        case 1: return launch_mfma_as<1, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, st);
-        case 2: return launch_mfma_as<2, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, st);
-        case 4: return launch_mfma_as<4, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, st);
-        case 8: return launch_mfma_as<8, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, st);
+        case 1: return launch_mfma_as<1, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
+        case 2: return launch_mfma_as<2, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
+        case 4: return launch_mfma_as<4, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
+        case 8: return launch_mfma_as<8, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
         }
     }
     return fail(CL_EINVAL, "internal: no dense-tile kernel for %d accumulators", nq);
@@ -897,8 +898,12 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
                                    x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K, grp0);
             HIP_TRY(hipGetLastError());
             if (!timed) timing_begin(st);
-            if (int32_t rc = launch_mfma(L, D, bf16, nq, launch_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, wt)) return rc;
+            // block rows that are not split need no adding up: the multiply kernel finishes the output
+            const bool direct = !bf16 && splits == 1;
+            const DirectOut out{direct ? y : nullptr, d_bias, ncols, pq, relu};
+            if (int32_t rc = launch_mfma(L, D, bf16, nq, launch_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, wt, out)) return rc;
             if (!timed) { timing_end(st, 1); timed = true; }
+            if (direct) continue;
             const int ct = reduce_col_tile(launch_panels, ncols);
             hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(launch_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
                                D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);

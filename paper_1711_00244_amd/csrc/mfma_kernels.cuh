@@ -270,12 +270,21 @@ template <int NQ> struct MfmaShape {
     static constexpr int kVecs = NQ / kVecW;                                  // loads per k-step
 };
 
+// Where a convolution's block rows are not split, nothing is left to add up and the
+// kernel finishes the output itself (bias, activation, NCHW) instead of writing
+// partial tiles for the finishing kernel: Y is null otherwise.
+struct DirectOut {
+    float *Y;              // batch x M x pq, or null
+    const float *bias;     // M values or null
+    int ncols, pq, relu;   // real columns (image x pixel), pixels per image
+};
+
 // With DENSE the blocks come decoded from device memory (wt, written by
 // decode_tiles_kernel) and the wavefronts 4 and up only copy them into LDS.
 template <int NQ, bool DENSE>
 __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
                                                                          int splits, int Bp, int panels_per_x, size_t x_stride,
-                                                                         const float *__restrict__ wt)
+                                                                         const float *__restrict__ wt, DirectOut out)
 {
     constexpr int kMfmaDecoders = MfmaShape<NQ>::kDecoders;
     constexpr int kMfmaThreads = MfmaShape<NQ>::kThreads;
@@ -374,8 +383,42 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
         __syncthreads();
     }
     // accumulator 4 v + q, element e of lane l: image 128 v + kVecW (8 (e / 4) + 4 (l / 32) + e % 4) + q
-    // of the tile, weight row 32 wave + l % 32; 32 lanes write 32 consecutive floats
+    // of the tile, weight row 32 wave + l % 32
     const int r = wave * 32 + m;
+    if (out.Y) {
+        // The output runs along the columns, the accumulators along the rows: turn the
+        // wavefront's 32 x kImages piece in LDS (the weight tiles are free now; the last
+        // barrier above was every wavefront's last use of them), then write each row's
+        // columns in runs, bias and activation on the way.
+        constexpr int kStride = kImages + 1;
+        float *t = tiles + wave * 32 * kStride;
+#pragma unroll
+        for (int v = 0; v < kVecs; ++v) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
+#pragma unroll
+                for (int q = 0; q < kVecW; ++q) t[m * kStride + kTile * v + kVecW * slot + q] = acc[4 * v + q][e];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int row_id = p * L.bh;
+        const int rows = min(32, min(L.bh, L.M - row_id) - wave * 32);
+        for (int rr = 0; rr < rows; ++rr) {
+            const int oc = row_id + wave * 32 + rr;
+            const float bv = out.bias ? out.bias[oc] : 0.0f;
+            for (int cc = lane; cc < kImages; cc += 64) {
+                const int c = nb * kImages + cc;
+                if (c >= out.ncols) break;
+                const float y = t[rr * kStride + cc] + bv;
+                out.Y[((size_t)(c / out.pq) * L.M + oc) * out.pq + (c % out.pq)] = out.relu ? fmaxf(y, 0.0f) : y;
+            }
+        }
+        return;
+    }
+    // 32 lanes write 32 consecutive floats of the workgroup's partial tile
     if (r < L.bh) {
         float *mine = part + ((size_t)pj * Bp + (size_t)nb * kImages) * L.bh + r;
 #pragma unroll
