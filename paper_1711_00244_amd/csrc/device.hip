@@ -893,9 +893,14 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             if (bf16)
                 hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8), groups), dim3(256), 0, st,
                                    x, (uint16_t *)xt, g, x_bytes / sizeof(uint16_t), ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np), grp0);
-            else
-                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)std::min((Np / 4 + 255) / 256, 1024), (unsigned)(L->nbw * kTile), groups), dim3(256), 0, st,
-                                   x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K, grp0);
+            else {
+                // rows per workgroup: as many (up to kIm2colRows) as leave a couple of thousand workgroups
+                const int64_t col_wgs = std::min((Np / 4 + 255) / 256, 4096);
+                int rpw = kIm2colRows;
+                while (rpw > 1 && col_wgs * (L->nbw * kTile / rpw) * groups < 2048) rpw >>= 1;
+                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)col_wgs, (unsigned)(L->nbw * kTile / rpw), groups), dim3(256), 0, st,
+                                   x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K, grp0, rpw);
+            }
             HIP_TRY(hipGetLastError());
             if (!timed) timing_begin(st);
             // block rows that are not split need no adding up: the multiply kernel finishes the output

@@ -51,38 +51,51 @@ struct ConvGeom {
     int C, H, W, R, S, stride, pad, Cg, P, Q;
 };
 
+constexpr int kIm2colRows = 16;          // most rows of XT a workgroup of im2col_pad_kernel writes for its columns (a power of two)
+
 __global__ __launch_bounds__(256) void im2col_pad_kernel(const float *__restrict__ X, float *XT, ConvGeom cg, size_t x_stride,
-                                                         int n_cols, int Np, int bw, int K, int grp0)
+                                                         int n_cols, int Np, int bw, int K, int grp0, int rows_per_wg)
 {
     const int c0 = (grp0 + (int)blockIdx.z) * cg.Cg;        // filter group grp0 + blockIdx.z: its input channels, matrix blockIdx.z
     XT += (size_t)blockIdx.z * x_stride;
-    const int k = xt_row_to_k((int)blockIdx.y, bw, K);      // (c, r, s) of this row, or a padding row
-    const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
     const int pq = cg.P * cg.Q;
-    const size_t plane = (size_t)cg.H * cg.W;
-    const float *xc = X + (size_t)(c0 + c) * plane;         // the row's channel in image 0
-    float4 *row = (float4 *)(XT + (size_t)blockIdx.y * Np);
-    // a thread writes four consecutive columns (Np is a multiple of the 32-column
-    // accumulator): output pixel and image are divided out once and stepped from there
+    const int plane = cg.H * cg.W;
+    const int row0 = (int)blockIdx.y * rows_per_wg;
+    // A thread writes four consecutive columns (Np is a multiple of the 32-column
+    // accumulator) of rows_per_wg rows: where its four output pixels sit in the input
+    // is worked out once, a row (c, r, s) then only shifts that by a uniform offset.
     for (int n4 = blockIdx.x * blockDim.x + threadIdx.x; n4 < Np / 4; n4 += gridDim.x * blockDim.x) {
-        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         const int n = 4 * n4;
-        if (k >= 0 && n < n_cols) {
+        int y0[4], x0[4];
+        size_t at[4];                                       // offset of (y0, x0) of the pixel's image, channel 0
+        {
             int img = n / pq;
             const int o = n - img * pq;
             int oy = o / cg.Q, ox = o - oy * cg.Q;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int y = oy * cg.stride - cg.pad + r, x = ox * cg.stride - cg.pad + s;
-                if (n + i < n_cols && y >= 0 && y < cg.H && x >= 0 && x < cg.W)
-                    v[i] = xc[(size_t)img * cg.C * plane + (size_t)y * cg.W + x];
+                // columns past the last one get coordinates that no (r, s) brings inside the image
+                y0[i] = n + i < n_cols ? oy * cg.stride - cg.pad : -(1 << 20);
+                x0[i] = ox * cg.stride - cg.pad;
+                at[i] = (size_t)img * cg.C * plane + (size_t)((int64_t)y0[i] * cg.W + x0[i]);
                 if (++ox == cg.Q) {
                     ox = 0;
                     if (++oy == cg.P) { oy = 0; ++img; }
                 }
             }
         }
-        row[n4] = make_float4(v[0], v[1], v[2], v[3]);
+        for (int rr = 0; rr < rows_per_wg; ++rr) {
+            const int k = xt_row_to_k(row0 + rr, bw, K);    // (c, r, s) of this row, or a padding row: uniform
+            float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (k >= 0) {
+                const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
+                const size_t shift = (size_t)(c0 + c) * plane + (size_t)(r * cg.W + s);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if ((unsigned)(y0[i] + r) < (unsigned)cg.H && (unsigned)(x0[i] + s) < (unsigned)cg.W) v[i] = X[at[i] + shift];
+            }
+            ((float4 *)(XT + (size_t)(row0 + rr) * Np))[n4] = make_float4(v[0], v[1], v[2], v[3]);
+        }
     }
 }
 
