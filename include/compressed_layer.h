@@ -225,7 +225,8 @@ int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path
  *  d_workspace / workspace_bytes   at least cl_fc_workspace_bytes(); may be NULL
  *          when that is 0
  * Errors: CL_EINVAL (null pointers, batch < 1, workspace too small, layer not
- * uploaded) - nothing is launched then. */
+ * uploaded), CL_EUNSUPPORTED (a dense-tile path with more than 2^21 images in one
+ * call, or a launch of more than 2^31 - 1 workgroups) - nothing is launched then. */
 int32_t cl_compressed_fc_forward(const cl_layer *layer, const float *d_X, const float *d_bias_or_null,
                                  float *d_Y, int32_t batch, int32_t relu, int32_t path,
                                  void *d_workspace, size_t workspace_bytes, void *stream);
@@ -293,8 +294,9 @@ int32_t cl_conv_workspace_bytes_min(const cl_layer *layer, const cl_conv_desc *c
  * runs instead, and below the minimum the call fails with CL_EINVAL.
  * path is CL_PATH_AUTO (= CL_PATH_MFMA_F32), CL_PATH_MFMA_F32 or
  * CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are blocks above
- * 128 x 128 and, with groups > 1, a block_h that does not divide
- * out_channels / groups. */
+ * 128 x 128, with groups > 1 a block_h that does not divide
+ * out_channels / groups, more than 2^21 output pixels per image and image planes
+ * of more than 2^30 pixels. */
 int32_t cl_compressed_conv_forward(const cl_layer *layer, const cl_conv_desc *conv, const float *d_X,
                                    const float *d_bias_or_null, float *d_Y, int32_t batch, int32_t relu,
                                    int32_t path, void *d_workspace, size_t workspace_bytes, void *stream);

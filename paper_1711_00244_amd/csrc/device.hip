@@ -22,6 +22,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <climits>
 #include <cstdio>
 #include <cstring>
 #include <vector>
@@ -34,6 +35,14 @@ namespace cl {
     do {                                                                                      \
         hipError_t e_ = (expr);                                                               \
         if (e_ != hipSuccess) return fail(CL_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// A launch of n workgroups along x; more than a grid holds is refused, not wrapped.
+#define GRID_TRY(g, n)                                                                        \
+    do {                                                                                      \
+        const int64_t n_ = (n);                                                               \
+        if (n_ < 1 || n_ > INT32_MAX) return fail(CL_EUNSUPPORTED, "a launch of %lld workgroups does not fit a grid", (long long)n_); \
+        (g) = dim3((unsigned)n_);                                                             \
     } while (0)
 
 constexpr int kWaves = 8;                 // wavefronts per workgroup
@@ -291,6 +300,10 @@ int reduce_col_tile(int panels, int ncols)
 // rows of the block-by-block activation layout, tail included
 size_t xt_rows(const cl_layer *L) { return (size_t)L->nbw * kTile + kXtTailRows; }
 
+// Most columns (images, or images x output pixels) of one dense-tile launch: keeps the
+// kernels' 32-bit column arithmetic and the y extent of the layout kernels' grids in range.
+constexpr int kMaxTileColumns = 1 << 21;
+
 bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->desc.block_w <= kTile; }
 
 // Image tile, padded column count and split of the block rows for `ncols` columns and
@@ -346,6 +359,7 @@ size_t xt_bytes_for(const cl_layer *L, int np, bool bf16)
 int32_t plan_mfma(const cl_layer *L, int batch, bool bf16, const DeviceLimits &dl, MfmaPlan &P)
 {
     if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the MFMA path needs blocks of at most %d x %d", kTile, kTile);
+    if (batch > kMaxTileColumns) return fail(CL_EUNSUPPORTED, "the dense-tile paths take at most %d images per call", kMaxTileColumns);
     P.bf16 = bf16;
     mfma_shape(L, L->n_panels, batch, dl.cus, bf16, P.nq, P.Bp, P.splits);
     P.lds = mfma_lds_bytes(L, bf16);
@@ -378,8 +392,9 @@ int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int pa
 {
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)fc_mfma_kernel<NQ, DENSE>, lds, seen)) return rc;
-    hipLaunchKernelGGL((fc_mfma_kernel<NQ, DENSE>), dim3((unsigned)(panels * splits * (np / MfmaShape<NQ>::kImages))),
-                       dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride, wt, out);
+    dim3 grid;
+    GRID_TRY(grid, (int64_t)panels * splits * (np / MfmaShape<NQ>::kImages));
+    hipLaunchKernelGGL((fc_mfma_kernel<NQ, DENSE>), grid, dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride, wt, out);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -390,8 +405,9 @@ int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int pa
 {
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)fc_mfma_bf16_kernel<NQ>, lds, seen)) return rc;
-    hipLaunchKernelGGL(fc_mfma_bf16_kernel<NQ>, dim3((unsigned)(panels * splits * (np / Bf16Shape<NQ>::kImages))),
-                       dim3(Bf16Shape<NQ>::kThreads), lds, st, D, xb, part, splits, np, plane_elems, panels_per_x, x_stride);
+    dim3 grid;
+    GRID_TRY(grid, (int64_t)panels * splits * (np / Bf16Shape<NQ>::kImages));
+    hipLaunchKernelGGL(fc_mfma_bf16_kernel<NQ>, grid, dim3(Bf16Shape<NQ>::kThreads), lds, st, D, xb, part, splits, np, plane_elems, panels_per_x, x_stride);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -472,7 +488,8 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
     SparsePlan P;
     if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P)) return rc;
     const int M = L->desc.M, K = L->desc.K;
-    const dim3 grid((unsigned)(L->n_panels * P.wg_per_panel));
+    dim3 grid;
+    if (L->n_chunks > 0) GRID_TRY(grid, (int64_t)L->n_panels * P.wg_per_panel);
     for (int b0 = 0; b0 < batch;) {
         int bt = P.bt_max;
         while (bt > batch - b0) bt >>= 1;
@@ -499,7 +516,9 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
             HIP_TRY(hipGetLastError());
             if (b0 == 0) timing_end(st, 1);
         }
-        hipLaunchKernelGGL(fc_reduce_kernel, dim3((unsigned)(L->n_panels * bt)), dim3(kRedThreads), 0, st,
+        dim3 rgrid;
+        GRID_TRY(rgrid, (int64_t)L->n_panels * bt);
+        hipLaunchKernelGGL(fc_reduce_kernel, rgrid, dim3(kRedThreads), 0, st,
                            D, part, d_bias, y, bt, bt, P.wg_per_panel, relu);
         HIP_TRY(hipGetLastError());
         b0 += bt;
@@ -540,7 +559,9 @@ static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPl
         while (rt > 32 && (int64_t)L->n_panels * ((cols + ct - 1) / ct) * ((L->desc.block_h + rt - 1) / rt) < 1024) rt >>= 1;
     }
     const int nrt = (L->desc.block_h + rt - 1) / rt;
-    hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(L->n_panels * ((cols + ct - 1) / ct) * nrt)), dim3(256), 0, st,
+    dim3 rgrid;
+    GRID_TRY(rgrid, (int64_t)L->n_panels * ((cols + ct - 1) / ct) * nrt);
+    hipLaunchKernelGGL(mfma_reduce_kernel, rgrid, dim3(256), 0, st,
                        D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, next_bp, ct, next_bp, rt);
     HIP_TRY(hipGetLastError());
     return CL_OK;
@@ -784,6 +805,8 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     g.P = (cv->H + 2 * cv->pad - cv->R) / cv->stride + 1;
     g.Q = (cv->W + 2 * cv->pad - cv->S) / cv->stride + 1;
     if (g.P < 1 || g.Q < 1) return fail(CL_EINVAL, "filter larger than the padded input");
+    if ((int64_t)cv->H * cv->W > INT32_MAX / 2 || (int64_t)g.P * g.Q > kMaxTileColumns || (int64_t)g.Cg * g.R * g.S > INT32_MAX / 2)
+        return fail(CL_EUNSUPPORTED, "image planes of more than 2^30 pixels or %d output pixels are not supported", kMaxTileColumns);
     if (L->desc.M != cv->out_channels || L->desc.K != g.Cg * g.R * g.S)
         return fail(CL_EINVAL, "layer is %d x %d, the convolution needs %d x %d", L->desc.M, L->desc.K, cv->out_channels, g.Cg * g.R * g.S);
     if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the convolution path needs blocks of at most %d x %d", kTile, kTile);
@@ -910,7 +933,9 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             if (!timed) { timing_end(st, 1); timed = true; }
             if (direct) continue;
             const int ct = reduce_col_tile(launch_panels, ncols);
-            hipLaunchKernelGGL(mfma_reduce_kernel, dim3((unsigned)(launch_panels * ((ncols + ct - 1) / ct))), dim3(256), 0, st,
+            dim3 rgrid;
+            GRID_TRY(rgrid, (int64_t)launch_panels * ((ncols + ct - 1) / ct));
+            hipLaunchKernelGGL(mfma_reduce_kernel, rgrid, dim3(256), 0, st,
                                D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
             HIP_TRY(hipGetLastError());
         }

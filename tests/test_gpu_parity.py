@@ -261,6 +261,42 @@ def test_fc_stack_forward(dims, blocks, B):
         L.free()
 
 
+@pytest.mark.parametrize("B", [1, 48])
+def test_fc_stack_replays_from_a_captured_graph(B):
+    """The stack call makes stream launches only, so a caller may capture it in a graph:
+    every replay (new input each time, eager calls and synchronisations in between) gives
+    what the eager call gives on the same input - bit for bit on the dense-tile path - and
+    that is within tolerance of the oracle."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(77 + B)
+    dims = (384, 256, 130)
+    layers, dense = _stack(dims, [(128, 128)] * 2, rng)
+    Xd = torch.zeros((B, dims[0]), device="cuda")
+    Yg = torch.empty((B, dims[-1]), device="cuda")
+    ws = torch.empty(max(256, cl.fc_stack_workspace_bytes(layers, B)), dtype=torch.uint8, device="cuda")
+    cl.compressed_fc_stack_forward(layers, Xd, out=Yg, workspace=ws)        # first call sets the kernels' LDS limits
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cl.compressed_fc_stack_forward(layers, Xd, out=Yg, workspace=ws)
+    for rep in range(4):
+        X = np.maximum(rng.standard_normal((B, dims[0])), 0).astype(np.float32)
+        Xd.copy_(torch.from_numpy(X))
+        Yg.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = cl.compressed_fc_stack_forward(layers, Xd)                  # own output and workspace
+        torch.cuda.synchronize()
+        if B > 4:
+            assert torch.equal(Yg, eager), rep
+        ref = oracle.fc_forward(dense[1], oracle.fc_forward(dense[0], X, None, True).astype(np.float32), None, False)
+        assert rel_err(Yg.cpu().numpy(), ref) <= 2 * TOL, rep
+        assert rel_err(eager.cpu().numpy(), ref) <= 2 * TOL, rep
+    del graph
+    for L in layers:
+        L.free()
+
+
 def test_fc_stack_mixed_paths():
     """A stack whose middle layer has 256-wide blocks: CL_PATH_AUTO runs it on the sparse
     path between two dense-tile layers (batch 33), all three on the sparse path at
@@ -547,6 +583,15 @@ def test_forward_rejects_bad_arguments():
     assert rc == binding.CL_EINVAL
     rc = binding.lib().cl_compressed_fc_forward(L.handle, C.c_void_p(X.data_ptr()), None, C.c_void_p(X.data_ptr()), 0, 0, 0, None, 0, None)
     assert rc == binding.CL_EINVAL
+    # sizes beyond what a launch holds are refused when the workspace is sized: nothing is launched
+    with pytest.raises(cl.CLError) as e:
+        cl.fc_workspace_bytes(L, (1 << 21) + 1, cl.PATH_MFMA_F32)
+    assert e.value.code == binding.CL_EUNSUPPORTED
+    assert cl.fc_workspace_bytes(L, 1 << 21, cl.PATH_MFMA_F32) > 0
+    Lc = cl.compress_layer(np.ones((4, 9), np.float32), 5, 4, 4, 9, upload=True)
+    with pytest.raises(cl.CLError) as e:
+        cl.conv_workspace_bytes(Lc, dict(C=1, H=2000, W=2000, R=3, S=3, stride=1, pad=1, groups=1, OC=4), 1)
+    assert e.value.code == binding.CL_EUNSUPPORTED
 
 
 @pytest.mark.parametrize("shape,size,stride", [((2, 5, 11, 9), 3, 2), ((1, 96, 55, 55), 3, 2), ((3, 7, 8, 8), 2, 2),
