@@ -360,7 +360,7 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
         float *cur = tiles + ((bi - blk_lo) & 1) * (kWTileBytes / 4);
         // B values of four steps: columns 64 kl + 4 g .. + 3 of weight row 32 wave + m
-        const float4 *wp = (const float4 *)(cur + (wave * 32 + m) * kWStride + 64 * kl);
+        float4 *wp = (float4 *)(cur + (wave * 32 + m) * kWStride + 64 * kl);
         float4 b_cur = wp[0];
         for (int ks = 0; ks < kTile / 2; ks += kAhead) {
             // steps are kept in program order (scheduling barriers): hoisting a group's
@@ -369,7 +369,14 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
 #pragma unroll
             for (int h4 = 0; h4 < kAhead / 4; ++h4) {
                 const float4 b_next = wp[min(ks / 4 + h4 + 1, kTile / 8 - 1)];
-                __builtin_amdgcn_sched_barrier(0);          // the LDS read goes out before these multiplies
+                // The four weights in b_cur are this lane's alone and have been read: zero them
+                // now, behind the multiplies, so that the decoders get a clean tile back (a
+                // copied tile is overwritten whole instead).
+                // The four weights in b_cur are this lane's alone and have been read: zero them
+                // now, behind the multiplies, so that the decoders get a clean tile back (a
+                // copied tile is overwritten whole instead).
+                if (!DENSE) wp[ks / 4 + h4] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                __builtin_amdgcn_sched_barrier(0);          // the LDS accesses go out before these multiplies
                 const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -387,13 +394,7 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
             // the loads of the group after next start the next block: skip this block's other half
             if (ks == kTile / 2 - 2 * kAhead) ap += (kTile / 2) * row_stride;
         }
-        // done with this tile: clear this wavefront's 32 rows of it (a decoded tile must be
-        // clean for the decoders; a copied one is overwritten whole)
-        if (!DENSE) {
-            uint4 *z = (uint4 *)(cur + wave * 32 * kWStride);
-            for (int t = lane; t < 32 * kWStride / 4; t += 64) z[t] = uint4{0, 0, 0, 0};
-        }
-        __syncthreads();
+        __syncthreads();                                    // done with this tile, and it is clean
     }
     // accumulator 4 v + q, element e of lane l: image 128 v + kVecW (8 (e / 4) + 4 (l / 32) + e % 4) + q
     // of the tile, weight row 32 wave + l % 32
