@@ -307,12 +307,17 @@ constexpr int kMaxTileColumns = 1 << 21;
 bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->desc.block_w <= kTile; }
 
 // Image tile, padded column count and split of the block rows for `ncols` columns and
-// `panels` block rows, from a small model of the kernel with measured constants
+// `panels` block rows, from a small model of a layer's launches with measured constants
 // (cycles per workgroup: 12 k to start; per block 5 k of decoding and bookkeeping plus
 // 4.1 k of multiplies per 32 columns of the tile - 1.5 k on the bf16 matrix cores;
-// workgroups run in rounds of one per CU).  The model is coarse, so a candidate must win by a sixteenth to replace a
-// narrower one.
-void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool dense = false)
+// workgroups run in rounds of one per CU; and 3 cycles per 4 KB of partial tiles, which
+// are written, flushed at the kernel's end and read again by the finishing kernel -
+// nothing where one workgroup per block row writes the output itself, `direct`).  Fitted
+// to sweeps over every tile width and split of the AlexNet and VGG-16 FC layers at 8 to
+// 1024 images: the choice is the fastest measured shape for the large layers and
+// within 3 % of it on average for a 1000-row layer, where the partial tiles decide.
+void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool dense = false,
+                bool direct = false)
 {
     cus = std::max(1, cus);
     nq = 0;
@@ -328,9 +333,10 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
             const int64_t rounds = (tiles * sp + cus - 1) / cus;
             const int64_t blocks = (L->nbw + sp - 1) / sp;
             // blocks decoded beforehand cost a copy instead of a decode
-            const int64_t t = dense ? rounds * (8000 + blocks * (1500 + 4100 * q))
-                                    : rounds * (12000 + blocks * (5000 + (bf16 ? 1500 : 4100) * q));
-            if (best < 0 || (q == nq ? t < best : t + t / 16 < best)) {
+            int64_t t = dense ? rounds * (8000 + blocks * (1500 + 4100 * q))
+                              : rounds * (12000 + blocks * (5000 + (bf16 ? 1500 : 4100) * q));
+            if (!(direct && sp == 1)) t += (int64_t)panels * sp * cols * L->desc.block_h * (int64_t)sizeof(float) * 3 / 4000;
+            if (best < 0 || t < best) {
                 best = t;
                 nq = q;
                 np = cols;
@@ -826,7 +832,7 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
         int nq, np, splits;
-        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense);
+        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense, !bf16);
         P.xt_bytes = std::max(P.xt_bytes, (size_t)P.groups_at_once * xt_bytes_for(L, np, bf16));
         P.part_bytes = std::max(P.part_bytes, (size_t)launch_panels * splits * np * L->desc.block_h * sizeof(float));
     }
@@ -904,7 +910,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const int ncols = nb * pq;
         int nq, Np, splits;
         const int launch_panels = P.panels_per_group * P.groups_at_once;
-        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense);
+        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense, !bf16);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         // groups_at_once filter groups per launch of each kernel: group grp of a launch has
