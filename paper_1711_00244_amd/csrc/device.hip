@@ -16,7 +16,7 @@
 // One translation unit: this file holds the host side (device image of a layer, launch
 // shapes, the entry points) and includes the kernels - decode.cuh (wavefront primitives,
 // decoding and placement passes), sparse_kernels.cuh, mfma_kernels.cuh, bf16_kernels.cuh,
-// finish_kernels.cuh, layer_kernels.cuh.
+// conv_kernels.cuh, finish_kernels.cuh, layer_kernels.cuh.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
@@ -101,6 +101,7 @@ static LayerDev make_dev(const cl_layer *L)
 #include "sparse_kernels.cuh"
 #include "mfma_kernels.cuh"
 #include "bf16_kernels.cuh"
+#include "conv_kernels.cuh"
 #include "finish_kernels.cuh"
 #include "layer_kernels.cuh"
 
@@ -317,12 +318,13 @@ bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->des
 // 1024 images: the choice is the fastest measured shape for the large layers and
 // within 3 % of it on average for a 1000-row layer, where the partial tiles decide.
 void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool dense = false,
-                bool direct = false)
+                bool direct = false, int only_q = 0)
 {
     cus = std::max(1, cus);
     nq = 0;
     int64_t best = -1;
     for (int q : {1, 2, 4, 8}) {
+        if (only_q && q != only_q) continue;
         const int w = 32 * q;
         const int cols = (ncols + w - 1) / w * w;
         const int64_t tiles = (int64_t)panels * (cols / w);
@@ -783,6 +785,7 @@ struct ConvPlan {
     ConvGeom cg{};
     int OCg = 0, panels_per_group = 0, imgs = 0;
     bool dense = false;        // decode every block once into a dense tile, then multiply from those
+    bool gather = false;       // no column matrix in memory: conv_mfma_kernel gathers it into LDS (implies dense)
     int groups_at_once = 1;    // filter groups per launch: all of them, or one (the compact form)
     size_t lds = 0, xt_bytes = 0, part_bytes = 0, wt_bytes = 0;
     size_t total() const { return xt_bytes + part_bytes + wt_bytes; }
@@ -794,6 +797,10 @@ struct ConvPlan {
 // columns on, 2-9 % slower around 3 000, where the extra launch costs more than the
 // repeated decoding).
 constexpr int64_t kConvDenseColumns = 4096;
+
+// From there on the fp32 path also leaves the column matrix out of memory: the multiply
+// kernel's gatherer wavefronts build each 128 x 128 piece of it in LDS from the input.
+constexpr bool kConvGather = true;
 
 // compact: the form that needs the least scratch - filter groups one after the other
 // through the same buffers, blocks decoded inside the multiply kernel.
@@ -826,15 +833,23 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     P.lds = mfma_lds_bytes(L, bf16);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
     P.dense = !compact && !bf16 && (int64_t)std::min(P.imgs, batch) * g.P * g.Q >= kConvDenseColumns;
+    P.gather = P.dense && kConvGather && (size_t)kConvLdsBytes <= dl.max_lds &&
+               (int64_t)(kConvColumns + 1) * g.C * g.H * g.W < (1 << 29) && g.R <= 32 && g.S <= 32;      // the gatherers' 32-bit byte offsets and tap masks
+    if (P.gather) {
+        // nothing but the launch size limits the images of a launch
+        P.imgs = (int)std::min<int64_t>(batch, kMaxTileColumns / ((int64_t)g.P * g.Q));
+        P.lds = kConvLdsBytes;
+    }
     P.wt_bytes = P.dense ? (size_t)L->n_blocks * kTile * kTile * sizeof(float) : 0;
     // workspace for the larger of a full image group and the last, smaller one
     P.xt_bytes = P.part_bytes = 0;
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
         int nq, np, splits;
-        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense, !bf16);
-        P.xt_bytes = std::max(P.xt_bytes, (size_t)P.groups_at_once * xt_bytes_for(L, np, bf16));
-        P.part_bytes = std::max(P.part_bytes, (size_t)launch_panels * splits * np * L->desc.block_h * sizeof(float));
+        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense, !bf16, P.gather ? kConvColumns / 32 : 0);
+        if (!P.gather) P.xt_bytes = std::max(P.xt_bytes, (size_t)P.groups_at_once * xt_bytes_for(L, np, bf16));
+        if (!(P.gather && splits == 1))
+            P.part_bytes = std::max(P.part_bytes, (size_t)launch_panels * splits * np * L->desc.block_h * sizeof(float));
     }
     return CL_OK;
 }
@@ -898,10 +913,10 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     float *part = (float *)((char *)d_workspace + P.xt_bytes);
     float *wt = P.dense ? (float *)((char *)d_workspace + P.xt_bytes + P.part_bytes) : nullptr;
     if (P.dense) {
-        const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + (size_t)kTile * kTile * sizeof(float);
+        const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + (size_t)kWTileBytes;
         static LdsLimit seen;
         if (int32_t rc = ensure_lds((const void *)decode_tiles_kernel, lds, seen)) return rc;
-        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, D, wt);
+        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, D, wt, P.gather ? 1 : 0);
         HIP_TRY(hipGetLastError());
     }
     bool timed = false;
@@ -910,9 +925,36 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const int ncols = nb * pq;
         int nq, Np, splits;
         const int launch_panels = P.panels_per_group * P.groups_at_once;
-        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense, !bf16);
+        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense, !bf16, P.gather ? kConvColumns / 32 : 0);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
+        if (P.gather) {
+            // one launch gathers and multiplies; it finishes the output itself unless the block rows are split
+            const bool direct = splits == 1;
+            const DirectOut out{direct ? y : nullptr, d_bias, ncols, pq, relu};
+            static LdsLimit seen[2];
+            const bool combined = g.R * g.S <= 32;
+            if (int32_t rc = ensure_lds(combined ? (const void *)conv_mfma_kernel<true> : (const void *)conv_mfma_kernel<false>, P.lds, seen[combined])) return rc;
+            dim3 grid;
+            GRID_TRY(grid, (int64_t)launch_panels * splits * (Np / kConvColumns));
+            if (!timed) timing_begin(st);
+            if (combined)
+                hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, part, g, ncols, Np, splits,
+                                   P.panels_per_group, out);
+            else
+                hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, part, g, ncols, Np, splits,
+                                   P.panels_per_group, out);
+            HIP_TRY(hipGetLastError());
+            if (!timed) { timing_end(st, 1); timed = true; }
+            if (direct) continue;
+            const int ct = reduce_col_tile(launch_panels, ncols);
+            dim3 rgrid;
+            GRID_TRY(rgrid, (int64_t)launch_panels * ((ncols + ct - 1) / ct));
+            hipLaunchKernelGGL(mfma_reduce_kernel, rgrid, dim3(256), 0, st,
+                               D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
+            HIP_TRY(hipGetLastError());
+            continue;
+        }
         // groups_at_once filter groups per launch of each kernel: group grp of a launch has
         // its column matrix at xt + grp * x_bytes and multiplies its own block rows
         const size_t x_bytes = xt_bytes_for(L, Np, bf16);

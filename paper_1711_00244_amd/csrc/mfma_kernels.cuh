@@ -209,21 +209,23 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
 
 // Every block of the layer decoded once into a dense 128 x 128 fp32 tile in device
 // memory (Algorithm 2 steps 5-9 for all blocks; rows and columns a block does not have
-// are zero): tiles_out[block][row][column].  One workgroup per block, a chunk per
-// wavefront at a time, the tile built in LDS and written out in one piece.  For layers
-// whose blocks would otherwise be decoded over and over - a convolution, where hundreds
-// of column tiles multiply the same few blocks.
-__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out)
+// are zero).  One workgroup per block, a chunk per wavefront at a time, the tile built
+// in LDS and written out in one piece: as tiles_out[block][row][column], or, with
+// `fragments`, as tiles_out[block][column / 4][row][column % 4] - the order in which
+// the lanes of a multiplying wavefront take their 16-byte pieces of a tile straight from
+// device memory.  For layers whose blocks would otherwise be decoded over and over - a
+// convolution, where hundreds of column tiles multiply the same few blocks.
+__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out, int fragments)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    float *tile = s.extra;                                  // [kTile][kTile]
+    float *tile = s.extra;                                  // [kTile][kWStride]
     const uint32_t b = blockIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
     const TableRegs tr = fetch_tables(L);
-    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) ((uint4 *)tile)[t] = uint4{0, 0, 0, 0};
+    for (int t = threadIdx.x; t < kTile * kWStride / 4; t += kThreads) ((uint4 *)tile)[t] = uint4{0, 0, 0, 0};
     store_tables(s, L, tr);
     __syncthreads();
     const BlockGeom g = block_geom(L, b);
@@ -234,12 +236,18 @@ __global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, floa
         for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
             uint32_t r, cc;
             split_pos(pos, g, r, cc);
-            if (v != 0 && cc < (uint32_t)kTile) tile[r * kTile + cc] = s.T.cb[v];
+            if (v != 0 && cc < (uint32_t)kTile) tile[r * kWStride + cc] = s.T.cb[v];
         });
     }
     __syncthreads();
     uint4 *dst = (uint4 *)(tiles_out + (size_t)b * kTile * kTile);
-    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) dst[t] = ((const uint4 *)tile)[t];
+    const uint4 *src = (const uint4 *)tile;
+    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) {
+        // piece t of the output: row t / 32, columns 4 (t % 32) ..., or in fragment order
+        // row t % 128, columns 4 (t / 128) ...
+        const int row = fragments ? t % kTile : t / (kTile / 4), c4 = fragments ? t / kTile : t % (kTile / 4);
+        dst[t] = src[row * (kWStride / 4) + c4];
+    }
 }
 
 // The loader wavefronts' side of the dense-tile kernel when the blocks have been decoded
@@ -291,6 +299,76 @@ struct DirectOut {
     const float *bias;     // M values or null
     int ncols, pq, relu;   // real columns (image x pixel), pixels per image
 };
+
+// What a multiplying wavefront does with its finished accumulators: accumulator 4 v + q,
+// element e of lane l holds column 128 v + kVecW (8 (e / 4) + 4 (l / 32) + e % 4) + q of the
+// workgroup's tile for weight row 32 wave + l % 32.  Either the finished output (out.Y:
+// bias, activation, NCHW, through `lds`, which must be free: every wavefront has passed
+// its last barrier) or the workgroup's partial tile for the finishing kernel.
+template <int NQ>
+__device__ __forceinline__ void store_accumulators(const floatx16 (&acc)[NQ], const LayerDev &L, float *lds, float *part,
+                                                   const DirectOut &out, int pj, int p, int nb, int Bp, int wave, int lane)
+{
+    constexpr int kImages = MfmaShape<NQ>::kImages;
+    constexpr int kVecW = MfmaShape<NQ>::kVecW, kVecs = MfmaShape<NQ>::kVecs;
+    const int kl = lane >> 5, m = lane & 31;
+    float *tiles = lds;
+    const int r = wave * 32 + m;
+    if (out.Y) {
+        // The output runs along the columns, the accumulators along the rows: turn the
+        // wavefront's 32 x kImages piece in LDS (the weight tiles are free now; the last
+        // barrier above was every wavefront's last use of them), then write each row's
+        // columns in runs, bias and activation on the way.
+        constexpr int kStride = kImages + 1;
+        float *t = tiles + wave * 32 * kStride;
+#pragma unroll
+        for (int v = 0; v < kVecs; ++v) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
+#pragma unroll
+                for (int q = 0; q < kVecW; ++q) t[m * kStride + kTile * v + kVecW * slot + q] = acc[4 * v + q][e];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int row_id = p * L.bh;
+        const int rows = min(32, min(L.bh, L.M - row_id) - wave * 32);
+        // a lane's columns are the same for every row: where they sit in Y is worked out once
+        constexpr int kMine = (kImages + 63) / 64;
+        size_t at[kMine];
+        bool live[kMine];
+#pragma unroll
+        for (int i = 0; i < kMine; ++i) {
+            const int c = nb * kImages + lane + 64 * i;
+            live[i] = lane + 64 * i < kImages && c < out.ncols;
+            at[i] = ((size_t)(c / out.pq) * L.M + row_id + wave * 32) * out.pq + (c % out.pq);
+        }
+        for (int rr = 0; rr < rows; ++rr) {
+            const float bv = out.bias ? out.bias[row_id + wave * 32 + rr] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < kMine; ++i) {
+                const float y = t[rr * kStride + lane + 64 * i] + bv;
+                if (live[i]) out.Y[at[i] + (size_t)rr * out.pq] = out.relu ? fmaxf(y, 0.0f) : y;
+            }
+        }
+        return;
+    }
+    // 32 lanes write 32 consecutive floats of the workgroup's partial tile
+    if (r < L.bh) {
+        float *mine = part + ((size_t)pj * Bp + (size_t)nb * kImages) * L.bh + r;
+#pragma unroll
+        for (int v = 0; v < kVecs; ++v) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
+#pragma unroll
+                for (int q = 0; q < kVecW; ++q) mine[(size_t)(kTile * v + kVecW * slot + q) * L.bh] = acc[4 * v + q][e];
+            }
+        }
+    }
+}
 
 // With DENSE the blocks come decoded from device memory (wt, written by
 // decode_tiles_kernel) and the wavefronts 4 and up only copy them into LDS.
@@ -372,9 +450,6 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
                 // The four weights in b_cur are this lane's alone and have been read: zero them
                 // now, behind the multiplies, so that the decoders get a clean tile back (a
                 // copied tile is overwritten whole instead).
-                // The four weights in b_cur are this lane's alone and have been read: zero them
-                // now, behind the multiplies, so that the decoders get a clean tile back (a
-                // copied tile is overwritten whole instead).
                 if (!DENSE) wp[ks / 4 + h4] = float4{0.0f, 0.0f, 0.0f, 0.0f};
                 __builtin_amdgcn_sched_barrier(0);          // the LDS accesses go out before these multiplies
                 const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
@@ -396,53 +471,5 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
         }
         __syncthreads();                                    // done with this tile, and it is clean
     }
-    // accumulator 4 v + q, element e of lane l: image 128 v + kVecW (8 (e / 4) + 4 (l / 32) + e % 4) + q
-    // of the tile, weight row 32 wave + l % 32
-    const int r = wave * 32 + m;
-    if (out.Y) {
-        // The output runs along the columns, the accumulators along the rows: turn the
-        // wavefront's 32 x kImages piece in LDS (the weight tiles are free now; the last
-        // barrier above was every wavefront's last use of them), then write each row's
-        // columns in runs, bias and activation on the way.
-        constexpr int kStride = kImages + 1;
-        float *t = tiles + wave * 32 * kStride;
-#pragma unroll
-        for (int v = 0; v < kVecs; ++v) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
-#pragma unroll
-                for (int q = 0; q < kVecW; ++q) t[m * kStride + kTile * v + kVecW * slot + q] = acc[4 * v + q][e];
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        const int row_id = p * L.bh;
-        const int rows = min(32, min(L.bh, L.M - row_id) - wave * 32);
-        for (int rr = 0; rr < rows; ++rr) {
-            const int oc = row_id + wave * 32 + rr;
-            const float bv = out.bias ? out.bias[oc] : 0.0f;
-            for (int cc = lane; cc < kImages; cc += 64) {
-                const int c = nb * kImages + cc;
-                if (c >= out.ncols) break;
-                const float y = t[rr * kStride + cc] + bv;
-                out.Y[((size_t)(c / out.pq) * L.M + oc) * out.pq + (c % out.pq)] = out.relu ? fmaxf(y, 0.0f) : y;
-            }
-        }
-        return;
-    }
-    // 32 lanes write 32 consecutive floats of the workgroup's partial tile
-    if (r < L.bh) {
-        float *mine = part + ((size_t)pj * Bp + (size_t)nb * kImages) * L.bh + r;
-#pragma unroll
-        for (int v = 0; v < kVecs; ++v) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int slot = 8 * (e / 4) + 4 * kl + (e & 3);
-#pragma unroll
-                for (int q = 0; q < kVecW; ++q) mine[(size_t)(kTile * v + kVecW * slot + q) * L.bh] = acc[4 * v + q][e];
-            }
-        }
-    }
+    store_accumulators<NQ>(acc, L, tiles, part, out, pj, p, nb, Bp, wave, lane);
 }
