@@ -26,13 +26,33 @@ constexpr int kConvColumns = kTile;                        // columns per workgr
 constexpr int kActStride = kTile + 4;                      // floats per row of an activation tile (16-byte rows, skewed)
 constexpr int kActTileFloats = kTile * kActStride;
 constexpr int kConvLdsBytes = 2 * kActTileFloats * 4;
-constexpr int kConvWAhead = 4;                             // 16-byte weight loads in flight per lane (four steps each)
+constexpr int kConvWAhead = 8;                             // 16-byte weight loads in flight per lane (four steps each)
 constexpr int kConvAAhead = 4;                             // steps of activations read ahead from LDS
+
+// What the gatherers need to know of a row of the column matrix, for every row of every
+// piece (piece bi, row kk = column bi bw + kk of the layer = (c, r, s)): x = byte offset
+// of (c, r, s) from a receptive field's corner at channel 0, y = which bit of a column's
+// tap masks says whether the tap is outside the image (r S + s, or r | s << 8 for the
+// separate masks), with the top bit set for a row the piece does not have.  Written once
+// per call; read with uniform loads.
+__global__ __launch_bounds__(256) void conv_rows_kernel(ConvGeom cg, int bw, int K, int n_rows, int combined, uint2 *rows)
+{
+    const int t = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (t >= n_rows) return;
+    const int kk = t % kTile, k = (t / kTile) * bw + kk;
+    uint2 e = make_uint2(0u, 0x80000000u);
+    if (kk < bw && k < K) {
+        const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
+        e.x = (uint32_t)(c * cg.H * cg.W + r * cg.W + s) * (uint32_t)sizeof(float);
+        e.y = combined ? (uint32_t)(r * cg.S + s) : (uint32_t)(r | s << 8);
+    }
+    rows[t] = e;
+}
 
 template <bool COMBINED>
 __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, const float *__restrict__ X, const float *__restrict__ wt,
-                                                                 float *part, ConvGeom cg, int n_cols, int Np, int splits,
-                                                                 int panels_per_group, DirectOut out)
+                                                                 const uint2 *__restrict__ rows, float *part, ConvGeom cg, int n_cols,
+                                                                 int Np, int splits, int panels_per_group, DirectOut out)
 {
     extern __shared__ __attribute__((aligned(16))) float act[];        // [2][kTile][kActStride]
     const int nbt = Np / kConvColumns;
@@ -45,9 +65,6 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
     if (wave >= 4) {
-        // the gatherers go first at the issue arbiter: a multiplying wavefront needs one issue
-        // slot per 64-cycle multiply, the gatherers next to it on the SIMD can have the rest
-        __builtin_amdgcn_s_setprio(3);
         const int d = wave - 4;
         const int pq = cg.P * cg.Q, plane = cg.H * cg.W;
         const int c0 = (p / panels_per_group) * cg.Cg;              // the filter group's input channels
@@ -94,32 +111,27 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
                 }
             }
         }
-        // Wavefront d gathers rows 16 d .. 16 d + 15 of a piece; a row is (c, r, s) of the
-        // block's column, uniform: found by division once per piece, then stepped.
+        // Wavefront d gathers rows 16 d .. 16 d + 15 of a piece; what a row is comes from
+        // the table (uniform loads), so a row costs no arithmetic of its own.
         constexpr int kRows = kTile / kConvGatherers;
         auto fill = [&](int bi, float *tile) {
-            const int kk0 = kRows * d, k0 = bi * L.bw + kk0;
-            int s = __builtin_amdgcn_readfirstlane(k0 % cg.S), t = k0 / cg.S;
-            int r = __builtin_amdgcn_readfirstlane(t % cg.R), c = __builtin_amdgcn_readfirstlane(t / cg.R);
+            const uint2 *rp = rows + (bi * kTile + kRows * d);
             float v[kRows][2];
 #pragma unroll
             for (int jj = 0; jj < kRows; ++jj) {
-                const uint32_t shift = (uint32_t)(c * plane + r * cg.W + s) * (uint32_t)sizeof(float);
-                const uint32_t no_row = kk0 + jj < L.bw && k0 + jj < L.K ? 0u : 0xffffffffu;      // a row the block does not have
+                const uint2 e = rp[jj];
+                const uint32_t no_row = (uint32_t)((int)e.y >> 31);
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const uint32_t out = COMBINED ? (uint32_t)__builtin_amdgcn_sbfe(bad[i], r * cg.S + s, 1)
-                                                  : (uint32_t)(__builtin_amdgcn_sbfe(bad[i], r, 1) | __builtin_amdgcn_sbfe(bad_s[i], s, 1));
-                    v[jj][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xb, (int)((at[i] + shift) | out | no_row), 0, 0));
-                }
-                if (++s == cg.S) {
-                    s = 0;
-                    if (++r == cg.R) { r = 0; ++c; }
+                    const uint32_t out = COMBINED ? (uint32_t)__builtin_amdgcn_sbfe(bad[i], e.y & 0xffu, 1)
+                                                  : (uint32_t)(__builtin_amdgcn_sbfe(bad[i], e.y & 0xffu, 1) |
+                                                               __builtin_amdgcn_sbfe(bad_s[i], (e.y >> 8) & 0xffu, 1));
+                    v[jj][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xb, (int)((at[i] + e.x) | out | no_row), 0, 0));
                 }
             }
 #pragma unroll
             for (int jj = 0; jj < kRows; ++jj)
-                *(float2 *)(tile + (kk0 + jj) * kActStride + 2 * lane) = make_float2(v[jj][0], v[jj][1]);
+                *(float2 *)(tile + (kRows * d + jj) * kActStride + 2 * lane) = make_float2(v[jj][0], v[jj][1]);
         };
         if (blk_lo < blk_hi) fill(blk_lo, act);
         __syncthreads();

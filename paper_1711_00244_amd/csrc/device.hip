@@ -317,14 +317,14 @@ bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->des
 // to sweeps over every tile width and split of the AlexNet and VGG-16 FC layers at 8 to
 // 1024 images: the choice is the fastest measured shape for the large layers and
 // within 3 % of it on average for a 1000-row layer, where the partial tiles decide.
-void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool dense = false,
-                bool direct = false, int only_q = 0)
+void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool gathered = false,
+                bool direct = false)
 {
     cus = std::max(1, cus);
     nq = 0;
     int64_t best = -1;
     for (int q : {1, 2, 4, 8}) {
-        if (only_q && q != only_q) continue;
+        if (gathered && 32 * q != kConvColumns) continue;      // conv_mfma_kernel has one tile width
         const int w = 32 * q;
         const int cols = (ncols + w - 1) / w * w;
         const int64_t tiles = (int64_t)panels * (cols / w);
@@ -334,8 +334,8 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
         for (int sp = 1; sp <= sp_max; ++sp) {
             const int64_t rounds = (tiles * sp + cus - 1) / cus;
             const int64_t blocks = (L->nbw + sp - 1) / sp;
-            // blocks decoded beforehand cost a copy instead of a decode
-            int64_t t = dense ? rounds * (8000 + blocks * (1500 + 4100 * q))
+            // blocks decoded beforehand: the gathering costs less than a decode
+            int64_t t = gathered ? rounds * (8000 + blocks * (1500 + 4100 * q))
                               : rounds * (12000 + blocks * (5000 + (bf16 ? 1500 : 4100) * q));
             if (!(direct && sp == 1)) t += (int64_t)panels * sp * cols * L->desc.block_h * (int64_t)sizeof(float) * 3 / 4000;
             if (best < 0 || t < best) {
@@ -394,15 +394,15 @@ static int32_t ensure_lds(const void *kernel, size_t lds, LdsLimit &seen)
     return CL_OK;
 }
 
-template <int NQ, bool DENSE>
+template <int NQ>
 int32_t launch_mfma_as(const LayerDev &D, int panels, int splits, int np, int panels_per_x, size_t x_stride, size_t lds,
-                       const float *xt, float *part, const float *wt, const DirectOut &out, hipStream_t st)
+                       const float *xt, float *part, const DirectOut &out, hipStream_t st)
 {
     static LdsLimit seen;
-    if (int32_t rc = ensure_lds((const void *)fc_mfma_kernel<NQ, DENSE>, lds, seen)) return rc;
+    if (int32_t rc = ensure_lds((const void *)fc_mfma_kernel<NQ>, lds, seen)) return rc;
     dim3 grid;
     GRID_TRY(grid, (int64_t)panels * splits * (np / MfmaShape<NQ>::kImages));
-    hipLaunchKernelGGL((fc_mfma_kernel<NQ, DENSE>), grid, dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride, wt, out);
+    hipLaunchKernelGGL(fc_mfma_kernel<NQ>, grid, dim3(MfmaShape<NQ>::kThreads), lds, st, D, xt, part, splits, np, panels_per_x, x_stride, out);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -422,9 +422,8 @@ int32_t launch_bf16_as(const LayerDev &D, int panels, int splits, int np, int pa
 
 // panels block rows in one launch; each run of panels_per_x of them multiplies an
 // activation matrix of its own, x_bytes after the one before
-// wt: the layer's blocks as dense tiles (decode_tiles_kernel), or null to decode them in the kernel
 int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int panels, int splits, int np, int panels_per_x,
-                    size_t x_bytes, size_t lds, const void *xt, float *part, hipStream_t st, const float *wt = nullptr,
+                    size_t x_bytes, size_t lds, const void *xt, float *part, hipStream_t st,
                     const DirectOut &out = DirectOut{nullptr, nullptr, 0, 1, 0})
 {
     const size_t x_stride = x_bytes / (bf16 ? sizeof(uint16_t) : sizeof(float));
@@ -436,19 +435,12 @@ int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int
         case 4: return launch_bf16_as<4>(D, panels, splits, np, panels_per_x, x_stride, lds, (const uint16_t *)xt, pe, part, st);
         case 8: return launch_bf16_as<8>(D, panels, splits, np, panels_per_x, x_stride, lds, (const uint16_t *)xt, pe, part, st);
         }
-    } else if (wt) {
-        switch (nq) {
-        case 1: return launch_mfma_as<1, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
-        case 2: return launch_mfma_as<2, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
-        case 4: return launch_mfma_as<4, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
-        case 8: return launch_mfma_as<8, true>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, wt, out, st);
-        }
     } else {
         switch (nq) {
-        case 1: return launch_mfma_as<1, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
-        case 2: return launch_mfma_as<2, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
-        case 4: return launch_mfma_as<4, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
-        case 8: return launch_mfma_as<8, false>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, nullptr, out, st);
+        case 1: return launch_mfma_as<1>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, out, st);
+        case 2: return launch_mfma_as<2>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, out, st);
+        case 4: return launch_mfma_as<4>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, out, st);
+        case 8: return launch_mfma_as<8>(D, panels, splits, np, panels_per_x, x_stride, lds, (const float *)xt, part, out, st);
         }
     }
     return fail(CL_EINVAL, "internal: no dense-tile kernel for %d accumulators", nq);
@@ -784,23 +776,20 @@ constexpr size_t kConvXtCap = (size_t)1024 << 20;
 struct ConvPlan {
     ConvGeom cg{};
     int OCg = 0, panels_per_group = 0, imgs = 0;
-    bool dense = false;        // decode every block once into a dense tile, then multiply from those
-    bool gather = false;       // no column matrix in memory: conv_mfma_kernel gathers it into LDS (implies dense)
+    bool gather = false;       // blocks decoded once per call, no column matrix in memory: conv_mfma_kernel
     int groups_at_once = 1;    // filter groups per launch: all of them, or one (the compact form)
-    size_t lds = 0, xt_bytes = 0, part_bytes = 0, wt_bytes = 0;
-    size_t total() const { return xt_bytes + part_bytes + wt_bytes; }
+    size_t lds = 0, xt_bytes = 0, part_bytes = 0, wt_bytes = 0, rows_bytes = 0;
+    size_t total() const { return xt_bytes + part_bytes + wt_bytes + rows_bytes; }
 };
 
-// From this many columns on (image x output pixel) a convolution decodes its blocks
-// once per call into dense tiles in the workspace instead of once per column tile
-// (measured on the AlexNet and VGG-16 convolutions: 4-10 % faster from about 6 000
-// columns on, 2-9 % slower around 3 000, where the extra launch costs more than the
-// repeated decoding).
-constexpr int64_t kConvDenseColumns = 4096;
-
-// From there on the fp32 path also leaves the column matrix out of memory: the multiply
-// kernel's gatherer wavefronts build each 128 x 128 piece of it in LDS from the input.
-constexpr bool kConvGather = true;
+// From this many columns on (image x output pixel) the fp32 path decodes the layer's
+// blocks once per call into dense tiles in the workspace, and a multiply kernel of its own
+// gathers each 128 x 128 piece of the column matrix into LDS straight from the input, so
+// that the column matrix never exists in memory.  Below, the blocks of a column tile
+// are decoded inside the multiply kernel, which costs less than the two extra launches
+// (measured on the AlexNet and VGG-16 convolutions: decoding once pays from about 6 000
+// columns on and loses around 3 000).
+constexpr int64_t kConvGatherColumns = 4096;
 
 // compact: the form that needs the least scratch - filter groups one after the other
 // through the same buffers, blocks decoded inside the multiply kernel.
@@ -832,21 +821,23 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     P.imgs = (int)std::max<size_t>(1, std::min<size_t>((size_t)batch, kConvXtCap / per_image));
     P.lds = mfma_lds_bytes(L, bf16);
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
-    P.dense = !compact && !bf16 && (int64_t)std::min(P.imgs, batch) * g.P * g.Q >= kConvDenseColumns;
-    P.gather = P.dense && kConvGather && (size_t)kConvLdsBytes <= dl.max_lds &&
+    const int64_t cols = (int64_t)batch * g.P * g.Q;
+    P.gather = !compact && !bf16 && cols >= kConvGatherColumns && (size_t)kConvLdsBytes <= dl.max_lds &&
+               2 * launch_panels * ((cols + kConvColumns - 1) / kConvColumns) >= dl.cus &&      // its one tile width must fill the chip
                (int64_t)(kConvColumns + 1) * g.C * g.H * g.W < (1 << 29) && g.R <= 32 && g.S <= 32;      // the gatherers' 32-bit byte offsets and tap masks
     if (P.gather) {
         // nothing but the launch size limits the images of a launch
         P.imgs = (int)std::min<int64_t>(batch, kMaxTileColumns / ((int64_t)g.P * g.Q));
         P.lds = kConvLdsBytes;
     }
-    P.wt_bytes = P.dense ? (size_t)L->n_blocks * kTile * kTile * sizeof(float) : 0;
+    P.wt_bytes = P.gather ? (size_t)L->n_blocks * kTile * kTile * sizeof(float) : 0;
+    P.rows_bytes = P.gather ? round256((size_t)L->nbw * kTile * sizeof(uint2)) : 0;
     // workspace for the larger of a full image group and the last, smaller one
     P.xt_bytes = P.part_bytes = 0;
     for (int imgs : {P.imgs, batch % P.imgs}) {
         if (imgs == 0) continue;
         int nq, np, splits;
-        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.dense, !bf16, P.gather ? kConvColumns / 32 : 0);
+        mfma_shape(L, launch_panels, imgs * g.P * g.Q, dl.cus, bf16, nq, np, splits, P.gather, !bf16);
         if (!P.gather) P.xt_bytes = std::max(P.xt_bytes, (size_t)P.groups_at_once * xt_bytes_for(L, np, bf16));
         if (!(P.gather && splits == 1))
             P.part_bytes = std::max(P.part_bytes, (size_t)launch_panels * splits * np * L->desc.block_h * sizeof(float));
@@ -911,12 +902,18 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
     const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
     void *xt = d_workspace;
     float *part = (float *)((char *)d_workspace + P.xt_bytes);
-    float *wt = P.dense ? (float *)((char *)d_workspace + P.xt_bytes + P.part_bytes) : nullptr;
-    if (P.dense) {
+    float *wt = P.gather ? (float *)((char *)d_workspace + P.xt_bytes + P.part_bytes) : nullptr;
+    uint2 *rows = P.gather ? (uint2 *)((char *)d_workspace + P.xt_bytes + P.part_bytes + P.wt_bytes) : nullptr;
+    const bool combined = g.R * g.S <= 32;      // one tap mask per column instead of one per filter row and one per filter column
+    if (P.gather) {
         const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + (size_t)kWTileBytes;
         static LdsLimit seen;
         if (int32_t rc = ensure_lds((const void *)decode_tiles_kernel, lds, seen)) return rc;
-        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, D, wt, P.gather ? 1 : 0);
+        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, D, wt);
+        HIP_TRY(hipGetLastError());
+        const int n_rows = L->nbw * kTile;
+        hipLaunchKernelGGL(conv_rows_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st, g, L->desc.block_w, K, n_rows,
+                           combined ? 1 : 0, rows);
         HIP_TRY(hipGetLastError());
     }
     bool timed = false;
@@ -925,7 +922,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const int ncols = nb * pq;
         int nq, Np, splits;
         const int launch_panels = P.panels_per_group * P.groups_at_once;
-        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.dense, !bf16, P.gather ? kConvColumns / 32 : 0);
+        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.gather, !bf16);
         const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
         float *y = d_Y + (size_t)b0 * M * pq;
         if (P.gather) {
@@ -933,16 +930,15 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             const bool direct = splits == 1;
             const DirectOut out{direct ? y : nullptr, d_bias, ncols, pq, relu};
             static LdsLimit seen[2];
-            const bool combined = g.R * g.S <= 32;
             if (int32_t rc = ensure_lds(combined ? (const void *)conv_mfma_kernel<true> : (const void *)conv_mfma_kernel<false>, P.lds, seen[combined])) return rc;
             dim3 grid;
             GRID_TRY(grid, (int64_t)launch_panels * splits * (Np / kConvColumns));
             if (!timed) timing_begin(st);
             if (combined)
-                hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, part, g, ncols, Np, splits,
+                hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, rows, part, g, ncols, Np, splits,
                                    P.panels_per_group, out);
             else
-                hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, part, g, ncols, Np, splits,
+                hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, rows, part, g, ncols, Np, splits,
                                    P.panels_per_group, out);
             HIP_TRY(hipGetLastError());
             if (!timed) { timing_end(st, 1); timed = true; }
@@ -977,7 +973,7 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             // block rows that are not split need no adding up: the multiply kernel finishes the output
             const bool direct = !bf16 && splits == 1;
             const DirectOut out{direct ? y : nullptr, d_bias, ncols, pq, relu};
-            if (int32_t rc = launch_mfma(L, D, bf16, nq, launch_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, wt, out)) return rc;
+            if (int32_t rc = launch_mfma(L, D, bf16, nq, launch_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, out)) return rc;
             if (!timed) { timing_end(st, 1); timed = true; }
             if (direct) continue;
             const int ct = reduce_col_tile(launch_panels, ncols);

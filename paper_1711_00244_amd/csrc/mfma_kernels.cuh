@@ -210,12 +210,11 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
 // Every block of the layer decoded once into a dense 128 x 128 fp32 tile in device
 // memory (Algorithm 2 steps 5-9 for all blocks; rows and columns a block does not have
 // are zero).  One workgroup per block, a chunk per wavefront at a time, the tile built
-// in LDS and written out in one piece: as tiles_out[block][row][column], or, with
-// `fragments`, as tiles_out[block][column / 4][row][column % 4] - the order in which
-// the lanes of a multiplying wavefront take their 16-byte pieces of a tile straight from
-// device memory.  For layers whose blocks would otherwise be decoded over and over - a
-// convolution, where hundreds of column tiles multiply the same few blocks.
-__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out, int fragments)
+// in LDS and written out in one piece as tiles_out[block][column / 4][row][column % 4]:
+// the order in which the lanes of a multiplying wavefront of conv_mfma_kernel take their
+// 16-byte pieces of a tile straight from device memory.  For a convolution, where
+// hundreds of column tiles multiply the same few blocks.
+__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
@@ -243,35 +242,8 @@ __global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, floa
     uint4 *dst = (uint4 *)(tiles_out + (size_t)b * kTile * kTile);
     const uint4 *src = (const uint4 *)tile;
     for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) {
-        // piece t of the output: row t / 32, columns 4 (t % 32) ..., or in fragment order
-        // row t % 128, columns 4 (t / 128) ...
-        const int row = fragments ? t % kTile : t / (kTile / 4), c4 = fragments ? t / kTile : t % (kTile / 4);
-        dst[t] = src[row * (kWStride / 4) + c4];
-    }
-}
-
-// The loader wavefronts' side of the dense-tile kernel when the blocks have been decoded
-// beforehand (decode_tiles_kernel): copy tile after tile from device memory into the
-// two alternating LDS tiles, one block ahead of the multipliers, meeting them at one
-// barrier per block like the decoders.  A copied tile overwrites all of the LDS tile,
-// so nothing has to be cleared.  Called by wavefronts 4 .. 4 + DEC - 1.
-template <int DEC>
-__device__ __forceinline__ void loader_role(const float *__restrict__ wt, float *tiles, int blk_lo, int blk_hi, uint32_t pb0,
-                                            int wave, int lane)
-{
-    auto fill = [&](int bi, float *tile) {
-        const float4 *src = (const float4 *)(wt + (size_t)(pb0 + (uint32_t)bi) * kTile * kTile);
-        float4 *dst = (float4 *)tile;
-#pragma unroll 8
-        for (int t = (wave - 4) * 64 + lane; t < kTile * kTile / 4; t += DEC * 64)
-            dst[(t >> 5) * (kWStride / 4) + (t & 31)] = src[t];
-    };
-    __syncthreads();
-    if (blk_lo < blk_hi) fill(blk_lo, tiles);
-    __syncthreads();
-    for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        if (bi + 1 < blk_hi) fill(bi + 1, tiles + (((bi - blk_lo) & 1) ^ 1) * (kWTileBytes / 4));
-        __syncthreads();
+        // piece t of the output: row t % 128, columns 4 (t / 128) .. 4 (t / 128) + 3
+        dst[t] = src[(t % kTile) * (kWStride / 4) + t / kTile];
     }
 }
 
@@ -345,12 +317,24 @@ __device__ __forceinline__ void store_accumulators(const floatx16 (&acc)[NQ], co
             live[i] = lane + 64 * i < kImages && c < out.ncols;
             at[i] = ((size_t)(c / out.pq) * L.M + row_id + wave * 32) * out.pq + (c % out.pq);
         }
-        for (int rr = 0; rr < rows; ++rr) {
-            const float bv = out.bias ? out.bias[row_id + wave * 32 + rr] : 0.0f;
+        // lane l holds the bias of the wavefront's row l % 32; eight rows at a time, their
+        // LDS reads ahead of their stores
+        const float bias_l = out.bias && m < rows ? out.bias[row_id + wave * 32 + m] : 0.0f;
+        for (int r0 = 0; r0 < rows; r0 += 8) {
+            float y[8][kMine];
 #pragma unroll
-            for (int i = 0; i < kMine; ++i) {
-                const float y = t[rr * kStride + lane + 64 * i] + bv;
-                if (live[i]) out.Y[at[i] + (size_t)rr * out.pq] = out.relu ? fmaxf(y, 0.0f) : y;
+            for (int u = 0; u < 8; ++u) {
+                const int rr = min(r0 + u, rows - 1);
+                const float bv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bias_l), rr));
+#pragma unroll
+                for (int i = 0; i < kMine; ++i) y[u][i] = t[rr * kStride + lane + 64 * i] + bv;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (r0 + u >= rows) break;
+#pragma unroll
+                for (int i = 0; i < kMine; ++i)
+                    if (live[i]) out.Y[at[i] + (size_t)(r0 + u) * out.pq] = out.relu ? fmaxf(y[u][i], 0.0f) : y[u][i];
             }
         }
         return;
@@ -370,12 +354,10 @@ __device__ __forceinline__ void store_accumulators(const floatx16 (&acc)[NQ], co
     }
 }
 
-// With DENSE the blocks come decoded from device memory (wt, written by
-// decode_tiles_kernel) and the wavefronts 4 and up only copy them into LDS.
-template <int NQ, bool DENSE>
+template <int NQ>
 __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerDev L, const float *__restrict__ XT, float *part,
                                                                          int splits, int Bp, int panels_per_x, size_t x_stride,
-                                                                         const float *__restrict__ wt, DirectOut out)
+                                                                         DirectOut out)
 {
     constexpr int kMfmaDecoders = MfmaShape<NQ>::kDecoders;
     constexpr int kMfmaThreads = MfmaShape<NQ>::kThreads;
@@ -384,7 +366,7 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     constexpr int kVecW = MfmaShape<NQ>::kVecW, kVecs = MfmaShape<NQ>::kVecs;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    float *tiles = DENSE ? (float *)smem_raw : (float *)s.extra;      // [2][kTile rows][kWStride]; no decode tables with DENSE
+    float *tiles = (float *)s.extra;                                  // [2][kTile rows][kWStride]
     const int nbt = Bp / kImages;
     const int nb = (int)blockIdx.x % nbt;
     const int pj = (int)blockIdx.x / nbt;
@@ -395,19 +377,13 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const bool producer = wave >= 4;
-    if (!DENSE) {
-        if (threadIdx.x < kThreads) store_tables(s, L, fetch_tables(L));
-        for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kMfmaThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
-    }
+    if (threadIdx.x < kThreads) store_tables(s, L, fetch_tables(L));
+    for (int t = threadIdx.x; t < 2 * kWTileBytes / 16; t += kMfmaThreads) ((uint4 *)tiles)[t] = uint4{0, 0, 0, 0};
     // this split's share of the block row's blocks
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
 
     if (producer) {
-        if (DENSE) {
-            loader_role<kMfmaDecoders>(wt, tiles, blk_lo, blk_hi, pb0, wave, lane);
-            return;
-        }
         decoder_role<kMfmaDecoders, false, kWTileBytes / 4>(L, s, tiles, blk_lo, blk_hi, pb0, wave, lane,
                                                              [&](uint32_t v) { return s.T.cb[v]; },
                                                              [&](float *tile, uint32_t r, uint32_t cc, float w) { tile[__umul24(r, (uint32_t)kWStride) + cc] = w; });
@@ -448,9 +424,8 @@ __global__ __launch_bounds__(MfmaShape<NQ>::kThreads) void fc_mfma_kernel(LayerD
             for (int h4 = 0; h4 < kAhead / 4; ++h4) {
                 const float4 b_next = wp[min(ks / 4 + h4 + 1, kTile / 8 - 1)];
                 // The four weights in b_cur are this lane's alone and have been read: zero them
-                // now, behind the multiplies, so that the decoders get a clean tile back (a
-                // copied tile is overwritten whole instead).
-                if (!DENSE) wp[ks / 4 + h4] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                // now, behind the multiplies, so that the decoders get a clean tile back.
+                wp[ks / 4 + h4] = float4{0.0f, 0.0f, 0.0f, 0.0f};
                 __builtin_amdgcn_sched_barrier(0);          // the LDS accesses go out before these multiplies
                 const float bv[4] = {b_cur.x, b_cur.y, b_cur.z, b_cur.w};
 #pragma unroll

@@ -435,21 +435,75 @@ def test_random_layers_all_paths(seed):
         L.free()
 
 
+GATHERED_CONVS = [
+    # 49 taps: separate row and column tap masks; stride 2, padding 3, two blocks
+    (dict(C=3, H=99, W=99, R=7, S=7, stride=2, pad=3, groups=1, OC=10), 7, False),
+    # two filter groups of six filters, one tap mask per column
+    (dict(C=8, H=48, W=52, R=3, S=3, stride=1, pad=1, groups=2, OC=12), 8, False),
+    # three blocks per block row, split among three workgroups: partial tiles and the finishing kernel
+    (dict(C=40, H=48, W=52, R=3, S=3, stride=1, pad=1, groups=1, OC=16), 8, True),
+    # 25 taps, a ragged second block row (130 filters), a ragged block (125 columns), a ragged last tile
+    (dict(C=5, H=37, W=41, R=5, S=5, stride=1, pad=2, groups=1, OC=130), 6, False),
+]
+
+
+@pytest.mark.parametrize("geom,B,split", GATHERED_CONVS)
+def test_conv_gathered_columns(geom, B, split):
+    """From a few thousand columns on the fp32 path keeps no column matrix in memory:
+    the multiply kernel gathers the receptive fields itself.  Its workspace is the
+    decoded blocks, the row table and (block rows split) the partial tiles - far less
+    than a column matrix - and the result is the oracle's direct convolution."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(geom["OC"] * 7 + B)
+    OC, groups = geom["OC"], geom["groups"]
+    Kc = geom["C"] // groups * geom["R"] * geom["S"]
+    W = rand_pruned(rng, OC, Kc, 0.4)
+    bh = cl.conv_block_h(OC, groups)
+    L, m, oW = check_decode(W, 8, 8, bh, 128)
+    X = (rng.random((B, geom["C"], geom["H"], geom["W"]), dtype=np.float32) - 0.3).astype(np.float32)
+    bias = rng.standard_normal(OC).astype(np.float32) * 0.1
+    P = (geom["H"] + 2 * geom["pad"] - geom["R"]) // geom["stride"] + 1
+    Q = (geom["W"] + 2 * geom["pad"] - geom["S"]) // geom["stride"] + 1
+    cols = B * P * Q
+    n_blocks = -(-OC // bh) * -(-Kc // 128)
+    fixed = n_blocks * 128 * 128 * 4 + -(-(-(-Kc // 128) * 128 * 8) // 256) * 256        # decoded blocks + row table
+    ws = cl.conv_workspace_bytes(L, geom, B)
+    assert ws < cols * 128 * 4                       # no column matrix (at least 128 rows of `cols` floats)
+    assert (ws > fixed) == split and ws >= fixed
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
+    for use_bias, relu in [(False, False), (True, True)]:
+        ref = oracle.conv_forward(oW, X, geom, bias if use_bias else None, relu, nthreads=8)
+        Y = cl.compressed_conv_forward(L, geom, Xd, bd if use_bias else None, relu=relu)
+        assert tuple(Y.shape) == ref.shape
+        assert rel_err(Y.cpu().numpy(), ref) <= TOL
+        assert torch.equal(Y, cl.compressed_conv_forward(L, geom, Xd, bd if use_bias else None, relu=relu))
+    assert cl.conv_workspace_bytes(L, geom, B, compact=True) == ws      # nothing needs less than this form
+    L.free()
+
+
 def test_conv_batch_cut_into_image_groups():
-    """A batch whose column matrices exceed the library's limit (1 GiB) runs as
-    several image groups, the last one smaller: VGG-16 conv1_2 (128 MB of columns per
-    image) with 9 images; outputs of sampled filters and images against the oracle."""
+    """A batch whose column matrices would exceed the library's limit (1 GiB) runs as
+    several image groups, the last one smaller, on the paths that keep the column
+    matrix in memory: VGG-16 conv1_2 (128 MB of columns per image) with 9 images on the
+    bf16 path and, for the same call on the fp32 path, the gathered form in one launch;
+    outputs of sampled filters and images against the oracle."""
     torch = torch_cuda()
     spec, W = wl.layer_weights(6, 1)
     g = spec.conv
     L, m, oW = check_decode(W, spec.r, spec.k, 128, 128)
     B = 9
     X = wl.activations(6, B, layer_index=1)
-    Y = cl.compressed_conv_forward(L, g, torch.from_numpy(X).cuda(), relu=True).cpu().numpy()
+    Xd = torch.from_numpy(X).cuda()
     rows = np.array([3, 40])
     imgs = [0, 7, 8]                                   # first group, its last image, the second group
-    ref = oracle.conv_forward(np.ascontiguousarray(oW[rows]), np.ascontiguousarray(X[imgs]), dict(g, OC=len(rows)), relu=True, nthreads=8)
+    sub = dict(g, OC=len(rows))
+    Ws, Xs = np.ascontiguousarray(oW[rows]), np.ascontiguousarray(X[imgs])
+    ref = oracle.conv_forward(Ws, Xs, sub, relu=True, nthreads=8)
+    Y = cl.compressed_conv_forward(L, g, Xd, relu=True).cpu().numpy()
     assert rel_err(Y[imgs][:, rows], ref) <= TOL
+    assert cl.conv_workspace_bytes(L, g, B, cl.PATH_MFMA_BF16) < 9 * 100 * 2 ** 20      # not all nine images' columns at once
+    Yb = cl.compressed_conv_forward(L, g, Xd, relu=True, path=cl.PATH_MFMA_BF16).cpu().numpy()
+    assert rel_err(Yb[imgs][:, rows], ref) <= bf16x3_bound(oracle.conv_forward(np.abs(Ws), np.abs(Xs), sub, nthreads=8), ref)
     L.free()
 
 
