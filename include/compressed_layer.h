@@ -272,26 +272,35 @@ typedef struct {
 
 int32_t cl_conv_workspace_bytes(const cl_layer *layer, const cl_conv_desc *conv, int32_t batch,
                                 int32_t path, size_t *out);
-/* The least scratch cl_compressed_conv_forward works with: given less than
- * cl_conv_workspace_bytes() but at least this, it takes the filter groups one after
- * the other through the same buffers and decodes the blocks inside the multiply
- * kernel - about half the memory for a layer with two filter groups, the same
- * results, more time (AlexNet conv2 at batch 1: 45 instead of 32 us). */
+/* The least scratch cl_compressed_conv_forward works with.  Where the call would
+ * keep the column matrices of all filter groups in the workspace (see below), it can,
+ * given less than cl_conv_workspace_bytes() but at least this, take the filter groups
+ * one after the other through the same buffers and decode the blocks inside the
+ * multiply kernel - about half the memory for a layer with two filter groups, the same
+ * results, more time (AlexNet conv2 at batch 1: 45 instead of 32 us).  Where the
+ * call gathers the columns itself, nothing needs less and the two sizes are equal. */
 int32_t cl_conv_workspace_bytes_min(const cl_layer *layer, const cl_conv_desc *conv, int32_t batch,
                                     int32_t path, size_t *out);
 
 /* d_X: batch x C x H x W fp32 (NCHW); d_Y: batch x out_channels x P x Q fp32 with
- * P = (H + 2 pad - R) / stride + 1, Q likewise.  The receptive fields are written
- * out as columns (Sec. III-A) in the workspace, one matrix per filter group and at
- * most 1 GiB of them at a time (the batch is cut into image groups accordingly),
- * and multiplied on an MFMA path, all filter groups in one launch.  From 4096
- * columns (images x output pixels) on, CL_PATH_MFMA_F32 first decodes every block
- * of the layer once into a dense 128 x 128 tile in the workspace (64 KiB per block)
- * and multiplies from those, instead of decoding the blocks again for every tile
- * of columns; the results are the same bit for bit.  All this is the form of the
- * call that cl_conv_workspace_bytes() sizes the workspace for; with a workspace
- * between cl_conv_workspace_bytes_min() and that, the compact form described there
- * runs instead, and below the minimum the call fails with CL_EINVAL.
+ * P = (H + 2 pad - R) / stride + 1, Q likewise.  The convolution is the product of the
+ * layer's matrix with the matrix whose columns are the receptive fields (Sec. III-A),
+ * computed on an MFMA path, all filter groups in one launch, in one of two forms:
+ *  - CL_PATH_MFMA_F32 from 4096 columns (images x output pixels) on, when 128-column
+ *    tiles fill the chip: every block of the layer is decoded once per call into a
+ *    dense 128 x 128 tile in the workspace (64 KiB per block), and the multiply kernel
+ *    gathers each 128 x 128 piece of the column matrix from d_X into LDS itself - the
+ *    column matrix is never written to memory.  Workspace: the decoded blocks, a row
+ *    table (8 bytes per row of the layout), partial tiles when block rows are split.
+ *    Needs R, S <= 32 and 129 images of input under 2^29 elements, else the other form.
+ *  - otherwise the receptive fields are written out as columns in the workspace, one
+ *    matrix per filter group and at most 1 GiB of them at a time (the batch is cut
+ *    into image groups accordingly), and multiplied by the kernels of the FC paths,
+ *    which decode the blocks for every tile of columns.  This is the form that
+ *    cl_conv_workspace_bytes() sizes the workspace for in that case; with a workspace
+ *    between cl_conv_workspace_bytes_min() and that, the compact form described there
+ *    runs instead.
+ * Below cl_conv_workspace_bytes_min() the call fails with CL_EINVAL.
  * path is CL_PATH_AUTO (= CL_PATH_MFMA_F32), CL_PATH_MFMA_F32 or
  * CL_PATH_MFMA_BF16, anything else is CL_EUNSUPPORTED, as are blocks above
  * 128 x 128, with groups > 1 a block_h that does not divide

@@ -15,6 +15,8 @@
 //   workgroup's whole life, so where its pixels sit in the input, and which filter taps
 //   fall outside the image there, is worked out once (COMBINED: one bit per tap, for
 //   filters of at most 32 taps; else one bit per filter row and one per filter column).
+//   What a row is - its offset from a receptive field's corner, its tap - comes from the
+//   table that decode_tiles_kernel writes (`rows`), read with uniform loads.
 //   Multipliers (wavefronts 0-3, one per SIMD): wavefront w owns filter rows 32w..32w+31
 //   and all 128 columns in four 32 x 32 accumulators, with the operand layout of
 //   fc_mfma_kernel<4> - but the weights come from device memory (every block decoded
@@ -28,26 +30,6 @@ constexpr int kActTileFloats = kTile * kActStride;
 constexpr int kConvLdsBytes = 2 * kActTileFloats * 4;
 constexpr int kConvWAhead = 8;                             // 16-byte weight loads in flight per lane (four steps each)
 constexpr int kConvAAhead = 4;                             // steps of activations read ahead from LDS
-
-// What the gatherers need to know of a row of the column matrix, for every row of every
-// piece (piece bi, row kk = column bi bw + kk of the layer = (c, r, s)): x = byte offset
-// of (c, r, s) from a receptive field's corner at channel 0, y = which bit of a column's
-// tap masks says whether the tap is outside the image (r S + s, or r | s << 8 for the
-// separate masks), with the top bit set for a row the piece does not have.  Written once
-// per call; read with uniform loads.
-__global__ __launch_bounds__(256) void conv_rows_kernel(ConvGeom cg, int bw, int K, int n_rows, int combined, uint2 *rows)
-{
-    const int t = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (t >= n_rows) return;
-    const int kk = t % kTile, k = (t / kTile) * bw + kk;
-    uint2 e = make_uint2(0u, 0x80000000u);
-    if (kk < bw && k < K) {
-        const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
-        e.x = (uint32_t)(c * cg.H * cg.W + r * cg.W + s) * (uint32_t)sizeof(float);
-        e.y = combined ? (uint32_t)(r * cg.S + s) : (uint32_t)(r | s << 8);
-    }
-    rows[t] = e;
-}
 
 template <bool COMBINED>
 __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, const float *__restrict__ X, const float *__restrict__ wt,

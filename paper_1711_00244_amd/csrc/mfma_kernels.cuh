@@ -214,8 +214,30 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
 // the order in which the lanes of a multiplying wavefront of conv_mfma_kernel take their
 // 16-byte pieces of a tile straight from device memory.  For a convolution, where
 // hundreds of column tiles multiply the same few blocks.
-__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out)
+//
+// The launch also writes what the gatherers of conv_mfma_kernel need to know of a row
+// of the column matrix, for every row of every 128 x 128 piece (piece bi, row kk = column
+// bi bw + kk of the layer = (c, r, s)): x = byte offset of (c, r, s) from a receptive
+// field's corner at channel 0, y = which bit of a column's tap masks says whether the tap
+// is outside the image (r S + s when `combined`, else r | s << 8), with the top bit set
+// for a row the piece does not have.  n_rows entries, one per thread of the launch's
+// first workgroups (a layer has at least as many blocks as pieces).
+__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out, ConvGeom cg, int n_rows, int combined,
+                                                                uint2 *rows)
 {
+    {
+        const int t = (int)(blockIdx.x * kThreads + threadIdx.x);
+        if (t < n_rows) {
+            const int kk = t % kTile, k = (t / kTile) * L.bw + kk;
+            uint2 e = make_uint2(0u, 0x80000000u);
+            if (kk < L.bw && k < L.K) {
+                const int s = k % cg.S, r = (k / cg.S) % cg.R, c = k / (cg.S * cg.R);
+                e.x = (uint32_t)(c * cg.H * cg.W + r * cg.W + s) * (uint32_t)sizeof(float);
+                e.y = combined ? (uint32_t)(r * cg.S + s) : (uint32_t)(r | s << 8);
+            }
+            rows[t] = e;
+        }
+    }
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
     float *tile = s.extra;                                  // [kTile][kWStride]
