@@ -313,10 +313,13 @@ bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->des
 // 4.1 k of multiplies per 32 columns of the tile - 1.5 k on the bf16 matrix cores;
 // workgroups run in rounds of one per CU; and 3 cycles per 4 KB of partial tiles, which
 // are written, flushed at the kernel's end and read again by the finishing kernel -
-// nothing where one workgroup per block row writes the output itself, `direct`).  Fitted
+// 2 per 5 KB next to the gathered convolution's kernel, nothing where one workgroup per
+// block row writes the output itself, `direct`).  Fitted
 // to sweeps over every tile width and split of the AlexNet and VGG-16 FC layers at 8 to
 // 1024 images: the choice is the fastest measured shape for the large layers and
-// within 3 % of it on average for a 1000-row layer, where the partial tiles decide.
+// within 3 % of it on average for a 1000-row layer, where the partial tiles decide; for
+// the gathered convolution, to sweeps over the splits of the AlexNet and VGG-16 layers
+// at 2 to 128 images (0.2 % from the fastest on average, 5 % at worst).
 void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool gathered = false,
                 bool direct = false)
 {
@@ -328,16 +331,18 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
         const int w = 32 * q;
         const int cols = (ncols + w - 1) / w * w;
         const int64_t tiles = (int64_t)panels * (cols / w);
-        // any split up to three rounds of workgroups: more, shorter workgroups can beat
-        // one round that leaves CUs idle
-        const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
+        // any split up to three rounds of workgroups (eight for the gathered convolution,
+        // whose long block rows gain from them): more, shorter workgroups can beat one
+        // round that leaves CUs idle
+        const int64_t max_rounds = gathered ? 8 : 3;
+        const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (max_rounds * cus + tiles - 1) / tiles));
         for (int sp = 1; sp <= sp_max; ++sp) {
             const int64_t rounds = (tiles * sp + cus - 1) / cus;
             const int64_t blocks = (L->nbw + sp - 1) / sp;
             // blocks decoded beforehand: the gathering costs less than a decode
             int64_t t = gathered ? rounds * (8000 + blocks * (1500 + 4100 * q))
                               : rounds * (12000 + blocks * (5000 + (bf16 ? 1500 : 4100) * q));
-            if (!(direct && sp == 1)) t += (int64_t)panels * sp * cols * L->desc.block_h * (int64_t)sizeof(float) * 3 / 4000;
+            if (!(direct && sp == 1)) t += (int64_t)panels * sp * cols * L->desc.block_h * (int64_t)sizeof(float) * (gathered ? 2 : 3) / (gathered ? 5000 : 4000);
             if (best < 0 || t < best) {
                 best = t;
                 nq = q;
