@@ -444,6 +444,12 @@ GATHERED_CONVS = [
     (dict(C=40, H=48, W=52, R=3, S=3, stride=1, pad=1, groups=1, OC=16), 8, True),
     # 25 taps, a ragged second block row (130 filters), a ragged block (125 columns), a ragged last tile
     (dict(C=5, H=37, W=41, R=5, S=5, stride=1, pad=2, groups=1, OC=130), 6, False),
+    # four output pixels per image: a tile of 128 columns spans 32 images; stride larger than the gaps it leaves
+    (dict(C=4, H=5, W=5, R=3, S=3, stride=2, pad=0, groups=1, OC=7), 5000, False),
+    # two filter groups of two block rows each (200 filters per group in 100-row blocks)
+    (dict(C=8, H=34, W=34, R=3, S=3, stride=1, pad=1, groups=2, OC=400), 4, False),
+    # a filter row entirely in the padding for the border pixels, 1 x 3 filter
+    (dict(C=6, H=70, W=66, R=1, S=3, stride=1, pad=2, groups=1, OC=5), 4, False),
 ]
 
 
@@ -461,6 +467,8 @@ def test_conv_gathered_columns(geom, B, split):
     bh = cl.conv_block_h(OC, groups)
     L, m, oW = check_decode(W, 8, 8, bh, 128)
     X = (rng.random((B, geom["C"], geom["H"], geom["W"]), dtype=np.float32) - 0.3).astype(np.float32)
+    X[:, :, 0, :] += 2.0                              # the border rows and columns differ from the inside: a shifted tap shows
+    X[:, :, :, -1] -= 1.0
     bias = rng.standard_normal(OC).astype(np.float32) * 0.1
     P = (geom["H"] + 2 * geom["pad"] - geom["R"]) // geom["stride"] + 1
     Q = (geom["W"] + 2 * geom["pad"] - geom["S"]) // geom["stride"] + 1
