@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true", help="skip the extra run on the bf16-tile path")
     ap.add_argument("--no-cold-pool", action="store_true", help="skip the batch-1 steady-state run over separately uploaded copies")
+    ap.add_argument("--no-conv", action="store_true", help="skip the side measurement of the AlexNet convolutions")
+    ap.add_argument("--conv-batch", type=int, default=64)
     ap.add_argument("--cold-copies", type=int, default=128)
     ap.add_argument("--cpu-batch", type=int, default=256, help="batch of the CPU-oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -282,6 +284,31 @@ def main():
     }
     if not args.no_bf16 and args.path == "auto":
         out["bf16_tiles"] = bf16_tiles(args.batch)
+
+    # ---- beside the metric: the five AlexNet convolutions (configs[3]) through cl_compressed_conv_forward ----
+    if not args.no_conv and args.path == "auto":
+        Bc, per_layer = args.conv_batch, {}
+        for li in range(5):
+            cspec, cW = wl.layer_weights(4, li)
+            g = cspec.conv
+            Lc = cl.compress_layer(cW, cspec.r, cspec.k, cl.conv_block_h(g["OC"], g["groups"]), 128, upload=True)
+            Xc = torch.from_numpy(wl.activations(4, Bc, layer_index=li)).cuda()
+            P = (g["H"] + 2 * g["pad"] - g["R"]) // g["stride"] + 1
+            Yc = torch.empty((Bc, g["OC"], P, P), device="cuda")
+            wsc = torch.empty(max(256, cl.conv_workspace_bytes(Lc, g, Bc)), dtype=torch.uint8, device="cuda")
+            for _ in range(5):
+                cl.compressed_conv_forward(Lc, g, Xc, relu=True, out=Yc, workspace=wsc)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                cl.compressed_conv_forward(Lc, g, Xc, relu=True, out=Yc, workspace=wsc)
+            torch.cuda.synchronize()
+            per_layer[cspec.name] = round((time.perf_counter() - t0) * 1e3 / 20, 5)
+            Lc.free()
+        total = sum(per_layer.values())
+        out["conv_alexnet"] = {"workload": "configs[3]: AlexNet conv1-5 at 84/38/35/37/37 % density, 8-bit codebook and relative index, ReLU",
+                               "batch": Bc, "ms_per_layer": per_layer, "ms_total": round(total, 5),
+                               "images_per_s": round(Bc / (total * 1e-3), 1), "dtype": "f32"}
 
     # ---- the CPU oracle on the host cores, same workload, bounded sample -----
     if not args.no_cpu_baseline:
