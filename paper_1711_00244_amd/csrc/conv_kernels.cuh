@@ -11,8 +11,9 @@
 //   column matrix that block i + 1 multiplies - row kk is (c, r, s) of the block's
 //   column kk, column n an output pixel - in one of two LDS tiles, reading the NCHW
 //   input directly (zero outside the image, past the last column and for rows the block
-//   does not have).  A row is uniform per wavefront, a lane owns two columns for the
-//   workgroup's whole life, so where its pixels sit in the input, and which filter taps
+//   does not have).  A row is uniform per wavefront, a lane owns two columns (l and l + 64:
+//   the 64 lanes of a load read neighbouring pixels) for the workgroup's whole life, so
+//   where its pixels sit in the input, and which filter taps
 //   fall outside the image there, is worked out once (COMBINED: one bit per tap, for
 //   filters of at most 32 taps; else one bit per filter row and one per filter column).
 //   What a row is - its offset from a receptive field's corner, its tap - comes from the
@@ -67,18 +68,18 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
         // at most 32 taps, else one per r and one per s.  Columns past the last are all outside.
         uint32_t at[2], bad[2], bad_s[2];
         {
-            const int n0 = nb * kConvColumns + 2 * lane;
-            int img = n0 / pq;
-            const int o = n0 - img * pq;
-            int oy = o / cg.Q, ox = o - oy * cg.Q;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
+                const int n = nb * kConvColumns + lane + 64 * i;
+                const int img = n / pq;
+                const int o = n - img * pq;
+                const int oy = o / cg.Q, ox = o - oy * cg.Q;
                 const int y0 = oy * cg.stride - cg.pad, x0 = ox * cg.stride - cg.pad;
                 at[i] = (uint32_t)((img - img0) * cg.C * plane + oy * cg.stride * cg.W + ox * cg.stride) * (uint32_t)sizeof(float);
                 uint32_t rb = 0, sb = 0;
                 for (int r = 0; r < cg.R; ++r) rb |= (uint32_t)((unsigned)(y0 + r) >= (unsigned)cg.H) << r;
                 for (int sx = 0; sx < cg.S; ++sx) sb |= (uint32_t)((unsigned)(x0 + sx) >= (unsigned)cg.W) << sx;
-                if (n0 + i >= n_cols) rb = sb = 0xffffffffu;
+                if (n >= n_cols) rb = sb = 0xffffffffu;
                 if (COMBINED) {
                     const uint32_t all_s = cg.S >= 32 ? 0xffffffffu : (1u << cg.S) - 1u;
                     uint32_t both = 0;
@@ -87,10 +88,6 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
                 }
                 bad[i] = rb;
                 bad_s[i] = sb;
-                if (++ox == cg.Q) {
-                    ox = 0;
-                    if (++oy == cg.P) { oy = 0; ++img; }
-                }
             }
         }
         // Wavefront d gathers rows 16 d .. 16 d + 15 of a piece; what a row is comes from
@@ -112,8 +109,10 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
                 }
             }
 #pragma unroll
-            for (int jj = 0; jj < kRows; ++jj)
-                *(float2 *)(tile + (kRows * d + jj) * kActStride + 2 * lane) = make_float2(v[jj][0], v[jj][1]);
+            for (int jj = 0; jj < kRows; ++jj) {
+                tile[(kRows * d + jj) * kActStride + lane] = v[jj][0];
+                tile[(kRows * d + jj) * kActStride + lane + 64] = v[jj][1];
+            }
         };
         if (blk_lo < blk_hi) fill(blk_lo, act);
         __syncthreads();
