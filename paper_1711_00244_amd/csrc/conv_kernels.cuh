@@ -53,10 +53,11 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
         const int c0 = (p / panels_per_group) * cg.Cg;              // the filter group's input channels
         // The input is read through a buffer descriptor that starts at the tile's first
         // image, channel c0, moved back by the padding so that a receptive field's corner
-        // has a non-negative offset (the launcher keeps 129 images under 2^30 elements),
-        // and ends with the input: a load past its end returns zero.  That is also how an
-        // element outside the image is read - its offset is turned into 0xffffffff - so a
-        // gathered element costs a bit test, an add, an or and a load, with no branch.
+        // has a non-negative offset (the launcher keeps 129 images under 2^29 elements, so
+        // byte offsets stay below 2^31), and ends with the input: a load past its end returns
+        // zero.  That is also how an element outside the image is read - its offset is turned
+        // into 0xffffffff - so a gathered element costs a bit test, an add, an or and a load,
+        // with no branch.  (Word 3 of the descriptor: 32-bit elements, plain addressing.)
         const int img0 = nb * kConvColumns / pq;
         const int n_img = (n_cols + pq - 1) / pq;
         const int64_t back = (int64_t)cg.pad * cg.W + cg.pad;
