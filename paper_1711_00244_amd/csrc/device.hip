@@ -879,6 +879,98 @@ extern "C" int32_t cl_conv_workspace_bytes_min(const cl_layer *L, const cl_conv_
     return CL_OK;
 }
 
+namespace {
+
+// One group of images of a convolution call: what the two forms share.
+struct ConvCall {
+    const cl_layer *L;
+    const ConvPlan *P;
+    LayerDev D;
+    const float *x;         // the group's input, images x C x H x W
+    float *y;               // its output, images x M x pq
+    const float *bias;
+    int ncols, pq, relu;    // columns = images x output pixels
+    int launch_panels, nq, Np, splits;
+    float *part;
+    hipStream_t st;
+    bool *timed;            // benchmarks time the first multiply launch of a call
+};
+
+// adds the splits of the block rows, bias, activation, NCHW
+int32_t conv_finish_splits(const ConvCall &c)
+{
+    const int ct = reduce_col_tile(c.launch_panels, c.ncols);
+    dim3 grid;
+    GRID_TRY(grid, (int64_t)c.launch_panels * ((c.ncols + ct - 1) / ct));
+    hipLaunchKernelGGL(mfma_reduce_kernel, grid, dim3(256), 0, c.st,
+                       c.D, c.part, c.bias, c.y, c.ncols, c.Np, c.splits, c.relu, c.pq, ct, 0, c.L->desc.block_h);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
+// The gathered form: one launch gathers the columns and multiplies them with the decoded
+// blocks (wt) of all filter groups; it finishes the output itself unless block rows are split.
+int32_t conv_gathered(const ConvCall &c, const float *wt, const uint2 *rows, bool combined)
+{
+    const ConvPlan &P = *c.P;
+    const bool direct = c.splits == 1;
+    const DirectOut out{direct ? c.y : nullptr, c.bias, c.ncols, c.pq, c.relu};
+    static LdsLimit seen[2];
+    if (int32_t rc = ensure_lds(combined ? (const void *)conv_mfma_kernel<true> : (const void *)conv_mfma_kernel<false>, P.lds, seen[combined]))
+        return rc;
+    dim3 grid;
+    GRID_TRY(grid, (int64_t)c.launch_panels * c.splits * (c.Np / kConvColumns));
+    if (!*c.timed) timing_begin(c.st);
+    if (combined)
+        hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(kConvThreads), P.lds, c.st, c.D, c.x, wt, rows, c.part, P.cg, c.ncols, c.Np,
+                           c.splits, P.panels_per_group, out);
+    else
+        hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(kConvThreads), P.lds, c.st, c.D, c.x, wt, rows, c.part, P.cg, c.ncols, c.Np,
+                           c.splits, P.panels_per_group, out);
+    HIP_TRY(hipGetLastError());
+    if (!*c.timed) { timing_end(c.st, 1); *c.timed = true; }
+    return direct ? CL_OK : conv_finish_splits(c);
+}
+
+// The form with the column matrix in memory: P.groups_at_once filter groups per launch of
+// each kernel; group grp of a launch has its column matrix at xt + grp * x_bytes and
+// multiplies its own block rows.
+int32_t conv_columns(ConvCall c, int groups_total, bool bf16, void *xt)
+{
+    const ConvPlan &P = *c.P;
+    const cl_layer *L = c.L;
+    const size_t x_bytes = xt_bytes_for(L, c.Np, bf16);
+    for (int grp0 = 0; grp0 < groups_total; grp0 += P.groups_at_once) {
+        const unsigned groups = (unsigned)P.groups_at_once;
+        c.D.panel0 = grp0 * P.panels_per_group;
+        if (bf16)
+            hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((c.Np + 63) / 64, 4096), (unsigned)(L->nbw * 8), groups), dim3(256), 0,
+                               c.st, c.x, (uint16_t *)xt, P.cg, x_bytes / sizeof(uint16_t), c.ncols, c.Np, L->desc.block_w, L->desc.K,
+                               xb_plane_elems(L, c.Np), grp0);
+        else {
+            // rows per workgroup: as many (up to kIm2colRows) as leave a couple of thousand workgroups
+            const int64_t col_wgs = std::min((c.Np / 4 + 255) / 256, 4096);
+            int rpw = kIm2colRows;
+            while (rpw > 1 && col_wgs * (L->nbw * kTile / rpw) * groups < 2048) rpw >>= 1;
+            hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)col_wgs, (unsigned)(L->nbw * kTile / rpw), groups), dim3(256), 0, c.st,
+                               c.x, (float *)xt, P.cg, x_bytes / sizeof(float), c.ncols, c.Np, L->desc.block_w, L->desc.K, grp0, rpw);
+        }
+        HIP_TRY(hipGetLastError());
+        if (!*c.timed) timing_begin(c.st);
+        // block rows that are not split need no adding up: the multiply kernel finishes the output
+        const bool direct = !bf16 && c.splits == 1;
+        const DirectOut out{direct ? c.y : nullptr, c.bias, c.ncols, c.pq, c.relu};
+        if (int32_t rc = launch_mfma(L, c.D, bf16, c.nq, c.launch_panels, c.splits, c.Np, P.panels_per_group, x_bytes, P.lds, xt, c.part, c.st, out))
+            return rc;
+        if (!*c.timed) { timing_end(c.st, 1); *c.timed = true; }
+        if (!direct)
+            if (int32_t rc = conv_finish_splits(c)) return rc;
+    }
+    return CL_OK;
+}
+
+}  // namespace
+
 extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_desc *cv, const float *d_X,
                                               const float *d_bias, float *d_Y, int32_t batch, int32_t relu,
                                               int32_t path, void *d_workspace, size_t workspace_bytes, void *stream)
@@ -902,90 +994,32 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
             return fail(CL_EINVAL, "workspace too small: %zu < %zu (%zu for the fast form)", workspace_bytes, P.total(), fast);
     }
     hipStream_t st = (hipStream_t)stream;
-    LayerDev D = make_dev(L);
     const ConvGeom &g = P.cg;
-    const int pq = g.P * g.Q, M = L->desc.M, K = L->desc.K;
-    void *xt = d_workspace;
-    float *part = (float *)((char *)d_workspace + P.xt_bytes);
-    float *wt = P.gather ? (float *)((char *)d_workspace + P.xt_bytes + P.part_bytes) : nullptr;
-    uint2 *rows = P.gather ? (uint2 *)((char *)d_workspace + P.xt_bytes + P.part_bytes + P.wt_bytes) : nullptr;
+    // the workspace: column matrices (not in the gathered form), partial tiles, decoded blocks, row table
+    char *ws = (char *)d_workspace;
+    void *xt = ws;
+    float *part = (float *)(ws + P.xt_bytes);
+    float *wt = (float *)(ws + P.xt_bytes + P.part_bytes);
+    uint2 *rows = (uint2 *)(ws + P.xt_bytes + P.part_bytes + P.wt_bytes);
     const bool combined = g.R * g.S <= 32;      // one tap mask per column instead of one per filter row and one per filter column
     if (P.gather) {
         const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + (size_t)kWTileBytes;
         static LdsLimit seen;
         if (int32_t rc = ensure_lds((const void *)decode_tiles_kernel, lds, seen)) return rc;
         // n_blocks workgroups of kThreads threads: more threads than the row table has entries
-        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, D, wt, g, L->nbw * kTile,
+        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, make_dev(L), wt, g, L->nbw * kTile,
                            combined ? 1 : 0, rows);
         HIP_TRY(hipGetLastError());
     }
     bool timed = false;
+    ConvCall c{L, &P, make_dev(L), nullptr, nullptr, d_bias, 0, g.P * g.Q, relu, P.panels_per_group * P.groups_at_once, 0, 0, 0, part, st, &timed};
     for (int b0 = 0; b0 < batch; b0 += P.imgs) {
         const int nb = std::min(P.imgs, batch - b0);
-        const int ncols = nb * pq;
-        int nq, Np, splits;
-        const int launch_panels = P.panels_per_group * P.groups_at_once;
-        mfma_shape(L, launch_panels, ncols, dl.cus, bf16, nq, Np, splits, P.gather, !bf16);
-        const float *x = d_X + (size_t)b0 * g.C * g.H * g.W;
-        float *y = d_Y + (size_t)b0 * M * pq;
-        if (P.gather) {
-            // one launch gathers and multiplies; it finishes the output itself unless the block rows are split
-            const bool direct = splits == 1;
-            const DirectOut out{direct ? y : nullptr, d_bias, ncols, pq, relu};
-            static LdsLimit seen[2];
-            if (int32_t rc = ensure_lds(combined ? (const void *)conv_mfma_kernel<true> : (const void *)conv_mfma_kernel<false>, P.lds, seen[combined])) return rc;
-            dim3 grid;
-            GRID_TRY(grid, (int64_t)launch_panels * splits * (Np / kConvColumns));
-            if (!timed) timing_begin(st);
-            if (combined)
-                hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, rows, part, g, ncols, Np, splits,
-                                   P.panels_per_group, out);
-            else
-                hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(kConvThreads), P.lds, st, D, x, wt, rows, part, g, ncols, Np, splits,
-                                   P.panels_per_group, out);
-            HIP_TRY(hipGetLastError());
-            if (!timed) { timing_end(st, 1); timed = true; }
-            if (direct) continue;
-            const int ct = reduce_col_tile(launch_panels, ncols);
-            dim3 rgrid;
-            GRID_TRY(rgrid, (int64_t)launch_panels * ((ncols + ct - 1) / ct));
-            hipLaunchKernelGGL(mfma_reduce_kernel, rgrid, dim3(256), 0, st,
-                               D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
-            HIP_TRY(hipGetLastError());
-            continue;
-        }
-        // groups_at_once filter groups per launch of each kernel: group grp of a launch has
-        // its column matrix at xt + grp * x_bytes and multiplies its own block rows
-        const size_t x_bytes = xt_bytes_for(L, Np, bf16);
-        for (int grp0 = 0; grp0 < cv->groups; grp0 += P.groups_at_once) {
-            const unsigned groups = (unsigned)P.groups_at_once;
-            D.panel0 = grp0 * P.panels_per_group;
-            if (bf16)
-                hipLaunchKernelGGL(im2col_split_kernel, dim3((unsigned)std::min((Np + 63) / 64, 4096), (unsigned)(L->nbw * 8), groups), dim3(256), 0, st,
-                                   x, (uint16_t *)xt, g, x_bytes / sizeof(uint16_t), ncols, Np, L->desc.block_w, K, xb_plane_elems(L, Np), grp0);
-            else {
-                // rows per workgroup: as many (up to kIm2colRows) as leave a couple of thousand workgroups
-                const int64_t col_wgs = std::min((Np / 4 + 255) / 256, 4096);
-                int rpw = kIm2colRows;
-                while (rpw > 1 && col_wgs * (L->nbw * kTile / rpw) * groups < 2048) rpw >>= 1;
-                hipLaunchKernelGGL(im2col_pad_kernel, dim3((unsigned)col_wgs, (unsigned)(L->nbw * kTile / rpw), groups), dim3(256), 0, st,
-                                   x, (float *)xt, g, x_bytes / sizeof(float), ncols, Np, L->desc.block_w, K, grp0, rpw);
-            }
-            HIP_TRY(hipGetLastError());
-            if (!timed) timing_begin(st);
-            // block rows that are not split need no adding up: the multiply kernel finishes the output
-            const bool direct = !bf16 && splits == 1;
-            const DirectOut out{direct ? y : nullptr, d_bias, ncols, pq, relu};
-            if (int32_t rc = launch_mfma(L, D, bf16, nq, launch_panels, splits, Np, P.panels_per_group, x_bytes, P.lds, xt, part, st, out)) return rc;
-            if (!timed) { timing_end(st, 1); timed = true; }
-            if (direct) continue;
-            const int ct = reduce_col_tile(launch_panels, ncols);
-            dim3 rgrid;
-            GRID_TRY(rgrid, (int64_t)launch_panels * ((ncols + ct - 1) / ct));
-            hipLaunchKernelGGL(mfma_reduce_kernel, rgrid, dim3(256), 0, st,
-                               D, part, d_bias, y, ncols, Np, splits, relu, pq, ct, 0, L->desc.block_h);
-            HIP_TRY(hipGetLastError());
-        }
+        c.ncols = nb * c.pq;
+        mfma_shape(L, c.launch_panels, c.ncols, dl.cus, bf16, c.nq, c.Np, c.splits, P.gather, !bf16);
+        c.x = d_X + (size_t)b0 * g.C * g.H * g.W;
+        c.y = d_Y + (size_t)b0 * L->desc.M * c.pq;
+        if (int32_t rc = P.gather ? conv_gathered(c, wt, rows, combined) : conv_columns(c, cv->groups, bf16, xt)) return rc;
     }
     clear_error();
     return CL_OK;
