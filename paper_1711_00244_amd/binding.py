@@ -75,6 +75,13 @@ def lib():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build_library()
+    # PyTorch brings a HIP runtime of its own, and device memory comes from PyTorch: its
+    # runtime has to be the one in the process before this library resolves its HIP
+    # symbols (loaded the other way round, PyTorch afterwards finds no GPU)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(_build.LIB)
     p, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.cl_last_error.restype = C.c_char_p

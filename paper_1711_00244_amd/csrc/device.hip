@@ -742,7 +742,7 @@ extern "C" int32_t cl_lrn_forward(const float *d_X, float *d_Y, int32_t batch, i
 {
     if (!d_X || !d_Y) return fail(CL_EINVAL, "null pointer");
     if (batch < 1 || C < 1 || H < 1 || W < 1 || n < 1 || !(n & 1)) return fail(CL_EINVAL, "bad normalisation geometry");
-    const int64_t hw = (int64_t)H * W, threads = (int64_t)batch * hw;
+    const int64_t hw = (int64_t)H * W, threads = (int64_t)batch * ((C + kLrnChunk - 1) / kLrnChunk) * hw;
     hipLaunchKernelGGL(lrn_kernel, dim3((unsigned)std::min<int64_t>((threads + 255) / 256, 65536)), dim3(256), 0, (hipStream_t)stream,
                        d_X, d_Y, batch, C, hw, n, alpha / (float)n, beta, k);
     HIP_TRY(hipGetLastError());

@@ -17,16 +17,25 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ 
     }
 }
 
-// One thread per (image, pixel) walks the channels with a sliding sum of squares.
+// One thread per (image, run of kLrnChunk channels, pixel): consecutive threads take
+// consecutive pixels, so every load and store of a wavefront is one contiguous run; a
+// channel's window is summed from the (cached) input as it stands, in channel order.
+// (One thread per pixel walking all channels took 214 us for one image of 256 x 27 x 27.)
+constexpr int kLrnChunk = 4;
+
 __global__ __launch_bounds__(256) void lrn_kernel(const float *__restrict__ X, float *Y, int B, int C, int64_t hw, int n,
                                                   float alpha_over_n, float beta, float k)
 {
     const int half = n / 2;
-    for (int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; t < (int64_t)B * hw; t += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t b = t / hw, i = t - b * hw;
+    const int n_chunks = (C + kLrnChunk - 1) / kLrnChunk;
+    const int64_t total = (int64_t)B * n_chunks * hw;
+    for (int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; t < total; t += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = t % hw, bc = t / hw;
+        const int chunk = (int)(bc % n_chunks);
+        const int64_t b = bc / n_chunks;
         const float *x = X + b * C * hw + i;
         float *y = Y + b * C * hw + i;
-        for (int c = 0; c < C; ++c) {
+        for (int c = chunk * kLrnChunk; c < min(C, (chunk + 1) * kLrnChunk); ++c) {
             float ss = 0.0f;
             for (int cc = max(0, c - half); cc <= min(C - 1, c + half); ++cc) {
                 const float v = x[(int64_t)cc * hw];

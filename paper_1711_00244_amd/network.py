@@ -112,7 +112,10 @@ class NetworkRunner(StackRunner):
     def layer_forward(self, li, X, out=None):
         return self.layers[li].forward(X.contiguous(), out)
 
-    def measure_times(self, batch_set, reps=10, warmup=2):
+    def measure_times(self, batch_set, reps=10, warmup=2, graphs=False):
+        """Time(i, B) in ms.  graphs: the `reps` calls of a layer are captured in a graph
+        and replayed, which leaves the caller's per-call cost (Python, ctypes: 10-20 us,
+        more than the kernels of a small layer take) out of the figure."""
         import torch
         t = np.zeros((len(self.layers), len(batch_set)))
         for j, B in enumerate(batch_set):
@@ -121,10 +124,21 @@ class NetworkRunner(StackRunner):
                 for _ in range(warmup):
                     out = self.layer_forward(li, a)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(reps):
-                    out = self.layer_forward(li, a, out)
-                e1.record()
+                if graphs:
+                    torch.cuda.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph):
+                        for _ in range(reps):
+                            out = self.layer_forward(li, a, out)
+                    graph.replay()
+                    e0.record()
+                    graph.replay()
+                    e1.record()
+                else:
+                    e0.record()
+                    for _ in range(reps):
+                        out = self.layer_forward(li, a, out)
+                    e1.record()
                 e1.synchronize()
                 t[li, j] = e0.elapsed_time(e1) / reps
                 a = out
@@ -197,13 +211,14 @@ def main(argv=None):
                     help="memory besides the model, in multiples of the compressed model size")
     ap.add_argument("--check", action="store_true", help="run the plan for K images and compare with one-batch execution")
     ap.add_argument("--density", type=float, default=None, help="uniform fraction of non-zeros for all layers")
+    ap.add_argument("--graphs", action="store_true", help="time the layers from replayed graphs (no per-call cost of the caller)")
     args = ap.parse_args(argv)
     fast = alexnet(density=args.density)
     nets = {"fast": fast, "compact": compact_copy(fast)}
     model_bytes = sum(op.layer.stats()["model_bytes"] for op in fast.layers if hasattr(op, "layer"))
     for K in args.images:
         batch_set = [b for b in range(1, K + 1) if K % b == 0]
-        times = {name: n.measure_times(batch_set) for name, n in nets.items()}
+        times = {name: n.measure_times(batch_set, graphs=args.graphs) for name, n in nets.items()}
         for mult in args.budgets:
             tot = int(mult * model_bytes)
             # the convolutions' scratch is part of the budget: both forms of the network are
@@ -215,7 +230,7 @@ def main(argv=None):
             plan = plans[form] if form else None
             fixed = fixeds[fform] + (fform,) if fform else None
             net = nets[form] if form else fast
-            rec = dict(images=K, density=args.density, budget_x_model=mult, budget_bytes=tot, model_bytes=model_bytes,
+            rec = dict(images=K, density=args.density, timed_from_graphs=args.graphs, budget_x_model=mult, budget_bytes=tot, model_bytes=model_bytes,
                        layers=[op.name for op in net.layers], conv_form=form)
             if plan is None or fixed is None:
                 rec["infeasible"] = True
