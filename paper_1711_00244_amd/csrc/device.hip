@@ -742,9 +742,15 @@ extern "C" int32_t cl_lrn_forward(const float *d_X, float *d_Y, int32_t batch, i
 {
     if (!d_X || !d_Y) return fail(CL_EINVAL, "null pointer");
     if (batch < 1 || C < 1 || H < 1 || W < 1 || n < 1 || !(n & 1)) return fail(CL_EINVAL, "bad normalisation geometry");
-    const int64_t hw = (int64_t)H * W, threads = (int64_t)batch * ((C + kLrnChunk - 1) / kLrnChunk) * hw;
-    hipLaunchKernelGGL(lrn_kernel, dim3((unsigned)std::min<int64_t>((threads + 255) / 256, 65536)), dim3(256), 0, (hipStream_t)stream,
-                       d_X, d_Y, batch, C, hw, n, alpha / (float)n, beta, k);
+    const int64_t hw = (int64_t)H * W, runs = (int64_t)batch * ((C + kLrnChunk - 1) / kLrnChunk);
+    if (runs > INT32_MAX) return fail(CL_EUNSUPPORTED, "batch x channels too large");
+    const dim3 grid((unsigned)((hw + 255) / 256), (unsigned)std::min<int64_t>(runs, 65535));
+    const float a_n = alpha / (float)n;
+    switch (n / 2) {
+    case 1: hipLaunchKernelGGL(lrn_kernel<1>, grid, dim3(256), 0, (hipStream_t)stream, d_X, d_Y, batch, C, hw, n, a_n, beta, k); break;
+    case 2: hipLaunchKernelGGL(lrn_kernel<2>, grid, dim3(256), 0, (hipStream_t)stream, d_X, d_Y, batch, C, hw, n, a_n, beta, k); break;
+    default: hipLaunchKernelGGL(lrn_kernel<-1>, grid, dim3(256), 0, (hipStream_t)stream, d_X, d_Y, batch, C, hw, n, a_n, beta, k); break;
+    }
     HIP_TRY(hipGetLastError());
     clear_error();
     return CL_OK;
