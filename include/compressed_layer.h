@@ -286,8 +286,9 @@ int32_t cl_conv_workspace_bytes_min(const cl_layer *layer, const cl_conv_desc *c
  * P = (H + 2 pad - R) / stride + 1, Q likewise.  The convolution is the product of the
  * layer's matrix with the matrix whose columns are the receptive fields (Sec. III-A),
  * computed on an MFMA path, all filter groups in one launch, in one of two forms:
- *  - CL_PATH_MFMA_F32 from 4096 columns (images x output pixels) on, when 128-column
- *    tiles fill the chip: every block of the layer is decoded once per call into a
+ *  - CL_PATH_MFMA_F32 from 512 columns (images x output pixels) on, when 128-column
+ *    tiles give the chip enough to do (work items for a sixteenth of the compute units,
+ *    block products for half): every block of the layer is decoded once per call into a
  *    dense 128 x 128 tile in the workspace (64 KiB per block), and the multiply kernel
  *    gathers each 128 x 128 piece of the column matrix from d_X into LDS itself - the
  *    column matrix is never written to memory.  Workspace: the decoded blocks, a row

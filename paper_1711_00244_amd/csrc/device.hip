@@ -796,11 +796,12 @@ struct ConvPlan {
 // From this many columns on (image x output pixel) the fp32 path decodes the layer's
 // blocks once per call into dense tiles in the workspace, and a multiply kernel of its own
 // gathers each 128 x 128 piece of the column matrix into LDS straight from the input, so
-// that the column matrix never exists in memory.  Below, the blocks of a column tile
-// are decoded inside the multiply kernel, which costs less than the two extra launches
-// (measured on the AlexNet and VGG-16 convolutions: decoding once pays from about 6 000
-// columns on and loses around 3 000).
-constexpr int64_t kConvGatherColumns = 4096;
+// that the column matrix never exists in memory.  Below, and for calls too small to
+// give that kernel's one tile width enough work items (see plan_conv), the column matrix
+// is written out and the blocks of a column tile are decoded inside the multiply kernel
+// (measured on the AlexNet and VGG-16 convolutions at 1 to 64 images: with these limits
+// the gathered form is the faster one wherever it is taken, by 4-25 %).
+constexpr int64_t kConvGatherColumns = 512;
 
 // compact: the form that needs the least scratch - filter groups one after the other
 // through the same buffers, blocks decoded inside the multiply kernel.
@@ -834,7 +835,10 @@ int32_t plan_conv(const cl_layer *L, const cl_conv_desc *cv, int batch, bool bf1
     if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the convolution path needs %zu bytes of LDS", P.lds);
     const int64_t cols = (int64_t)batch * g.P * g.Q;
     P.gather = !compact && !bf16 && cols >= kConvGatherColumns && (size_t)kConvLdsBytes <= dl.max_lds &&
-               2 * launch_panels * ((cols + kConvColumns - 1) / kConvColumns) >= dl.cus &&      // its one tile width must fill the chip
+               // its one tile width must give the chip something to do: work items for a
+               // sixteenth of the CUs before the block rows are split, 128 x 128 products for half
+               16 * launch_panels * ((cols + kConvColumns - 1) / kConvColumns) >= dl.cus &&
+               2 * launch_panels * ((cols + kConvColumns - 1) / kConvColumns) * L->nbw >= dl.cus &&
                (int64_t)(kConvColumns + 1) * g.C * g.H * g.W < (1 << 29) && g.R <= 32 && g.S <= 32;      // the gatherers' 32-bit byte offsets and tap masks
     if (P.gather) {
         // nothing but the launch size limits the images of a launch
