@@ -19,8 +19,8 @@
 //   What a row is - its offset from a receptive field's corner, its tap - comes from the
 //   table that decode_tiles_kernel writes (`rows`), read with uniform loads.
 //   Multipliers (wavefronts 0-3, one per SIMD): wavefront w owns filter rows 32w..32w+31
-//   and all 128 columns in four 32 x 32 accumulators, with the operand layout of
-//   fc_mfma_kernel<4> - but the weights come from device memory (every block decoded
+//   and all 128 columns in four 32 x 32 accumulators (HALF: 32 of 64 rows and 64 columns
+//   in two), with the operand layout of fc_mfma_kernel<4> - but the weights come from device memory (every block decoded
 //   once per call by decode_tiles_kernel, in fragment order: a lane's four steps of one
 //   row are one 16-byte load, 32 lanes contiguous) and the activations from LDS.
 constexpr int kConvGatherers = 8;
@@ -32,7 +32,7 @@ constexpr int kConvLdsBytes = 2 * kActTileFloats * 4;
 constexpr int kConvWAhead = 8;                             // 16-byte weight loads in flight per lane (four steps each)
 constexpr int kConvAAhead = 4;                             // steps of activations read ahead from LDS
 
-template <bool COMBINED>
+template <bool COMBINED, bool HALF>
 __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, const float *__restrict__ X, const float *__restrict__ wt,
                                                                  const uint2 *__restrict__ rows, float *part, ConvGeom cg, int n_cols,
                                                                  int Np, int splits, int panels_per_group, DirectOut out)
@@ -124,25 +124,33 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
         return;
     }
 
-    floatx16 acc[4];
+    // NA accumulators of 32 filter rows x 32 columns per multiplying wavefront.  Blocks of
+    // up to 128 rows: wavefront w takes rows 32 w .. 32 w + 31 and all 128 columns (NA = 4,
+    // accumulator q holds columns 4 i + q).  HALF, for layers whose blocks have at most 64
+    // rows: wavefront w takes rows 32 (w % 2) .. and columns 64 (w / 2) .. + 63 (NA = 2,
+    // accumulator q holds columns 64 (w / 2) + 2 i + q), so that no wavefront multiplies
+    // rows that no block has.
+    constexpr int NA = HALF ? 2 : 4;
+    const int strip = HALF ? wave & 1 : wave, chalf = HALF ? wave >> 1 : 0;
+    floatx16 acc[NA];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = floatx16{0};
+    for (int q = 0; q < NA; ++q) acc[q] = floatx16{0};
     const int kl = lane >> 5, m = lane & 31;
-    // piece (column group 16 kl + g, row 32 wave + m) of a tile in fragment order: steps
+    // piece (column group 16 kl + g, row 32 strip + m) of a tile in fragment order: steps
     // 4 g .. 4 g + 3 of this lane's row; groups follow each other 128 pieces apart
-    const float4 *wf = (const float4 *)wt + ((size_t)(pb0 + (uint32_t)blk_lo) * (kTile / 4) + 16 * kl) * kTile + 32 * wave + m;
+    const float4 *wf = (const float4 *)wt + ((size_t)(pb0 + (uint32_t)blk_lo) * (kTile / 4) + 16 * kl) * kTile + 32 * strip + m;
     float4 w[kConvWAhead];
 #pragma unroll
     for (int i = 0; i < kConvWAhead; ++i) w[i] = wf[i * kTile];
     __syncthreads();                                        // first piece of the column matrix gathered
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        const float *ap = act + ((bi - blk_lo) & 1) * kActTileFloats + 64 * kl * kActStride + 4 * m;
+        const float *ap = act + ((bi - blk_lo) & 1) * kActTileFloats + 64 * kl * kActStride + 64 * chalf + NA * m;
         // the pieces loaded towards the end of this block are the next block's first ones
         // (the last block re-reads its own: valid memory, never multiplied)
         const float4 *wnext = bi + 1 < blk_hi ? wf + (kTile / 4) * kTile : wf;
-        float4 a[kConvAAhead];
+        float a[kConvAAhead][NA];
 #pragma unroll
-        for (int i = 0; i < kConvAAhead; ++i) a[i] = *(const float4 *)(ap + i * kActStride);
+        for (int i = 0; i < kConvAAhead; ++i) load_floats<NA>(ap + i * kActStride, a[i]);
 #pragma unroll
         for (int g = 0; g < kTile / 8; ++g) {
             // program order is pinned (scheduling barriers): left alone, the compiler sinks the
@@ -155,18 +163,67 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int s = 4 * g + u;
-                const float4 av = a[s % kConvAAhead];
+                float av[NA];
+#pragma unroll
+                for (int q = 0; q < NA; ++q) av[q] = a[s % kConvAAhead][q];
                 __builtin_amdgcn_sched_barrier(0);
-                if (s + kConvAAhead < kTile / 2) a[s % kConvAAhead] = *(const float4 *)(ap + (s + kConvAAhead) * kActStride);
+                if (s + kConvAAhead < kTile / 2) load_floats<NA>(ap + (s + kConvAAhead) * kActStride, a[s % kConvAAhead]);
                 __builtin_amdgcn_sched_barrier(0);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, wu[u], acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, wu[u], acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, wu[u], acc[2], 0, 0, 0);
-                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, wu[u], acc[3], 0, 0, 0);
+#pragma unroll
+                for (int q = 0; q < NA; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q], wu[u], acc[q], 0, 0, 0);
             }
         }
         wf = wnext;
         __syncthreads();                                    // done with this piece
     }
-    store_accumulators<4>(acc, L, act, part, out, pj, p, nb, Np, wave, lane);
+    if constexpr (!HALF) {
+        store_accumulators<4>(acc, L, act, part, out, pj, p, nb, Np, wave, lane);
+        return;
+    } else {
+    // HALF: accumulator q, element e of lane (kl, m) is column 64 chalf + 16 (e / 4) + 8 kl +
+    // 2 (e % 4) + q of the tile for filter row 32 strip + m
+    const int row_id = p * L.bh;
+    const int n_rows = min(32, min(L.bh, L.M - row_id) - 32 * strip);
+    if (!out.Y) {
+        // the workgroup's partial tile: 32 lanes write 32 consecutive rows of a column
+        if (m < n_rows) {
+            float *mine = part + ((size_t)pj * Np + (size_t)nb * kConvColumns + 64 * chalf) * L.bh + 32 * strip + m;
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+#pragma unroll
+                for (int q = 0; q < NA; ++q) mine[(size_t)(16 * (e / 4) + 8 * kl + 2 * (e & 3) + q) * L.bh] = acc[q][e];
+        }
+        return;
+    }
+    // the finished output: the wavefront's 32 x 64 piece turned in its own part of LDS (the
+    // tiles are free: the last barrier was every wavefront's last use of them), then each
+    // filter row's 64 columns written as one run, bias (lane l holds that of row l % 32) and
+    // activation on the way
+    constexpr int kStride = 65;
+    float *t = act + wave * 32 * kStride;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+#pragma unroll
+        for (int q = 0; q < NA; ++q) t[m * kStride + 16 * (e / 4) + 8 * kl + 2 * (e & 3) + q] = acc[q][e];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    const int c = nb * kConvColumns + 64 * chalf + lane;        // this lane's column
+    const bool live = c < out.ncols;
+    const size_t y_at = ((size_t)(c / out.pq) * L.M + row_id + 32 * strip) * out.pq + (c % out.pq);
+    const float bias_l = out.bias && m < n_rows ? out.bias[row_id + 32 * strip + m] : 0.0f;
+    for (int r0 = 0; r0 < n_rows; r0 += 8) {
+        float y[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int rr = min(r0 + u, n_rows - 1);
+            y[u] = t[rr * kStride + lane] + __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bias_l), rr));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (r0 + u >= n_rows) break;
+            if (live) out.Y[y_at + (size_t)(r0 + u) * out.pq] = out.relu ? fmaxf(y[u], 0.0f) : y[u];
+        }
+    }
+    }
 }

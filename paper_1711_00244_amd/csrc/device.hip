@@ -925,18 +925,19 @@ int32_t conv_gathered(const ConvCall &c, const float *wt, const uint2 *rows, boo
     const ConvPlan &P = *c.P;
     const bool direct = c.splits == 1;
     const DirectOut out{direct ? c.y : nullptr, c.bias, c.ncols, c.pq, c.relu};
-    static LdsLimit seen[2];
-    if (int32_t rc = ensure_lds(combined ? (const void *)conv_mfma_kernel<true> : (const void *)conv_mfma_kernel<false>, P.lds, seen[combined]))
-        return rc;
+    // blocks of at most 64 rows: the kernel form whose multiplying wavefronts share the columns instead of rows no block has
+    const bool half = c.L->desc.block_h <= 64;
+    using Kernel = void (*)(LayerDev, const float *, const float *, const uint2 *, float *, ConvGeom, int, int, int, int, DirectOut);
+    static const Kernel kernels[4] = {conv_mfma_kernel<false, false>, conv_mfma_kernel<true, false>, conv_mfma_kernel<false, true>,
+                                      conv_mfma_kernel<true, true>};
+    static LdsLimit seen[4];
+    const int which = (combined ? 1 : 0) + (half ? 2 : 0);
+    if (int32_t rc = ensure_lds((const void *)kernels[which], P.lds, seen[which])) return rc;
     dim3 grid;
     GRID_TRY(grid, (int64_t)c.launch_panels * c.splits * (c.Np / kConvColumns));
     if (!*c.timed) timing_begin(c.st);
-    if (combined)
-        hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(kConvThreads), P.lds, c.st, c.D, c.x, wt, rows, c.part, P.cg, c.ncols, c.Np,
-                           c.splits, P.panels_per_group, out);
-    else
-        hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(kConvThreads), P.lds, c.st, c.D, c.x, wt, rows, c.part, P.cg, c.ncols, c.Np,
-                           c.splits, P.panels_per_group, out);
+    hipLaunchKernelGGL(kernels[which], grid, dim3(kConvThreads), P.lds, c.st, c.D, c.x, wt, rows, c.part, P.cg, c.ncols, c.Np, c.splits,
+                       P.panels_per_group, out);
     HIP_TRY(hipGetLastError());
     if (!*c.timed) { timing_end(c.st, 1); *c.timed = true; }
     return direct ? CL_OK : conv_finish_splits(c);
