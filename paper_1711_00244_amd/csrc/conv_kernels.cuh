@@ -19,8 +19,8 @@
 //   What a row is - its offset from a receptive field's corner, its tap - comes from the
 //   table that decode_tiles_kernel writes (`rows`), read with uniform loads.
 //   Multipliers (wavefronts 0-3, one per SIMD): wavefront w owns filter rows 32w..32w+31
-//   and all 128 columns in four 32 x 32 accumulators (HALF: 32 of 64 rows and 64 columns
-//   in two), with the operand layout of fc_mfma_kernel<4> - but the weights come from device memory (every block decoded
+//   and all 128 columns in four 32 x 32 accumulators (other divisions for lower blocks,
+//   below), with the operand layout of fc_mfma_kernel<4> - but the weights come from device memory (every block decoded
 //   once per call by decode_tiles_kernel, in fragment order: a lane's four steps of one
 //   row are one 16-byte load, 32 lanes contiguous) and the activations from LDS.
 constexpr int kConvGatherers = 8;
@@ -32,7 +32,7 @@ constexpr int kConvLdsBytes = 2 * kActTileFloats * 4;
 constexpr int kConvWAhead = 8;                             // 16-byte weight loads in flight per lane (four steps each)
 constexpr int kConvAAhead = 4;                             // steps of activations read ahead from LDS
 
-template <bool COMBINED, bool HALF>
+template <bool COMBINED, int S, int Q>
 __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, const float *__restrict__ X, const float *__restrict__ wt,
                                                                  const uint2 *__restrict__ rows, float *part, ConvGeom cg, int n_cols,
                                                                  int Np, int splits, int panels_per_group, DirectOut out)
@@ -124,106 +124,140 @@ __global__ __launch_bounds__(kConvThreads) void conv_mfma_kernel(LayerDev L, con
         return;
     }
 
-    // NA accumulators of 32 filter rows x 32 columns per multiplying wavefront.  Blocks of
-    // up to 128 rows: wavefront w takes rows 32 w .. 32 w + 31 and all 128 columns (NA = 4,
-    // accumulator q holds columns 4 i + q).  HALF, for layers whose blocks have at most 64
-    // rows: wavefront w takes rows 32 (w % 2) .. and columns 64 (w / 2) .. + 63 (NA = 2,
-    // accumulator q holds columns 64 (w / 2) + 2 i + q), so that no wavefront multiplies
-    // rows that no block has.
-    constexpr int NA = HALF ? 2 : 4;
-    const int strip = HALF ? wave & 1 : wave, chalf = HALF ? wave >> 1 : 0;
-    floatx16 acc[NA];
+    // S x Q accumulators of 32 filter rows x 32 columns per multiplying wavefront w, by the
+    // height of the layer's blocks:
+    //   up to 128 rows (S = 1, Q = 4): rows 32 w .. 32 w + 31, all 128 columns;
+    //   up to  96 rows (S = 3, Q = 1): all 96 rows, columns 32 w .. 32 w + 31;
+    //   up to  64 rows (S = 1, Q = 2): rows 32 (w % 2) .., columns 64 (w / 2) .. + 63;
+    // so that no wavefront multiplies rows that no block has.  Accumulator (s, q) holds,
+    // for element e of lane (kl, m), filter row 32 (sbase + s) + m and column
+    // cbase + Q i + q of the tile, i = 8 (e / 4) + 4 kl + e % 4.
+    const int sbase = S == 3 ? 0 : (Q == 4 ? wave : wave & 1);
+    const int cbase = S == 3 ? 32 * wave : (Q == 4 ? 0 : 64 * (wave >> 1));
+    constexpr int kWA = S == 3 ? kConvWAhead / 2 : kConvWAhead;     // weight loads in flight per strip
+    floatx16 acc[S][Q];
 #pragma unroll
-    for (int q = 0; q < NA; ++q) acc[q] = floatx16{0};
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int q = 0; q < Q; ++q) acc[s][q] = floatx16{0};
     const int kl = lane >> 5, m = lane & 31;
     // piece (column group 16 kl + g, row 32 strip + m) of a tile in fragment order: steps
-    // 4 g .. 4 g + 3 of this lane's row; groups follow each other 128 pieces apart
-    const float4 *wf = (const float4 *)wt + ((size_t)(pb0 + (uint32_t)blk_lo) * (kTile / 4) + 16 * kl) * kTile + 32 * strip + m;
-    float4 w[kConvWAhead];
+    // 4 g .. 4 g + 3 of this lane's row; groups follow each other 128 pieces apart, strips 32
+    const float4 *wf = (const float4 *)wt + ((size_t)(pb0 + (uint32_t)blk_lo) * (kTile / 4) + 16 * kl) * kTile + 32 * sbase + m;
+    float4 w[S][kWA];
 #pragma unroll
-    for (int i = 0; i < kConvWAhead; ++i) w[i] = wf[i * kTile];
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int i = 0; i < kWA; ++i) w[s][i] = wf[i * kTile + 32 * s];
     __syncthreads();                                        // first piece of the column matrix gathered
     for (int bi = blk_lo; bi < blk_hi; ++bi) {
-        const float *ap = act + ((bi - blk_lo) & 1) * kActTileFloats + 64 * kl * kActStride + 64 * chalf + NA * m;
+        const float *ap = act + ((bi - blk_lo) & 1) * kActTileFloats + 64 * kl * kActStride + cbase + Q * m;
         // the pieces loaded towards the end of this block are the next block's first ones
         // (the last block re-reads its own: valid memory, never multiplied)
         const float4 *wnext = bi + 1 < blk_hi ? wf + (kTile / 4) * kTile : wf;
-        float a[kConvAAhead][NA];
+        float a[kConvAAhead][Q];
 #pragma unroll
-        for (int i = 0; i < kConvAAhead; ++i) load_floats<NA>(ap + i * kActStride, a[i]);
+        for (int i = 0; i < kConvAAhead; ++i) load_floats<Q>(ap + i * kActStride, a[i]);
 #pragma unroll
         for (int g = 0; g < kTile / 8; ++g) {
             // program order is pinned (scheduling barriers): left alone, the compiler sinks the
             // loads to just before their use and their latency lands in front of the multiplies
-            const float4 wv = w[g % kConvWAhead];
+            float4 wv[S];
+#pragma unroll
+            for (int s = 0; s < S; ++s) wv[s] = w[s][g % kWA];
             __builtin_amdgcn_sched_barrier(0);
-            w[g % kConvWAhead] = g + kConvWAhead < kTile / 8 ? wf[(g + kConvWAhead) * kTile] : wnext[(g + kConvWAhead - kTile / 8) * kTile];
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+                w[s][g % kWA] = g + kWA < kTile / 8 ? wf[(g + kWA) * kTile + 32 * s] : wnext[(g + kWA - kTile / 8) * kTile + 32 * s];
             __builtin_amdgcn_sched_barrier(0);
-            const float wu[4] = {wv.x, wv.y, wv.z, wv.w};
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int s = 4 * g + u;
-                float av[NA];
+                const int st = 4 * g + u;
+                float av[Q];
 #pragma unroll
-                for (int q = 0; q < NA; ++q) av[q] = a[s % kConvAAhead][q];
+                for (int q = 0; q < Q; ++q) av[q] = a[st % kConvAAhead][q];
                 __builtin_amdgcn_sched_barrier(0);
-                if (s + kConvAAhead < kTile / 2) load_floats<NA>(ap + (s + kConvAAhead) * kActStride, a[s % kConvAAhead]);
+                if (st + kConvAAhead < kTile / 2) load_floats<Q>(ap + (st + kConvAAhead) * kActStride, a[st % kConvAAhead]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = 0; q < NA; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q], wu[u], acc[q], 0, 0, 0);
+                for (int s = 0; s < S; ++s) {
+                    const float wu = u == 0 ? wv[s].x : u == 1 ? wv[s].y : u == 2 ? wv[s].z : wv[s].w;
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) acc[s][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q], wu, acc[s][q], 0, 0, 0);
+                }
             }
         }
         wf = wnext;
         __syncthreads();                                    // done with this piece
     }
-    if constexpr (!HALF) {
-        store_accumulators<4>(acc, L, act, part, out, pj, p, nb, Np, wave, lane);
-        return;
-    } else {
-    // HALF: accumulator q, element e of lane (kl, m) is column 64 chalf + 16 (e / 4) + 8 kl +
-    // 2 (e % 4) + q of the tile for filter row 32 strip + m
+
     const int row_id = p * L.bh;
-    const int n_rows = min(32, min(L.bh, L.M - row_id) - 32 * strip);
+    const int block_rows = min(L.bh, L.M - row_id);
     if (!out.Y) {
-        // the workgroup's partial tile: 32 lanes write 32 consecutive rows of a column
-        if (m < n_rows) {
-            float *mine = part + ((size_t)pj * Np + (size_t)nb * kConvColumns + 64 * chalf) * L.bh + 32 * strip + m;
+        // the workgroup's partial tile for the finishing kernel: 32 lanes write 32 consecutive rows of a column
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (32 * (sbase + s) + m >= block_rows) continue;
+            float *mine = part + ((size_t)pj * Np + (size_t)nb * kConvColumns + cbase) * L.bh + 32 * (sbase + s) + m;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
 #pragma unroll
-                for (int q = 0; q < NA; ++q) mine[(size_t)(16 * (e / 4) + 8 * kl + 2 * (e & 3) + q) * L.bh] = acc[q][e];
+                for (int q = 0; q < Q; ++q) mine[(size_t)(Q * (8 * (e / 4) + 4 * kl + (e & 3)) + q) * L.bh] = acc[s][q][e];
         }
         return;
     }
-    // the finished output: the wavefront's 32 x 64 piece turned in its own part of LDS (the
-    // tiles are free: the last barrier was every wavefront's last use of them), then each
-    // filter row's 64 columns written as one run, bias (lane l holds that of row l % 32) and
-    // activation on the way
-    constexpr int kStride = 65;
-    float *t = act + wave * 32 * kStride;
+    // The finished output (block rows that are not split).  The output runs along the
+    // columns, the accumulators along the rows: the wavefront turns its 32 S x 32 Q piece in
+    // its own part of LDS (the tiles are free: the last barrier was every wavefront's last
+    // use of them), then writes each filter row's columns as one run - two rows at a time
+    // where a row has 32 columns - bias (lane l holds that of row l % 32 of each strip) and
+    // activation on the way.
+    constexpr int kCols = 32 * Q, kStride = kCols + 1;
+    constexpr int kPerLane = kCols > 64 ? kCols / 64 : 1;       // columns of a row per lane
+    constexpr int kRowsAtOnce = kCols < 64 ? 64 / kCols : 1;    // rows per pass of the wavefront
+    float *t = act + wave * (32 * S) * kStride;
 #pragma unroll
-    for (int e = 0; e < 16; ++e)
+    for (int s = 0; s < S; ++s)
 #pragma unroll
-        for (int q = 0; q < NA; ++q) t[m * kStride + 16 * (e / 4) + 8 * kl + 2 * (e & 3) + q] = acc[q][e];
+        for (int e = 0; e < 16; ++e)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) t[(32 * s + m) * kStride + Q * (8 * (e / 4) + 4 * kl + (e & 3)) + q] = acc[s][q][e];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const int c = nb * kConvColumns + 64 * chalf + lane;        // this lane's column
-    const bool live = c < out.ncols;
-    const size_t y_at = ((size_t)(c / out.pq) * L.M + row_id + 32 * strip) * out.pq + (c % out.pq);
-    const float bias_l = out.bias && m < n_rows ? out.bias[row_id + 32 * strip + m] : 0.0f;
-    for (int r0 = 0; r0 < n_rows; r0 += 8) {
-        float y[8];
+    const int my_col = kRowsAtOnce > 1 ? lane % kCols : lane, my_row = kRowsAtOnce > 1 ? lane / kCols : 0;
+    size_t y_at[kPerLane];
+    bool live[kPerLane];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int rr = min(r0 + u, n_rows - 1);
-            y[u] = t[rr * kStride + lane] + __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bias_l), rr));
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            if (r0 + u >= n_rows) break;
-            if (live) out.Y[y_at + (size_t)(r0 + u) * out.pq] = out.relu ? fmaxf(y[u], 0.0f) : y[u];
-        }
+    for (int i = 0; i < kPerLane; ++i) {
+        const int c = nb * kConvColumns + cbase + my_col + 64 * i;
+        live[i] = c < out.ncols;
+        y_at[i] = ((size_t)(c / out.pq) * L.M + row_id) * out.pq + (c % out.pq);
     }
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        const int first = 32 * (sbase + s);                       // the strip's first row in the block
+        const int n_rows = min(32, block_rows - first);
+        const float bias_l = out.bias && m < n_rows ? out.bias[row_id + first + m] : 0.0f;
+        for (int r0 = 0; r0 < n_rows; r0 += 8 * kRowsAtOnce) {
+            float y[8][kPerLane];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int ru = min(r0 + kRowsAtOnce * u, 31);     // uniform; this lane's row is ru + my_row
+                const float b0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bias_l), ru));
+                const float b1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, bias_l), min(ru + 1, 31)));
+                const int rr = min(ru + my_row, 31);
+#pragma unroll
+                for (int i = 0; i < kPerLane; ++i) y[u][i] = t[(32 * s + rr) * kStride + my_col + 64 * i] + (my_row ? b1 : b0);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int rr = r0 + kRowsAtOnce * u + my_row;
+                if (rr >= n_rows) continue;
+#pragma unroll
+                for (int i = 0; i < kPerLane; ++i)
+                    if (live[i]) out.Y[y_at[i] + (size_t)(first + rr) * out.pq] = out.relu ? fmaxf(y[u][i], 0.0f) : y[u][i];
+            }
+        }
     }
 }

@@ -925,13 +925,13 @@ int32_t conv_gathered(const ConvCall &c, const float *wt, const uint2 *rows, boo
     const ConvPlan &P = *c.P;
     const bool direct = c.splits == 1;
     const DirectOut out{direct ? c.y : nullptr, c.bias, c.ncols, c.pq, c.relu};
-    // blocks of at most 64 rows: the kernel form whose multiplying wavefronts share the columns instead of rows no block has
-    const bool half = c.L->desc.block_h <= 64;
+    // the kernel form for the height of the layer's blocks: how the multiplying wavefronts divide the tile
+    const int bh = c.L->desc.block_h, form = bh <= 64 ? 2 : bh <= 96 ? 1 : 0;
     using Kernel = void (*)(LayerDev, const float *, const float *, const uint2 *, float *, ConvGeom, int, int, int, int, DirectOut);
-    static const Kernel kernels[4] = {conv_mfma_kernel<false, false>, conv_mfma_kernel<true, false>, conv_mfma_kernel<false, true>,
-                                      conv_mfma_kernel<true, true>};
-    static LdsLimit seen[4];
-    const int which = (combined ? 1 : 0) + (half ? 2 : 0);
+    static const Kernel kernels[6] = {conv_mfma_kernel<false, 1, 4>, conv_mfma_kernel<true, 1, 4>, conv_mfma_kernel<false, 3, 1>,
+                                      conv_mfma_kernel<true, 3, 1>,  conv_mfma_kernel<false, 1, 2>, conv_mfma_kernel<true, 1, 2>};
+    static LdsLimit seen[6];
+    const int which = (combined ? 1 : 0) + 2 * form;
     if (int32_t rc = ensure_lds((const void *)kernels[which], P.lds, seen[which])) return rc;
     dim3 grid;
     GRID_TRY(grid, (int64_t)c.launch_panels * c.splits * (c.Np / kConvColumns));

@@ -450,21 +450,28 @@ GATHERED_CONVS = [
     (dict(C=8, H=34, W=34, R=3, S=3, stride=1, pad=1, groups=2, OC=400), 4, False),
     # a filter row entirely in the padding for the border pixels, 1 x 3 filter
     (dict(C=6, H=70, W=66, R=1, S=3, stride=1, pad=2, groups=1, OC=5), 4, False),
+    # 96-row blocks (two groups of 96 filters): a multiplying wavefront takes all three 32-row strips
+    (dict(C=8, H=40, W=40, R=3, S=3, stride=1, pad=1, groups=2, OC=192), 8, False),
+    # the same division with split block rows, and a last block row of 90 + 6 rows (186 filters in 96-row blocks)
+    (dict(C=64, H=40, W=40, R=3, S=3, stride=1, pad=1, groups=1, OC=186, block_h=96), 4, None),
+    # 64-row blocks with split block rows
+    (dict(C=64, H=40, W=40, R=3, S=3, stride=1, pad=1, groups=1, OC=64), 4, None),
 ]
 
 
 @pytest.mark.parametrize("geom,B,split", GATHERED_CONVS)
 def test_conv_gathered_columns(geom, B, split):
-    """From a few thousand columns on the fp32 path keeps no column matrix in memory:
+    """From a few hundred columns on the fp32 path keeps no column matrix in memory:
     the multiply kernel gathers the receptive fields itself.  Its workspace is the
-    decoded blocks, the row table and (block rows split) the partial tiles - far less
-    than a column matrix - and the result is the oracle's direct convolution."""
+    decoded blocks, the row table and (block rows split) the partial tiles, and the
+    result is the oracle's direct convolution."""
     torch = torch_cuda()
     rng = np.random.default_rng(geom["OC"] * 7 + B)
     OC, groups = geom["OC"], geom["groups"]
     Kc = geom["C"] // groups * geom["R"] * geom["S"]
     W = rand_pruned(rng, OC, Kc, 0.4)
-    bh = cl.conv_block_h(OC, groups)
+    geom = dict(geom)
+    bh = geom.pop("block_h", None) or cl.conv_block_h(OC, groups)
     L, m, oW = check_decode(W, 8, 8, bh, 128)
     X = (rng.random((B, geom["C"], geom["H"], geom["W"]), dtype=np.float32) - 0.3).astype(np.float32)
     X[:, :, 0, :] += 2.0                              # the border rows and columns differ from the inside: a shifted tap shows
@@ -476,8 +483,13 @@ def test_conv_gathered_columns(geom, B, split):
     n_blocks = -(-OC // bh) * -(-Kc // 128)
     fixed = n_blocks * 128 * 128 * 4 + -(-(-(-Kc // 128) * 128 * 8) // 256) * 256        # decoded blocks + row table
     ws = cl.conv_workspace_bytes(L, geom, B)
-    assert ws < cols * 128 * 4                       # no column matrix (at least 128 rows of `cols` floats)
-    assert (ws > fixed) == split and ws >= fixed
+    # decoded blocks + row table + a whole number of partial-tile sets (one per split of the block rows)
+    # and nothing else: no column matrix
+    bh = min(bh, OC // groups)                        # the library cuts the block height to the matrix
+    part_set = -(-OC // bh) * (-(-cols // 128) * 128) * bh * 4
+    assert ws >= fixed and (ws - fixed) % part_set == 0 and (ws - fixed) // part_set != 1
+    assert split is None or (ws > fixed) == split                       # None: the launch shape decides
+    print("split" if ws > fixed else "unsplit", end=" ")
     Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
     for use_bias, relu in [(False, False), (True, True)]:
         ref = oracle.conv_forward(oW, X, geom, bias if use_bias else None, relu, nthreads=8)
