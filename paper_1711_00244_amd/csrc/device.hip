@@ -1017,8 +1017,8 @@ extern "C" int32_t cl_compressed_conv_forward(const cl_layer *L, const cl_conv_d
         const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits) + (size_t)kWTileBytes;
         static LdsLimit seen;
         if (int32_t rc = ensure_lds((const void *)decode_tiles_kernel, lds, seen)) return rc;
-        // n_blocks workgroups of kThreads threads: more threads than the row table has entries
-        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kThreads), lds, st, make_dev(L), wt, g, L->nbw * kTile,
+        // n_blocks workgroups of kTileDecodeThreads threads: more threads than the row table has entries
+        hipLaunchKernelGGL(decode_tiles_kernel, dim3((unsigned)L->n_blocks), dim3(kTileDecodeThreads), lds, st, make_dev(L), wt, g, L->nbw * kTile,
                            combined ? 1 : 0, rows);
         HIP_TRY(hipGetLastError());
     }

@@ -222,11 +222,15 @@ __device__ __forceinline__ void decoder_role(const LayerDev &L, const Smem &s, f
 // is outside the image (r S + s when `combined`, else r | s << 8), with the top bit set
 // for a row the piece does not have.  n_rows entries, one per thread of the launch's
 // first workgroups (a layer has at least as many blocks as pieces).
-__global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out, ConvGeom cg, int n_rows, int combined,
+// Sixteen wavefronts: a dense block has up to 35 chunks, and the launch is as long as its rounds of chunks.
+constexpr int kTileDecodeWaves = 16;
+constexpr int kTileDecodeThreads = kTileDecodeWaves * 64;
+
+__global__ __launch_bounds__(kTileDecodeThreads) void decode_tiles_kernel(LayerDev L, float *tiles_out, ConvGeom cg, int n_rows, int combined,
                                                                 uint2 *rows)
 {
     {
-        const int t = (int)(blockIdx.x * kThreads + threadIdx.x);
+        const int t = (int)(blockIdx.x * kTileDecodeThreads + threadIdx.x);
         if (t < n_rows) {
             const int kk = t % kTile, k = (t / kTile) * L.bw + kk;
             uint2 e = make_uint2(0u, 0x80000000u);
@@ -245,12 +249,13 @@ __global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, floa
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
     const uint32_t c0 = L.block_chunk[b], c1 = L.block_chunk[b + 1];
-    const TableRegs tr = fetch_tables(L);
-    for (int t = threadIdx.x; t < kTile * kWStride / 4; t += kThreads) ((uint4 *)tile)[t] = uint4{0, 0, 0, 0};
-    store_tables(s, L, tr);
+    TableRegs tr;
+    if (threadIdx.x < kThreads) tr = fetch_tables(L);           // the table image is copied by kThreads threads
+    for (int t = threadIdx.x; t < kTile * kWStride / 4; t += kTileDecodeThreads) ((uint4 *)tile)[t] = uint4{0, 0, 0, 0};
+    if (threadIdx.x < kThreads) store_tables(s, L, tr);
     __syncthreads();
     const BlockGeom g = block_geom(L, b);
-    for (uint32_t c = c0 + (uint32_t)wave; c < c1; c += kWaves) {       // uniform per wavefront
+    for (uint32_t c = c0 + (uint32_t)wave; c < c1; c += kTileDecodeWaves) {       // uniform per wavefront
         const ChunkHead h = load_head(L, c);
         const Symbols y = decode_record(load_record(L, h, lane), s.T);
         const LaneStart st = lane_starts(y, h.m.pos0);
@@ -263,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void decode_tiles_kernel(LayerDev L, floa
     __syncthreads();
     uint4 *dst = (uint4 *)(tiles_out + (size_t)b * kTile * kTile);
     const uint4 *src = (const uint4 *)tile;
-    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kThreads) {
+    for (int t = threadIdx.x; t < kTile * kTile / 4; t += kTileDecodeThreads) {
         // piece t of the output: row t % 128, columns 4 (t / 128) .. 4 (t / 128) + 3
         dst[t] = src[(t % kTile) * (kWStride / 4) + t / kTile];
     }
