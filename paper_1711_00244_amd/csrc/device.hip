@@ -729,9 +729,12 @@ extern "C" int32_t cl_maxpool_forward(const float *d_X, float *d_Y, int32_t batc
     if (!d_X || !d_Y) return fail(CL_EINVAL, "null pointer");
     if (batch < 1 || C < 1 || size < 1 || stride < 1 || H < size || W < size) return fail(CL_EINVAL, "bad pooling geometry");
     const int P = (H - size) / stride + 1, Q = (W - size) / stride + 1;
-    const int64_t n_out = (int64_t)batch * C * P * Q;
-    hipLaunchKernelGGL(maxpool_kernel, dim3((unsigned)std::min<int64_t>((n_out + 255) / 256, 65536)), dim3(256), 0, (hipStream_t)stream,
-                       d_X, d_Y, n_out, H, W, P, Q, size, stride);
+    if ((int64_t)P * Q > (1 << 30)) return fail(CL_EUNSUPPORTED, "more than 2^30 outputs per plane");
+    const int64_t planes = (int64_t)batch * C;
+    const int pq = P * Q, planes_per_block = pq >= 256 ? 1 : 256 / pq;
+    const dim3 grid((unsigned)((pq + 255) / 256), (unsigned)std::min<int64_t>((planes + planes_per_block - 1) / planes_per_block, 65535));
+    auto kernel = size == 3 ? maxpool_kernel<3> : size == 2 ? maxpool_kernel<2> : maxpool_kernel<0>;
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, (hipStream_t)stream, d_X, d_Y, planes, H, W, P, Q, size, stride, planes_per_block);
     HIP_TRY(hipGetLastError());
     clear_error();
     return CL_OK;

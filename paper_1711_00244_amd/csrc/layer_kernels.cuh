@@ -3,17 +3,32 @@
 // in the order given there.
 #pragma once
 
-__global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ X, float *Y, int64_t n_out, int H, int W,
-                                                      int P, int Q, int size, int stride)
+// One thread per output.  blockIdx.x and the thread give the output's place in its
+// plane (and, where a plane has fewer than 256 outputs, which of the workgroup's
+// planes_per_block planes it is in) with two 32-bit divisions; blockIdx.y, strided,
+// walks the (image, channel) planes.  SIZE: the window when it is 2 or 3 (its loads
+// are then all in flight together), 0: any window.
+// (Taking image, channel, row and column from one flat 64-bit index cost three 64-bit
+// divisions per output: 38 us for 64 x 96 x 55 x 55, where the copy rate allows 13.)
+template <int SIZE>
+__global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ X, float *Y, int64_t planes, int H, int W,
+                                                      int P, int Q, int size, int stride, int planes_per_block)
 {
-    for (int64_t o = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; o < n_out; o += (int64_t)gridDim.x * blockDim.x) {
-        const int q = (int)(o % Q), p = (int)((o / Q) % P);
-        const int64_t bc = o / ((int64_t)P * Q);
-        const float *x = X + (bc * H + (int64_t)p * stride) * W + (int64_t)q * stride;
+    const unsigned pq = (unsigned)P * (unsigned)Q;
+    const unsigned t = blockIdx.x * 256u + threadIdx.x;
+    const unsigned lp = t / pq, i = t - lp * pq;
+    if (lp >= (unsigned)planes_per_block) return;
+    const unsigned p = i / (unsigned)Q, q = i - p * (unsigned)Q;
+    const int64_t in_off = ((int64_t)p * W + q) * stride, hw = (int64_t)H * W;
+    const int sz = SIZE ? SIZE : size;
+    for (int64_t pl = (int64_t)blockIdx.y * planes_per_block + lp; pl < planes; pl += (int64_t)gridDim.y * planes_per_block) {
+        const float *x = X + pl * hw + in_off;
         float m = x[0];
-        for (int r = 0; r < size; ++r)
-            for (int s = 0; s < size; ++s) m = fmaxf(m, x[(int64_t)r * W + s]);
-        Y[o] = m;
+#pragma unroll
+        for (int r = 0; r < sz; ++r)
+#pragma unroll
+            for (int s = 0; s < sz; ++s) m = fmaxf(m, x[(int64_t)r * W + s]);
+        Y[pl * pq + i] = m;
     }
 }
 
@@ -23,7 +38,19 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ 
 // and a channel's window is summed from registers, in channel order; HALF < 0: any
 // window, summed from the (cached) input as it stands.
 // (One thread per pixel walking all channels took 214 us for one image of 256 x 27 x 27.)
-constexpr int kLrnChunk = 4;
+constexpr int kLrnChunk = 8;
+
+// base^(-beta).  For a positive, normal, finite base: exp2(-beta * log2(base)) with the
+// two hardware instructions (v_log_f32, v_exp_f32), whose error of about one unit in the
+// last place each leaves a relative error near 1e-7 * (1 + |beta * log2(base)|) in the
+// result; any other base goes through the library's powf, which alone took 120
+// instructions per element and made the kernel ALU-bound (67 us for 64 x 96 x 55 x 55,
+// three times a copy).
+__device__ __forceinline__ float pow_neg(float base, float beta)
+{
+    if (!(base >= 1.17549435e-38f && base <= 3.0e38f)) return powf(base, -beta);
+    return __builtin_amdgcn_exp2f(-beta * __builtin_amdgcn_logf(base));
+}
 
 template <int HALF>
 __global__ __launch_bounds__(256) void lrn_kernel(const float *__restrict__ X, float *Y, int B, int C, int64_t hw, int n,
@@ -51,7 +78,7 @@ __global__ __launch_bounds__(256) void lrn_kernel(const float *__restrict__ X, f
                 float ss = 0.0f;
 #pragma unroll
                 for (int w = 0; w <= 2 * HALF; ++w) ss += v[j + w] * v[j + w];
-                if (c0 + j < C) y[(int64_t)(c0 + j) * hw] = v[j + HALF] * powf(k + alpha_over_n * ss, -beta);
+                if (c0 + j < C) y[(int64_t)(c0 + j) * hw] = v[j + HALF] * pow_neg(k + alpha_over_n * ss, beta);
             }
         } else {
             for (int c = c0; c < min(C, c0 + kLrnChunk); ++c) {
@@ -60,7 +87,7 @@ __global__ __launch_bounds__(256) void lrn_kernel(const float *__restrict__ X, f
                     const float v = x[(int64_t)cc * hw];
                     ss += v * v;
                 }
-                y[(int64_t)c * hw] = x[(int64_t)c * hw] * powf(k + alpha_over_n * ss, -beta);
+                y[(int64_t)c * hw] = x[(int64_t)c * hw] * pow_neg(k + alpha_over_n * ss, beta);
             }
         }
     }
