@@ -669,10 +669,15 @@ def test_forward_rejects_bad_arguments():
 
 
 @pytest.mark.parametrize("shape,size,stride", [((2, 5, 11, 9), 3, 2), ((1, 96, 55, 55), 3, 2), ((3, 7, 8, 8), 2, 2),
-                                               ((1, 1, 3, 3), 3, 1), ((2, 3, 6, 7), 1, 1)])
+                                               ((1, 1, 3, 3), 3, 1), ((2, 3, 6, 7), 1, 1), ((5, 3, 13, 13), 4, 3),
+                                               ((3, 50, 6, 6), 3, 1), ((2, 2, 40, 40), 3, 2), ((70000, 1, 17, 17), 2, 1),
+                                               ((66000, 256, 1, 1), 1, 1)])
 def test_maxpool_forward(shape, size, stride):
     """Max pooling (the pool rows of Table IV) against the oracle: exact, a maximum
-    of fp32 values has no rounding."""
+    of fp32 values has no rounding.  The cases cover planes of fewer outputs than a
+    workgroup has threads (several planes per workgroup, the last one partly filled),
+    planes of several workgroups, windows of 1 to 4, and more planes than the launch
+    has workgroup rows (the last two)."""
     torch = torch_cuda()
     rng = np.random.default_rng(sum(shape) + size)
     X = rng.standard_normal(shape).astype(np.float32)
@@ -683,14 +688,17 @@ def test_maxpool_forward(shape, size, stride):
 
 
 @pytest.mark.parametrize("shape,n", [((2, 9, 3, 4), 5), ((1, 96, 55, 55), 5), ((2, 256, 27, 27), 5), ((3, 4, 5, 5), 3),
-                                     ((1, 2, 2, 2), 1)])
+                                     ((1, 2, 2, 2), 1), ((2, 13, 3, 3), 3), ((2, 20, 3, 3), 7), ((4100, 128, 1, 1), 5)])
 def test_lrn_forward(shape, n):
     """Across-channel normalisation (the norm rows of Table IV) against the oracle's
-    fp64, with AlexNet's constants and with ones that make the denominator matter."""
+    fp64, with AlexNet's constants, with ones that make the denominator matter, with a
+    base near 1e7 and with other exponents; channel counts that are no multiple of a
+    thread's run, a window wider than the kernels specialise for, and more runs than
+    the launch has workgroup rows."""
     torch = torch_cuda()
     rng = np.random.default_rng(sum(shape) + n)
     X = (rng.standard_normal(shape) * 3).astype(np.float32)
-    for alpha, beta, k in [(1e-4, 0.75, 1.0), (0.5, 0.75, 2.0)]:
+    for alpha, beta, k in [(1e-4, 0.75, 1.0), (0.5, 0.75, 2.0), (1e6, 0.5, 1.0), (2.0, 1.5, 0.1)]:
         Y = cl.lrn_forward(torch.from_numpy(X).cuda(), n, alpha, beta, k)
         assert rel_err(Y.cpu().numpy(), oracle.lrn_forward(X, n, alpha, beta, k)) <= TOL
     with pytest.raises(cl.CLError):
