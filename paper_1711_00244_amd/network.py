@@ -212,8 +212,16 @@ def main(argv=None):
     ap.add_argument("--check", action="store_true", help="run the plan for K images and compare with one-batch execution")
     ap.add_argument("--density", type=float, default=None, help="uniform fraction of non-zeros for all layers")
     ap.add_argument("--graphs", action="store_true", help="time the layers from replayed graphs (no per-call cost of the caller)")
+    ap.add_argument("--layer-times", type=int, default=None, metavar="B",
+                    help="only time every layer at batch B (fast form) and print ms per layer")
     args = ap.parse_args(argv)
     fast = alexnet(density=args.density)
+    if args.layer_times:
+        t = fast.measure_times([args.layer_times], graphs=args.graphs)[:, 0]
+        print(json.dumps(dict(batch=args.layer_times, density=args.density, timed_from_graphs=args.graphs,
+                              ms_per_layer={op.name: round(float(x), 5) for op, x in zip(fast.layers, t)},
+                              ms_total=round(float(t.sum()), 4))), flush=True)
+        return 0
     nets = {"fast": fast, "compact": compact_copy(fast)}
     model_bytes = sum(op.layer.stats()["model_bytes"] for op in fast.layers if hasattr(op, "layer"))
     for K in args.images:
