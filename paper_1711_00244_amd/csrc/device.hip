@@ -731,10 +731,11 @@ extern "C" int32_t cl_maxpool_forward(const float *d_X, float *d_Y, int32_t batc
     const int P = (H - size) / stride + 1, Q = (W - size) / stride + 1;
     if ((int64_t)P * Q > (1 << 30)) return fail(CL_EUNSUPPORTED, "more than 2^30 outputs per plane");
     const int64_t planes = (int64_t)batch * C;
-    const int pq = P * Q, planes_per_block = pq >= 256 ? 1 : 256 / pq;
-    const dim3 grid((unsigned)((pq + 255) / 256), (unsigned)std::min<int64_t>((planes + planes_per_block - 1) / planes_per_block, 65535));
+    const int pq = P * Q, planes_per_row = (int)std::min<int64_t>(planes, std::max(1, 2048 / pq));
+    const dim3 grid((unsigned)(((int64_t)planes_per_row * pq + 255) / 256),
+                    (unsigned)std::min<int64_t>((planes + planes_per_row - 1) / planes_per_row, 65535));
     auto kernel = size == 3 ? maxpool_kernel<3> : size == 2 ? maxpool_kernel<2> : maxpool_kernel<0>;
-    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, (hipStream_t)stream, d_X, d_Y, planes, H, W, P, Q, size, stride, planes_per_block);
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, (hipStream_t)stream, d_X, d_Y, planes, H, W, P, Q, size, stride, planes_per_row);
     HIP_TRY(hipGetLastError());
     clear_error();
     return CL_OK;

@@ -3,25 +3,25 @@
 // in the order given there.
 #pragma once
 
-// One thread per output.  blockIdx.x and the thread give the output's place in its
-// plane (and, where a plane has fewer than 256 outputs, which of the workgroup's
-// planes_per_block planes it is in) with two 32-bit divisions; blockIdx.y, strided,
-// walks the (image, channel) planes.  SIZE: the window when it is 2 or 3 (its loads
-// are then all in flight together), 0: any window.
+// One thread per output.  A row of workgroups (blockIdx.y, strided) takes planes_per_row
+// whole (image, channel) planes - as many as give it about 2048 outputs, so that small
+// planes still fill the workgroups - and blockIdx.x with the thread gives the plane within
+// the row and the output's place in it with two 32-bit divisions.  SIZE: the window when it
+// is 2 or 3 (its loads are then all in flight together), 0: any window.
 // (Taking image, channel, row and column from one flat 64-bit index cost three 64-bit
 // divisions per output: 38 us for 64 x 96 x 55 x 55, where the copy rate allows 13.)
 template <int SIZE>
 __global__ __launch_bounds__(256) void maxpool_kernel(const float *__restrict__ X, float *Y, int64_t planes, int H, int W,
-                                                      int P, int Q, int size, int stride, int planes_per_block)
+                                                      int P, int Q, int size, int stride, int planes_per_row)
 {
     const unsigned pq = (unsigned)P * (unsigned)Q;
     const unsigned t = blockIdx.x * 256u + threadIdx.x;
     const unsigned lp = t / pq, i = t - lp * pq;
-    if (lp >= (unsigned)planes_per_block) return;
+    if (lp >= (unsigned)planes_per_row) return;
     const unsigned p = i / (unsigned)Q, q = i - p * (unsigned)Q;
     const int64_t in_off = ((int64_t)p * W + q) * stride, hw = (int64_t)H * W;
     const int sz = SIZE ? SIZE : size;
-    for (int64_t pl = (int64_t)blockIdx.y * planes_per_block + lp; pl < planes; pl += (int64_t)gridDim.y * planes_per_block) {
+    for (int64_t pl = (int64_t)blockIdx.y * planes_per_row + lp; pl < planes; pl += (int64_t)gridDim.y * planes_per_row) {
         const float *x = X + pl * hw + in_off;
         float m = x[0];
 #pragma unroll
