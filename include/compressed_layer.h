@@ -344,7 +344,7 @@ int32_t cl_plan_batches(int32_t n_layers, const int32_t *batch_set, int32_t n_ba
  *   exp2(-beta * log2(base)), relative error near 1e-7 * (1 + |beta * log2(base)|).
  * Errors: CL_EINVAL (null pointers, non-positive sizes, window larger than the
  * image, even n), CL_EUNSUPPORTED (pooling with more than 2^30 outputs per plane,
- * normalisation with batch x C / 4 above 2^31 - 1) - nothing is launched then; CL_EHIP. */
+ * normalisation with batch x ceil(C / 8) above 2^31 - 1) - nothing is launched then; CL_EHIP. */
 int32_t cl_maxpool_forward(const float *d_X, float *d_Y, int32_t batch, int32_t C, int32_t H, int32_t W,
                            int32_t size, int32_t stride, void *stream);
 int32_t cl_lrn_forward(const float *d_X, float *d_Y, int32_t batch, int32_t C, int32_t H, int32_t W,
