@@ -237,8 +237,11 @@ int32_t cl_compressed_fc_forward(const cl_layer *layer, const float *d_X, const 
  * intermediate activations kept in the workspace.  Between two layers on the
  * dense-tile paths the finishing kernel writes the next layer's activations in the
  * layout its multiply kernel reads (when that layer has 128-column blocks and K a
- * multiple of 128), which saves the separate transposition; the results are the
- * same bit for bit as those of per-layer calls.  The workspace holds up to four
+ * multiple of 128), which saves the separate transposition; on the run-to-run
+ * identical paths the results are the same bit for bit as those of per-layer calls,
+ * and where a layer runs on CL_PATH_SPARSE they are, like that path's own results
+ * from one call to the next, the same within the rounding of a different order of
+ * additions (see cl_compressed_fc_forward), not bit for bit.  The workspace holds up to four
  * copies of each scratch buffer, used in rotation (a kernel that writes where
  * another has just read runs slower on this chip).
  *  layers          n_layers uploaded layers, layers[i]->K == layers[i-1]->M
@@ -332,7 +335,9 @@ int32_t cl_plan_batches(int32_t n_layers, const int32_t *batch_set, int32_t n_ba
 /* The fixed-function layers between the convolutions of a whole network (the norm
  * and pool rows of Table IV; Sec. II: pooling layers "implement fixed functions"),
  * so that a network can run end to end on the device with per-layer batch sizes.
- * d_X: batch x C x H x W fp32 (NCHW), device.  Asynchronous on `stream`.
+ * d_X: batch x C x H x W fp32 (NCHW), device.  Asynchronous on `stream`.  Neither call
+ * works in place: d_Y must not overlap d_X (an output's inputs are read by other
+ * workgroups than the one that writes it).
  *
  * cl_maxpool_forward: maximum over size x size windows at the given stride, no
  *   padding, windows fully inside the image; d_Y: batch x C x P x Q with

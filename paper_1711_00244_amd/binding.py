@@ -135,6 +135,17 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def _want(t, shape, what):
+    """A tensor handed to the library as a raw pointer must be what the kernels
+    assume: fp32, contiguous, on the GPU, of exactly this shape."""
+    import torch
+    if t is None:
+        return
+    if t.dtype != torch.float32 or tuple(t.shape) != tuple(shape) or not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous float32 CUDA tensor of shape {tuple(shape)}, "
+                         f"got {t.dtype} {tuple(t.shape)}")
+
+
 class Layer:
     """Owns a cl_layer handle."""
 
@@ -268,6 +279,9 @@ def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO
     if X.dtype != torch.float32 or X.dim() != 2 or X.shape[1] != K:
         raise ValueError(f"X must be (B, {K}) float32")
     B = X.shape[0]
+    _want(X, (B, K), "X")
+    _want(bias, (M,), "bias")
+    _want(out, (B, M), "out")
     Y = out if out is not None else torch.empty((B, M), dtype=torch.float32, device=X.device)
     need = fc_workspace_bytes(layer, B, path)
     if workspace is None and need:
@@ -296,6 +310,13 @@ def compressed_fc_stack_forward(layers, X, biases=None, relu_hidden=True, relu_l
     if X.dtype != torch.float32 or X.dim() != 2 or X.shape[1] != layers[0].K:
         raise ValueError(f"X must be (B, {layers[0].K}) float32")
     B = X.shape[0]
+    _want(X, (B, layers[0].K), "X")
+    _want(out, (B, layers[-1].M), "out")
+    if biases is not None:
+        if len(biases) != len(layers):
+            raise ValueError("one bias (or None) per layer")
+        for b, l in zip(biases, layers):
+            _want(b, (l.M,), "bias")
     Y = out if out is not None else torch.empty((B, layers[-1].M), dtype=torch.float32, device=X.device)
     if workspace is None:
         workspace = torch.empty(max(256, fc_stack_workspace_bytes(layers, B, path)), dtype=torch.uint8, device=X.device)
@@ -321,9 +342,14 @@ def compressed_conv_forward(layer: Layer, conv: dict, X, bias=None, relu=False, 
     """X: (B, C, H, W) fp32 CUDA tensor -> (B, OC, P, Q)."""
     import torch
     cd = ConvDesc(conv["C"], conv["H"], conv["W"], conv["R"], conv["S"], conv["stride"], conv["pad"], conv["groups"], conv["OC"])
+    if X.dim() != 4:
+        raise ValueError("X must be (B, C, H, W)")
     B = X.shape[0]
     P = (conv["H"] + 2 * conv["pad"] - conv["R"]) // conv["stride"] + 1
     Q = (conv["W"] + 2 * conv["pad"] - conv["S"]) // conv["stride"] + 1
+    _want(X, (B, conv["C"], conv["H"], conv["W"]), "X")
+    _want(bias, (conv["OC"],), "bias")
+    _want(out, (B, conv["OC"], P, Q), "out")
     Y = out if out is not None else torch.empty((B, conv["OC"], P, Q), dtype=torch.float32, device=X.device)
     need = conv_workspace_bytes(layer, conv, B, path)
     if workspace is None and need:
@@ -341,6 +367,9 @@ def maxpool_forward(X, size: int, stride: int, out=None):
         raise ValueError("X must be a contiguous (B, C, H, W) float32 tensor")
     B, Cc, H, W = X.shape
     P, Q = (H - size) // stride + 1, (W - size) // stride + 1
+    _want(out, (B, Cc, max(P, 0), max(Q, 0)), "out")
+    if out is not None and out.data_ptr() == X.data_ptr():
+        raise ValueError("pooling is not in place")
     Y = out if out is not None else torch.empty((B, Cc, max(P, 0), max(Q, 0)), dtype=torch.float32, device=X.device)
     _check(lib().cl_maxpool_forward(_dev_ptr(X), _dev_ptr(Y), B, Cc, H, W, size, stride, _stream()))
     return Y
@@ -352,6 +381,9 @@ def lrn_forward(X, n: int = 5, alpha: float = 1e-4, beta: float = 0.75, k: float
     if X.dtype != torch.float32 or X.dim() != 4 or not X.is_contiguous():
         raise ValueError("X must be a contiguous (B, C, H, W) float32 tensor")
     B, Cc, H, W = X.shape
+    _want(out, (B, Cc, H, W), "out")
+    if out is not None and out.data_ptr() == X.data_ptr():
+        raise ValueError("normalisation is not in place: neighbouring channels are read by other workgroups")
     Y = out if out is not None else torch.empty_like(X)
     _check(lib().cl_lrn_forward(_dev_ptr(X), _dev_ptr(Y), B, Cc, H, W, n, float(alpha), float(beta), float(k), _stream()))
     return Y

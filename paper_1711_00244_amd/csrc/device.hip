@@ -14,9 +14,9 @@
 //           multiply-accumulate it (sparse forward) or place it in a dense tile (MFMA forward)
 //
 // One translation unit: this file holds the host side (device image of a layer, launch
-// shapes, the entry points) and includes the kernels - decode.cuh (wavefront primitives,
-// decoding and placement passes), sparse_kernels.cuh, mfma_kernels.cuh, bf16_kernels.cuh,
-// conv_kernels.cuh, finish_kernels.cuh, layer_kernels.cuh.
+// shapes, the entry points) and includes the kernels - decode.hpp (wavefront primitives,
+// decoding and placement passes), sparse_kernels.hpp, mfma_kernels.hpp, bf16_kernels.hpp,
+// conv_kernels.hpp, finish_kernels.hpp, layer_kernels.hpp.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
@@ -97,13 +97,13 @@ static LayerDev make_dev(const cl_layer *L)
     return d;
 }
 
-#include "decode.cuh"
-#include "sparse_kernels.cuh"
-#include "mfma_kernels.cuh"
-#include "bf16_kernels.cuh"
-#include "conv_kernels.cuh"
-#include "finish_kernels.cuh"
-#include "layer_kernels.cuh"
+#include "decode.hpp"
+#include "sparse_kernels.hpp"
+#include "mfma_kernels.hpp"
+#include "bf16_kernels.hpp"
+#include "conv_kernels.hpp"
+#include "finish_kernels.hpp"
+#include "layer_kernels.hpp"
 
 // ------------------------------------------------------------------------- //
 // host side

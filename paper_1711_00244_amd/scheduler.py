@@ -11,9 +11,12 @@ program (``cl_plan_batches``), every layer runs in the library's kernels.
                        at batch B, the layers before it run B / b times at batch b,
                        their outputs parked until B of them are there.
 * ``simulate``       - single-image requests arriving as a Poisson stream; batches
-                       are formed under a per-request latency cap.  The clock is
-                       simulated from the measured Time table (reproducible); the
-                       GPU work of every dispatched batch is real.
+                       are formed under a per-request latency cap.  The GPU work of
+                       every dispatched batch is real; the clock advances either by
+                       the cost the dynamic program assigns to the per-layer batch
+                       sizes that were dispatched (``clock="model"``, reproducible)
+                       or by the duration of the dispatch measured with HIP events
+                       (``clock="measured"``).
 """
 from __future__ import annotations
 
@@ -36,10 +39,22 @@ class Plan:
     ws_bytes: list
     tot_bytes: int
 
-    def batch_ms(self, B: int) -> float:
-        """Time to push B images (B in batch_set) through the whole stack at a
-        fixed batch B."""
-        return float(self.time_ms[:, self.batch_set.index(B)].sum())
+    def dispatch_ms(self, bpl) -> float:
+        """Cost of running bpl[-1] images with per-layer batch sizes bpl (a monotone
+        divisor chain of members of batch_set): the recurrence of Sec. V-C,
+        cost(i) = Time(i, bpl[i]) + (bpl[i] / bpl[i-1]) cost(i-1) - every earlier
+        layer is repeated until the later layer's batch is full."""
+        cost = 0.0
+        for i, b in enumerate(bpl):
+            reps = 1 if i == 0 else b // bpl[i - 1]
+            cost = float(self.time_ms[i, self.batch_set.index(b)]) + reps * cost
+        return cost
+
+    def bpl_for(self, B: int) -> list:
+        """Per-layer batch sizes for a dispatch of B images (B in batch_set): the plan's,
+        capped at B; a size that does not divide B gives way to B."""
+        bpl = [min(b, B) for b in self.batch_per_layer]
+        return [b if B % b == 0 else B for b in bpl]
 
 
 class StackRunner:
@@ -126,15 +141,20 @@ class StackRunner:
         return Plan(bpl, ms, list(batch_set), time_ms, ws, int(tot_bytes))
 
 
-def simulate(runner: StackRunner, plan: Plan, arrivals_s, inputs, latency_cap_ms):
+def simulate(runner: StackRunner, plan: Plan, arrivals_s, inputs, latency_cap_ms, clock="model"):
     """Serve single-image requests arriving at arrivals_s (ascending, seconds).
 
     When the GPU is idle and requests wait, the largest candidate batch B <= queue
     is dispatched as soon as (i) the queue has reached the plan's batch, or (ii)
     waiting for the next larger candidate would push the oldest request past the
-    cap (its wait so far + the time of that larger batch), or no more requests
-    will come.  Returns (outputs in request order, stats)."""
+    cap (its wait so far + the cost of that larger dispatch), or no more requests
+    will come.  A dispatch of B images runs with the per-layer batch sizes
+    plan.bpl_for(B) and is charged plan.dispatch_ms of exactly those sizes
+    (clock="model") or its measured duration (clock="measured": HIP events around
+    the dispatch, the device idle before it).  Returns (outputs in request order,
+    stats)."""
     import torch
+    assert clock in ("model", "measured")
     n = len(arrivals_s)
     bs = [b for b in plan.batch_set if b <= plan.batch_per_layer[-1]] or [plan.batch_set[0]]
     target = bs[-1]
@@ -142,6 +162,7 @@ def simulate(runner: StackRunner, plan: Plan, arrivals_s, inputs, latency_cap_ms
     done = np.zeros(n)
     outputs = [None] * n
     now, head, served = 0.0, 0, 0
+    predicted_ms = charged_ms = 0.0
     batches = []
     while served < n:
         if head <= served:                                   # nobody waiting: jump to the next arrival
@@ -154,15 +175,26 @@ def simulate(runner: StackRunner, plan: Plan, arrivals_s, inputs, latency_cap_ms
             nxt = min(b for b in bs if b > B)                # next larger candidate
             t_fill = arrivals_s[served + nxt - 1] if served + nxt - 1 < n else np.inf
             # keep waiting only if the oldest request would still meet the cap with the larger batch
-            if t_fill + plan.batch_ms(nxt) * 1e-3 - arrivals_s[served] <= cap_s:
+            if t_fill + plan.dispatch_ms(plan.bpl_for(nxt)) * 1e-3 - arrivals_s[served] <= cap_s:
                 now = t_fill
                 continue
         idx = list(range(served, served + B))
         X = torch.stack([inputs[i] for i in idx], 0)
-        bpl = [min(b, B) for b in plan.batch_per_layer]
-        bpl = [b if B % b == 0 else B for b in bpl]
-        Y = runner.run(X, bpl)
-        now += plan.batch_ms(B) * 1e-3
+        bpl = plan.bpl_for(B)
+        if clock == "measured":
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            Y = runner.run(X, bpl)
+            e1.record()
+            e1.synchronize()
+            spent_ms = e0.elapsed_time(e1)
+        else:
+            Y = runner.run(X, bpl)
+            spent_ms = plan.dispatch_ms(bpl)
+        predicted_ms += plan.dispatch_ms(bpl)
+        charged_ms += spent_ms
+        now += spent_ms * 1e-3
         for k, i in enumerate(idx):
             outputs[i] = Y[k]
             done[i] = now
@@ -171,7 +203,8 @@ def simulate(runner: StackRunner, plan: Plan, arrivals_s, inputs, latency_cap_ms
     lat = (done - np.asarray(arrivals_s)) * 1e3
     stats = dict(requests=n, batches=len(batches), mean_batch=float(np.mean(batches)), p50_ms=float(np.percentile(lat, 50)),
                  p99_ms=float(np.percentile(lat, 99)), max_ms=float(lat.max()), span_s=float(done.max() - arrivals_s[0]),
-                 images_per_s=float(n / (done.max() - arrivals_s[0])), over_cap=int((lat > latency_cap_ms + 1e-9).sum()))
+                 images_per_s=float(n / (done.max() - arrivals_s[0])), over_cap=int((lat > latency_cap_ms + 1e-9).sum()),
+                 clock=clock, gpu_ms_charged=charged_ms, gpu_ms_predicted=predicted_ms)
     return outputs, stats
 
 
@@ -186,6 +219,7 @@ def main(argv=None):
     ap.add_argument("--budget-mb", type=float, default=64.0)
     ap.add_argument("--latency-cap-ms", type=float, default=10.0)
     ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--clock", choices=["model", "measured"], default="measured")
     args = ap.parse_args(argv)
     layers = []
     for li in range(3):
@@ -199,7 +233,7 @@ def main(argv=None):
         return 1
     arrivals = wl.poisson_arrivals(args.requests, args.rate, wl.BASE_SEED + 5000)
     X = torch.from_numpy(wl.activations(5, args.requests, K=layers[0].K)).cuda()
-    _, stats = simulate(runner, plan, arrivals, [X[i] for i in range(args.requests)], args.latency_cap_ms)
+    _, stats = simulate(runner, plan, arrivals, [X[i] for i in range(args.requests)], args.latency_cap_ms, clock=args.clock)
     stats.update(rate=args.rate, plan=plan.batch_per_layer, plan_ms_per_image=plan.ms_per_image,
                  budget_bytes=plan.tot_bytes, ws_bytes=plan.ws_bytes,
                  time_ms={str(b): [round(float(t), 4) for t in plan.time_ms[:, j]] for j, b in enumerate(plan.batch_set)})

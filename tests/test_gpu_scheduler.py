@@ -79,6 +79,48 @@ def test_plan_and_poisson_stream(vgg_stack):
     assert np.abs(Y - ref).max() / np.abs(ref).max() <= 3e-5
 
 
+def test_config5_full_size_plan_and_stream():
+    """configs[4] at full size: the VGG-16 FC stack (fc6 is 4096 x 25088) planned over
+    the batch sizes 1..256 under the 64 MB decoded-buffer / activation budget and the
+    10 ms latency cap, then one seeded Poisson stream of 256 single-image requests
+    served with that plan, the clock advancing by the measured duration of every
+    dispatch.  Outputs of sampled requests against the oracle's chain on its own decode
+    (layer by layer in fp64, activations handed on in fp32 as the device does)."""
+    import torch
+    layers, dense = [], []
+    for li in range(3):
+        spec, W = wl.layer_weights(5, li)
+        layers.append(cl.compress_layer(W, spec.r, spec.k, 128, 128, upload=True))
+        dense.append(oracle.dense_weights(oracle.compress_layer(W, spec.r, spec.k, 128, 128)))
+        del W
+    runner = scheduler.StackRunner(layers)
+    batch_set = wl.CONFIGS[5]["batches"]
+    assert batch_set[0] == 1 and batch_set[-1] == 256
+    budget, cap = 64 << 20, 10.0
+    plan = runner.plan(batch_set, budget, latency_cap_ms=cap)
+    assert plan is not None
+    bpl = plan.batch_per_layer
+    assert all(a <= b and b % a == 0 for a, b in zip(bpl, bpl[1:]))
+    for li, L in enumerate(layers):
+        assert bpl[li] * (L.K + L.M) * 4 + plan.ws_bytes[li] <= budget
+    assert abs(plan.dispatch_ms(bpl) / bpl[-1] - plan.ms_per_image) <= 1e-9 * plan.ms_per_image
+    assert plan.dispatch_ms(bpl) <= cap
+    n = 256
+    arrivals = wl.poisson_arrivals(n, 20000.0, wl.BASE_SEED + 5000)
+    X = wl.activations(5, n, K=layers[0].K)
+    Xd = torch.from_numpy(X).cuda()
+    outs, stats = scheduler.simulate(runner, plan, arrivals, [Xd[i] for i in range(n)], cap, clock="measured")
+    print({k: (round(v, 3) if isinstance(v, float) else v) for k, v in stats.items()}, "plan", bpl, end=" ")
+    assert stats["requests"] == n and stats["over_cap"] == 0 and stats["max_ms"] <= cap
+    assert 1 <= stats["mean_batch"] <= bpl[-1]
+    Y = torch.stack(outs, 0).cpu().numpy()
+    sample = np.sort(np.random.default_rng(5).choice(n, size=12, replace=False))
+    ref = oracle_stack(dense, X[sample])
+    assert np.abs(Y[sample] - ref).max() / np.abs(ref).max() <= 3e-5
+    for L in layers:
+        L.free()
+
+
 def test_alexnet_whole_network_with_per_layer_batches():
     """The thirteen layers of Table IV end to end on the device with per-layer batch
     sizes (small early, larger late, as in Table V), against the oracle's chain of

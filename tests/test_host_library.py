@@ -286,6 +286,31 @@ def test_planner_matches_oracle_dp(seed):
                 A = -(-(A + (plan[i] - plan[i - 1]) * inb[i]) // step) * step
 
 
+def test_scheduler_charges_a_dispatch_what_the_recurrence_says():
+    """The scheduler's cost of a dispatch with per-layer batch sizes is the Sec. V-C
+    recurrence for exactly those sizes (earlier layers repeated until the later
+    layer's batch is full): equal to the oracle's optimum when the sizes are the
+    plan's, and to a hand count on a small case."""
+    from paper_1711_00244_amd import scheduler
+    rng = np.random.default_rng(3)
+    bs = [1, 2, 4, 8, 16]
+    for _ in range(10):
+        f = int(rng.integers(1, 5))
+        time_ms = np.sort(rng.random((f, len(bs))) + 0.1, axis=1)
+        inb, outb, ws = [int(x) for x in rng.integers(100, 5000, f)], [int(x) for x in rng.integers(100, 5000, f)], [0] * f
+        tot = int(rng.integers(20000, 200000))
+        want, plan = odp.plan_batches(time_ms.tolist(), bs, inb, outb, ws, tot, 1024)
+        if plan is None:
+            continue
+        p = scheduler.Plan(list(plan), want, bs, time_ms, ws, tot)
+        assert p.dispatch_ms(plan) / plan[-1] == pytest.approx(want, rel=1e-12)
+    t = np.array([[1.0, 1.5, 2.0], [10.0, 11.0, 12.0], [100.0, 101.0, 102.0]])
+    p = scheduler.Plan([1, 2, 4], 0.0, [1, 2, 4], t, [0, 0, 0], 0)
+    assert p.dispatch_ms([1, 2, 4]) == 102.0 + 2 * (11.0 + 2 * 1.0)
+    assert p.dispatch_ms([4, 4, 4]) == 2.0 + 12.0 + 102.0
+    assert p.bpl_for(2) == [1, 2, 2] and p.bpl_for(4) == [1, 2, 4] and p.bpl_for(1) == [1, 1, 1]
+
+
 def test_planner_rejects_bad_arguments():
     with pytest.raises(cl.CLError):
         cl.plan_batches([[1.0, 2.0]], [2, 1], [1], [1], [0], 100, 1)
