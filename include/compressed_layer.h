@@ -61,7 +61,7 @@ enum {
                           /*   of at most 128 x 128, else CL_EUNSUPPORTED            */
     CL_PATH_MFMA_BF16 = 3 /* the same on the bf16 matrix cores: weights and activations */
                           /*   split into two bf16 terms each, three products per    */
-                          /*   fp32 product, fp32 accumulation; error below 3 * 2^-18 */
+                          /*   fp32 product, fp32 accumulation; error below 3 * 2^-16 */
                           /*   of sum |w x| per output; never picked by CL_PATH_AUTO  */
 };
 

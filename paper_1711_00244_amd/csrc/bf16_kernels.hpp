@@ -7,10 +7,10 @@
 // dense tiles on the bf16 matrix cores, three products per fp32 product
 // ------------------------------------------------------------------------- //
 // A weight w and an activation x are each split into two bf16 terms, w = wh + wl,
-// x = xh + xl (round to nearest even; the residual of each is below 2^-18 of the value),
+// x = xh + xl (round to nearest even; the residual of each is below 2^-16 of the value),
 // and w x is taken as xh wh + xh wl + xl wh with fp32 accumulation in
 // v_mfma_f32_32x32x16_bf16: three multiplies at sixteen times the fp32 rate.  What is
-// dropped (xl wl and the two residuals) is below 3 * 2^-18 of |w x|.
+// dropped (xl wl and the two residuals) is below 3 * 2^-16 of |w x|.
 __device__ __forceinline__ uint32_t bf16_bits(float f)
 {
     uint32_t u = __float_as_uint(f);

@@ -59,7 +59,7 @@ def errors(Y, ref: Ref, relu: bool):
 
 def assert_close(Y, ref: Ref, relu: bool, tol=TOL, product_rel=0.0, what=None):
     """Both gates.  product_rel is the relative error each product may carry on top of
-    the fp32 accumulation (0 for exact fp32 products; 3 * 2^-18 for the three-term
+    the fp32 accumulation (0 for exact fp32 products; 3 * 2^-16 for the three-term
     bf16 split), in which case the normwise gate widens by the same amount times the
     condition sum."""
     assert Y.shape == ref.pre.shape, (Y.shape, ref.pre.shape, what)

@@ -12,7 +12,7 @@ from paper_1711_00244_amd import binding, workloads as wl
 from gates import TOL, assert_close, conv_ref, errors, fc_ref
 
 pytestmark = pytest.mark.gpu
-BF16X3 = 3.0 * 2.0 ** -18          # relative error of a product on the three-term bf16 split
+BF16X3 = 3.0 * 2.0 ** -16          # relative error of a product on the three-term bf16 split
 
 
 def torch_cuda():
@@ -130,7 +130,7 @@ def test_fc_forward_mfma_tile_widths(bh, bw, B):
 
 
 def assert_close_bf16(Y, ref, relu):
-    """The three-product bf16 split: each product w x is off by at most 3 * 2^-18 |w x|
+    """The three-product bf16 split: each product w x is off by at most 3 * 2^-16 |w x|
     (the dropped lo x lo term and the two split residuals) on top of the fp32
     accumulation - per component, and relative to the largest output it stays far
     inside the 2e-3 allowed for bf16 tiles."""
