@@ -231,6 +231,22 @@ int32_t cl_compressed_fc_forward(const cl_layer *layer, const float *d_X, const 
                                  float *d_Y, int32_t batch, int32_t relu, int32_t path,
                                  void *d_workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or pass a workspace - code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc: the same call as
+ * cl_compressed_fc_forward (same arguments, kernels, paths and results) with the scratch
+ * in an array that is part of the library's device image, CL_STATIC_SCRATCH_BYTES per
+ * GPU, held by every GPU the library runs on until the process ends.  The call allocates
+ * and frees nothing; the array's address on a device is looked up once, when the first
+ * layer is uploaded to that device.  A (layer, batch, path) whose
+ * cl_fc_workspace_bytes() exceeds CL_STATIC_SCRATCH_BYTES is refused with
+ * CL_EUNSUPPORTED and nothing is launched.  No kernel reads the scratch before writing
+ * it, so nothing has to be cleared between calls; but every call on a GPU uses that
+ * GPU's one array: calls that may overlap on one GPU (different streams, or host
+ * threads) race and must be serialised by the caller. */
+#define CL_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t cl_compressed_fc_forward_static(const cl_layer *layer, const float *d_X, const float *d_bias_or_null,
+                                        float *d_Y, int32_t batch, int32_t relu, int32_t path, void *stream);
+
 /* A stack of fully connected layers, layer i + 1 reading what layer i writes
  * (Eq. 1 applied layer after layer; the FC6-8 stack of Table IV): the same kernels
  * as cl_compressed_fc_forward, layer by layer on the given stream, with the

@@ -17,11 +17,12 @@ from . import build as _build
 CL_OK, CL_EINVAL, CL_ENOMEM, CL_ECORRUPT, CL_EUNSUPPORTED, CL_EHIP = 0, -1, -2, -3, -4, -5
 PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32, PATH_MFMA_BF16 = 0, 1, 2, 3
 CHUNK_BITS, RECORD_BITS, RECORDS_PER_CHUNK, MAX_RECORD_ENTRIES, MAX_CODE_LEN = 4096, 64, 64, 15, 12
+STATIC_SCRATCH_BYTES = 16 << 20        # CL_STATIC_SCRATCH_BYTES
 
 EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
-    "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_fc_stack_workspace_bytes",
+    "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_compressed_fc_forward_static", "cl_fc_stack_workspace_bytes",
     "cl_compressed_fc_stack_forward", "cl_conv_workspace_bytes", "cl_conv_workspace_bytes_min",
     "cl_compressed_conv_forward", "cl_plan_batches", "cl_maxpool_forward", "cl_lrn_forward",
     "cl_set_kernel_timing", "cl_last_kernel_ms",
@@ -94,6 +95,7 @@ def lib():
     L.cl_layer_deserialize.argtypes = [p, sz, C.POINTER(p)]
     L.cl_decode_layer.argtypes = [p, p, p, p, p, p]
     L.cl_fc_workspace_bytes.argtypes = [p, i32, i32, C.POINTER(sz)]
+    L.cl_compressed_fc_forward_static.argtypes = [p, p, p, p, i32, i32, i32, p]
     L.cl_compressed_fc_forward.argtypes = [p, p, p, p, i32, i32, i32, p, sz, p]
     L.cl_fc_stack_workspace_bytes.argtypes = [p, i32, i32, i32, C.POINTER(sz)]
     L.cl_compressed_fc_stack_forward.argtypes = [p, i32, p, p, p, i32, i32, i32, i32, p, sz, p]
@@ -290,6 +292,20 @@ def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO
     _check(lib().cl_compressed_fc_forward(layer.handle, _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B, int(relu), path,
                                           _dev_ptr(workspace), wbytes, _stream()))
     return Y
+
+
+def compressed_fc_forward_static(layer: Layer, X, out, bias=None, relu=False, path=PATH_AUTO):
+    """cl_compressed_fc_forward_static: scratch in the library's static device array; the
+    caller brings the output, nothing is allocated here or in the library."""
+    B = X.shape[0] if X.dim() == 2 else -1
+    _want(X, (B, layer.K), "X")
+    _want(bias, (layer.M,), "bias")
+    if out is None:
+        raise ValueError("the non-allocating call needs the caller's output tensor")
+    _want(out, (B, layer.M), "out")
+    _check(lib().cl_compressed_fc_forward_static(layer.handle, _dev_ptr(X), _dev_ptr(bias), _dev_ptr(out), B, int(relu), path,
+                                                 _stream()))
+    return out
 
 
 def _handles(layers):

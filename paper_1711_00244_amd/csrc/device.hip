@@ -153,6 +153,31 @@ static void timing_end(hipStream_t st, int launches)
     g_timing.valid = hipEventRecord(g_timing.b, st) == hipSuccess;
 }
 
+// Scratch for the entry point that may not allocate: one array per GPU, placed by the
+// loader, held until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress; kernels get the address that call returns for the current
+// device.
+static __device__ __align__(256) unsigned char g_static_scratch[CL_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxScratchDevices = 64;
+static std::atomic<void *> g_static_scratch_ptr[kMaxScratchDevices];
+
+// Address of the current device's copy of the scratch array (looked up once per device).
+static int32_t static_scratch(void **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxScratchDevices) return fail(CL_EUNSUPPORTED, "device %d: static scratch is tracked for devices 0..%d", dev, kMaxScratchDevices - 1);
+    void *p = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+        if (!p) return fail(CL_EHIP, "hipGetSymbolAddress gave a null address");
+        g_static_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return CL_OK;
+}
+
 void release_device(cl_layer *L)
 {
     if (L->dev.blob) {
@@ -183,6 +208,14 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
     int dev = -1;
     HIP_TRY(hipGetDevice(&dev));
     if (L->dev.blob && L->dev.device == dev) return CL_OK;
+    {
+        // set-up time: find this device's copy of the static scratch array now, so that the
+        // non-allocating entry point has nothing left to look up (a device beyond the
+        // tracked range is refused there, not here)
+        void *scratch = nullptr;
+        if (dev >= 0 && dev < kMaxScratchDevices)
+            if (int32_t rc = static_scratch(&scratch)) return rc;
+    }
     release_device(L);
     struct Sec { const void *src; size_t bytes; size_t off; };
     // decode tables + codebook, laid out as in LDS
@@ -580,9 +613,8 @@ static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLi
     return run_mfma_layer(L, D, P, d_X, ws, (float *)(ws + P.xt_bytes), d_bias, d_Y, 0, batch, relu, st);
 }
 
-extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X, const float *d_bias,
-                                            float *d_Y, int32_t batch, int32_t relu, int32_t path,
-                                            void *d_workspace, size_t workspace_bytes, void *stream)
+static int32_t fc_forward_checked(const cl_layer *L, const float *d_X, const float *d_bias, float *d_Y, int32_t batch,
+                                  int32_t relu, int32_t path, void *d_workspace, size_t workspace_bytes, void *stream)
 {
     if (int32_t rc = require_device(L)) return rc;
     if (!d_X || !d_Y) return fail(CL_EINVAL, "null activation pointer");
@@ -602,6 +634,28 @@ extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X,
         rc = forward_sparse(L, D, dl, d_X, d_bias, d_Y, batch, relu, (float *)d_workspace, (hipStream_t)stream);
     if (rc == CL_OK) clear_error();
     return rc;
+}
+
+extern "C" int32_t cl_compressed_fc_forward(const cl_layer *L, const float *d_X, const float *d_bias,
+                                            float *d_Y, int32_t batch, int32_t relu, int32_t path,
+                                            void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    return fc_forward_checked(L, d_X, d_bias, d_Y, batch, relu, path, d_workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t cl_compressed_fc_forward_static(const cl_layer *L, const float *d_X, const float *d_bias,
+                                                   float *d_Y, int32_t batch, int32_t relu, int32_t path, void *stream)
+{
+    if (int32_t rc = require_device(L)) return rc;
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    size_t need = 0;
+    if (int32_t rc = cl_fc_workspace_bytes(L, batch, path, &need)) return rc;
+    if (need > (size_t)CL_STATIC_SCRATCH_BYTES)
+        return fail(CL_EUNSUPPORTED, "this call needs %zu bytes of scratch, the static scratch area holds %zu: use cl_compressed_fc_forward with a workspace",
+                    need, (size_t)CL_STATIC_SCRATCH_BYTES);
+    void *scratch = nullptr;
+    if (int32_t rc = static_scratch(&scratch)) return rc;
+    return fc_forward_checked(L, d_X, d_bias, d_Y, batch, relu, path, scratch, (size_t)CL_STATIC_SCRATCH_BYTES, stream);
 }
 
 // ------------------------------------------------------------------------- //
