@@ -59,10 +59,16 @@ enum {
     CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
     CL_PATH_MFMA_F32 = 2, /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
                           /*   of at most 128 x 128, else CL_EUNSUPPORTED            */
-    CL_PATH_MFMA_BF16 = 3 /* the same on the bf16 matrix cores: weights and activations */
+    CL_PATH_MFMA_BF16 = 3,/* the same on the bf16 matrix cores: weights and activations */
                           /*   split into two bf16 terms each, three products per    */
                           /*   fp32 product, fp32 accumulation; error below 3 * 2^-16 */
                           /*   of sum |w x| per output; never picked by CL_PATH_AUTO  */
+    CL_PATH_SPARSE_WIDE = 4 /* large batches on the vector ALUs: the sparse product of  */
+                          /*   Algorithm 2 step 12 as written, one fp32 multiply-add   */
+                          /*   per surviving weight and image, images across the lanes; */
+                          /*   blocks of at most 128 x 128 whose surviving weights fit  */
+                          /*   the kernel's LDS list, else CL_EUNSUPPORTED; run-to-run  */
+                          /*   identical                                               */
 };
 
 /* How a weight matrix is compressed.
@@ -161,6 +167,9 @@ typedef struct {
     const uint64_t *records;       /* n_records                                      */
     int64_t n_blocks, n_chunks, n_records, n_entries;
     int32_t n_panels;
+    const uint32_t *chunk_nz;      /* n_chunks + 1: entries that are not padding in all */
+                                   /*   chunks before this one (derived at load time)  */
+    int64_t max_block_nnz;         /* most surviving weights in one block              */
 } cl_host_view;
 
 const char *cl_last_error(void);

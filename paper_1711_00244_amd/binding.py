@@ -15,7 +15,7 @@ import numpy as np
 from . import build as _build
 
 CL_OK, CL_EINVAL, CL_ENOMEM, CL_ECORRUPT, CL_EUNSUPPORTED, CL_EHIP = 0, -1, -2, -3, -4, -5
-PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32, PATH_MFMA_BF16 = 0, 1, 2, 3
+PATH_AUTO, PATH_SPARSE, PATH_MFMA_F32, PATH_MFMA_BF16, PATH_SPARSE_WIDE = 0, 1, 2, 3, 4
 CHUNK_BITS, RECORD_BITS, RECORDS_PER_CHUNK, MAX_RECORD_ENTRIES, MAX_CODE_LEN = 4096, 64, 64, 15, 12
 STATIC_SCRATCH_BYTES = 16 << 20        # CL_STATIC_SCRATCH_BYTES
 
@@ -49,7 +49,7 @@ class HostView(C.Structure):
                 ("block_ptr", C.POINTER(C.c_uint32)), ("panel_chunk", C.POINTER(C.c_uint32)),
                 ("chunk_meta", C.POINTER(ChunkMeta)), ("records", C.POINTER(C.c_uint64)),
                 ("n_blocks", C.c_int64), ("n_chunks", C.c_int64), ("n_records", C.c_int64), ("n_entries", C.c_int64),
-                ("n_panels", C.c_int32)]
+                ("n_panels", C.c_int32), ("chunk_nz", C.POINTER(C.c_uint32)), ("max_block_nnz", C.c_int64)]
 
 
 class ConvDesc(C.Structure):
@@ -206,6 +206,7 @@ class Layer:
                     idx_code=arr(v.idx_code, nidx, np.uint32), block_ptr=arr(v.block_ptr, int(v.n_blocks) + 1, np.uint32),
                     panel_chunk=arr(v.panel_chunk, int(v.n_panels) + 1, np.uint32), chunk_meta=meta,
                     records=arr(v.records, int(v.n_records), np.uint64),
+                    chunk_nz=arr(v.chunk_nz, nc + 1, np.uint32), max_block_nnz=int(v.max_block_nnz),
                     n_blocks=int(v.n_blocks), n_chunks=nc, n_records=int(v.n_records), n_entries=int(v.n_entries),
                     n_panels=int(v.n_panels))
 

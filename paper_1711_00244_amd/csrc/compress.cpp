@@ -129,8 +129,10 @@ int32_t finalize_and_validate(cl_layer *L)
     int64_t cur_blk = -1;
     uint64_t possum = 0;
     int panel = 0;
+    L->chunk_nz.assign((size_t)L->n_chunks + 1, 0u);
     for (int64_t c = 0; c < L->n_chunks; ++c) {
         const cl_chunk_meta &m = L->meta[c];
+        L->chunk_nz[c] = (uint32_t)nnz;
         const uint64_t r0 = m.rec_off, r1 = L->meta[c + 1].rec_off;
         if (r0 != next_rec || r1 <= r0 || r1 - r0 > (uint64_t)kLanes || r1 > (uint64_t)L->n_records)
             return fail(CL_ECORRUPT, "chunk %lld: bad record range", (long long)c);
@@ -181,6 +183,7 @@ int32_t finalize_and_validate(cl_layer *L)
         next_rec = r1;
     }
     if (next_entry != (uint64_t)L->entries) return fail(CL_ECORRUPT, "records do not add up to the entry count");
+    L->chunk_nz[L->n_chunks] = (uint32_t)nnz;
     // every non-empty block must have been covered in full
     for (int64_t c = 0; c < L->n_chunks; ++c) {
         const cl_chunk_meta &m = L->meta[c];
@@ -193,6 +196,9 @@ int32_t finalize_and_validate(cl_layer *L)
     for (int64_t c = L->n_chunks - 1; c >= 0; --c) L->block_chunk[L->meta[c].blk] = (uint32_t)c;
     for (int64_t b = g.n_blocks - 1; b >= 0; --b)
         if (L->block_ptr[b] == L->block_ptr[b + 1]) L->block_chunk[b] = L->block_chunk[b + 1];
+    L->max_block_nnz = 0;
+    for (int64_t b = 0; b < g.n_blocks; ++b)
+        L->max_block_nnz = std::max<int64_t>(L->max_block_nnz, (int64_t)L->chunk_nz[L->block_chunk[b + 1]] - L->chunk_nz[L->block_chunk[b]]);
     L->nnz = nnz;
     L->padding = L->entries - nnz;
     L->val_bits = vbits;
@@ -393,6 +399,8 @@ extern "C" int32_t cl_layer_host_view(const cl_layer *L, cl_host_view *v)
     v->block_ptr = L->block_ptr.data();
     v->panel_chunk = L->panel_chunk.data();
     v->chunk_meta = L->meta.data();
+    v->chunk_nz = L->chunk_nz.data();
+    v->max_block_nnz = L->max_block_nnz;
     v->records = L->records.data();
     v->n_blocks = L->n_blocks;
     v->n_chunks = L->n_chunks;

@@ -15,7 +15,7 @@
 //
 // One translation unit: this file holds the host side (device image of a layer, launch
 // shapes, the entry points) and includes the kernels - decode.hpp (wavefront primitives,
-// decoding and placement passes), sparse_kernels.hpp, mfma_kernels.hpp, bf16_kernels.hpp,
+// decoding and placement passes), sparse_kernels.hpp, mfma_kernels.hpp, wide_kernels.hpp, bf16_kernels.hpp,
 // conv_kernels.hpp, finish_kernels.hpp, layer_kernels.hpp.
 #include <hip/hip_runtime.h>
 #include <type_traits>
@@ -56,6 +56,7 @@ struct LayerDev {
     const cl_chunk_meta *meta;
     const uint32_t *panel_chunk;
     const uint32_t *block_chunk;
+    const uint32_t *chunk_nz;
     const float *codebook;
     const lut_t *val_lut;
     const lut_t *idx_lut;
@@ -80,6 +81,7 @@ static LayerDev make_dev(const cl_layer *L)
     d.meta = L->dev.meta;
     d.panel_chunk = L->dev.panel_chunk;
     d.block_chunk = L->dev.block_chunk;
+    d.chunk_nz = L->dev.chunk_nz;
     d.codebook = L->dev.codebook;
     d.val_lut = L->dev.val_lut;
     d.idx_lut = L->dev.idx_lut;
@@ -100,6 +102,7 @@ static LayerDev make_dev(const cl_layer *L)
 #include "decode.hpp"
 #include "sparse_kernels.hpp"
 #include "mfma_kernels.hpp"
+#include "wide_kernels.hpp"
 #include "bf16_kernels.hpp"
 #include "conv_kernels.hpp"
 #include "finish_kernels.hpp"
@@ -227,13 +230,14 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
         std::memcpy(image.data() + vb, L->idx_lut.data(), ib);
         std::memcpy(image.data() + ((vb + ib + 15) & ~(size_t)15), L->codebook.data(), L->codebook.size() * 4);
     }
-    Sec secs[6] = {
+    Sec secs[7] = {
         {L->records.data(), L->records.size() * 8, 0},
         {L->meta.data(), L->meta.size() * sizeof(cl_chunk_meta), 0},
         {L->block_ptr.data(), L->block_ptr.size() * 4, 0},
         {L->panel_chunk.data(), L->panel_chunk.size() * 4, 0},
         {image.data(), image.size(), 0},
         {L->block_chunk.data(), L->block_chunk.size() * 4, 0},
+        {L->chunk_nz.data(), L->chunk_nz.size() * 4, 0},
     };
     size_t total = 0;
     for (auto &s : secs) { s.off = total; total += (s.bytes + 255) / 256 * 256; }
@@ -255,6 +259,7 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
     L->dev.block_ptr = (const uint32_t *)(blob + secs[2].off);
     L->dev.panel_chunk = (const uint32_t *)(blob + secs[3].off);
     L->dev.block_chunk = (const uint32_t *)(blob + secs[5].off);
+    L->dev.chunk_nz = (const uint32_t *)(blob + secs[6].off);
     L->dev.val_lut = (const lut_t *)(blob + secs[4].off);
     L->dev.idx_lut = L->dev.val_lut + L->val_lut.size();
     L->dev.codebook = (const float *)(blob + secs[4].off + ((L->val_lut.size() + L->idx_lut.size()) * sizeof(lut_t) + 15) / 16 * 16);
@@ -484,6 +489,65 @@ int32_t launch_mfma(const cl_layer *L, const LayerDev &D, bool bf16, int nq, int
     return fail(CL_EINVAL, "internal: no dense-tile kernel for %d accumulators", nq);
 }
 
+// Launch shape of the wide sparse path (large batches on the vector ALUs).
+struct WidePlan {
+    int ipl = 4;             // images per lane: the image tile is 64 * ipl images
+    int Bp = 0;              // batch rounded up to whole image tiles
+    int splits = 1;          // workgroups sharing the blocks of one block row
+    int cap = 0;             // entries the kernel's list of one block holds
+    size_t lds = 0;
+    size_t xt_bytes = 0, part_bytes = 0;
+};
+
+int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan &P)
+{
+    if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the wide sparse path needs blocks of at most %d x %d", kTile, kTile);
+    if (batch > kMaxTileColumns) return fail(CL_EUNSUPPORTED, "the wide sparse path takes at most %d images per call", kMaxTileColumns);
+    P.cap = (int)((std::max<int64_t>(L->max_block_nnz, 1) + 63) / 64 * 64);
+    const size_t tables = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
+    // the widest image tile the batch can use whose slabs leave room for the block's list
+    P.ipl = batch > 128 ? 4 : batch > 64 ? 2 : 1;
+    while (P.ipl > 1 && wide_lds_bytes(tables, P.cap, P.ipl) > dl.max_lds) P.ipl >>= 1;
+    const int tile = 64 * P.ipl;
+    P.Bp = (batch + tile - 1) / tile * tile;
+    P.lds = wide_lds_bytes(tables, P.cap, P.ipl);
+    if (P.lds > dl.max_lds)
+        return fail(CL_EUNSUPPORTED, "the wide sparse path keeps a block's %lld surviving weights in LDS: %zu bytes needed, %zu there",
+                    (long long)L->max_block_nnz, P.lds, dl.max_lds);
+    // Split of the block rows, from a small model of a launch (cycles per workgroup: a
+    // start, per block the decoding and the multiplies of its surviving weights - about
+    // 8 + 6.5 ipl cycles per weight on each of four SIMDs - and the partial tiles, written
+    // and read again, as on the dense-tile path; workgroups run in rounds of one per CU).
+    const int64_t tiles = (int64_t)L->n_panels * (P.Bp / tile);
+    const int cus = std::max(1, dl.cus);
+    const int64_t per_block = 2500 + (L->n_blocks ? L->nnz / L->n_blocks : 0) * (16 + 13 * P.ipl) / 8;
+    const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
+    int64_t best = -1;
+    for (int sp = 1; sp <= sp_max; ++sp) {
+        const int64_t rounds = (tiles * sp + cus - 1) / cus, blocks = (L->nbw + sp - 1) / sp;
+        const int64_t t = rounds * (15000 + blocks * per_block) + (int64_t)L->n_panels * sp * P.Bp * kTile * (int64_t)sizeof(float) * 3 / 4000;
+        if (best < 0 || t < best) {
+            best = t;
+            P.splits = sp;
+        }
+    }
+    P.xt_bytes = xt_bytes_for(L, P.Bp, false);
+    P.part_bytes = (size_t)L->n_panels * P.splits * kTile * P.Bp * sizeof(float);
+    return CL_OK;
+}
+
+template <int IPL>
+int32_t launch_wide_as(const LayerDev &D, int panels, const WidePlan &P, const float *xt, float *part, hipStream_t st)
+{
+    static LdsLimit seen;
+    if (int32_t rc = ensure_lds((const void *)fc_wide_kernel<IPL>, P.lds, seen)) return rc;
+    dim3 grid;
+    GRID_TRY(grid, (int64_t)panels * P.splits * (P.Bp / (64 * IPL)));
+    hipLaunchKernelGGL(fc_wide_kernel<IPL>, grid, dim3(kWideThreads), P.lds, st, D, xt, part, panels, P.splits, P.Bp, P.cap);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
 // CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images, the dense-tile path
 // above when the blocks fit a tile.  Measured on the AlexNet-shaped stack (fc6 / fc7 /
 // fc8, ms): sparse 0.037 / 0.024 / 0.019 at 4 images and 0.061 / 0.038 / 0.028 at 5-8
@@ -498,17 +562,24 @@ int resolve_path(const cl_layer *L, int batch, int path)
 
 bool is_mfma(int path) { return path == CL_PATH_MFMA_F32 || path == CL_PATH_MFMA_BF16; }
 
+// the paths that read the activations transposed and laid out block by block
+bool reads_xt(int path) { return is_mfma(path) || path == CL_PATH_SPARSE_WIDE; }
+
 }  // namespace
 
 extern "C" int32_t cl_fc_workspace_bytes(const cl_layer *L, int32_t batch, int32_t path, size_t *out)
 {
     if (!L || !out) return fail(CL_EINVAL, "null argument");
     if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
-    if (path < CL_PATH_AUTO || path > CL_PATH_MFMA_BF16) return fail(CL_EINVAL, "unknown path %d", path);
+    if (path < CL_PATH_AUTO || path > CL_PATH_SPARSE_WIDE) return fail(CL_EINVAL, "unknown path %d", path);
     DeviceLimits dl;
     if (int32_t rc = device_limits(dl)) return rc;
     const int chosen = resolve_path(L, batch, path);
-    if (is_mfma(chosen)) {
+    if (chosen == CL_PATH_SPARSE_WIDE) {
+        WidePlan P;
+        if (int32_t rc = plan_wide(L, batch, dl, P)) return rc;
+        *out = P.xt_bytes + P.part_bytes;
+    } else if (is_mfma(chosen)) {
         MfmaPlan P;
         if (int32_t rc = plan_mfma(L, batch, chosen == CL_PATH_MFMA_BF16, dl, P)) return rc;
         *out = P.xt_bytes + P.part_bytes;
@@ -605,6 +676,41 @@ static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPl
     return CL_OK;
 }
 
+// One layer on the wide sparse path with launch shape P; arguments as run_mfma_layer.
+static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePlan &P, const float *d_X, float *xt, float *part,
+                              const float *d_bias, float *d_Y, int next_bp, int batch, int relu, hipStream_t st)
+{
+    if (d_X) {
+        const int rows = L->nbw * kTile;
+        hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
+                           d_X, xt, batch, L->desc.K, P.Bp, L->desc.block_w, rows);
+        HIP_TRY(hipGetLastError());
+    }
+    timing_begin(st);
+    int32_t rc = CL_EINVAL;
+    switch (P.ipl) {
+    case 1: rc = launch_wide_as<1>(D, L->n_panels, P, xt, part, st); break;
+    case 2: rc = launch_wide_as<2>(D, L->n_panels, P, xt, part, st); break;
+    case 4: rc = launch_wide_as<4>(D, L->n_panels, P, xt, part, st); break;
+    }
+    if (rc) return rc;
+    timing_end(st, 1);
+    const int ncol = std::max(P.Bp, next_bp);
+    dim3 rgrid;
+    GRID_TRY(rgrid, (int64_t)L->n_panels * (kTile / kWideRedRows) * ((ncol + kWideRedImages - 1) / kWideRedImages));
+    hipLaunchKernelGGL(wide_reduce_kernel, rgrid, dim3(256), 0, st, D, part, d_bias, d_Y, batch, P.Bp, P.splits, relu, next_bp);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
+static int32_t forward_wide(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, const float *d_X, const float *d_bias,
+                            float *d_Y, int batch, int relu, char *ws, hipStream_t st)
+{
+    WidePlan P;
+    if (int32_t rc = plan_wide(L, batch, dl, P)) return rc;
+    return run_wide_layer(L, D, P, d_X, (float *)ws, (float *)(ws + P.xt_bytes), d_bias, d_Y, 0, batch, relu, st);
+}
+
 static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, bool bf16, const float *d_X,
                             const float *d_bias, float *d_Y, int batch, int relu, char *ws, hipStream_t st)
 {
@@ -628,7 +734,9 @@ static int32_t fc_forward_checked(const cl_layer *L, const float *d_X, const flo
     const LayerDev D = make_dev(L);
     int32_t rc;
     const int chosen = resolve_path(L, batch, path);
-    if (is_mfma(chosen))
+    if (chosen == CL_PATH_SPARSE_WIDE)
+        rc = forward_wide(L, D, dl, d_X, d_bias, d_Y, batch, relu, (char *)d_workspace, (hipStream_t)stream);
+    else if (is_mfma(chosen))
         rc = forward_mfma(L, D, dl, chosen == CL_PATH_MFMA_BF16, d_X, d_bias, d_Y, batch, relu, (char *)d_workspace, (hipStream_t)stream);
     else
         rc = forward_sparse(L, D, dl, d_X, d_bias, d_Y, batch, relu, (float *)d_workspace, (hipStream_t)stream);

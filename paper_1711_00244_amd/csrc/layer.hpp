@@ -31,6 +31,7 @@ struct DeviceImage {
     const uint32_t *block_ptr = nullptr;
     const uint32_t *panel_chunk = nullptr;
     const uint32_t *block_chunk = nullptr;
+    const uint32_t *chunk_nz = nullptr;
     const float *codebook = nullptr;
     const lut_t *val_lut = nullptr;
     const lut_t *idx_lut = nullptr;
@@ -50,6 +51,9 @@ struct cl_layer {
     std::vector<uint32_t> val_code, idx_code;       // codewords, bit j = j-th bit in tree-walk order
     std::vector<uint32_t> block_ptr, panel_chunk;
     std::vector<uint32_t> block_chunk;              // n_blocks + 1: first chunk of each block (derived)
+    std::vector<uint32_t> chunk_nz;                 // n_chunks + 1: surviving weights (entries that are not padding) in all
+                                                    //   chunks before this one (derived)
+    int64_t max_block_nnz = 0;                      // most surviving weights in one block
     std::vector<cl_chunk_meta> meta;                // n_chunks + 1
     std::vector<uint64_t> records;
     std::vector<cl::lut_t> val_lut, idx_lut;        // indexed by the next val_lut_bits / idx_lut_bits stream bits

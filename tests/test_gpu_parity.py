@@ -112,6 +112,56 @@ def test_fc_forward_mfma_path(M, K, d, r, k, B):
     assert rel_err(Ys, Ym.astype(np.float64)) <= 2 * TOL
 
 
+WIDE_CASES = [(200, 333, 128, 128, 0.09, 5, 4), (1000, 520, 128, 128, 0.25, 5, 4), (256, 1024, 128, 128, 0.09, 5, 4),
+              (128, 256, 128, 128, 0.0, 5, 4), (515, 700, 128, 128, 0.001, 5, 4), (384, 300, 128, 128, 0.37, 8, 8),
+              (300, 437, 64, 48, 0.12, 5, 4), (300, 437, 32, 128, 0.12, 5, 4), (300, 437, 128, 20, 0.3, 5, 4),
+              (130, 70, 16, 16, 0.3, 5, 4), (96, 363, 96, 100, 0.5, 8, 8)]
+
+
+@pytest.mark.parametrize("M,K,bh,bw,d,r,k", WIDE_CASES)
+@pytest.mark.parametrize("B", [5, 64, 100, 256, 300])
+def test_fc_forward_wide_path(M, K, bh, bw, d, r, k, B):
+    """Large batches on the vector ALUs (Algorithm 2 step 12 as a sparse product, the
+    images across the lanes): image tiles of 64, 128 and 256 images with ragged batches,
+    ragged last block row and column, blocks narrower than a slab (one phase per block),
+    wider (two), lower than a tile, empty and nearly empty layers (blocks without
+    entries, rows without entries), a block dense enough for several chunks per
+    decoding wavefront; both gates, and run-to-run identical."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(M + K * 3 + B)
+    W = rand_pruned(rng, M, K, d)
+    L, m, oW = check_decode(W, r, k, bh, bw)
+    X = np.maximum(rng.standard_normal((B, K)), 0).astype(np.float32)
+    bias = rng.standard_normal(M).astype(np.float32) * 0.1
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
+    for use_bias, relu in [(False, False), (True, True)]:
+        ref = fc_ref(oW, X, bias if use_bias else None)
+        Y = cl.compressed_fc_forward(L, Xd, bd if use_bias else None, relu=relu, path=cl.PATH_SPARSE_WIDE)
+        torch.cuda.synchronize()
+        assert_close(Y.cpu().numpy(), ref, relu)
+        assert torch.equal(Y, cl.compressed_fc_forward(L, Xd, bd if use_bias else None, relu=relu, path=cl.PATH_SPARSE_WIDE))
+    L.free()
+
+
+def test_wide_path_full_blocks_and_big_blocks():
+    """A completely dense layer (16 384 entries per block: the kernel falls back to the
+    image tile whose slabs leave room for the block's list) against the oracle, and
+    blocks above 128 x 128 refused with nothing launched."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(9)
+    W = rand_pruned(rng, 200, 300, 1.0)
+    L, m, oW = check_decode(W, 5, 4, 128, 128)
+    X = np.maximum(rng.standard_normal((256, 300)), 0).astype(np.float32)
+    Y = cl.compressed_fc_forward(L, torch.from_numpy(X).cuda(), relu=True, path=cl.PATH_SPARSE_WIDE)
+    assert_close(Y.cpu().numpy(), fc_ref(oW, X), True)
+    L.free()
+    L = cl.compress_layer(rand_pruned(rng, 256, 256, 0.1), 5, 4, 256, 256, upload=True)
+    with pytest.raises(cl.CLError) as e:
+        cl.compressed_fc_forward(L, torch.zeros((64, 256), device="cuda"), path=cl.PATH_SPARSE_WIDE)
+    assert e.value.code == binding.CL_EUNSUPPORTED
+    L.free()
+
+
 @pytest.mark.parametrize("bh,bw", [(128, 128), (64, 48), (32, 128), (128, 20)])
 @pytest.mark.parametrize("B", [5, 33, 70, 129, 300])
 def test_fc_forward_mfma_tile_widths(bh, bw, B):
@@ -171,7 +221,7 @@ def test_conv_forward_bf16_path(li):
     assert_close_bf16(Y, conv_ref(oW, X, g), True)
 
 
-CANCELLATION_PATHS = [cl.PATH_SPARSE, cl.PATH_MFMA_F32]
+CANCELLATION_PATHS = [cl.PATH_SPARSE, cl.PATH_MFMA_F32, cl.PATH_SPARSE_WIDE]
 
 
 @pytest.mark.parametrize("path", CANCELLATION_PATHS)
@@ -480,7 +530,7 @@ def test_random_layers_all_paths(seed):
             bias = rng.standard_normal(M).astype(np.float32) * 0.1
             ref = fc_ref(oW, X, bias)
             Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
-            for path in (cl.PATH_AUTO, cl.PATH_SPARSE, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16):
+            for path in (cl.PATH_AUTO, cl.PATH_SPARSE, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16, cl.PATH_SPARSE_WIDE):
                 if path == cl.PATH_SPARSE and B > 64:
                     continue
                 Y = cl.compressed_fc_forward(L, Xd, bd, relu=True, path=path)

@@ -108,6 +108,12 @@ def test_oracle_decodes_library_streams(M, K, bh, bw, d, r, k):
     if val.size > 1000:
         assert st["val_bits"] <= 1.01 * vbits + 64 and st["idx_bits"] <= 1.01 * cbits + 64
     assert max(st["val_max_len"], st["idx_max_len"]) <= binding.MAX_CODE_LEN
+    # the derived table of entries that are not padding before each chunk, and the fullest block,
+    # from the oracle's own entries
+    before = np.concatenate([[0], np.cumsum(m.extra["val"] != 0)])
+    assert np.array_equal(hv["chunk_nz"], before[hv["chunk_meta"]["sym_off"]])
+    per_block = before[m.extra["block_ptr"][1:]] - before[m.extra["block_ptr"][:-1]]
+    assert hv["max_block_nnz"] == (int(per_block.max()) if per_block.size else 0)
     # rebuilt dense matrix from the library's entries equals the oracle's
     Wd = oracle.reconstruct(val, idx, bp, hv["codebook"], M, K, min(bh, M), min(bw, K), k)
     assert np.array_equal(Wd, oracle.dense_weights(m))
