@@ -54,8 +54,12 @@ enum {
 
 /* Kernel selection for the forward entry points. */
 enum {
-    CL_PATH_AUTO = 0,     /* CL_PATH_SPARSE for up to 4 images, CL_PATH_MFMA_F32 above */
-                          /*   when the blocks fit a tile (else CL_PATH_SPARSE)       */
+    CL_PATH_AUTO = 0,     /* CL_PATH_SPARSE for up to 4 images and for blocks above      */
+                          /*   128 x 128; else whichever of CL_PATH_MFMA_F32 and        */
+                          /*   CL_PATH_SPARSE_WIDE the library's launch models price    */
+                          /*   lower for this layer and batch (the dense tile multiplies */
+                          /*   every zero of a block: at 9 % density the sparse product  */
+                          /*   wins from about 200 images on, at 25 % it does not)       */
     CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
     CL_PATH_MFMA_F32 = 2, /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
                           /*   of at most 128 x 128, else CL_EUNSUPPORTED            */

@@ -359,7 +359,7 @@ bool mfma_capable(const cl_layer *L) { return L->desc.block_h <= kTile && L->des
 // the gathered convolution, to sweeps over the splits of the AlexNet and VGG-16 layers
 // at 2 to 128 images (0.2 % from the fastest on average, 5 % at worst).
 void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, int &nq, int &np, int &splits, bool gathered = false,
-                bool direct = false)
+                bool direct = false, int64_t *cost = nullptr)
 {
     cus = std::max(1, cus);
     nq = 0;
@@ -389,6 +389,7 @@ void mfma_shape(const cl_layer *L, int panels, int ncols, int cus, bool bf16, in
             }
         }
     }
+    if (cost) *cost = best;
 }
 
 size_t mfma_lds_bytes(const cl_layer *L, bool bf16)
@@ -495,6 +496,7 @@ struct WidePlan {
     int Bp = 0;              // batch rounded up to whole image tiles
     int splits = 1;          // workgroups sharing the blocks of one block row
     int cap = 0;             // entries the kernel's list of one block holds
+    int64_t cost = 0;        // modelled cycles of the launch (same units as mfma_shape's)
     size_t lds = 0;
     size_t xt_bytes = 0, part_bytes = 0;
 };
@@ -515,12 +517,13 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
         return fail(CL_EUNSUPPORTED, "the wide sparse path keeps a block's %lld surviving weights in LDS: %zu bytes needed, %zu there",
                     (long long)L->max_block_nnz, P.lds, dl.max_lds);
     // Split of the block rows, from a small model of a launch (cycles per workgroup: a
-    // start, per block the decoding and the multiplies of its surviving weights - about
-    // 8 + 6.5 ipl cycles per weight on each of four SIMDs - and the partial tiles, written
-    // and read again, as on the dense-tile path; workgroups run in rounds of one per CU).
+    // start; per block 13 + 1.2 ipl cycles per surviving weight - measured on the AlexNet-
+    // shaped layers at 64, 128 and 256 images: 14.4, 16 and 17.8; and the partial tiles,
+    // written and read again, as on the dense-tile path; workgroups run in rounds of one
+    // per CU).
     const int64_t tiles = (int64_t)L->n_panels * (P.Bp / tile);
     const int cus = std::max(1, dl.cus);
-    const int64_t per_block = 2500 + (L->n_blocks ? L->nnz / L->n_blocks : 0) * (16 + 13 * P.ipl) / 8;
+    const int64_t per_block = (L->n_blocks ? L->nnz / L->n_blocks : 0) * (53 + 5 * P.ipl) / 4;
     const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
     int64_t best = -1;
     for (int sp = 1; sp <= sp_max; ++sp) {
@@ -531,6 +534,7 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
             P.splits = sp;
         }
     }
+    P.cost = best;
     P.xt_bytes = xt_bytes_for(L, P.Bp, false);
     P.part_bytes = (size_t)L->n_panels * P.splits * kTile * P.Bp * sizeof(float);
     return CL_OK;
@@ -548,16 +552,30 @@ int32_t launch_wide_as(const LayerDev &D, int panels, const WidePlan &P, const f
     return CL_OK;
 }
 
-// CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images, the dense-tile path
-// above when the blocks fit a tile.  Measured on the AlexNet-shaped stack (fc6 / fc7 /
-// fc8, ms): sparse 0.037 / 0.024 / 0.019 at 4 images and 0.061 / 0.038 / 0.028 at 5-8
-// (its batch tile is a power of two); dense tiles of 32 images 0.048 / 0.028 / 0.021.
+// CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images; above, when the blocks
+// fit a tile, whichever of the dense-tile path and the wide sparse path the two launch
+// models price lower (same units, both fitted to measured launches).  Measured on the
+// AlexNet-shaped stack (fc6 / fc7 / fc8, ms): sparse 0.037 / 0.024 / 0.019 at 4 images
+// and 0.061 / 0.038 / 0.028 at 5-8 (its batch tile is a power of two); dense tiles of 32
+// images 0.048 / 0.028 / 0.021; at 256 images dense tiles 0.176 / 0.095 / 0.043, wide
+// sparse 0.135 / 0.077 / 0.060 - the dense tile multiplies eleven times the necessary
+// products at a 9 % density but four at 25 %, and at 128 images its 0.105 beats 0.118.
 constexpr int kAutoSparseBatch = 4;
 
-int resolve_path(const cl_layer *L, int batch, int path)
+int resolve_path(const cl_layer *L, int batch, int path, const DeviceLimits &dl)
 {
     if (path != CL_PATH_AUTO) return path;
-    return (batch > kAutoSparseBatch && mfma_capable(L)) ? CL_PATH_MFMA_F32 : CL_PATH_SPARSE;
+    if (batch <= kAutoSparseBatch || !mfma_capable(L)) return CL_PATH_SPARSE;
+    if (batch > kMaxTileColumns) return CL_PATH_MFMA_F32;      // refused there with its message
+    WidePlan W;
+    if (plan_wide(L, batch, dl, W) != CL_OK) {
+        clear_error();
+        return CL_PATH_MFMA_F32;
+    }
+    int nq, np, splits;
+    int64_t dense = 0;
+    mfma_shape(L, L->n_panels, batch, dl.cus, false, nq, np, splits, false, false, &dense);
+    return W.cost < dense ? CL_PATH_SPARSE_WIDE : CL_PATH_MFMA_F32;
 }
 
 bool is_mfma(int path) { return path == CL_PATH_MFMA_F32 || path == CL_PATH_MFMA_BF16; }
@@ -574,7 +592,7 @@ extern "C" int32_t cl_fc_workspace_bytes(const cl_layer *L, int32_t batch, int32
     if (path < CL_PATH_AUTO || path > CL_PATH_SPARSE_WIDE) return fail(CL_EINVAL, "unknown path %d", path);
     DeviceLimits dl;
     if (int32_t rc = device_limits(dl)) return rc;
-    const int chosen = resolve_path(L, batch, path);
+    const int chosen = resolve_path(L, batch, path, dl);
     if (chosen == CL_PATH_SPARSE_WIDE) {
         WidePlan P;
         if (int32_t rc = plan_wide(L, batch, dl, P)) return rc;
@@ -733,7 +751,7 @@ static int32_t fc_forward_checked(const cl_layer *L, const float *d_X, const flo
     if (int32_t rc = device_limits(dl)) return rc;
     const LayerDev D = make_dev(L);
     int32_t rc;
-    const int chosen = resolve_path(L, batch, path);
+    const int chosen = resolve_path(L, batch, path, dl);
     if (chosen == CL_PATH_SPARSE_WIDE)
         rc = forward_wide(L, D, dl, d_X, d_bias, d_Y, batch, relu, (char *)d_workspace, (hipStream_t)stream);
     else if (is_mfma(chosen))
@@ -774,6 +792,7 @@ namespace {
 struct StackPlan {
     std::vector<int> path;            // per layer: the path it runs on
     std::vector<MfmaPlan> mfma;       // per layer on a dense-tile path
+    std::vector<WidePlan> wide;       // per layer on the wide sparse path
     std::vector<SparsePlan> sparse;   // per layer on the sparse path
     std::vector<char> xt_in;          // layer reads its transposed activations straight from the layer before
     size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0;
@@ -789,8 +808,9 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
 {
     if (!layers || n < 1) return fail(CL_EINVAL, "a stack needs at least one layer");
     if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
-    if (path < CL_PATH_AUTO || path > CL_PATH_MFMA_BF16) return fail(CL_EINVAL, "unknown path %d", path);
+    if (path < CL_PATH_AUTO || path > CL_PATH_SPARSE_WIDE) return fail(CL_EINVAL, "unknown path %d", path);
     P.path.assign(n, 0);
+    P.wide.assign(n, WidePlan{});
     P.mfma.assign(n, MfmaPlan{});
     P.sparse.assign(n, SparsePlan{});
     P.xt_in.assign(n, 0);
@@ -799,16 +819,21 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
         if (!L) return fail(CL_EINVAL, "layer %d is null", i);
         if (i > 0 && L->desc.K != layers[i - 1]->desc.M)
             return fail(CL_EINVAL, "layer %d takes %d inputs, layer %d gives %d outputs", i, L->desc.K, i - 1, layers[i - 1]->desc.M);
-        P.path[i] = resolve_path(L, batch, path);
-        if (is_mfma(P.path[i])) {
+        P.path[i] = resolve_path(L, batch, path, dl);
+        // the finishing kernel of the layer before can write this layer's transposed
+        // activations itself when their row order is the plain one (128-column blocks,
+        // no ragged last block): 2-3 % of a step on the AlexNet-shaped stack
+        const bool plain_rows = L->desc.block_w == kTile && L->desc.K % kTile == 0;
+        if (P.path[i] == CL_PATH_SPARSE_WIDE) {
+            if (int32_t rc = plan_wide(L, batch, dl, P.wide[i])) return rc;
+            P.xt_bytes = std::max(P.xt_bytes, P.wide[i].xt_bytes);
+            P.part_bytes = std::max(P.part_bytes, round256(P.wide[i].part_bytes));
+            P.xt_in[i] = i > 0 && reads_xt(P.path[i - 1]) && plain_rows;
+        } else if (is_mfma(P.path[i])) {
             if (int32_t rc = plan_mfma(L, batch, P.path[i] == CL_PATH_MFMA_BF16, dl, P.mfma[i])) return rc;
             P.xt_bytes = std::max(P.xt_bytes, P.mfma[i].xt_bytes);
             P.part_bytes = std::max(P.part_bytes, round256(P.mfma[i].part_bytes));
-            // the finishing kernel of the layer before can write this layer's transposed
-            // activations itself when their row order is the plain one (128-column blocks,
-            // no ragged last block): 2-3 % of a step on the AlexNet-shaped stack
-            P.xt_in[i] = i > 0 && is_mfma(P.path[i - 1]) && P.path[i] == CL_PATH_MFMA_F32 && L->desc.block_w == kTile &&
-                         L->desc.K % kTile == 0;
+            P.xt_in[i] = i > 0 && reads_xt(P.path[i - 1]) && P.path[i] == CL_PATH_MFMA_F32 && plain_rows;
         } else {
             if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P.sparse[i])) return rc;
             P.part_bytes = std::max(P.part_bytes, round256(P.sparse[i].part_bytes));
@@ -866,11 +891,18 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
         const float *bias = d_bias_or_null ? d_bias_or_null[i] : nullptr;
         const int relu = last ? relu_last : relu_hidden;
         float *out = last ? d_Y : (float *)region(act0, P.act_bytes, i);
-        if (is_mfma(P.path[i])) {
+        if (reads_xt(P.path[i])) {
+            // towards a following layer that takes its activations transposed, this layer's finishing
+            // kernel writes them so, the image axis padded to that layer's tile
             const bool to_xt = !last && P.xt_in[i + 1];
             float *dst = to_xt ? (float *)region(xt0, P.xt_bytes, i + 1) : out;
-            if (int32_t rc = run_mfma_layer(L, D, P.mfma[i], in, region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i), bias, dst, to_xt ? P.mfma[i + 1].Bp : 0, batch, relu, st))
-                return rc;
+            const int next_bp = !to_xt ? 0 : P.path[i + 1] == CL_PATH_SPARSE_WIDE ? P.wide[i + 1].Bp : P.mfma[i + 1].Bp;
+            int32_t rc;
+            if (P.path[i] == CL_PATH_SPARSE_WIDE)
+                rc = run_wide_layer(L, D, P.wide[i], in, (float *)region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i), bias, dst, next_bp, batch, relu, st);
+            else
+                rc = run_mfma_layer(L, D, P.mfma[i], in, region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i), bias, dst, next_bp, batch, relu, st);
+            if (rc) return rc;
             in = to_xt ? nullptr : out;
         } else {
             if (int32_t rc = forward_sparse(L, D, dl, in, bias, out, batch, relu, (float *)region(part0, P.part_bytes, i), st)) return rc;

@@ -272,8 +272,9 @@ def test_mfma_path_is_deterministic_and_refuses_big_blocks():
 
 def test_config3_alexnet_fc_stack_batch256():
     """configs[2] at full size, in the launch configuration the benchmark times:
-    fc6 -> ReLU -> fc7 -> ReLU -> fc8 at batch 256 (AUTO picks the MFMA path) and
-    at batch 4 (sparse path)."""
+    fc6 -> ReLU -> fc7 -> ReLU -> fc8 at batch 256 (AUTO: the wide sparse path for the
+    9 % layers, dense tiles for fc8) and at batch 4 (sparse path); at batch 256 also
+    every layer on each of the two large-batch paths by name."""
     torch = torch_cuda()
     layers, dense = [], []
     for li in range(3):
@@ -287,11 +288,16 @@ def test_config3_alexnet_fc_stack_batch256():
             ref = fc_ref(dense[li], a_ref, nthreads=16)
             a = cl.compressed_fc_forward(layers[li], a, relu=(li < 2))
             assert_close(a.cpu().numpy(), ref, li < 2, what=(B, li))
+            if B == 256:
+                given = torch.from_numpy(a_ref).cuda()
+                for path in (cl.PATH_MFMA_F32, cl.PATH_SPARSE_WIDE):
+                    Yp = cl.compressed_fc_forward(layers[li], given, relu=(li < 2), path=path)
+                    assert_close(Yp.cpu().numpy(), ref, li < 2, what=(B, li, path))
             a_ref = (np.maximum(ref.pre, 0) if li < 2 else ref.pre).astype(np.float32)
             a = torch.from_numpy(a_ref).cuda()          # each layer is fed the oracle's activations
 
 
-STACK_PATHS = (cl.PATH_AUTO, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16, cl.PATH_SPARSE)
+STACK_PATHS = (cl.PATH_AUTO, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16, cl.PATH_SPARSE, cl.PATH_SPARSE_WIDE)
 ATOMIC_PATHS = (cl.PATH_SPARSE,)      # unordered LDS float atomics: tolerance-identical, not bit-identical, from run to run
 
 
