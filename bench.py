@@ -33,7 +33,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=256, help="headline batch size")
-    ap.add_argument("--path", choices=["auto", "sparse", "mfma", "bf16"], default="auto")
+    ap.add_argument("--path", choices=["auto", "sparse", "mfma", "bf16", "wide"], default="auto")
+    ap.add_argument("--min-warmup-ms", type=float, default=60.0,
+                    help="keep running untimed steps after the --warmup ones until this much time has passed (clocks settle)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch sweep 1,4,16,64,256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16", action="store_true", help="skip the extra run on the bf16-tile path")
@@ -58,13 +60,15 @@ def main():
     import torch
 
     import paper_1711_00244_amd as cl
-    from paper_1711_00244_amd import binding, workloads as wl
+    from paper_1711_00244_amd import binding, counters, workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    path = {"auto": cl.PATH_AUTO, "sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32, "bf16": cl.PATH_MFMA_BF16}[args.path]
+    path = {"auto": cl.PATH_AUTO, "sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32, "bf16": cl.PATH_MFMA_BF16,
+            "wide": cl.PATH_SPARSE_WIDE}[args.path]
+    path_names = {cl.PATH_SPARSE: "sparse", cl.PATH_MFMA_F32: "mfma", cl.PATH_MFMA_BF16: "bf16", cl.PATH_SPARSE_WIDE: "wide"}
 
     # ---- the workload: configs[2], synthetic AlexNet fc6/fc7/fc8 -------------
     cfg = 3
@@ -97,9 +101,16 @@ def main():
                                               workspace=stack_ws[B])
 
     def timed(B, steps, warmup):
+        # the asked-for warm-up steps, then more of them until min-warmup-ms have passed: a
+        # handful of sub-millisecond steps does not bring the clocks up
+        t_w = time.perf_counter()
         for _ in range(warmup):
             step(B)
         torch.cuda.synchronize()
+        while (time.perf_counter() - t_w) * 1e3 < args.min_warmup_ms:
+            for _ in range(10):
+                step(B)
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
             step(B)
@@ -129,53 +140,78 @@ def main():
     # ---- roofline of the dominant kernel (fc6's main kernel), live HIP events ----
     # The library brackets the first main-kernel launch of a forward call with HIP
     # events on the call's stream; fc6 carries 63 % of the stack's entries.
-    def kernel_time(li, B, reps=50):
-        X, ys, ws = bufs[B]
+    def kernel_time(li, B, p, reps=50):
+        X, ys, _ = bufs[B]
         a = X if li == 0 else ys[li - 1]
+        w = torch.empty(max(1, cl.fc_workspace_bytes(layers[li], B, p)), dtype=torch.uint8, device="cuda")
         binding.set_kernel_timing(True)
         ts = []
-        for i in range(reps + 5):
-            cl.compressed_fc_forward(layers[li], a, relu=(li < 2), path=path, out=ys[li], workspace=ws[li])
+        for i in range(reps + 10):
+            cl.compressed_fc_forward(layers[li], a, relu=(li < 2), path=p, out=ys[li], workspace=w)
             t, n = binding.last_kernel_ms()
-            if i >= 5:
+            if i >= 10:
                 ts.append(t / n)
         binding.set_kernel_timing(False)
         return float(np.mean(ts))
 
-    def uses_mfma(B):
-        return path == cl.PATH_MFMA_F32 or (path == cl.PATH_AUTO and B > 4)
+    def traffic_of(kind, B):
+        """HBM bytes of the fc6 launch from the counter runs recorded in profiles/counters.json
+        (FETCH_SIZE / WRITE_SIZE, scaled by the reference copy's reading), and whether the
+        kernel sources have changed since they were taken."""
+        fig, stale = counters.lookup(f"{kind}/fc6/{B}")
+        if not fig or "fetch_bytes" not in fig or "write_bytes" not in fig:
+            return None, None, fig
+        return fig["fetch_bytes"] + fig["write_bytes"], stale, fig
 
-    # HBM bytes (read + written) of the fc6 launch from the FETCH_SIZE / WRITE_SIZE counter runs
-    # summarised under profiles/ (scaled by the reference copy's reading); they hold for the
-    # default workload and block size only
-    measured_traffic = {("mfma", 256): 14.7e6 + 33.6e6, ("sparse", 1): 5.59e6 + 0.59e6}
-
-    def traffic_for(kind, B):
-        return measured_traffic.get((kind, B))
-
-    def roofline_for(B):
-        ms_launch = kernel_time(0, B)
+    def kernel_roofline(kind, B):
+        """fc6's main kernel on the named path at batch B against the roof that bounds it."""
+        p = {"sparse": cl.PATH_SPARSE, "mfma": cl.PATH_MFMA_F32, "wide": cl.PATH_SPARSE_WIDE}[kind]
+        ms_launch = kernel_time(0, B, p)
         s0, sp = stats[0], specs[0]
-        if uses_mfma(B):
-            Bp = -(-B // 128) * 128
-            executed = 2.0 * sp.M * sp.K * Bp            # every 128x128x128 tile product the kernel issues
-            useful = 2.0 * s0["nnz"] * B
+        useful = 2.0 * s0["nnz"] * B                      # the method's own work: one multiply-add per surviving weight and image
+        traffic, stale, fig = traffic_of(kind, B)
+        if kind == "mfma":
+            Bp = -(-B // 32) * 32
+            executed = 2.0 * sp.M * sp.K * Bp            # every tile product the kernel issues
             r = {"bound": "mfma", "achieved": round(executed / (ms_launch * 1e-3) / 1e12, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
-                 "unit": "TFLOP/s", "traffic": traffic_for("mfma", B), "kernel": "fc_mfma_kernel", "flops_counted": "executed dense-tile flops 2*M*K*B",
-                 "useful_TFLOPs": round(useful / (ms_launch * 1e-3) / 1e12, 3), "images_per_launch": B}
+                 "unit": "TFLOP/s", "kernel": "fc_mfma_kernel", "flops_counted": "executed dense-tile flops 2*M*K*B"}
+        elif kind == "wide":
+            r = {"bound": "alu", "achieved": round(useful / (ms_launch * 1e-3) / 1e12, 3), "peak": FP32_VECTOR_PEAK_TFLOPS,
+                 "unit": "TFLOP/s", "kernel": "fc_wide_kernel", "flops_counted": "2*nnz*B, all of them useful",
+                 "peak_note": "157.3 = 256 CUs x 128 lanes x 2 flops x 2.4 GHz needs packed fp32; this build issues unpacked "
+                              "multiply-adds, whose ceiling is 78.6"}
         else:
             imgs = min(B, 16)                            # the sparse kernel takes batch tiles of up to 16 images
             alg_bytes = s0["model_bytes"] + imgs * (sp.K + sp.M) * 4
+            useful = 2.0 * s0["nnz"] * imgs
             r = {"bound": "hbm", "achieved": round(alg_bytes / (ms_launch * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBS,
-                 "unit": "GB/s", "traffic": traffic_for("sparse", B), "kernel": "fc_sparse_kernel",
-                 "algorithmic_bytes_per_launch": int(alg_bytes), "images_per_launch": imgs,
-                 "useful_TFLOPs": round(2.0 * s0["nnz"] * imgs / (ms_launch * 1e-3) / 1e12, 4)}
+                 "unit": "GB/s", "kernel": "fc_sparse_kernel", "algorithmic_bytes_per_launch": int(alg_bytes),
+                 "images_per_launch": imgs}
         r["frac"] = round(r["achieved"] / r["peak"], 5)
+        r["useful_TFLOPs"] = round(useful / (ms_launch * 1e-3) / 1e12, 4)
+        r["frac_useful"] = round(useful / (ms_launch * 1e-3) / 1e12 / (FP32_MFMA_PEAK_TFLOPS if kind == "mfma" else FP32_VECTOR_PEAK_TFLOPS), 5)
+        r["traffic"] = traffic
+        if traffic is not None:
+            r["traffic_stale"] = bool(stale)
         r.update({"layer": "fc6", "batch": B, "launch_ms": round(ms_launch, 5)})
-        return r
+        return r, fig
 
-    headline = roofline_for(args.batch)
-    b1 = roofline_for(1)
+    def roofline_for(B):
+        kind = path_names[cl.fc_resolved_path(layers[0], B, path)]
+        if kind == "bf16":
+            kind = "mfma"
+        return kernel_roofline(kind, B)
+
+    headline, _ = roofline_for(args.batch)
+    b1, b1_fig = roofline_for(1)
+    # both large-batch kernels at the headline batch, so that the choice between them shows
+    side = {}
+    if args.batch > 4:
+        for kind in ("mfma", "wide"):
+            try:
+                side[kind] = headline if headline["kernel"] == f"fc_{kind}_kernel" else kernel_roofline(kind, args.batch)[0]
+            except cl.CLError as e:
+                side[kind] = {"error": str(e)}
 
     def cold_pool(copies, n_streams, rounds=3):
         """Steady state at batch 1: `copies` separately uploaded copies of fc6 (together
@@ -251,11 +287,13 @@ def main():
 
     # The batch-1 kernel against what binds it: vector-ALU issue.  Peak = 256 CUs x 4 SIMDs x
     # 2.4 GHz / 4 cycles per wavefront instruction; the instruction count of the fc6 launch is
-    # the SQ_INSTS_VALU counter summarised under profiles/ (default workload only).
-    valu_insts = 3006258
-    b1["alu"] = {"bound": "alu", "achieved": round(valu_insts / (b1["launch_ms"] * 1e-3) / 1e9, 1), "peak": 614.4,
-                 "unit": "G wavefront VALU instructions/s", "valu_instructions_per_launch": valu_insts}
-    b1["alu"]["frac"] = round(b1["alu"]["achieved"] / b1["alu"]["peak"], 4)
+    # the SQ_INSTS_VALU counter recorded in profiles/counters.json.
+    if b1_fig and "SQ_INSTS_VALU" in b1_fig:
+        valu_insts = b1_fig["SQ_INSTS_VALU"]
+        b1["alu"] = {"bound": "alu", "achieved": round(valu_insts / (b1["launch_ms"] * 1e-3) / 1e9, 1), "peak": 614.4,
+                     "unit": "G wavefront VALU instructions/s", "valu_instructions_per_launch": int(valu_insts),
+                     "stale": bool(counters.lookup("sparse/fc6/1")[1])}
+        b1["alu"]["frac"] = round(b1["alu"]["achieved"] / b1["alu"]["peak"], 4)
 
     if not args.no_cold_pool:
         b1["steady_state_cold"] = [cold_pool(args.cold_copies, 1), cold_pool(args.cold_copies, 4)]
@@ -281,6 +319,7 @@ def main():
         "sweep": sweep,
         "roofline": headline,
         "roofline_batch1": b1,
+        "large_batch_kernels": side,
     }
     if not args.no_bf16 and args.path == "auto":
         out["bf16_tiles"] = bf16_tiles(args.batch)
@@ -315,26 +354,41 @@ def main():
         import oracle
         Bc = args.cpu_batch
         Xc = wl.activations(cfg, Bc)
-        t_dec = t_rec = t_mm = 0.0
+        try:
+            ncores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            ncores = os.cpu_count() or 1
+        ncores = max(1, min(ncores, int(os.environ.get("OMP_NUM_THREADS", ncores) or ncores)))
         t_all0 = time.perf_counter()
-        a = Xc
-        for li, (spec, W) in enumerate(zip(specs, dense_host)):
-            m = oracle.compress_layer(W, spec.r, spec.k, BLOCK[0], BLOCK[1])     # offline step, not timed
+        models = [oracle.compress_layer(W, spec.r, spec.k, BLOCK[0], BLOCK[1]) for spec, W in zip(specs, dense_host)]   # offline, not timed
+        t_dec = t_rec = 0.0
+        dense = []
+        for m in models:
             t0 = time.perf_counter()
-            v3, i3, bp = oracle.decode_layer(m)          # Algorithm 2 steps 3-6, block by block
+            v3, i3, bp = oracle.decode_layer(m)          # Algorithm 2 steps 3-6, block by block (one thread: a bit-serial walk)
             t_dec += time.perf_counter() - t0
             t0 = time.perf_counter()
-            Wd = oracle.dense_weights(m, v3, i3, bp)
+            dense.append(oracle.dense_weights(m, v3, i3, bp))
             t_rec += time.perf_counter() - t0
-            t0 = time.perf_counter()
-            y = oracle.fc_forward(Wd, a, None, relu=(li < 2), nthreads=1)
-            t_mm += time.perf_counter() - t0
-            a = y.astype(np.float32)
-        t_cpu = t_dec + t_rec + t_mm
+
+        def products(nthreads):
+            a, t = Xc, 0.0
+            for li, Wd in enumerate(dense):
+                t0 = time.perf_counter()
+                y = oracle.fc_forward(Wd, a, None, relu=(li < 2), nthreads=nthreads)
+                t += time.perf_counter() - t0
+                a = y.astype(np.float32)
+            return t
+        t_mm_all = products(ncores)
+        t_mm_one = products(1)
+        t_cpu = t_dec + t_rec + t_mm_all
         out["cpu_baseline"] = {
-            "value": round(Bc / t_cpu, 2), "unit": "images/s", "cores": 1, "kind": "oracle",
+            "value": round(Bc / t_cpu, 2), "unit": "images/s", "cores": ncores, "kind": "oracle",
             "sample": f"one pass of the same FC6-8 stack at batch {Bc}: bit-serial Huffman decode {t_dec:.2f} s + dense "
-                      f"rebuild {t_rec:.2f} s + triple-loop fp64 product {t_mm:.2f} s (compression not timed)",
+                      f"rebuild {t_rec:.2f} s (one thread each) + triple-loop fp64 product {t_mm_all:.2f} s on {ncores} threads "
+                      f"(compression not timed)",
+            "one_thread": {"value": round(Bc / (t_dec + t_rec + t_mm_one), 2), "unit": "images/s", "cores": 1,
+                           "product_s": round(t_mm_one, 2)},
             "host_cpus": os.cpu_count(), "wall_s": round(time.perf_counter() - t_all0, 1)}
     print(json.dumps(out))
 

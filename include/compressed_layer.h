@@ -226,6 +226,11 @@ int32_t cl_decode_layer(const cl_layer *layer, uint8_t *d_val_sym, uint8_t *d_id
  * planes for CL_PATH_MFMA_BF16).  Needs a HIP device (CL_EHIP otherwise). */
 int32_t cl_fc_workspace_bytes(const cl_layer *layer, int32_t batch, int32_t path, size_t *out);
 
+/* The path a forward call with these arguments runs on: `path` itself unless it is
+ * CL_PATH_AUTO, else the library's choice for this layer and batch on the current
+ * device (see CL_PATH_AUTO).  Needs a HIP device (CL_EHIP otherwise). */
+int32_t cl_fc_resolved_path(const cl_layer *layer, int32_t batch, int32_t path, int32_t *out);
+
 /* Y = act(X W^T + v) straight from the compressed layer (Eq. 1-2 with the
  * decoding steps of Algorithm 2 fused in).
  *  d_X     batch x K fp32        d_bias  M fp32 or NULL

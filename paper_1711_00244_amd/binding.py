@@ -22,7 +22,7 @@ STATIC_SCRATCH_BYTES = 16 << 20        # CL_STATIC_SCRATCH_BYTES
 EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
-    "cl_fc_workspace_bytes", "cl_compressed_fc_forward", "cl_compressed_fc_forward_static", "cl_fc_stack_workspace_bytes",
+    "cl_fc_workspace_bytes", "cl_fc_resolved_path", "cl_compressed_fc_forward", "cl_compressed_fc_forward_static", "cl_fc_stack_workspace_bytes",
     "cl_compressed_fc_stack_forward", "cl_conv_workspace_bytes", "cl_conv_workspace_bytes_min",
     "cl_compressed_conv_forward", "cl_plan_batches", "cl_maxpool_forward", "cl_lrn_forward",
     "cl_set_kernel_timing", "cl_last_kernel_ms",
@@ -95,6 +95,7 @@ def lib():
     L.cl_layer_deserialize.argtypes = [p, sz, C.POINTER(p)]
     L.cl_decode_layer.argtypes = [p, p, p, p, p, p]
     L.cl_fc_workspace_bytes.argtypes = [p, i32, i32, C.POINTER(sz)]
+    L.cl_fc_resolved_path.argtypes = [p, i32, i32, C.POINTER(i32)]
     L.cl_compressed_fc_forward_static.argtypes = [p, p, p, p, i32, i32, i32, p]
     L.cl_compressed_fc_forward.argtypes = [p, p, p, p, i32, i32, i32, p, sz, p]
     L.cl_fc_stack_workspace_bytes.argtypes = [p, i32, i32, i32, C.POINTER(sz)]
@@ -273,6 +274,13 @@ def fc_workspace_bytes(layer: Layer, batch: int, path: int = PATH_AUTO) -> int:
         _check(lib().cl_fc_workspace_bytes(layer.handle, batch, path, C.byref(n)))
         layer._ws_cache[key] = n.value
     return layer._ws_cache[key]
+
+
+def fc_resolved_path(layer: Layer, batch: int, path: int = PATH_AUTO) -> int:
+    """The path cl_compressed_fc_forward takes for (layer, batch, path)."""
+    out = C.c_int32(0)
+    _check(lib().cl_fc_resolved_path(layer.handle, batch, path, C.byref(out)))
+    return out.value
 
 
 def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO, out=None, workspace=None):

@@ -609,6 +609,17 @@ extern "C" int32_t cl_fc_workspace_bytes(const cl_layer *L, int32_t batch, int32
     return CL_OK;
 }
 
+extern "C" int32_t cl_fc_resolved_path(const cl_layer *L, int32_t batch, int32_t path, int32_t *out)
+{
+    if (!L || !out) return fail(CL_EINVAL, "null argument");
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    if (path < CL_PATH_AUTO || path > CL_PATH_SPARSE_WIDE) return fail(CL_EINVAL, "unknown path %d", path);
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    *out = resolve_path(L, batch, path, dl);
+    return CL_OK;
+}
+
 static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, const float *d_X,
                               const float *d_bias, float *d_Y, int batch, int relu, float *part, hipStream_t st)
 {
