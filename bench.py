@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--conv-batch", type=int, default=64)
     ap.add_argument("--cold-copies", type=int, default=128)
     ap.add_argument("--cpu-batch", type=int, default=256, help="batch of the CPU-oracle sample")
+    ap.add_argument("--counter-run", type=int, default=None, metavar="LAYER",
+                    help="profiling aid: only run 25 forward calls of this layer of the stack (0 = fc6) at --batch on --path, "
+                         "so that a rocprofv3 --pmc run sees the dispatches of one layer; prints a short JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 256 MiB device copy a few times (reference kernel of known traffic for rocprofv3 --pmc)")
     return ap.parse_args()
@@ -123,6 +126,17 @@ def main():
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize()
+
+    if args.counter_run is not None:
+        li, B = args.counter_run, args.batch
+        X, ys, ws = bufs[B]
+        a = X if li == 0 else torch.rand((B, specs[li].K), device="cuda")
+        for _ in range(25):
+            cl.compressed_fc_forward(layers[li], a, relu=(li < 2), path=path, out=ys[li], workspace=ws[li])
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_run": specs[li].name, "batch": B, "path": path_names[cl.fc_resolved_path(layers[li], B, path)],
+                          "source_hash": counters.source_hash()}))
+        return
 
     ms = timed(args.batch, args.steps, args.warmup)
     value = args.batch / (ms * 1e-3)
