@@ -517,13 +517,14 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
         return fail(CL_EUNSUPPORTED, "the wide sparse path keeps a block's %lld surviving weights in LDS: %zu bytes needed, %zu there",
                     (long long)L->max_block_nnz, P.lds, dl.max_lds);
     // Split of the block rows, from a small model of a launch (cycles per workgroup: a
-    // start; per block 13 + 1.2 ipl cycles per surviving weight - measured on the AlexNet-
-    // shaped layers at 64, 128 and 256 images: 14.4, 16 and 17.8; and the partial tiles,
-    // written and read again, as on the dense-tile path; workgroups run in rounds of one
-    // per CU).
+    // start; per block 4 k cycles and 10 + 1.25 ipl cycles per surviving weight - measured
+    // on the AlexNet-shaped layers at 64, 128 and 256 images: 21, 23.6 and 26 k cycles per
+    // block of 1 474 weights; and the partial tiles, written and read again, as on the
+    // dense-tile path; workgroups run in rounds of one per CU).
     const int64_t tiles = (int64_t)L->n_panels * (P.Bp / tile);
     const int cus = std::max(1, dl.cus);
-    const int64_t per_block = (L->n_blocks ? L->nnz / L->n_blocks : 0) * (53 + 5 * P.ipl) / 4;
+    // (a block of at most 64 columns is one short phase: 6 k, from 64 x 64 blocks at 16 images)
+    const int64_t per_block = (L->desc.block_w > kHalf ? 4000 : 6000) + (L->n_blocks ? L->nnz / L->n_blocks : 0) * (40 + 5 * P.ipl) / 4;
     const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
     int64_t best = -1;
     for (int sp = 1; sp <= sp_max; ++sp) {
