@@ -174,6 +174,18 @@ typedef struct {
     const uint32_t *chunk_nz;      /* n_chunks + 1: entries that are not padding in all */
                                    /*   chunks before this one (derived at load time)  */
     int64_t max_block_nnz;         /* most surviving weights in one block              */
+    int32_t max_group_blocks;      /* most blocks touched by the chunks c0 + 8 g ..    */
+                                   /*   c0 + 8 g + 7 of a block row whose first chunk  */
+                                   /*   is c0 (derived at load time)                   */
+    /* Layers with blocks of at most 128 x 128 (else both null): the order in which the   */
+    /* large-batch sparse path lists a block's surviving weights - those in the block's    */
+    /* columns 0-63 first, then those in columns 64-127, each half row by row (derived at  */
+    /* load time).                                                                         */
+    const uint32_t *chunk_half;    /* 2 n_chunks: list position of the first surviving  */
+                                   /*   weight of chunk c in half 0 (2c) and 1 (2c + 1) */
+    const uint32_t *group_ptr;     /* n_blocks x 2 x 17: list position where rows 8q .. */
+                                   /*   of half h of block b start ([b][h][q]); [16]:   */
+                                   /*   where the half ends                             */
 } cl_host_view;
 
 const char *cl_last_error(void);

@@ -49,7 +49,8 @@ class HostView(C.Structure):
                 ("block_ptr", C.POINTER(C.c_uint32)), ("panel_chunk", C.POINTER(C.c_uint32)),
                 ("chunk_meta", C.POINTER(ChunkMeta)), ("records", C.POINTER(C.c_uint64)),
                 ("n_blocks", C.c_int64), ("n_chunks", C.c_int64), ("n_records", C.c_int64), ("n_entries", C.c_int64),
-                ("n_panels", C.c_int32), ("chunk_nz", C.POINTER(C.c_uint32)), ("max_block_nnz", C.c_int64)]
+                ("n_panels", C.c_int32), ("chunk_nz", C.POINTER(C.c_uint32)), ("max_block_nnz", C.c_int64),
+                ("max_group_blocks", C.c_int32), ("chunk_half", C.POINTER(C.c_uint32)), ("group_ptr", C.POINTER(C.c_uint32))]
 
 
 class ConvDesc(C.Structure):
@@ -208,6 +209,10 @@ class Layer:
                     panel_chunk=arr(v.panel_chunk, int(v.n_panels) + 1, np.uint32), chunk_meta=meta,
                     records=arr(v.records, int(v.n_records), np.uint64),
                     chunk_nz=arr(v.chunk_nz, nc + 1, np.uint32), max_block_nnz=int(v.max_block_nnz),
+                    max_group_blocks=int(v.max_group_blocks),
+                    chunk_half=None if not v.group_ptr else
+                    arr(v.chunk_half, 2 * nc, np.uint32).reshape(nc, 2) if nc else np.zeros((0, 2), np.uint32),
+                    group_ptr=arr(v.group_ptr, int(v.n_blocks) * 34, np.uint32).reshape(int(v.n_blocks), 2, 17) if v.group_ptr else None,
                     n_blocks=int(v.n_blocks), n_chunks=nc, n_records=int(v.n_records), n_entries=int(v.n_entries),
                     n_panels=int(v.n_panels))
 

@@ -199,6 +199,62 @@ int32_t finalize_and_validate(cl_layer *L)
     L->max_block_nnz = 0;
     for (int64_t b = 0; b < g.n_blocks; ++b)
         L->max_block_nnz = std::max<int64_t>(L->max_block_nnz, (int64_t)L->chunk_nz[L->block_chunk[b + 1]] - L->chunk_nz[L->block_chunk[b]]);
+    // the half-by-half order of the wide path (blocks of at most 128 x 128 only)
+    L->chunk_half.clear();
+    L->group_ptr.clear();
+    if (d.block_h <= 128 && d.block_w <= 128) {
+        constexpr int kGroups = 16, kPer = 2 * (kGroups + 1);
+        L->chunk_half.assign((size_t)L->n_chunks * 2, 0u);
+        L->group_ptr.assign((size_t)g.n_blocks * kPer, 0u);
+        std::vector<uint32_t> cnt(2 * kGroups);
+        for (int64_t b = 0; b < g.n_blocks; ++b) {
+            const uint32_t c0 = L->block_chunk[b], c1 = L->block_chunk[b + 1];
+            const uint32_t start = L->chunk_nz[c0];
+            std::fill(cnt.begin(), cnt.end(), 0u);
+            int row_id, col_id, bhp, bwp;
+            g.block(b, row_id, col_id, bhp, bwp);
+            uint32_t n[2] = {0, 0};
+            for (uint32_t c = c0; c < c1; ++c) {
+                L->chunk_half[2 * (size_t)c] = n[0];            // within the half for now
+                L->chunk_half[2 * (size_t)c + 1] = n[1];
+                uint64_t pos = L->meta[c].pos0;
+                for (uint64_t r = L->meta[c].rec_off; r < L->meta[c + 1].rec_off; ++r) {
+                    const uint64_t w = L->records[r];
+                    uint64_t vbuf = w >> kCountBits, ibuf = bit_reverse64(w);
+                    for (int j = 0, nj = (int)(w & 15u); j < nj; ++j) {
+                        const lut_t ev = L->val_lut[(uint32_t)vbuf & vmask], ei = L->idx_lut[(uint32_t)ibuf & imask];
+                        vbuf >>= lut_len(ev);
+                        ibuf >>= lut_len(ei);
+                        pos += (uint64_t)lut_sym(ei) + 1;
+                        if (!lut_sym(ev)) continue;
+                        const uint32_t at = (uint32_t)(pos - 1), row = at / (uint32_t)bwp, col = at % (uint32_t)bwp;
+                        const int h = col >= 64 ? 1 : 0;
+                        ++n[h];
+                        ++cnt[(size_t)h * kGroups + (row >> 3)];
+                    }
+                }
+            }
+            for (uint32_t c = c0; c < c1; ++c) {
+                L->chunk_half[2 * (size_t)c] += start;
+                L->chunk_half[2 * (size_t)c + 1] += start + n[0];
+            }
+            uint32_t at = start;
+            for (int h = 0; h < 2; ++h) {
+                uint32_t *gp = &L->group_ptr[(size_t)b * kPer + (size_t)h * (kGroups + 1)];
+                for (int q = 0; q < kGroups; ++q) {
+                    gp[q] = at;
+                    at += cnt[(size_t)h * kGroups + q];
+                }
+                gp[kGroups] = at;
+            }
+        }
+    }
+    L->max_group_blocks = 0;
+    for (int p = 0; p < g.nbh; ++p)
+        for (uint32_t c = L->panel_chunk[p]; c < L->panel_chunk[p + 1]; c += 8) {
+            const uint32_t last = std::min<uint32_t>(c + 8, L->panel_chunk[p + 1]) - 1;
+            L->max_group_blocks = std::max<int32_t>(L->max_group_blocks, (int32_t)(L->meta[last].blk - L->meta[c].blk) + 1);
+        }
     L->nnz = nnz;
     L->padding = L->entries - nnz;
     L->val_bits = vbits;
@@ -401,6 +457,9 @@ extern "C" int32_t cl_layer_host_view(const cl_layer *L, cl_host_view *v)
     v->chunk_meta = L->meta.data();
     v->chunk_nz = L->chunk_nz.data();
     v->max_block_nnz = L->max_block_nnz;
+    v->max_group_blocks = L->max_group_blocks;
+    v->chunk_half = L->chunk_half.empty() ? nullptr : L->chunk_half.data();
+    v->group_ptr = L->group_ptr.empty() ? nullptr : L->group_ptr.data();
     v->records = L->records.data();
     v->n_blocks = L->n_blocks;
     v->n_chunks = L->n_chunks;

@@ -57,6 +57,8 @@ struct LayerDev {
     const uint32_t *panel_chunk;
     const uint32_t *block_chunk;
     const uint32_t *chunk_nz;
+    const uint32_t *chunk_half;          // null unless the blocks are at most 128 x 128 (with group_ptr)
+    const uint32_t *group_ptr;
     const float *codebook;
     const lut_t *val_lut;
     const lut_t *idx_lut;
@@ -82,6 +84,8 @@ static LayerDev make_dev(const cl_layer *L)
     d.panel_chunk = L->dev.panel_chunk;
     d.block_chunk = L->dev.block_chunk;
     d.chunk_nz = L->dev.chunk_nz;
+    d.chunk_half = L->dev.chunk_half;
+    d.group_ptr = L->dev.group_ptr;
     d.codebook = L->dev.codebook;
     d.val_lut = L->dev.val_lut;
     d.idx_lut = L->dev.idx_lut;
@@ -230,7 +234,7 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
         std::memcpy(image.data() + vb, L->idx_lut.data(), ib);
         std::memcpy(image.data() + ((vb + ib + 15) & ~(size_t)15), L->codebook.data(), L->codebook.size() * 4);
     }
-    Sec secs[7] = {
+    Sec secs[9] = {
         {L->records.data(), L->records.size() * 8, 0},
         {L->meta.data(), L->meta.size() * sizeof(cl_chunk_meta), 0},
         {L->block_ptr.data(), L->block_ptr.size() * 4, 0},
@@ -238,6 +242,8 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
         {image.data(), image.size(), 0},
         {L->block_chunk.data(), L->block_chunk.size() * 4, 0},
         {L->chunk_nz.data(), L->chunk_nz.size() * 4, 0},
+        {L->chunk_half.data(), L->chunk_half.size() * 4, 0},
+        {L->group_ptr.data(), L->group_ptr.size() * 4, 0},
     };
     size_t total = 0;
     for (auto &s : secs) { s.off = total; total += (s.bytes + 255) / 256 * 256; }
@@ -260,6 +266,8 @@ extern "C" int32_t cl_layer_upload(cl_layer *L)
     L->dev.panel_chunk = (const uint32_t *)(blob + secs[3].off);
     L->dev.block_chunk = (const uint32_t *)(blob + secs[5].off);
     L->dev.chunk_nz = (const uint32_t *)(blob + secs[6].off);
+    L->dev.chunk_half = L->group_ptr.empty() ? nullptr : (const uint32_t *)(blob + secs[7].off);
+    L->dev.group_ptr = L->group_ptr.empty() ? nullptr : (const uint32_t *)(blob + secs[8].off);
     L->dev.val_lut = (const lut_t *)(blob + secs[4].off);
     L->dev.idx_lut = L->dev.val_lut + L->val_lut.size();
     L->dev.codebook = (const float *)(blob + secs[4].off + ((L->val_lut.size() + L->idx_lut.size()) * sizeof(lut_t) + 15) / 16 * 16);
@@ -316,6 +324,17 @@ int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
     P.wg_per_panel = (int)((L->max_panel_chunks + kWaves * kSparseChunksPerWave - 1) / (kWaves * kSparseChunksPerWave));
     P.part_bytes = (size_t)L->n_panels * P.wg_per_panel * L->desc.block_h * P.bt_max * sizeof(float);
     return CL_OK;
+}
+
+// Whether a stack could leave out the finishing kernel between two layers on this path,
+// as far as this layer goes (as producer or consumer): the batch is a single batch tile,
+// so that there is one set of partial tiles, and - for the consumer - every workgroup
+// stages its activation columns in LDS, where the sum of the tiles is formed.
+bool sparse_can_fold(const cl_layer *L, const SparsePlan &P, int batch)
+{
+    if (batch > P.bt_max || (batch & (batch - 1))) return false;
+    const int64_t widest = std::min<int64_t>(L->desc.K, (int64_t)L->max_group_blocks * L->desc.block_w);
+    return widest <= P.xcap_for(batch);
 }
 
 // Launch shape of the MFMA path.
@@ -498,6 +517,9 @@ struct WidePlan {
     int cap = 0;             // entries the kernel's list of one block holds
     int64_t cost = 0;        // modelled cycles of the launch (same units as mfma_shape's)
     size_t lds = 0;
+    bool two_pass = true;    // decode to an entry list in the workspace, then multiply
+    size_t tile_bytes = 0;   // the partial tiles; behind them in the workspace's partial-tile part:
+    size_t ent_bytes = 0;    //   the entry list
     size_t xt_bytes = 0, part_bytes = 0;
 };
 
@@ -509,10 +531,14 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
     const size_t tables = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
     // the widest image tile the batch can use whose slabs leave room for the block's list
     P.ipl = batch > 128 ? 4 : batch > 64 ? 2 : 1;
-    while (P.ipl > 1 && wide_lds_bytes(tables, P.cap, P.ipl) > dl.max_lds) P.ipl >>= 1;
+    P.two_pass = P.ipl == 4;
+    auto lds_for = [&](int ipl) {
+        return P.two_pass ? 2 * (size_t)kHalf * 64 * ipl * 4 + ((size_t)4 << L->desc.weight_bits) : wide_lds_bytes(tables, P.cap, ipl);
+    };
+    while (P.ipl > 1 && lds_for(P.ipl) > dl.max_lds) P.ipl >>= 1;
     const int tile = 64 * P.ipl;
     P.Bp = (batch + tile - 1) / tile * tile;
-    P.lds = wide_lds_bytes(tables, P.cap, P.ipl);
+    P.lds = lds_for(P.ipl);
     if (P.lds > dl.max_lds)
         return fail(CL_EUNSUPPORTED, "the wide sparse path keeps a block's %lld surviving weights in LDS: %zu bytes needed, %zu there",
                     (long long)L->max_block_nnz, P.lds, dl.max_lds);
@@ -537,7 +563,23 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
     }
     P.cost = best;
     P.xt_bytes = xt_bytes_for(L, P.Bp, false);
-    P.part_bytes = (size_t)L->n_panels * P.splits * kTile * P.Bp * sizeof(float);
+    P.tile_bytes = (size_t)L->n_panels * P.splits * kTile * P.Bp * sizeof(float);
+    if (P.two_pass) {
+        P.ent_bytes = ((size_t)L->nnz * sizeof(WideEntry) + 255) / 256 * 256;
+    }
+    P.part_bytes = P.tile_bytes + P.ent_bytes;
+    return CL_OK;
+}
+
+int32_t launch_wide_mul(const LayerDev &D, int panels, const WidePlan &P, const float *xt, float *part, hipStream_t st)
+{
+    static LdsLimit seen;
+    if (int32_t rc = ensure_lds((const void *)wide_mul_kernel, P.lds, seen)) return rc;
+    dim3 grid;
+    GRID_TRY(grid, (int64_t)panels * P.splits * (P.Bp / 256));
+    const WideEntry *ent = (const WideEntry *)((const char *)part + P.tile_bytes);
+    hipLaunchKernelGGL(wide_mul_kernel, grid, dim3(kWideThreads), P.lds, st, D, xt, ent, part, panels, P.splits, P.Bp);
+    HIP_TRY(hipGetLastError());
     return CL_OK;
 }
 
@@ -621,11 +663,18 @@ extern "C" int32_t cl_fc_resolved_path(const cl_layer *L, int32_t batch, int32_t
     return CL_OK;
 }
 
+// The small-batch path for one layer.  With `prev` the input is not d_X but the partial
+// tiles of the layer before (see PrevSlots); with finish == false the layer's own
+// finishing kernel is left to the layer after it in the same way.  Both only where
+// sparse_can_fold allows.
 static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, const float *d_X,
-                              const float *d_bias, float *d_Y, int batch, int relu, float *part, hipStream_t st)
+                              const float *d_bias, float *d_Y, int batch, int relu, float *part, hipStream_t st,
+                              const PrevSlots *prev = nullptr, bool finish = true)
 {
     SparsePlan P;
     if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P)) return rc;
+    const PrevSlots from = prev ? *prev : PrevSlots{nullptr, nullptr, nullptr, 1, 0, 0, 0};
+    if ((prev || !finish) && !sparse_can_fold(L, P, batch)) return fail(CL_EINVAL, "internal: layer cannot take or leave partial tiles");
     const int M = L->desc.M, K = L->desc.K;
     dim3 grid;
     if (L->n_chunks > 0) GRID_TRY(grid, (int64_t)L->n_panels * P.wg_per_panel);
@@ -642,7 +691,7 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
     do {                                                                                                           \
         if (lds > 64 * 1024)                                                                                       \
             HIP_TRY(hipFuncSetAttribute((const void *)fc_sparse_kernel<BTV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-        hipLaunchKernelGGL(fc_sparse_kernel<BTV>, grid, dim3(kThreads), lds, st, D, x, part, P.wg_per_panel, xcap); \
+        hipLaunchKernelGGL(fc_sparse_kernel<BTV>, grid, dim3(kThreads), lds, st, D, x, part, P.wg_per_panel, xcap, from); \
     } while (0)
             switch (bt) {
             case 16: CL_LAUNCH_SPARSE(16); break;
@@ -655,11 +704,13 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
             HIP_TRY(hipGetLastError());
             if (b0 == 0) timing_end(st, 1);
         }
-        dim3 rgrid;
-        GRID_TRY(rgrid, (int64_t)L->n_panels * bt);
-        hipLaunchKernelGGL(fc_reduce_kernel, rgrid, dim3(kRedThreads), 0, st,
-                           D, part, d_bias, y, bt, bt, P.wg_per_panel, relu);
-        HIP_TRY(hipGetLastError());
+        if (finish) {
+            dim3 rgrid;
+            GRID_TRY(rgrid, (int64_t)L->n_panels * bt);
+            hipLaunchKernelGGL(fc_reduce_kernel, rgrid, dim3(kRedThreads), 0, st,
+                               D, part, d_bias, y, bt, bt, P.wg_per_panel, relu);
+            HIP_TRY(hipGetLastError());
+        }
         b0 += bt;
     }
     return CL_OK;
@@ -716,12 +767,26 @@ static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePl
                            d_X, xt, batch, L->desc.K, P.Bp, L->desc.block_w, rows);
         HIP_TRY(hipGetLastError());
     }
-    timing_begin(st);
     int32_t rc = CL_EINVAL;
-    switch (P.ipl) {
-    case 1: rc = launch_wide_as<1>(D, L->n_panels, P, xt, part, st); break;
-    case 2: rc = launch_wide_as<2>(D, L->n_panels, P, xt, part, st); break;
-    case 4: rc = launch_wide_as<4>(D, L->n_panels, P, xt, part, st); break;
+    if (P.two_pass) {
+        if (L->n_chunks > 0) {
+            static LdsLimit seen;
+            const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
+            if ((rc = ensure_lds((const void *)wide_expand_kernel, lds, seen))) return rc;
+            dim3 egrid;
+            GRID_TRY(egrid, (L->n_chunks + kWaves - 1) / kWaves);
+            hipLaunchKernelGGL(wide_expand_kernel, egrid, dim3(kThreads), lds, st, D, (WideEntry *)((char *)part + P.tile_bytes));
+            HIP_TRY(hipGetLastError());
+        }
+        timing_begin(st);
+        rc = launch_wide_mul(D, L->n_panels, P, xt, part, st);
+    } else {
+        timing_begin(st);
+        switch (P.ipl) {
+        case 1: rc = launch_wide_as<1>(D, L->n_panels, P, xt, part, st); break;
+        case 2: rc = launch_wide_as<2>(D, L->n_panels, P, xt, part, st); break;
+        case 4: rc = launch_wide_as<4>(D, L->n_panels, P, xt, part, st); break;
+        }
     }
     if (rc) return rc;
     timing_end(st, 1);
@@ -807,6 +872,7 @@ struct StackPlan {
     std::vector<WidePlan> wide;       // per layer on the wide sparse path
     std::vector<SparsePlan> sparse;   // per layer on the sparse path
     std::vector<char> xt_in;          // layer reads its transposed activations straight from the layer before
+    std::vector<char> fold_in;        // layer adds up the partial tiles of the layer before itself (both on the sparse path)
     size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0;
     int regions = 1;                  // copies of each buffer, used in rotation
     size_t total() const { return (size_t)regions * (xt_bytes + part_bytes + act_bytes); }
@@ -826,6 +892,7 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
     P.mfma.assign(n, MfmaPlan{});
     P.sparse.assign(n, SparsePlan{});
     P.xt_in.assign(n, 0);
+    P.fold_in.assign(n, 0);
     for (int i = 0; i < n; ++i) {
         const cl_layer *L = layers[i];
         if (!L) return fail(CL_EINVAL, "layer %d is null", i);
@@ -849,6 +916,10 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
         } else {
             if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P.sparse[i])) return rc;
             P.part_bytes = std::max(P.part_bytes, round256(P.sparse[i].part_bytes));
+            // (measured on the AlexNet-shaped stack: 39.8 -> 37.1 us at one image, no gain at
+            // two, a loss at four - every workgroup of a block column adds the same tiles up)
+            P.fold_in[i] = batch == 1 && i > 0 && P.path[i - 1] == CL_PATH_SPARSE && sparse_can_fold(layers[i - 1], P.sparse[i - 1], batch) &&
+                           sparse_can_fold(L, P.sparse[i], batch);
         }
         if (i + 1 < n) P.act_bytes = std::max(P.act_bytes, round256((size_t)batch * L->desc.M * sizeof(float)));
     }
@@ -917,7 +988,19 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
             if (rc) return rc;
             in = to_xt ? nullptr : out;
         } else {
-            if (int32_t rc = forward_sparse(L, D, dl, in, bias, out, batch, relu, (float *)region(part0, P.part_bytes, i), st)) return rc;
+            // between two layers of this path at one image the finishing kernel is left out:
+            // the next layer adds the partial tiles up as it stages its input
+            PrevSlots prev{};
+            if (P.fold_in[i]) {
+                const cl_layer *Lp = layers[i - 1];
+                prev = PrevSlots{(const float *)region(part0, P.part_bytes, i - 1), make_dev(Lp).panel_chunk,
+                                 d_bias_or_null ? d_bias_or_null[i - 1] : nullptr, Lp->desc.block_h, P.sparse[i - 1].wg_per_panel,
+                                 batch, relu_hidden};
+            }
+            const bool finish = last || !P.fold_in[i + 1];
+            if (int32_t rc = forward_sparse(L, D, dl, in, bias, out, batch, relu, (float *)region(part0, P.part_bytes, i), st,
+                                            P.fold_in[i] ? &prev : nullptr, finish))
+                return rc;
             in = out;
         }
     }

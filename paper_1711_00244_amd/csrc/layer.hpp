@@ -32,6 +32,8 @@ struct DeviceImage {
     const uint32_t *panel_chunk = nullptr;
     const uint32_t *block_chunk = nullptr;
     const uint32_t *chunk_nz = nullptr;
+    const uint32_t *chunk_half = nullptr;
+    const uint32_t *group_ptr = nullptr;
     const float *codebook = nullptr;
     const lut_t *val_lut = nullptr;
     const lut_t *idx_lut = nullptr;
@@ -54,6 +56,16 @@ struct cl_layer {
     std::vector<uint32_t> chunk_nz;                 // n_chunks + 1: surviving weights (entries that are not padding) in all
                                                     //   chunks before this one (derived)
     int64_t max_block_nnz = 0;                      // most surviving weights in one block
+    int32_t max_group_blocks = 0;                   // most blocks touched by eight consecutive chunks of a block row that start
+                                                    //   at a multiple of eight from the block row's first (the share of one
+                                                    //   workgroup of the small-batch kernel)
+    // For layers whose blocks are at most 128 x 128 (else empty), the order in which the wide
+    // path lists a block's surviving weights: first those in the block's columns 0-63, then
+    // those in columns 64-127, each half row by row (derived).
+    std::vector<uint32_t> chunk_half;               // 2 n_chunks: where in that list the chunk's first surviving weight of
+                                                    //   each half goes
+    std::vector<uint32_t> group_ptr;                // n_blocks x 2 x 17: where each group of eight rows starts in each
+                                                    //   half of the block's part of the list, and where the half ends
     std::vector<cl_chunk_meta> meta;                // n_chunks + 1
     std::vector<uint64_t> records;
     std::vector<cl::lut_t> val_lut, idx_lut;        // indexed by the next val_lut_bits / idx_lut_bits stream bits

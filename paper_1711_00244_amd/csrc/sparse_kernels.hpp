@@ -55,9 +55,22 @@ __global__ void fill_kernel(float *p, size_t n, float v)
 // the row changes.  The activation columns of the blocks the workgroup's chunks
 // belong to are staged in LDS first when they fit xcap columns; otherwise they are
 // read from global memory.  A padding entry carries codebook value 0 and adds 0.
+// Where a layer's input comes from when the layer before it ran on this path too and
+// its finishing kernel is left out (a stack of layers at one image, where a launch costs
+// as much as the work in it): the partial tiles of that layer's
+// workgroups, part[block row][slot][image][row], to be added up in slot order, plus its
+// bias, through its activation (Eq. 1) - what fc_reduce_kernel would have written as
+// X[image][k], taken by each workgroup for the columns of its own slab only.
+struct PrevSlots {
+    const float *part;              // null: the input is X
+    const uint32_t *panel_chunk;    // of the layer before: how many slots each of its block rows filled
+    const float *bias;              // of the layer before, or null
+    int bh, wg_per_panel, part_b, relu;
+};
+
 template <int BT>
 __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *part,
-                                                             int wg_per_panel, int xcap)
+                                                             int wg_per_panel, int xcap, PrevSlots prev)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
@@ -93,7 +106,31 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
     const int col_b = min(L.K, (int)(L.meta[c_last].blk - pb0 + 1u) * L.bw);
     const int width = col_b - col_a;
     const bool slab = width <= xcap;
-    if (slab) {
+    if (slab && prev.part) {
+        // (the host takes this form only for layers whose every workgroup has a slab)
+        constexpr uint32_t kPerWg = kWaves * kSparseChunksPerWave;
+        for (int t = threadIdx.x; t < width; t += blockDim.x) {
+            const int k = col_a + t, pp = k / prev.bh, r = k - pp * prev.bh;
+            const int active = (int)((prev.panel_chunk[pp + 1] - prev.panel_chunk[pp] + kPerWg - 1) / kPerWg);
+            const float *src = prev.part + (size_t)pp * prev.wg_per_panel * prev.part_b * prev.bh + r;
+            const size_t step = (size_t)prev.part_b * prev.bh;
+            const float bv = prev.bias ? prev.bias[k] : 0.0f;
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                float acc = 0.0f;
+                for (int j = 0; j < active; j += 12) {      // twelve loads in flight, added in slot order
+                    float a[12];
+#pragma unroll
+                    for (int u = 0; u < 12; ++u) a[u] = src[(size_t)(j + u < active ? j + u : j) * step + (size_t)b * prev.bh];
+#pragma unroll
+                    for (int u = 0; u < 12; ++u)
+                        if (j + u < active) acc += a[u];
+                }
+                acc += bv;
+                xs[t * BT + b] = prev.relu ? fmaxf(acc, 0.0f) : acc;
+            }
+        }
+    } else if (slab) {
 #pragma unroll
         for (int b = 0; b < BT; ++b)
             for (int t = threadIdx.x; t < width; t += blockDim.x) xs[t * BT + b] = X[(size_t)b * L.K + col_a + t];

@@ -393,3 +393,280 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(LayerDev L, const floa
         }
     }
 }
+
+// ------------------------------------------------------------------------- //
+// The wide path for tiles of 256 images, in two launches: decode to an entry
+// list, then multiply
+// ------------------------------------------------------------------------- //
+// wide_expand_kernel decodes the whole layer once per call (Algorithm 2 steps 5-9, one
+// wavefront per chunk as in decode_kernel) into a list in global memory: a block's
+// surviving weights - the padding entries dropped - in the order the multiplying kernel
+// takes them: first those in the block's columns 0-63, then those in columns 64-127,
+// each half row by row.  Where a chunk's entries go in that order does not depend on the
+// activations: the layer carries, per chunk, the list position of its first surviving
+// weight of each half (chunk_half), and, per block and half, where each group of eight
+// rows starts (group_ptr), both counted when the layer was loaded.  An entry is one word:
+// the value index (bits 16-23), the column within the half (bits 8-13) and four times the
+// row within its group of eight (bits 0-7).
+// wide_mul_kernel then holds no decode tables, decodes nothing and waits for no decoder:
+// sixteen wavefronts multiply, each owning the eight rows of one group, the weights looked
+// up in the codebook (Algorithm 2 step 8) 64 entries at a time, and every image tile of a
+// large batch reads the same list.
+typedef uint32_t WideEntry;
+constexpr int kMulRows = kTile / kWideWaves;            // rows of a block row per wavefront: a group
+constexpr int kGroupPtrs = 2 * (kWideWaves + 1);        // group_ptr words per block
+
+__global__ __launch_bounds__(kThreads) void wide_expand_kernel(LayerDev L, WideEntry *ent)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    const Smem s = carve(smem_raw, L);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const uint32_t c = blockIdx.x * kWaves + (uint32_t)wave;
+    const bool have = c < L.n_chunks;
+    ChunkHead h{};
+    LaneRecord rec{};
+    uint32_t base0 = 0, base1 = 0;
+    if (have) {
+        h = load_head(L, c);
+        rec = load_record(L, h, lane);
+        base0 = L.chunk_half[2 * (size_t)c];
+        base1 = L.chunk_half[2 * (size_t)c + 1];
+    }
+    store_tables(s, L, fetch_tables(L));
+    __syncthreads();
+    if (!have) return;
+    const BlockGeom g = block_geom(L, h.m.blk);
+    const Symbols y = decode_record(rec, s.T);
+    const LaneStart st = lane_starts(y, h.m.pos0);
+    // the lane's surviving weights per half, then where its first of each half goes
+    uint32_t mine = 0;
+    for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+        uint32_t r, cc;
+        split_pos(pos, g, r, cc);
+        if (v != 0u) mine += cc >= (uint32_t)kHalf ? 0x10000u : 1u;
+    });
+    const uint32_t excl = wave_incl_scan(mine) - mine;
+    uint32_t at0 = base0 + (excl & 0xffffu), at1 = base1 + (excl >> 16);
+    for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+        uint32_t r, cc;
+        split_pos(pos, g, r, cc);
+        if (v == 0u) return;
+        const WideEntry e = (v << 16) | ((cc & (uint32_t)(kHalf - 1)) << 8) | ((r & (uint32_t)(kMulRows - 1)) * 4u);
+        if (cc >= (uint32_t)kHalf) ent[at1++] = e;
+        else ent[at0++] = e;
+    });
+}
+
+// The multiply-add of up to 64 entries, one per lane of (entry word, weight) - lanes past
+// the last entry holding a copy of the last one with weight zero - into the sums of the
+// entries' rows: sums[4 r + q] += w * x[column][4 lane + q].  The rows differ from entry to entry
+// and the sums live in registers, so the register a product is added to is picked at run
+// time: the sums sit in v[64:95], the additions run in the vector-register index mode
+// with the entry's row offset as the index (destination and addend relative), and
+// everything between switching the mode on and off is written out here.  Entries are
+// taken four at a time, the activations of the next four requested from LDS (into
+// v[96:127], alternating halves) before the products of the present four are formed, so
+// that the loads and the arithmetic overlap from one end of the list to the other
+// whatever the rows' lengths.
+#define WM_RL(i, slot)                                                                       \
+    "v_readlane_b32 %[c" #slot "], %[vat], " #i "\n"                                         \
+    "v_readlane_b32 %[w" #slot "], %[vw], " #i "\n"
+#define WM_AD(slot, tmp)                                                                     \
+    "s_and_b32 %[" #tmp "], %[c" #slot "], 0x3f00\n"                                        \
+    "v_lshl_add_u32 v[" #slot "*4+96], %[" #tmp "], 2, %[base]\n"
+#define WM_RD(slot) "ds_read_b128 v[" #slot "*4+96:" #slot "*4+99], v[" #slot "*4+96]\n"
+#define WM_FMA1(slot)                                                                        \
+    "s_set_gpr_idx_on %[c" #slot "], 0xc\n"                                                  \
+    "v_fma_f32 v64, %[w" #slot "], v[" #slot "*4+96], v64\n"                                 \
+    "v_fma_f32 v65, %[w" #slot "], v[" #slot "*4+97], v65\n"                                 \
+    "v_fma_f32 v66, %[w" #slot "], v[" #slot "*4+98], v66\n"                                 \
+    "v_fma_f32 v67, %[w" #slot "], v[" #slot "*4+99], v67\n"
+#define WM_LOAD4(i0, i1, i2, i3, s0, s1, s2, s3)                                             \
+    WM_RL(i0, s0) WM_RL(i1, s1) WM_RL(i2, s2) WM_RL(i3, s3)                                  \
+    WM_AD(s0, t) WM_AD(s1, t2) WM_AD(s2, t) WM_AD(s3, t2)                                    \
+    WM_RD(s0) WM_RD(s1) WM_RD(s2) WM_RD(s3)
+#define WM_FMA4(s0, s1, s2, s3) WM_FMA1(s0) WM_FMA1(s1) WM_FMA1(s2) WM_FMA1(s3) "s_set_gpr_idx_off\n"
+// entries i0 .. i0 + 3 are in flight in slots (a); request i0 + 4 .. i0 + 7 into slots (b), then add (a)
+#define WM_STEP(prio, n_done, j0, j1, j2, j3, a0, a1, a2, a3, b0, b1, b2, b3)                \
+    "s_setprio " #prio "\n"                                                                  \
+    WM_LOAD4(j0, j1, j2, j3, b0, b1, b2, b3)                                                 \
+    "s_waitcnt lgkmcnt(4)\n"                                                                 \
+    WM_FMA4(a0, a1, a2, a3)                                                                  \
+    "s_cmp_le_u32 %[n], " #n_done "\n"                                                       \
+    "s_cbranch_scc1 1f\n"
+#define WM_LAST(a0, a1, a2, a3)                                                              \
+    "s_waitcnt lgkmcnt(0)\n"                                                                 \
+    WM_FMA4(a0, a1, a2, a3)
+// The four wavefronts of a SIMD would otherwise be served oldest first, finish a list one
+// after the other, and the last, alone, cannot keep the vector unit busy (one wavefront
+// issues an instruction every four to five cycles, of which 7 in 12 are vector
+// arithmetic here): each raises and lowers its priority from step to step (p0..p3), and
+// as the four are never at the same step for long, all four advance together.
+#define WM_BODY(p0, p1, p2, p3)                                                              \
+    WM_LOAD4(0, 1, 2, 3, 0, 1, 2, 3)                                                         \
+    WM_STEP(p0, 4, 4, 5, 6, 7, 0, 1, 2, 3, 4, 5, 6, 7)                                       \
+    WM_STEP(p0, 8, 8, 9, 10, 11, 4, 5, 6, 7, 0, 1, 2, 3)                                     \
+    WM_STEP(p0, 12, 12, 13, 14, 15, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_STEP(p1, 16, 16, 17, 18, 19, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
+    WM_STEP(p1, 20, 20, 21, 22, 23, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_STEP(p1, 24, 24, 25, 26, 27, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
+    WM_STEP(p2, 28, 28, 29, 30, 31, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_STEP(p2, 32, 32, 33, 34, 35, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
+    WM_STEP(p2, 36, 36, 37, 38, 39, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_STEP(p3, 40, 40, 41, 42, 43, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
+    WM_STEP(p3, 44, 44, 45, 46, 47, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_STEP(p3, 48, 48, 49, 50, 51, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
+    WM_STEP(p3, 52, 52, 53, 54, 55, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_STEP(p3, 56, 56, 57, 58, 59, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
+    WM_STEP(p3, 60, 60, 61, 62, 63, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
+    WM_LAST(4, 5, 6, 7)                                                                      \
+    "1:\n"                                                                                   \
+    "s_waitcnt lgkmcnt(0)\n"                                                                 \
+    "s_setprio 0\n"
+#define WM_OPERANDS                                                                                                           \
+    : "+{v[64:95]}"(sums), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [c4] "=&s"(c4), [c5] "=&s"(c5),   \
+      [c6] "=&s"(c6), [c7] "=&s"(c7), [w0] "=&s"(w0), [w1] "=&s"(w1), [w2] "=&s"(w2), [w3] "=&s"(w3), [w4] "=&s"(w4),         \
+      [w5] "=&s"(w5), [w6] "=&s"(w6), [w7] "=&s"(w7), [t] "=&s"(t), [t2] "=&s"(t2)                                            \
+    : [vat] "v"(vat), [vw] "v"(vw), [base] "v"(base), [n] "s"(n)                                                              \
+    : "memory", "scc", "m0", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107",      \
+      "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", \
+      "v123", "v124", "v125", "v126", "v127"
+
+typedef float WideSums __attribute__((ext_vector_type(32)));
+
+__device__ __forceinline__ void wide_fma_entries(WideSums &sums, uint32_t vat, uint32_t vw, uint32_t base, int n)
+{
+    uint32_t c0, c1, c2, c3, c4, c5, c6, c7, w0, w1, w2, w3, w4, w5, w6, w7, t, t2;
+    asm volatile(WM_BODY(3, 2, 1, 0) WM_OPERANDS);
+}
+
+// Workgroup (block row p, split j of its blocks, image tile nb) of sixteen wavefronts, one
+// to a CU.  A phase is half a block: its 64 columns' activations for the 256 images sit
+// in one of two 64 KB slabs, every wavefront multiplies its group's entries of that half,
+// and meanwhile brings in its four rows of the next phase's slab (registers first, LDS
+// after its arithmetic) and the first 64 of its next entries; one barrier ends the phase.
+__global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, const float *__restrict__ XT,
+                                                                const WideEntry *__restrict__ ent, float *part, int panels,
+                                                                int splits, int Bp)
+{
+    constexpr int IPL = 4, kImages = 64 * IPL;
+    typedef typename WideVec<IPL>::type vec_t;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    float *slabs = (float *)smem_raw;                                   // [2][kHalf][kImages]
+    float *cb = slabs + 2 * kHalf * kImages;                            // [ncode]
+    // consecutive workgroups take the splits of one block row (see fc_wide_kernel)
+    const int j = (int)blockIdx.x % splits, rest = (int)blockIdx.x / splits;
+    const int p = rest % panels, nb = rest / panels;
+    const int pj = p * splits + j;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    for (int t = (int)threadIdx.x; t < L.ncode; t += kWideThreads) cb[t] = L.codebook[t];
+    const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
+    const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
+    const int nh = L.bw > kHalf ? 2 : 1;
+    const int phases = (blk_hi - blk_lo) * nh;
+
+    // A wavefront's share of a slab: rows 4 wave .. 4 wave + 3, four floats per lane and row.  The
+    // slab of phase ph starts at row (blk_lo + ph / nh) 128 + (ph % nh) 64 of the activations: a
+    // uniform base that moves from phase to phase, and per lane a constant byte offset per row.
+    const char *xbase = (const char *)(XT + (size_t)nb * kImages);
+    uint32_t xoff[kSlabRowsPerWave];
+#pragma unroll
+    for (int q = 0; q < kSlabRowsPerWave; ++q) xoff[q] = (uint32_t)((wave * kSlabRowsPerWave + q) * Bp + lane * IPL) * 4u;
+    vec_t stage[kSlabRowsPerWave];
+    auto slab_fetch = [&](int ph) {
+        const char *src = xbase + ((size_t)(blk_lo + ph / nh) * kTile + (size_t)(ph % nh) * kHalf) * (size_t)Bp * 4;
+#pragma unroll
+        for (int q = 0; q < kSlabRowsPerWave; ++q) stage[q] = *(const vec_t *)(src + xoff[q]);
+    };
+    auto slab_store = [&](int ph) {
+        float *dst = slabs + (size_t)(ph & 1) * kHalf * kImages + (size_t)(wave * kSlabRowsPerWave) * kImages + lane * IPL;
+#pragma unroll
+        for (int q = 0; q < kSlabRowsPerWave; ++q) *(vec_t *)(dst + q * kImages) = stage[q];
+    };
+    // The wavefront's part of the list in each phase - its group of rows in that half of that
+    // block - for 64 phases at a time, phase ph0 + lane in lane `lane`: fetched ahead of
+    // the loop so that no phase starts by waiting for a pointer.
+    uint32_t seg_a = 0, seg_e = 0;
+    auto segments = [&](int ph0) {
+        const int ph = min(ph0 + lane, phases - 1);
+        const uint32_t b = pb0 + (uint32_t)(blk_lo + ph / nh);
+        const uint32_t *gp = L.group_ptr + ((size_t)b * 2 + (size_t)(ph % nh)) * (kWideWaves + 1) + wave;
+        seg_a = gp[0];
+        seg_e = gp[1];
+    };
+    auto segment = [&](int ph, uint32_t &a, uint32_t &e) {
+        a = (uint32_t)__builtin_amdgcn_readlane((int)seg_a, ph & 63);
+        e = (uint32_t)__builtin_amdgcn_readlane((int)seg_e, ph & 63);
+    };
+    // up to 64 entries from list position a on, one per lane
+    const uint32_t lane4 = (uint32_t)lane * 4u;
+    auto window = [&](uint32_t a, uint32_t e) {
+        uint32_t v = 0u;
+        if ((uint32_t)lane < e - a) v = *(const uint32_t *)((const char *)(ent + a) + lane4);
+        return v;
+    };
+    auto weight_of = [&](uint32_t entry) { return cb[(entry >> 16) & 0xffu]; };
+
+    WideSums sums;
+#pragma unroll
+    for (int q = 0; q < kMulRows * IPL; ++q) sums[q] = 0.0f;
+    if (phases > 0) {
+        uint32_t a_cur = 0, e_cur = 0;
+        segments(0);
+        segment(0, a_cur, e_cur);
+        uint32_t ev = e_cur > a_cur ? window(a_cur, e_cur) : 0u;
+        slab_fetch(0);
+        slab_store(0);
+        __syncthreads();
+        float wv = weight_of(ev);
+        for (int ph = 0; ph < phases; ++ph) {
+            const bool more = ph + 1 < phases;
+            // what the next phase needs is requested now: the first 64 of its entries and its slab rows
+            uint32_t a_nxt = 0, e_nxt = 0;
+            uint32_t evn = 0u;
+            if (more) {
+                if (((ph + 1) & 63) == 0) segments(ph + 1);
+                segment(ph + 1, a_nxt, e_nxt);
+                if (e_nxt > a_nxt) evn = window(a_nxt, e_nxt);
+                slab_fetch(ph + 1);
+            }
+            const uint32_t base = (uint32_t)(uintptr_t)(slabs + (size_t)(ph & 1) * kHalf * kImages) + (uint32_t)lane * (IPL * 4);
+            // 64 entries at a time; a second 64 (a group of rows with more than 64 surviving weights
+            // in 64 columns) are waited for where they are requested, so that the wait in front of
+            // the first counts only what was requested before it
+            uint32_t v = ev;
+            float w = wv;
+            for (uint32_t a = a_cur; a < e_cur;) {
+                const int n = (int)min(64u, e_cur - a);
+                // lanes past the last entry: that entry again with weight zero
+                const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)v, n - 1);
+                const uint32_t vat = lane < n ? v : last, vw = lane < n ? __builtin_bit_cast(uint32_t, w) : 0u;
+                wide_fma_entries(sums, vat, vw, base, n);
+                a += 64u;
+                if (a < e_cur) {
+                    v = window(a, e_cur);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+                    w = weight_of(v);
+                }
+            }
+            if (more) slab_store(ph + 1);
+            ev = evn;
+            wv = weight_of(evn);                                        // (the slab rows were waited for: so were the entries)
+            asm volatile("" : "+v"(wv));                                // looked up here, not after the next phase's requests
+            a_cur = a_nxt;
+            e_cur = e_nxt;
+            __syncthreads();
+        }
+    }
+    // the wavefront's rows of the workgroup's partial tile, part[pj][row][Bp]: a row's images are contiguous
+    float *mine = part + ((size_t)pj * kTile + (size_t)wave * kMulRows) * (size_t)Bp + (size_t)nb * kImages + (size_t)lane * IPL;
+#pragma unroll
+    for (int r = 0; r < kMulRows; ++r) {
+        vec_t v;
+#pragma unroll
+        for (int q = 0; q < IPL; ++q) v[q] = sums[r * IPL + q];
+        *(vec_t *)(mine + (size_t)r * Bp) = v;
+    }
+}

@@ -131,14 +131,21 @@ class StackRunner:
         return t
 
     def plan(self, batch_set, tot_bytes, mem_step_bytes=100 * 1024, latency_cap_ms=None, time_ms=None):
+        """The dynamic program over batch_set.  WS(i) is one figure per layer - the most
+        scratch the layer asks for at any candidate batch size - so a candidate whose
+        scratch alone breaks the budget would rule out every plan: the largest candidates
+        are dropped one by one until a plan exists (None if not even the smallest fits)."""
+        batch_set = list(batch_set)
         time_ms = self.measure_times(batch_set) if time_ms is None else np.asarray(time_ms, float)
         inb = [L.K * 4 for L in self.layers]
         outb = [L.M * 4 for L in self.layers]
-        ws = [max(cl.fc_workspace_bytes(L, B, self.path) for B in batch_set) for L in self.layers]
-        ms, bpl = cl.plan_batches(time_ms, batch_set, inb, outb, ws, tot_bytes, mem_step_bytes, latency_cap_ms)
-        if bpl is None:
-            return None
-        return Plan(bpl, ms, list(batch_set), time_ms, ws, int(tot_bytes))
+        for cut in range(len(batch_set), 0, -1):
+            bs = batch_set[:cut]
+            ws = [max(cl.fc_workspace_bytes(L, B, self.path) for B in bs) for L in self.layers]
+            ms, bpl = cl.plan_batches(time_ms[:, :cut], bs, inb, outb, ws, tot_bytes, mem_step_bytes, latency_cap_ms)
+            if bpl is not None:
+                return Plan(bpl, ms, bs, time_ms[:, :cut], ws, int(tot_bytes))
+        return None
 
 
 def simulate(runner: StackRunner, plan: Plan, arrivals_s, inputs, latency_cap_ms, clock="model"):

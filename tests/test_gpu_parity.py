@@ -313,7 +313,7 @@ def _stack(dims, blocks, rng, density=0.12):
 @pytest.mark.parametrize("dims,blocks", [((640, 384, 256, 100), [(128, 128)] * 3),          # every hand-over in the multiply layout
                                          ((300, 437, 200, 64), [(128, 128), (64, 48), (128, 128)]),   # none: ragged K, narrow blocks
                                          ((256, 256), [(128, 128)])])
-@pytest.mark.parametrize("B", [1, 4, 5, 33, 256])
+@pytest.mark.parametrize("B", [1, 2, 4, 5, 33, 256])
 def test_fc_stack_forward(dims, blocks, B):
     """A stack of layers in one call (bias and ReLU between the layers, none after the
     last): on the deterministic paths bit for bit what per-layer calls give, and every
@@ -436,6 +436,15 @@ def test_fc_stack_alexnet_batch256_and_errors():
         for li in range(3):
             a = cl.compressed_fc_forward(layers[li], a, relu=li < 2)
         assert torch.equal(Y, a)
+    # the small-batch path; at one image the stack call leaves out the finishing kernel
+    # between layers and the next layer adds the partial tiles up itself
+    for B in (1, 2, 4, 3):
+        Xd = torch.from_numpy(wl.activations(3, B)).cuda()
+        Y = cl.compressed_fc_stack_forward(layers, Xd)
+        a = Xd
+        for li in range(3):
+            a = cl.compressed_fc_forward(layers[li], a, relu=li < 2)
+        assert rel_err(Y.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= TOL, B
     with pytest.raises(cl.CLError):
         cl.compressed_fc_stack_forward([layers[2], layers[0]], torch.zeros((2, layers[2].K), device="cuda"))
     with pytest.raises(cl.CLError):

@@ -114,6 +114,42 @@ def test_oracle_decodes_library_streams(M, K, bh, bw, d, r, k):
     assert np.array_equal(hv["chunk_nz"], before[hv["chunk_meta"]["sym_off"]])
     per_block = before[m.extra["block_ptr"][1:]] - before[m.extra["block_ptr"][:-1]]
     assert hv["max_block_nnz"] == (int(per_block.max()) if per_block.size else 0)
+    # and the most blocks that eight consecutive chunks of a block row (counted from its first) touch
+    widest, pc, blk = 0, hv["panel_chunk"], hv["chunk_meta"]["blk"]
+    for p in range(len(pc) - 1):
+        for c in range(int(pc[p]), int(pc[p + 1]), 8):
+            widest = max(widest, int(blk[min(c + 8, int(pc[p + 1])) - 1]) - int(blk[c]) + 1)
+    assert hv["max_group_blocks"] == widest
+    # the order of the large-batch sparse path - per block the surviving weights of columns 0-63,
+    # then those of columns 64-127, each half row by row: where each chunk's first weight of each
+    # half goes and where each group of eight rows starts, from the oracle's entries
+    if bh <= 128 and bw <= 128:
+        bhh, bww = min(bh, M), min(bw, K)
+        nbw_ = -(-K // bww)
+        want_gp = np.zeros((len(bp) - 1, 2, 17), np.uint32)
+        want_ch = np.zeros((hv["n_chunks"], 2), np.uint32)
+        sym_off, blk_of = hv["chunk_meta"]["sym_off"], hv["chunk_meta"]["blk"]
+        start = 0
+        for b in range(len(bp) - 1):
+            bwp = min(bww, K - (b % nbw_) * bww)
+            v_b, z_b = m.extra["val"][bp[b]:bp[b + 1]], m.extra["idx"][bp[b]:bp[b + 1]].astype(np.int64)
+            pos = np.cumsum(z_b + 1) - 1
+            live = v_b != 0
+            half = (pos % bwp >= 64).astype(np.int64)
+            group = pos // bwp // 8
+            n0 = int((live & (half == 0)).sum())
+            for h in range(2):
+                sel = live & (half == h)
+                counts = np.bincount(group[sel], minlength=16)[:16]
+                want_gp[b, h, :] = start + h * n0 + np.concatenate([[0], np.cumsum(counts)])
+                before = np.concatenate([[0], np.cumsum(sel)])
+                for c in np.nonzero(blk_of[:hv["n_chunks"]] == b)[0]:
+                    want_ch[c, h] = start + h * n0 + before[sym_off[c] - bp[b]]
+            start += int(live.sum())
+        assert np.array_equal(hv["group_ptr"], want_gp)
+        assert np.array_equal(hv["chunk_half"], want_ch)
+    else:
+        assert hv["group_ptr"] is None and hv["chunk_half"] is None
     # rebuilt dense matrix from the library's entries equals the oracle's
     Wd = oracle.reconstruct(val, idx, bp, hv["codebook"], M, K, min(bh, M), min(bw, K), k)
     assert np.array_equal(Wd, oracle.dense_weights(m))
