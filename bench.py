@@ -191,7 +191,8 @@ def main():
                  "unit": "TFLOP/s", "kernel": "fc_mfma_kernel", "flops_counted": "executed dense-tile flops 2*M*K*B"}
         elif kind == "wide":
             r = {"bound": "alu", "achieved": round(useful / (ms_launch * 1e-3) / 1e12, 3), "peak": FP32_VECTOR_PEAK_TFLOPS,
-                 "unit": "TFLOP/s", "kernel": "fc_wide_kernel", "flops_counted": "2*nnz*B, all of them useful",
+                 "unit": "TFLOP/s", "kernel": "wide_mul_kernel" if B > 128 else "fc_wide_kernel",
+                 "flops_counted": "2*nnz*B, all of them useful",
                  "peak_note": "157.3 = 256 CUs x 128 lanes x 2 flops x 2.4 GHz needs packed fp32; this build issues unpacked "
                               "multiply-adds, whose ceiling is 78.6"}
         else:
@@ -207,7 +208,9 @@ def main():
         r["traffic"] = traffic
         if traffic is not None:
             r["traffic_stale"] = bool(stale)
-        r.update({"layer": "fc6", "batch": B, "launch_ms": round(ms_launch, 5)})
+        r.update({"layer": "fc6", "batch": B, "launch_ms": round(ms_launch, 5), "path": kind})
+        if kind == "wide" and B > 128:
+            r["other_launches"] = "wide_expand_kernel decodes the layer once per call before this kernel (its duration: profiles/)"
         return r, fig
 
     def roofline_for(B):
@@ -223,7 +226,7 @@ def main():
     if args.batch > 4:
         for kind in ("mfma", "wide"):
             try:
-                side[kind] = headline if headline["kernel"] == f"fc_{kind}_kernel" else kernel_roofline(kind, args.batch)[0]
+                side[kind] = headline if headline["path"] == kind else kernel_roofline(kind, args.batch)[0]
             except cl.CLError as e:
                 side[kind] = {"error": str(e)}
 

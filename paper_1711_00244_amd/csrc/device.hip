@@ -542,20 +542,27 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
     if (P.lds > dl.max_lds)
         return fail(CL_EUNSUPPORTED, "the wide sparse path keeps a block's %lld surviving weights in LDS: %zu bytes needed, %zu there",
                     (long long)L->max_block_nnz, P.lds, dl.max_lds);
-    // Split of the block rows, from a small model of a launch (cycles per workgroup: a
-    // start; per block 4 k cycles and 10 + 1.25 ipl cycles per surviving weight - measured
-    // on the AlexNet-shaped layers at 64, 128 and 256 images: 21, 23.6 and 26 k cycles per
-    // block of 1 474 weights; and the partial tiles, written and read again, as on the
-    // dense-tile path; workgroups run in rounds of one per CU).
+    // Split of the block rows, from a small model of a launch, in cycles per workgroup:
+    // a start; per block a fixed part and a part per surviving weight; the partial tiles,
+    // written and read again, as on the dense-tile path; workgroups run in rounds of one
+    // per CU.  The fused kernel (tiles of 64 and 128 images): 4 k cycles per block and
+    // 10 + 1.25 ipl per weight (21 and 23.6 k per block of 1 474 weights at 64 and 128
+    // images), 6 k for a block of at most 64 columns (one short phase).  The two launches
+    // (tiles of 256): 2 k per phase and 9 per weight in the multiplying kernel (AlexNet-
+    // shaped fc6 / fc7 / fc8 at 256 images: 68.7 / 35.1 / 24.8 us), and once per call the
+    // decoding launch, 13 k and 6 per thousand entries (16.2 / 8.5 / 8.0 us).
     const int64_t tiles = (int64_t)L->n_panels * (P.Bp / tile);
     const int cus = std::max(1, dl.cus);
-    // (a block of at most 64 columns is one short phase: 6 k, from 64 x 64 blocks at 16 images)
-    const int64_t per_block = (L->desc.block_w > kHalf ? 4000 : 6000) + (L->n_blocks ? L->nnz / L->n_blocks : 0) * (40 + 5 * P.ipl) / 4;
+    const int64_t nnz_block = L->n_blocks ? L->nnz / L->n_blocks : 0;
+    const int64_t per_block = P.two_pass ? (L->desc.block_w > kHalf ? 4000 : 2000) + nnz_block * 9
+                                         : (L->desc.block_w > kHalf ? 4000 : 6000) + nnz_block * (40 + 5 * P.ipl) / 4;
+    const int64_t start = P.two_pass ? 12000 : 15000, once = P.two_pass ? 13000 + L->entries * 6 / 1000 : 0;
     const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
     int64_t best = -1;
     for (int sp = 1; sp <= sp_max; ++sp) {
         const int64_t rounds = (tiles * sp + cus - 1) / cus, blocks = (L->nbw + sp - 1) / sp;
-        const int64_t t = rounds * (15000 + blocks * per_block) + (int64_t)L->n_panels * sp * P.Bp * kTile * (int64_t)sizeof(float) * 3 / 4000;
+        const int64_t t = once + rounds * (start + blocks * per_block) +
+                          (int64_t)L->n_panels * sp * P.Bp * kTile * (int64_t)sizeof(float) * 3 / 4000;
         if (best < 0 || t < best) {
             best = t;
             P.splits = sp;

@@ -613,51 +613,71 @@ __global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, cons
 #pragma unroll
     for (int q = 0; q < kMulRows * IPL; ++q) sums[q] = 0.0f;
     if (phases > 0) {
-        uint32_t a_cur = 0, e_cur = 0;
-        segments(0);
-        segment(0, a_cur, e_cur);
-        uint32_t ev = e_cur > a_cur ? window(a_cur, e_cur) : 0u;
-        slab_fetch(0);
-        slab_store(0);
-        __syncthreads();
-        float wv = weight_of(ev);
-        for (int ph = 0; ph < phases; ++ph) {
-            const bool more = ph + 1 < phases;
-            // what the next phase needs is requested now: the first 64 of its entries and its slab rows
-            uint32_t a_nxt = 0, e_nxt = 0;
-            uint32_t evn = 0u;
-            if (more) {
-                if (((ph + 1) & 63) == 0) segments(ph + 1);
-                segment(ph + 1, a_nxt, e_nxt);
-                if (e_nxt > a_nxt) evn = window(a_nxt, e_nxt);
-                slab_fetch(ph + 1);
+        // Requests run two phases ahead of the arithmetic: while phase ph is multiplied, the slab
+        // rows and the first 64 entries of phase ph + 1 are in registers or on their way, and
+        // those of ph + 2 are requested at the end of ph - after the rows of ph + 1 have gone
+        // from their registers into LDS - by each wavefront as it gets there, not by all
+        // sixteen at once behind the barrier.
+        // (two sets of registers take turns, the loop is written out for an even and an odd phase:
+        // handing a set on from phase to phase would make each phase wait for what it has just requested)
+        struct Ahead {
+            uint32_t a = 0, e = 0;      // the wavefront's part of the list in that phase
+            uint32_t ev = 0;            // its first 64 entries, one per lane
+            float w = 0.0f;             // and their weights
+        } even, odd;
+        // The entries are requested behind the compiler's back and before the slab rows: loads
+        // come back in order, so the wait for the slab rows (in slab_store) covers them, and a
+        // wait for them alone - which the compiler would place at the top of the next phase,
+        // where it would stall on what was requested a moment before - is never issued.
+        auto request = [&](int ph, Ahead &x) {
+            x = Ahead{};
+            if (ph >= phases) return;
+            if (ph > 0 && (ph & 63) == 0) segments(ph);
+            segment(ph, x.a, x.e);
+            if ((uint32_t)lane < x.e - x.a && x.e > x.a) {
+                const uint32_t *src = (const uint32_t *)((const char *)(ent + x.a) + lane4);
+                asm volatile("global_load_dword %0, %1, off" : "=v"(x.ev) : "v"(src) : "memory");
             }
+            slab_fetch(ph);
+        };
+        auto arrived = [&](Ahead &x) { asm volatile("" : "+v"(x.ev) : : "memory"); };
+        auto phase = [&](int ph, Ahead &cur, Ahead &nxt) {
             const uint32_t base = (uint32_t)(uintptr_t)(slabs + (size_t)(ph & 1) * kHalf * kImages) + (uint32_t)lane * (IPL * 4);
             // 64 entries at a time; a second 64 (a group of rows with more than 64 surviving weights
             // in 64 columns) are waited for where they are requested, so that the wait in front of
             // the first counts only what was requested before it
-            uint32_t v = ev;
-            float w = wv;
-            for (uint32_t a = a_cur; a < e_cur;) {
-                const int n = (int)min(64u, e_cur - a);
+            uint32_t v = cur.ev;
+            float w = cur.w;
+            for (uint32_t a = cur.a; a < cur.e;) {
+                const int n = (int)min(64u, cur.e - a);
                 // lanes past the last entry: that entry again with weight zero
                 const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)v, n - 1);
                 const uint32_t vat = lane < n ? v : last, vw = lane < n ? __builtin_bit_cast(uint32_t, w) : 0u;
                 wide_fma_entries(sums, vat, vw, base, n);
                 a += 64u;
-                if (a < e_cur) {
-                    v = window(a, e_cur);
+                if (a < cur.e) {
+                    v = window(a, cur.e);
                     __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
                     w = weight_of(v);
                 }
             }
-            if (more) slab_store(ph + 1);
-            ev = evn;
-            wv = weight_of(evn);                                        // (the slab rows were waited for: so were the entries)
-            asm volatile("" : "+v"(wv));                                // looked up here, not after the next phase's requests
-            a_cur = a_nxt;
-            e_cur = e_nxt;
+            if (ph + 1 < phases) slab_store(ph + 1);
+            arrived(nxt);
+            nxt.w = weight_of(nxt.ev);
+            asm volatile("" : "+v"(nxt.w));                             // looked up here, not behind the requests below
+            request(ph + 2, cur);
             __syncthreads();
+        };
+        segments(0);
+        request(0, even);
+        slab_store(0);
+        arrived(even);
+        request(1, odd);
+        __syncthreads();
+        even.w = weight_of(even.ev);
+        for (int ph = 0; ph < phases; ph += 2) {
+            phase(ph, even, odd);
+            if (ph + 1 < phases) phase(ph + 1, odd, even);
         }
     }
     // the wavefront's rows of the workgroup's partial tile, part[pj][row][Bp]: a row's images are contiguous
