@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 PAPER_FC_STACK_IMAGES_PER_S = {16: 1000.0 * 16 / 82.49, 256: 1000.0 * 256 / 181.84}   # Table IV, Xeon E5-2697, MKL 4 threads
 HBM_PEAK_GBS = 8000.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+LDS_PEAK_TBS = 256 * 128 * 2.4e9 / 1e12            # 256 CUs x 128 bytes per clock x 2.4 GHz
 FP32_MFMA_PEAK_TFLOPS = 157.3
 BLOCK = (128, 128)
 
@@ -209,6 +210,13 @@ def main():
         if traffic is not None:
             r["traffic_stale"] = bool(stale)
         r.update({"layer": "fc6", "batch": B, "launch_ms": round(ms_launch, 5), "path": kind})
+        if kind == "wide":
+            # what binds this kernel in practice: every surviving weight reads its column's activations for the
+            # image tile from LDS once (4 bytes per multiply-add) through a port of 128 bytes per clock and CU
+            lds_bytes = 4.0 * s0["nnz"] * B
+            r["lds"] = {"achieved": round(lds_bytes / (ms_launch * 1e-3) / 1e12, 2), "peak": LDS_PEAK_TBS, "unit": "TB/s",
+                        "frac": round(lds_bytes / (ms_launch * 1e-3) / 1e12 / LDS_PEAK_TBS, 4),
+                        "note": "4 bytes of activations from LDS per multiply-add; 256 CUs x 128 B/clk x 2.4 GHz"}
         if kind == "wide" and B > 128:
             r["other_launches"] = "wide_expand_kernel decodes the layer once per call before this kernel (its duration: profiles/)"
         return r, fig
