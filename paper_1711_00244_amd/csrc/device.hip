@@ -605,11 +605,12 @@ int32_t launch_wide_as(const LayerDev &D, int panels, const WidePlan &P, const f
 // CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images; above, when the blocks
 // fit a tile, whichever of the dense-tile path and the wide sparse path the two launch
 // models price lower (same units, both fitted to measured launches).  Measured on the
-// AlexNet-shaped stack (fc6 / fc7 / fc8, ms): sparse 0.037 / 0.024 / 0.019 at 4 images
-// and 0.061 / 0.038 / 0.028 at 5-8 (its batch tile is a power of two); dense tiles of 32
-// images 0.048 / 0.028 / 0.021; at 256 images dense tiles 0.176 / 0.095 / 0.043, wide
-// sparse 0.135 / 0.077 / 0.060 - the dense tile multiplies eleven times the necessary
-// products at a 9 % density but four at 25 %, and at 128 images its 0.105 beats 0.118.
+// AlexNet-shaped stack (fc6 / fc7 / fc8, ms per layer call): sparse 0.037 / 0.024 / 0.019
+// at 4 images and 0.061 / 0.038 / 0.028 at 5-8 (its batch tile is a power of two); dense
+// tiles of 32 images 0.048 / 0.028 / 0.021; at 256 images dense tiles 0.176 / 0.095 /
+// 0.044, wide sparse 0.102 / 0.061 / 0.054 - the dense tile multiplies eleven times the
+// necessary products at a 9 % density but four at 25 %; at 128 images (the fused wide
+// kernel) dense tiles' 0.105 beat 0.118.
 constexpr int kAutoSparseBatch = 4;
 
 int resolve_path(const cl_layer *L, int batch, int path, const DeviceLimits &dl)

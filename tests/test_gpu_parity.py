@@ -126,7 +126,8 @@ def test_fc_forward_wide_path(M, K, bh, bw, d, r, k, B):
     ragged last block row and column, blocks narrower than a slab (one phase per block),
     wider (two), lower than a tile, empty and nearly empty layers (blocks without
     entries, rows without entries), a block dense enough for several chunks per
-    decoding wavefront; both gates, and run-to-run identical."""
+    decoding wavefront; from 129 images on the two-launch form (entry list in the
+    workspace); both gates, and run-to-run identical."""
     torch = torch_cuda()
     rng = np.random.default_rng(M + K * 3 + B)
     W = rand_pruned(rng, M, K, d)
@@ -144,8 +145,8 @@ def test_fc_forward_wide_path(M, K, bh, bw, d, r, k, B):
 
 
 def test_wide_path_full_blocks_and_big_blocks():
-    """A completely dense layer (16 384 entries per block: the kernel falls back to the
-    image tile whose slabs leave room for the block's list) against the oracle, and
+    """A completely dense layer (16 384 entries per block, 512 per wavefront and phase:
+    eight fetches of 64 entries where a sparse layer needs one) against the oracle, and
     blocks above 128 x 128 refused with nothing launched."""
     torch = torch_cuda()
     rng = np.random.default_rng(9)
