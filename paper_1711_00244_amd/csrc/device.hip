@@ -578,13 +578,13 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
     return CL_OK;
 }
 
-int32_t launch_wide_mul(const LayerDev &D, int panels, const WidePlan &P, const float *xt, float *part, hipStream_t st)
+int32_t launch_wide_mul(const LayerDev &D, int panels, const WidePlan &P, const float *xt, float *part, const WideEntry *ent,
+                        hipStream_t st)
 {
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)wide_mul_kernel, P.lds, seen)) return rc;
     dim3 grid;
     GRID_TRY(grid, (int64_t)panels * P.splits * (P.Bp / 256));
-    const WideEntry *ent = (const WideEntry *)((const char *)part + P.tile_bytes);
     hipLaunchKernelGGL(wide_mul_kernel, grid, dim3(kWideThreads), P.lds, st, D, xt, ent, part, panels, P.splits, P.Bp);
     HIP_TRY(hipGetLastError());
     return CL_OK;
@@ -765,9 +765,42 @@ static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPl
     return CL_OK;
 }
 
-// One layer on the wide sparse path with launch shape P; arguments as run_mfma_layer.
+// The decoding launch of the 256-image wide path for up to kExpandJobs layers at once, each
+// into its own list.  Layers without chunks are skipped (their lists are empty).
+static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *const *ents, int n, hipStream_t st)
+{
+    ExpandJobs jobs{};
+    size_t lds = 0;
+    int64_t wgs = 0;
+    int used = 0;
+    for (int i = 0; i < n; ++i) {
+        const cl_layer *L = layers[i];
+        if (L->n_chunks == 0) continue;
+        jobs.L[used] = make_dev(L);
+        jobs.ent[used] = ents[i];
+        jobs.wg0[used] = (uint32_t)wgs;
+        wgs += (L->n_chunks + kWaves - 1) / kWaves;
+        lds = std::max(lds, table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits));
+        ++used;
+    }
+    if (!used) return CL_OK;
+    for (int i = used; i <= kExpandJobs; ++i) jobs.wg0[i] = i == used ? (uint32_t)wgs : UINT32_MAX;
+    for (int i = used; i < kExpandJobs; ++i) jobs.L[i] = jobs.L[0];
+    static LdsLimit seen;
+    if (int32_t rc = ensure_lds((const void *)wide_expand_kernel, lds, seen)) return rc;
+    dim3 egrid;
+    GRID_TRY(egrid, wgs);
+    hipLaunchKernelGGL(wide_expand_kernel, egrid, dim3(kThreads), lds, st, jobs);
+    HIP_TRY(hipGetLastError());
+    return CL_OK;
+}
+
+// One layer on the wide sparse path with launch shape P; arguments as run_mfma_layer.  On the
+// two-launch form the entry list is `ent`; with expanded it has been written already (by a
+// launch_wide_expand that took several layers of a stack together).
 static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePlan &P, const float *d_X, float *xt, float *part,
-                              const float *d_bias, float *d_Y, int next_bp, int batch, int relu, hipStream_t st)
+                              WideEntry *ent, bool expanded, const float *d_bias, float *d_Y, int next_bp, int batch, int relu,
+                              hipStream_t st)
 {
     if (d_X) {
         const int rows = L->nbw * kTile;
@@ -777,17 +810,10 @@ static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePl
     }
     int32_t rc = CL_EINVAL;
     if (P.two_pass) {
-        if (L->n_chunks > 0) {
-            static LdsLimit seen;
-            const size_t lds = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
-            if ((rc = ensure_lds((const void *)wide_expand_kernel, lds, seen))) return rc;
-            dim3 egrid;
-            GRID_TRY(egrid, (L->n_chunks + kWaves - 1) / kWaves);
-            hipLaunchKernelGGL(wide_expand_kernel, egrid, dim3(kThreads), lds, st, D, (WideEntry *)((char *)part + P.tile_bytes));
-            HIP_TRY(hipGetLastError());
-        }
+        if (!expanded)
+            if ((rc = launch_wide_expand(&L, &ent, 1, st))) return rc;
         timing_begin(st);
-        rc = launch_wide_mul(D, L->n_panels, P, xt, part, st);
+        rc = launch_wide_mul(D, L->n_panels, P, xt, part, ent, st);
     } else {
         timing_begin(st);
         switch (P.ipl) {
@@ -811,7 +837,8 @@ static int32_t forward_wide(const cl_layer *L, const LayerDev &D, const DeviceLi
 {
     WidePlan P;
     if (int32_t rc = plan_wide(L, batch, dl, P)) return rc;
-    return run_wide_layer(L, D, P, d_X, (float *)ws, (float *)(ws + P.xt_bytes), d_bias, d_Y, 0, batch, relu, st);
+    return run_wide_layer(L, D, P, d_X, (float *)ws, (float *)(ws + P.xt_bytes), (WideEntry *)(ws + P.xt_bytes + P.tile_bytes), false,
+                          d_bias, d_Y, 0, batch, relu, st);
 }
 
 static int32_t forward_mfma(const cl_layer *L, const LayerDev &D, const DeviceLimits &dl, bool bf16, const float *d_X,
@@ -881,9 +908,10 @@ struct StackPlan {
     std::vector<SparsePlan> sparse;   // per layer on the sparse path
     std::vector<char> xt_in;          // layer reads its transposed activations straight from the layer before
     std::vector<char> fold_in;        // layer adds up the partial tiles of the layer before itself (both on the sparse path)
-    size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0;
+    std::vector<size_t> ent_off;      // per layer on the two-launch wide path: its entry list in the area behind the rotating buffers
+    size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0, ent_bytes = 0;
     int regions = 1;                  // copies of each buffer, used in rotation
-    size_t total() const { return (size_t)regions * (xt_bytes + part_bytes + act_bytes); }
+    size_t total() const { return (size_t)regions * (xt_bytes + part_bytes + act_bytes) + ent_bytes; }
 };
 
 size_t round256(size_t n) { return (n + 255) / 256 * 256; }
@@ -901,6 +929,7 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
     P.sparse.assign(n, SparsePlan{});
     P.xt_in.assign(n, 0);
     P.fold_in.assign(n, 0);
+    P.ent_off.assign(n, 0);
     for (int i = 0; i < n; ++i) {
         const cl_layer *L = layers[i];
         if (!L) return fail(CL_EINVAL, "layer %d is null", i);
@@ -914,7 +943,9 @@ int32_t plan_stack(const cl_layer *const *layers, int n, int batch, int path, co
         if (P.path[i] == CL_PATH_SPARSE_WIDE) {
             if (int32_t rc = plan_wide(L, batch, dl, P.wide[i])) return rc;
             P.xt_bytes = std::max(P.xt_bytes, P.wide[i].xt_bytes);
-            P.part_bytes = std::max(P.part_bytes, round256(P.wide[i].part_bytes));
+            P.part_bytes = std::max(P.part_bytes, round256(P.wide[i].tile_bytes));
+            P.ent_off[i] = P.ent_bytes;
+            P.ent_bytes += round256(P.wide[i].ent_bytes);
             P.xt_in[i] = i > 0 && reads_xt(P.path[i - 1]) && plain_rows;
         } else if (is_mfma(P.path[i])) {
             if (int32_t rc = plan_mfma(L, batch, P.path[i] == CL_PATH_MFMA_BF16, dl, P.mfma[i])) return rc;
@@ -974,6 +1005,28 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
     const int R = P.regions;
     auto region = [&](size_t base, size_t bytes, int i) { return ws + base + (size_t)(i % R) * bytes; };
     const size_t xt0 = 0, part0 = (size_t)R * P.xt_bytes, act0 = part0 + (size_t)R * P.part_bytes;
+    // The layers on the two-launch wide path are decoded up front, kExpandJobs to a launch: the
+    // lists depend on the weights only, and one launch for two layers is shorter than two
+    // (the fixed part of such a launch - start, tables, the dependent loads - is a third of fc7's).
+    const size_t ent0 = act0 + (size_t)R * P.act_bytes;
+    auto ent_of = [&](int i) { return (WideEntry *)(ws + ent0 + P.ent_off[i]); };
+    {
+        const cl_layer *todo[kExpandJobs];
+        WideEntry *ents[kExpandJobs];
+        int n = 0;
+        for (int i = 0; i <= n_layers; ++i) {
+            const bool mine = i < n_layers && P.path[i] == CL_PATH_SPARSE_WIDE && P.wide[i].two_pass;
+            if (mine) {
+                todo[n] = layers[i];
+                ents[n] = ent_of(i);
+                ++n;
+            }
+            if (n == kExpandJobs || (i == n_layers && n > 0)) {
+                if (int32_t rc = launch_wide_expand(todo, ents, n, st)) return rc;
+                n = 0;
+            }
+        }
+    }
     const float *in = d_X;              // the layer's input as batch x K, or null when it sits in its xt region
     for (int i = 0; i < n_layers; ++i) {
         const cl_layer *L = layers[i];
@@ -990,7 +1043,8 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
             const int next_bp = !to_xt ? 0 : P.path[i + 1] == CL_PATH_SPARSE_WIDE ? P.wide[i + 1].Bp : P.mfma[i + 1].Bp;
             int32_t rc;
             if (P.path[i] == CL_PATH_SPARSE_WIDE)
-                rc = run_wide_layer(L, D, P.wide[i], in, (float *)region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i), bias, dst, next_bp, batch, relu, st);
+                rc = run_wide_layer(L, D, P.wide[i], in, (float *)region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i),
+                                    ent_of(i), true, bias, dst, next_bp, batch, relu, st);
             else
                 rc = run_mfma_layer(L, D, P.mfma[i], in, region(xt0, P.xt_bytes, i), (float *)region(part0, P.part_bytes, i), bias, dst, next_bp, batch, relu, st);
             if (rc) return rc;

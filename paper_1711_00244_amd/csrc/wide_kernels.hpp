@@ -416,13 +416,28 @@ typedef uint32_t WideEntry;
 constexpr int kMulRows = kTile / kWideWaves;            // rows of a block row per wavefront: a group
 constexpr int kGroupPtrs = 2 * (kWideWaves + 1);        // group_ptr words per block
 
-__global__ __launch_bounds__(kThreads) void wide_expand_kernel(LayerDev L, WideEntry *ent)
+// (One launch can decode several layers - those of a stack that take this path - each into
+// its own list: workgroups wg0[i] .. wg0[i + 1] - 1 belong to job i.)
+constexpr int kExpandJobs = 4;
+struct ExpandJobs {
+    LayerDev L[kExpandJobs];
+    WideEntry *ent[kExpandJobs];
+    uint32_t wg0[kExpandJobs + 1];
+};
+
+__global__ __launch_bounds__(kThreads) void wide_expand_kernel(ExpandJobs jobs)
 {
+    int job = 0;
+#pragma unroll
+    for (int i = 1; i < kExpandJobs; ++i)
+        if (blockIdx.x >= jobs.wg0[i]) job = i;
+    const LayerDev &L = jobs.L[job];
+    WideEntry *ent = jobs.ent[job];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    const uint32_t c = blockIdx.x * kWaves + (uint32_t)wave;
+    const uint32_t c = (blockIdx.x - jobs.wg0[job]) * kWaves + (uint32_t)wave;
     const bool have = c < L.n_chunks;
     ChunkHead h{};
     LaneRecord rec{};
@@ -561,7 +576,6 @@ __global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, cons
     const int pj = p * splits + j;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63);
-    for (int t = (int)threadIdx.x; t < L.ncode; t += kWideThreads) cb[t] = L.codebook[t];
     const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     const int nh = L.bw > kHalf ? 2 : 1;
@@ -625,11 +639,10 @@ __global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, cons
             uint32_t ev = 0;            // its first 64 entries, one per lane
             float w = 0.0f;             // and their weights
         } even, odd;
-        // The entries are requested behind the compiler's back and before the slab rows: loads
-        // come back in order, so the wait for the slab rows (in slab_store) covers them, and a
-        // wait for them alone - which the compiler would place at the top of the next phase,
-        // where it would stall on what was requested a moment before - is never issued.
-        auto request = [&](int ph, Ahead &x) {
+        // The entries are requested behind the compiler's back and waited for by hand (arrived): a
+        // wait of the compiler's own would stand at the top of the next phase, where it would stall
+        // on what was requested a moment before.
+        auto request_entries = [&](int ph, Ahead &x) {
             x = Ahead{};
             if (ph >= phases) return;
             if (ph > 0 && (ph & 63) == 0) segments(ph);
@@ -638,9 +651,16 @@ __global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, cons
                 const uint32_t *src = (const uint32_t *)((const char *)(ent + x.a) + lane4);
                 asm volatile("global_load_dword %0, %1, off" : "=v"(x.ev) : "v"(src) : "memory");
             }
-            slab_fetch(ph);
         };
-        auto arrived = [&](Ahead &x) { asm volatile("" : "+v"(x.ev) : : "memory"); };
+        auto request = [&](int ph, Ahead &x) {
+            request_entries(ph, x);
+            if (ph < phases) slab_fetch(ph);
+        };
+        // (nothing younger than the entries is in flight where this is called, so the wait is for them alone)
+        auto arrived = [&](Ahead &x) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
+            asm volatile("" : "+v"(x.ev) : : "memory");
+        };
         auto phase = [&](int ph, Ahead &cur, Ahead &nxt) {
             const uint32_t base = (uint32_t)(uintptr_t)(slabs + (size_t)(ph & 1) * kHalf * kImages) + (uint32_t)lane * (IPL * 4);
             // 64 entries at a time; a second 64 (a group of rows with more than 64 surviving weights
@@ -668,8 +688,13 @@ __global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, cons
             request(ph + 2, cur);
             __syncthreads();
         };
+        // what the first phase needs, all requested before anything is waited for: the first slab
+        // rows, the pointers, the codebook; then the entries (they need the pointers)
+        slab_fetch(0);
         segments(0);
-        request(0, even);
+        const float cbv = (int)threadIdx.x < L.ncode ? L.codebook[threadIdx.x] : 0.0f;
+        request_entries(0, even);
+        if ((int)threadIdx.x < L.ncode) cb[threadIdx.x] = cbv;
         slab_store(0);
         arrived(even);
         request(1, odd);
