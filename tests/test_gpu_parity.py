@@ -398,6 +398,27 @@ def test_fc_stack_replays_from_a_captured_graph(B):
         L.free()
 
 
+def test_fc_stack_of_six_wide_layers():
+    """Six layers on the wide sparse path at 256 images: the stack call decodes its layers in
+    launches of up to four up front, so six take two; bit for bit what per-layer calls
+    give, every layer gated on the input it was given."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(606)
+    dims = (300, 256, 140, 384, 200, 130, 64)
+    layers, dense = _stack(dims, [(128, 128)] * 6, rng, density=0.15)
+    X = np.maximum(rng.standard_normal((256, dims[0])), 0).astype(np.float32)
+    Xd = torch.from_numpy(X).cuda()
+    Y = cl.compressed_fc_stack_forward(layers, Xd, path=cl.PATH_SPARSE_WIDE)
+    a = Xd
+    for li in range(6):
+        given = a
+        a = cl.compressed_fc_forward(layers[li], given, relu=li < 5, path=cl.PATH_SPARSE_WIDE)
+        assert_close(a.cpu().numpy(), fc_ref(dense[li], given.cpu().numpy()), li < 5, what=li)
+    assert torch.equal(Y, a)
+    for L in layers:
+        L.free()
+
+
 def test_fc_stack_mixed_paths():
     """A stack whose middle layer has 256-wide blocks: CL_PATH_AUTO runs it on the sparse
     path between two dense-tile layers (batch 33), all three on the sparse path at
