@@ -309,6 +309,33 @@ int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers, int32_t n_
                                        int32_t relu_hidden, int32_t relu_last, int32_t path, void *d_workspace,
                                        size_t workspace_bytes, void *stream);
 
+/* Several layers of one shape in one grid (Sec. V: requests for different models, or layers
+ * whose inputs do not depend on each other, served together; Algorithm 2 per layer on the
+ * small-batch kernel).  One launch does the decode-and-multiply of all n layers, one the
+ * finishing - where n calls of cl_compressed_fc_forward pay 2 n launches and n times the
+ * fixed part of a launch.
+ * cl_layer_group_create: layers must be uploaded to the current device and agree in M, K,
+ * block_h and block_w (CL_EINVAL otherwise); the group keeps the pointers, not the layers:
+ * they must outlive it.  The group owns a small device table; free it with
+ * cl_layer_group_free (NULL is allowed).
+ * cl_compressed_fc_group_forward:
+ *  batch           1 .. 16 images per layer (one batch tile of the small-batch kernel; more
+ *                  is CL_EUNSUPPORTED)
+ *  d_X             layer i's input, batch x K fp32, at d_X + i * x_stride (x_stride in
+ *                  floats; 0: every layer reads the same input)
+ *  d_bias_or_null  NULL, or layer i's M fp32 at d_bias + i * bias_stride (0: shared)
+ *  d_Y             layer i's output, batch x M fp32, at d_Y + i * batch * M; overwritten
+ *  d_workspace     at least cl_fc_group_workspace_bytes(), 256-byte aligned
+ * Results as CL_PATH_SPARSE gives them (tolerance-identical from call to call).
+ * Errors: CL_EINVAL, CL_EUNSUPPORTED, CL_EHIP - nothing is launched on the first two. */
+typedef struct cl_layer_group cl_layer_group;
+int32_t cl_layer_group_create(const cl_layer *const *layers, int32_t n_layers, cl_layer_group **out);
+void cl_layer_group_free(cl_layer_group *group);
+int32_t cl_fc_group_workspace_bytes(const cl_layer_group *group, int32_t batch, size_t *out);
+int32_t cl_compressed_fc_group_forward(const cl_layer_group *group, const float *d_X, size_t x_stride,
+                                       const float *d_bias_or_null, size_t bias_stride, float *d_Y, int32_t batch,
+                                       int32_t relu, void *d_workspace, size_t workspace_bytes, void *stream);
+
 /* Convolution geometry.  The layer's matrix has M = out_channels rows and
  * K = (C / groups) * R * S columns, row oc being filter oc flattened as
  * ((c * R + r) * S + s) (Sec. III-A: filters become rows, receptive fields

@@ -23,7 +23,8 @@ EXPORTS = [
     "cl_last_error", "cl_compress_layer", "cl_layer_upload", "cl_layer_free", "cl_layer_stats",
     "cl_layer_host_view", "cl_layer_serialize", "cl_layer_deserialize", "cl_decode_layer",
     "cl_fc_workspace_bytes", "cl_fc_resolved_path", "cl_compressed_fc_forward", "cl_compressed_fc_forward_static", "cl_fc_stack_workspace_bytes",
-    "cl_compressed_fc_stack_forward", "cl_conv_workspace_bytes", "cl_conv_workspace_bytes_min",
+    "cl_compressed_fc_stack_forward", "cl_layer_group_create", "cl_layer_group_free", "cl_fc_group_workspace_bytes",
+    "cl_compressed_fc_group_forward", "cl_conv_workspace_bytes", "cl_conv_workspace_bytes_min",
     "cl_compressed_conv_forward", "cl_plan_batches", "cl_maxpool_forward", "cl_lrn_forward",
     "cl_set_kernel_timing", "cl_last_kernel_ms",
 ]
@@ -101,6 +102,9 @@ def lib():
     L.cl_compressed_fc_forward.argtypes = [p, p, p, p, i32, i32, i32, p, sz, p]
     L.cl_fc_stack_workspace_bytes.argtypes = [p, i32, i32, i32, C.POINTER(sz)]
     L.cl_compressed_fc_stack_forward.argtypes = [p, i32, p, p, p, i32, i32, i32, i32, p, sz, p]
+    L.cl_layer_group_create.argtypes = [p, i32, C.POINTER(p)]
+    L.cl_fc_group_workspace_bytes.argtypes = [p, i32, C.POINTER(sz)]
+    L.cl_compressed_fc_group_forward.argtypes = [p, p, sz, p, sz, p, i32, i32, p, sz, p]
     L.cl_conv_workspace_bytes.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
     L.cl_conv_workspace_bytes_min.argtypes = [p, C.POINTER(ConvDesc), i32, i32, C.POINTER(sz)]
     L.cl_compressed_conv_forward.argtypes = [p, C.POINTER(ConvDesc), p, p, p, i32, i32, i32, p, sz, p]
@@ -110,8 +114,10 @@ def lib():
     L.cl_set_kernel_timing.argtypes = [i32]
     L.cl_last_kernel_ms.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
     for name in EXPORTS:
-        if name != "cl_last_error":
+        if name not in ("cl_last_error", "cl_layer_group_free"):
             getattr(L, name).restype = i32
+    L.cl_layer_group_free.restype = None
+    L.cl_layer_group_free.argtypes = [C.c_void_p]
     _lib = L
     return L
 
@@ -304,7 +310,7 @@ def compressed_fc_forward(layer: Layer, X, bias=None, relu=False, path=PATH_AUTO
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().cl_compressed_fc_forward(layer.handle, _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B, int(relu), path,
-                                          _dev_ptr(workspace), wbytes, _stream()))
+                                          _dev_ptr(workspace), C.c_size_t(wbytes), _stream()))
     return Y
 
 
@@ -355,8 +361,60 @@ def compressed_fc_stack_forward(layers, X, biases=None, relu_hidden=True, relu_l
         bias_ptrs = (C.c_void_p * len(layers))(*[None if b is None else _dev_ptr(b).value for b in biases])
     _check(lib().cl_compressed_fc_stack_forward(_handles(layers), len(layers), _dev_ptr(X), bias_ptrs, _dev_ptr(Y), B,
                                                 int(relu_hidden), int(relu_last), path, _dev_ptr(workspace),
-                                                workspace.numel() * workspace.element_size(), _stream()))
+                                                C.c_size_t(workspace.numel() * workspace.element_size()), _stream()))
     return Y
+
+
+class LayerGroup:
+    """Several uploaded layers of one shape, run in one grid (cl_layer_group_*)."""
+
+    def __init__(self, layers):
+        self.layers = list(layers)                       # kept alive: the group holds pointers to them
+        h = C.c_void_p()
+        _check(lib().cl_layer_group_create(_handles(self.layers), len(self.layers), C.byref(h)))
+        self.handle = h
+
+    def free(self):
+        if self.handle:
+            lib().cl_layer_group_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    def workspace_bytes(self, batch: int) -> int:
+        n = C.c_size_t(0)
+        _check(lib().cl_fc_group_workspace_bytes(self.handle, batch, C.byref(n)))
+        return n.value
+
+    def forward(self, X, bias=None, relu=False, out=None, workspace=None):
+        """X: (n, B, K) - one input per layer - or (B, K) shared by all; bias (n, M), (M,) or
+        None -> (n, B, M) fp32 CUDA tensor."""
+        import torch
+        n, L0 = len(self.layers), self.layers[0]
+        if X.dtype != torch.float32 or X.dim() not in (2, 3) or X.shape[-1] != L0.K or (X.dim() == 3 and X.shape[0] != n):
+            raise ValueError(f"X must be ({n}, B, {L0.K}) or (B, {L0.K}) float32")
+        B = X.shape[-2]
+        _want(X, tuple(X.shape), "X")
+        x_stride = B * L0.K if X.dim() == 3 else 0
+        bias_stride = 0
+        if bias is not None:
+            if bias.dim() == 2:
+                _want(bias, (n, L0.M), "bias")
+                bias_stride = L0.M
+            else:
+                _want(bias, (L0.M,), "bias")
+        _want(out, (n, B, L0.M), "out")
+        Y = out if out is not None else torch.empty((n, B, L0.M), dtype=torch.float32, device=X.device)
+        if workspace is None:
+            workspace = torch.empty(max(256, self.workspace_bytes(B)), dtype=torch.uint8, device=X.device)
+        _check(lib().cl_compressed_fc_group_forward(self.handle, _dev_ptr(X), C.c_size_t(x_stride), _dev_ptr(bias) if bias is not None else None,
+                                                    C.c_size_t(bias_stride), _dev_ptr(Y), B, int(relu), _dev_ptr(workspace),
+                                                    C.c_size_t(workspace.numel() * workspace.element_size()), _stream()))
+        return Y
 
 
 def conv_workspace_bytes(layer: Layer, conv: dict, batch: int, path: int = PATH_AUTO, compact: bool = False) -> int:
@@ -386,7 +444,7 @@ def compressed_conv_forward(layer: Layer, conv: dict, X, bias=None, relu=False, 
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().cl_compressed_conv_forward(layer.handle, C.byref(cd), _dev_ptr(X), _dev_ptr(bias), _dev_ptr(Y), B,
-                                            int(relu), path, _dev_ptr(workspace), wbytes, _stream()))
+                                            int(relu), path, _dev_ptr(workspace), C.c_size_t(wbytes), _stream()))
     return Y
 
 

@@ -25,6 +25,7 @@
 #include <climits>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <vector>
 
 #include "layer.hpp"
@@ -1066,6 +1067,149 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
             in = out;
         }
     }
+    clear_error();
+    return CL_OK;
+}
+
+// ------------------------------------------------------------------------- //
+// several layers of one shape in one grid
+// ------------------------------------------------------------------------- //
+struct cl_layer_group {
+    std::vector<const cl_layer *> layers;
+    LayerDev *table = nullptr;        // device copy of the layers' LayerDev, in order
+    int device = -1;
+    int64_t max_panel_chunks = 0;     // over all layers
+    size_t table_bytes = 0;           // largest table image (LDS) of any layer
+    bool any_chunks = false;
+};
+
+namespace {
+
+struct GroupPlan {
+    SparsePlan sp;
+    uint32_t wgs_per_layer = 0;
+    size_t part_stride = 0;           // floats between the layers' partial tiles
+    size_t lds = 0;
+    int xcap = 0;
+};
+
+int32_t plan_group(const cl_layer_group *G, int batch, const DeviceLimits &dl, GroupPlan &P)
+{
+    const cl_layer *L = G->layers[0];
+    if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
+    if (batch > 16 || (batch & (batch - 1))) return fail(CL_EUNSUPPORTED, "a group call takes 1, 2, 4, 8 or 16 images per layer");
+    if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P.sp)) return rc;
+    if (P.sp.bt_max < batch) return fail(CL_EUNSUPPORTED, "%d images do not fit one batch tile of this layer shape", batch);
+    const int bt = batch;
+    P.sp.bt_max = bt;
+    P.sp.fixed = G->table_bytes;
+    P.sp.wg_per_panel = (int)((G->max_panel_chunks + kWaves * kSparseChunksPerWave - 1) / (kWaves * kSparseChunksPerWave));
+    P.wgs_per_layer = (uint32_t)std::max<int64_t>(1, (int64_t)L->n_panels * P.sp.wg_per_panel);
+    P.part_stride = (size_t)P.wgs_per_layer * L->desc.block_h * bt;
+    P.lds = P.sp.lds_for(L, bt);
+    if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the layers' tables and a tile of %d images need more LDS than a workgroup has", bt);
+    P.xcap = P.sp.xcap_for(bt);
+    return CL_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t cl_layer_group_create(const cl_layer *const *layers, int32_t n_layers, cl_layer_group **out)
+{
+    if (!layers || !out || n_layers < 1) return fail(CL_EINVAL, "a group needs at least one layer");
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    std::unique_ptr<cl_layer_group> G(new cl_layer_group());
+    std::vector<LayerDev> host;
+    for (int i = 0; i < n_layers; ++i) {
+        const cl_layer *L = layers[i];
+        if (int32_t rc = require_device(L)) return rc;
+        const cl_layer *F = layers[0];
+        if (L->desc.M != F->desc.M || L->desc.K != F->desc.K || L->desc.block_h != F->desc.block_h || L->desc.block_w != F->desc.block_w)
+            return fail(CL_EINVAL, "layer %d differs from layer 0 in shape or block size", i);
+        G->layers.push_back(L);
+        host.push_back(make_dev(L));
+        G->max_panel_chunks = std::max(G->max_panel_chunks, L->max_panel_chunks);
+        G->table_bytes = std::max(G->table_bytes, table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits));
+        G->any_chunks = G->any_chunks || L->n_chunks > 0;
+    }
+    G->device = dev;
+    if (hipMalloc((void **)&G->table, host.size() * sizeof(LayerDev)) != hipSuccess)
+        return fail(CL_ENOMEM, "hipMalloc of the group table failed");
+    if (hipMemcpy(G->table, host.data(), host.size() * sizeof(LayerDev), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(G->table);
+        return fail(CL_EHIP, "hipMemcpy of the group table failed");
+    }
+    *out = G.release();
+    clear_error();
+    return CL_OK;
+}
+
+extern "C" void cl_layer_group_free(cl_layer_group *G)
+{
+    if (!G) return;
+    if (G->table) (void)hipFree(G->table);
+    delete G;
+}
+
+extern "C" int32_t cl_fc_group_workspace_bytes(const cl_layer_group *G, int32_t batch, size_t *out)
+{
+    if (!G || !out) return fail(CL_EINVAL, "null argument");
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    GroupPlan P;
+    if (int32_t rc = plan_group(G, batch, dl, P)) return rc;
+    *out = G->layers.size() * P.part_stride * sizeof(float);
+    return CL_OK;
+}
+
+extern "C" int32_t cl_compressed_fc_group_forward(const cl_layer_group *G, const float *d_X, size_t x_stride,
+                                                  const float *d_bias_or_null, size_t bias_stride, float *d_Y, int32_t batch,
+                                                  int32_t relu, void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!G || !d_X || !d_Y) return fail(CL_EINVAL, "null argument");
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != G->device) return fail(CL_EINVAL, "the group was created on device %d, the current device is %d", G->device, dev);
+    DeviceLimits dl;
+    if (int32_t rc = device_limits(dl)) return rc;
+    GroupPlan P;
+    if (int32_t rc = plan_group(G, batch, dl, P)) return rc;
+    const size_t n = G->layers.size(), need = n * P.part_stride * sizeof(float);
+    if (workspace_bytes < need || !d_workspace) return fail(CL_EINVAL, "workspace too small: %zu < %zu", workspace_bytes, need);
+    if ((uintptr_t)d_workspace % 256) return fail(CL_EINVAL, "workspace must be 256-byte aligned");
+    const cl_layer *L = G->layers[0];
+    hipStream_t st = (hipStream_t)stream;
+    float *part = (float *)d_workspace;
+    const int bt = P.sp.bt_max;
+    if (G->any_chunks) {
+        dim3 grid;
+        GRID_TRY(grid, (int64_t)n * P.wgs_per_layer);
+        timing_begin(st);
+#define CL_LAUNCH_GROUP(BTV)                                                                                        \
+    do {                                                                                                            \
+        if (P.lds > 64 * 1024)                                                                                      \
+            HIP_TRY(hipFuncSetAttribute((const void *)fc_sparse_group_kernel<BTV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)P.lds)); \
+        hipLaunchKernelGGL(fc_sparse_group_kernel<BTV>, grid, dim3(kThreads), P.lds, st, G->table, P.wgs_per_layer, d_X, x_stride, part, \
+                           P.part_stride, P.sp.wg_per_panel, P.xcap);                                               \
+    } while (0)
+        switch (bt) {
+        case 16: CL_LAUNCH_GROUP(16); break;
+        case 8: CL_LAUNCH_GROUP(8); break;
+        case 4: CL_LAUNCH_GROUP(4); break;
+        case 2: CL_LAUNCH_GROUP(2); break;
+        default: CL_LAUNCH_GROUP(1); break;
+        }
+#undef CL_LAUNCH_GROUP
+        HIP_TRY(hipGetLastError());
+        timing_end(st, 1);
+    }
+    const int red_per_layer = L->n_panels * bt;
+    dim3 rgrid;
+    GRID_TRY(rgrid, (int64_t)n * red_per_layer);
+    hipLaunchKernelGGL(fc_reduce_group_kernel, rgrid, dim3(kRedThreads), 0, st, G->table, red_per_layer, part, P.part_stride,
+                       d_bias_or_null, bias_stride, d_Y, (size_t)batch * L->desc.M, bt, P.sp.wg_per_panel, relu);
+    HIP_TRY(hipGetLastError());
     clear_error();
     return CL_OK;
 }

@@ -68,13 +68,14 @@ struct PrevSlots {
     int bh, wg_per_panel, part_b, relu;
 };
 
+// (wg: the workgroup's number within the layer's share of the grid)
 template <int BT>
-__global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *part,
-                                                             int wg_per_panel, int xcap, PrevSlots prev)
+__device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *__restrict__ X, float *part, int wg_per_panel,
+                                               int xcap, const PrevSlots &prev, uint32_t wg)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    const int p = (int)(blockIdx.x / (uint32_t)wg_per_panel), j = (int)(blockIdx.x % (uint32_t)wg_per_panel);
+    const int p = (int)(wg / (uint32_t)wg_per_panel), j = (int)(wg % (uint32_t)wg_per_panel);
     const uint32_t pc1 = L.panel_chunk[p + 1];
     const uint32_t my0 = L.panel_chunk[p] + (uint32_t)j * (kWaves * kSparseChunksPerWave);
     if (my0 >= pc1) return;
@@ -198,8 +199,30 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
         }
     }
     __syncthreads();
-    float *mine = part + (size_t)blockIdx.x * L.bh * BT;
+    float *mine = part + (size_t)wg * L.bh * BT;
     for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) mine[t] = ytile[t];
+}
+
+template <int BT>
+__global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *part,
+                                                             int wg_per_panel, int xcap, PrevSlots prev)
+{
+    fc_sparse_body<BT>(L, X, part, wg_per_panel, xcap, prev, blockIdx.x);
+}
+
+// Several layers of one shape in one grid (the same layer of several models, or layers
+// whose inputs do not depend on each other): workgroups wgs_per_layer i ..
+// wgs_per_layer (i + 1) - 1 do layer i's share of Algorithm 2, from its own input
+// (x_stride floats apart; 0: one input for all) into its own partial tiles.
+template <int BT>
+__global__ __launch_bounds__(kThreads) void fc_sparse_group_kernel(const LayerDev *__restrict__ table, uint32_t wgs_per_layer,
+                                                                   const float *__restrict__ X, size_t x_stride, float *part,
+                                                                   size_t part_stride, int wg_per_panel, int xcap)
+{
+    const uint32_t job = blockIdx.x / wgs_per_layer, wg = blockIdx.x - job * wgs_per_layer;
+    const LayerDev L = table[job];
+    fc_sparse_body<BT>(L, X + job * x_stride, part + job * part_stride, wg_per_panel, xcap,
+                       PrevSlots{nullptr, nullptr, nullptr, 1, 0, 0, 0}, wg);
 }
 
 // Finishes the sparse path: adds up the partial tiles of each block row in a fixed
@@ -210,12 +233,11 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const f
 // with twelve loads in flight, LDS adds the slices in order.
 constexpr int kRedThreads = 512;
 
-__global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
-                                                                const float *__restrict__ bias, float *Y, int B,
-                                                                int part_b, int wg_per_panel, int relu)
+__device__ __forceinline__ void fc_reduce_body(const LayerDev &L, const float *__restrict__ part, const float *__restrict__ bias,
+                                               float *Y, int B, int part_b, int wg_per_panel, int relu, int wg)
 {
     __shared__ float slice_sum[kRedThreads];
-    const int p = (int)blockIdx.x / B, b = (int)blockIdx.x - p * B;
+    const int p = wg / B, b = wg - p * B;
     const int row_id = p * L.bh;
     const int bhp = min(L.bh, L.M - row_id);
     // the sparse kernel fills one slot per workgroup's worth of chunks of the block row
@@ -257,4 +279,24 @@ __global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, cons
             Y[(size_t)b * L.M + row_id + r] = relu ? fmaxf(acc, 0.0f) : acc;
         }
     }
+}
+
+__global__ __launch_bounds__(kRedThreads) void fc_reduce_kernel(LayerDev L, const float *__restrict__ part,
+                                                                const float *__restrict__ bias, float *Y, int B,
+                                                                int part_b, int wg_per_panel, int relu)
+{
+    fc_reduce_body(L, part, bias, Y, B, part_b, wg_per_panel, relu, (int)blockIdx.x);
+}
+
+// The finishing kernel for fc_sparse_group_kernel: layer i's outputs at Y + i * y_stride,
+// its bias (if any) at bias + i * bias_stride.
+__global__ __launch_bounds__(kRedThreads) void fc_reduce_group_kernel(const LayerDev *__restrict__ table, int wgs_per_layer,
+                                                                      const float *__restrict__ part, size_t part_stride,
+                                                                      const float *__restrict__ bias, size_t bias_stride, float *Y,
+                                                                      size_t y_stride, int B, int wg_per_panel, int relu)
+{
+    const int job = (int)blockIdx.x / wgs_per_layer, wg = (int)blockIdx.x - job * wgs_per_layer;
+    const LayerDev L = table[job];
+    fc_reduce_body(L, part + job * part_stride, bias ? bias + job * bias_stride : nullptr, Y + job * y_stride, B, B, wg_per_panel, relu,
+                   wg);
 }

@@ -398,6 +398,48 @@ def test_fc_stack_replays_from_a_captured_graph(B):
         L.free()
 
 
+@pytest.mark.parametrize("B", [1, 2, 4, 16])
+def test_layer_group_in_one_grid(B):
+    """Five different layers of one shape (different weights, densities, codes, one of them
+    empty) in one grid, each with its own input and bias: every layer under both gates
+    against the oracle, and what a per-layer call on the small-batch path gives within
+    the tolerance; a shared input and a shared bias; refusals."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(50 + B)
+    M, K = 300, 437
+    layers, dense = [], []
+    for d, r in [(0.12, 5), (0.3, 5), (0.0, 5), (0.05, 8), (0.2, 3)]:
+        L, m, oW = check_decode(rand_pruned(rng, M, K, d), r, 4, 128, 128)
+        layers.append(L)
+        dense.append(oW)
+    G = cl.LayerGroup(layers)
+    X = np.maximum(rng.standard_normal((5, B, K)), 0).astype(np.float32)
+    bias = (rng.standard_normal((5, M)) * 0.1).astype(np.float32)
+    Xd, bd = torch.from_numpy(X).cuda(), torch.from_numpy(bias).cuda()
+    Y = G.forward(Xd, bd, relu=True).cpu().numpy()
+    for i in range(5):
+        assert_close(Y[i], fc_ref(dense[i], X[i], bias[i]), True, what=i)
+        one = cl.compressed_fc_forward(layers[i], Xd[i], bd[i], relu=True, path=cl.PATH_SPARSE).cpu().numpy()
+        assert rel_err(Y[i], one.astype(np.float64)) <= TOL, i
+    Y = G.forward(Xd[1], bd[2], relu=False).cpu().numpy()          # one input, one bias for all
+    for i in range(5):
+        assert_close(Y[i], fc_ref(dense[i], X[1], bias[2]), False, what=i)
+    Y = G.forward(Xd, None).cpu().numpy()
+    for i in range(5):
+        assert_close(Y[i], fc_ref(dense[i], X[i]), False, what=i)
+    with pytest.raises(cl.CLError):
+        G.forward(torch.zeros((5, 3, K), device="cuda"))             # three images are not a batch tile
+    with pytest.raises(cl.CLError):
+        G.forward(Xd, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    other = cl.compress_layer(rand_pruned(rng, M, K + 1, 0.1), 5, 4, 128, 128, upload=True)
+    with pytest.raises(cl.CLError):
+        cl.LayerGroup([layers[0], other])
+    G.free()
+    other.free()
+    for L in layers:
+        L.free()
+
+
 def test_fc_stack_of_six_wide_layers():
     """Six layers on the wide sparse path at 256 images: the stack call decodes its layers in
     launches of up to four up front, so six take two; bit for bit what per-layer calls
