@@ -192,7 +192,7 @@ def main():
                  "unit": "TFLOP/s", "kernel": "fc_mfma_kernel", "flops_counted": "executed dense-tile flops 2*M*K*B"}
         elif kind == "wide":
             r = {"bound": "alu", "achieved": round(useful / (ms_launch * 1e-3) / 1e12, 3), "peak": FP32_VECTOR_PEAK_TFLOPS,
-                 "unit": "TFLOP/s", "kernel": "wide_mul_kernel" if B > 128 else "fc_wide_kernel",
+                 "unit": "TFLOP/s", "kernel": "wide_mul_kernel",
                  "flops_counted": "2*nnz*B, all of them useful",
                  "peak_note": "157.3 = 256 CUs x 128 lanes x 2 flops x 2.4 GHz needs packed fp32; this build issues unpacked "
                               "multiply-adds, whose ceiling is 78.6"}
@@ -217,7 +217,7 @@ def main():
             r["lds"] = {"achieved": round(lds_bytes / (ms_launch * 1e-3) / 1e12, 2), "peak": LDS_PEAK_TBS, "unit": "TB/s",
                         "frac": round(lds_bytes / (ms_launch * 1e-3) / 1e12 / LDS_PEAK_TBS, 4),
                         "note": "4 bytes of activations from LDS per multiply-add; 256 CUs x 128 B/clk x 2.4 GHz"}
-        if kind == "wide" and B > 128:
+        if kind == "wide":
             r["other_launches"] = "wide_expand_kernel decodes the layer once per call before this kernel (its duration: profiles/)"
         return r, fig
 

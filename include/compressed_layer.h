@@ -59,7 +59,7 @@ enum {
                           /*   CL_PATH_SPARSE_WIDE the library's launch models price    */
                           /*   lower for this layer and batch (the dense tile multiplies */
                           /*   every zero of a block: at 9 % density the sparse product  */
-                          /*   wins from 129 images on, at 25 % it does not)             */
+                          /*   wins from about 100 images on, at 25 % it does not)       */
     CL_PATH_SPARSE = 1,   /* fused decode + sparse multiply on the vector ALUs      */
     CL_PATH_MFMA_F32 = 2, /* decode blocks to dense LDS tiles, fp32 MFMA; needs blocks */
                           /*   of at most 128 x 128, else CL_EUNSUPPORTED            */
@@ -70,11 +70,11 @@ enum {
     CL_PATH_SPARSE_WIDE = 4 /* large batches on the vector ALUs: the sparse product of  */
                           /*   Algorithm 2 step 12 as written, one fp32 multiply-add   */
                           /*   per surviving weight and image, images across the lanes; */
-                          /*   blocks of at most 128 x 128, else CL_EUNSUPPORTED.  Up   */
-                          /*   to 128 images one launch decodes and multiplies; above,  */
-                          /*   one launch decodes the layer into a list of 4 bytes per  */
-                          /*   surviving weight in the workspace and one multiplies it  */
-                          /*   for every tile of 256 images.  Run-to-run identical      */
+                          /*   blocks of at most 128 x 128, else CL_EUNSUPPORTED.  One  */
+                          /*   launch decodes the layer into a list of 4 bytes per      */
+                          /*   surviving weight in the workspace, one multiplies it for */
+                          /*   every tile of 64, 128 or 256 images (by batch).          */
+                          /*   Run-to-run identical                                     */
 };
 
 /* How a weight matrix is compressed.

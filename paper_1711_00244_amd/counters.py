@@ -32,7 +32,7 @@ OUT = os.path.join(ROOT, "profiles", "counters.json")
 FETCH_KIB_FACTOR = 2.0
 WRITE_KIB_FACTOR = 1.0
 
-KERNELS = {"wide_mul_kernel": "wide", "wide_expand_kernel": "wide_expand", "fc_wide_kernel": "wide_fused", "fc_mfma_kernel": "mfma", "fc_sparse_kernel": "sparse",
+KERNELS = {"wide_mul_kernel": "wide", "wide_expand_kernel": "wide_expand", "fc_mfma_kernel": "mfma", "fc_sparse_kernel": "sparse",
            "mfma_reduce_kernel": "mfma_reduce", "wide_reduce_kernel": "wide_reduce", "fc_reduce_kernel": "sparse_reduce"}
 
 

@@ -515,10 +515,8 @@ struct WidePlan {
     int ipl = 4;             // images per lane: the image tile is 64 * ipl images
     int Bp = 0;              // batch rounded up to whole image tiles
     int splits = 1;          // workgroups sharing the blocks of one block row
-    int cap = 0;             // entries the kernel's list of one block holds
-    int64_t cost = 0;        // modelled cycles of the launch (same units as mfma_shape's)
+    int64_t cost = 0;        // modelled cycles of the launches (same units as mfma_shape's)
     size_t lds = 0;
-    bool two_pass = true;    // decode to an entry list in the workspace, then multiply
     size_t tile_bytes = 0;   // the partial tiles; behind them in the workspace's partial-tile part:
     size_t ent_bytes = 0;    //   the entry list
     size_t xt_bytes = 0, part_bytes = 0;
@@ -528,36 +526,26 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
 {
     if (!mfma_capable(L)) return fail(CL_EUNSUPPORTED, "the wide sparse path needs blocks of at most %d x %d", kTile, kTile);
     if (batch > kMaxTileColumns) return fail(CL_EUNSUPPORTED, "the wide sparse path takes at most %d images per call", kMaxTileColumns);
-    P.cap = (int)((std::max<int64_t>(L->max_block_nnz, 1) + 63) / 64 * 64);
-    const size_t tables = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
-    // the widest image tile the batch can use whose slabs leave room for the block's list
     P.ipl = batch > 128 ? 4 : batch > 64 ? 2 : 1;
-    P.two_pass = P.ipl == 4;
-    auto lds_for = [&](int ipl) {
-        return P.two_pass ? 2 * (size_t)kHalf * 64 * ipl * 4 + ((size_t)4 << L->desc.weight_bits) : wide_lds_bytes(tables, P.cap, ipl);
-    };
-    while (P.ipl > 1 && lds_for(P.ipl) > dl.max_lds) P.ipl >>= 1;
     const int tile = 64 * P.ipl;
     P.Bp = (batch + tile - 1) / tile * tile;
-    P.lds = lds_for(P.ipl);
-    if (P.lds > dl.max_lds)
-        return fail(CL_EUNSUPPORTED, "the wide sparse path keeps a block's %lld surviving weights in LDS: %zu bytes needed, %zu there",
-                    (long long)L->max_block_nnz, P.lds, dl.max_lds);
-    // Split of the block rows, from a small model of a launch, in cycles per workgroup:
-    // a start; per block a fixed part and a part per surviving weight; the partial tiles,
-    // written and read again, as on the dense-tile path; workgroups run in rounds of one
-    // per CU.  The fused kernel (tiles of 64 and 128 images): 4 k cycles per block and
-    // 10 + 1.25 ipl per weight (21 and 23.6 k per block of 1 474 weights at 64 and 128
-    // images), 6 k for a block of at most 64 columns (one short phase).  The two launches
-    // (tiles of 256): 2 k per phase and 9 per weight in the multiplying kernel (AlexNet-
-    // shaped fc6 / fc7 / fc8 at 256 images: 68.7 / 35.1 / 24.8 us), and once per call the
-    // decoding launch, 13 k and 6 per thousand entries (16.2 / 8.5 / 8.0 us).
+    // two slabs of 64 columns x tile images, and the codebook
+    P.lds = 2 * (size_t)kHalf * tile * sizeof(float) + ((size_t)4 << L->desc.weight_bits);
+    if (P.lds > dl.max_lds) return fail(CL_EUNSUPPORTED, "the wide sparse path needs %zu bytes of LDS, %zu there", P.lds, dl.max_lds);
+    // Split of the block rows, from a small model of the launches, in cycles per workgroup:
+    // a start; per block two phases (one for blocks of at most 64 columns) of 2 k cycles and
+    // a part per surviving weight - 9, 6.5 and 5.5 cycles at 4, 2 and 1 images per lane (at 4
+    // the LDS port's 8 cycles per KB binds, below it the vector ALUs: 5 and 4 instructions
+    // per weight over four SIMDs); the partial tiles, written and read again, as on the
+    // dense-tile path; workgroups run in rounds of one per CU; and once per call the
+    // decoding launch, 13 k and 6 per thousand entries.  Fitted to the AlexNet-shaped
+    // fc6 / fc7 / fc8 at 256 images (multiply 68.7 / 35.1 / 24.8 us, decode 16.2 / 8.5 / 8.0 us).
     const int64_t tiles = (int64_t)L->n_panels * (P.Bp / tile);
     const int cus = std::max(1, dl.cus);
     const int64_t nnz_block = L->n_blocks ? L->nnz / L->n_blocks : 0;
-    const int64_t per_block = P.two_pass ? (L->desc.block_w > kHalf ? 4000 : 2000) + nnz_block * 9
-                                         : (L->desc.block_w > kHalf ? 4000 : 6000) + nnz_block * (40 + 5 * P.ipl) / 4;
-    const int64_t start = P.two_pass ? 12000 : 15000, once = P.two_pass ? 13000 + L->entries * 6 / 1000 : 0;
+    const int64_t per_weight_x2 = P.ipl == 4 ? 18 : P.ipl == 2 ? 13 : 11;
+    const int64_t per_block = (L->desc.block_w > kHalf ? 4000 : 2000) + nnz_block * per_weight_x2 / 2;
+    const int64_t start = 12000, once = 13000 + L->entries * 6 / 1000;
     const int sp_max = (int)std::max<int64_t>(1, std::min<int64_t>(L->nbw, (3 * (int64_t)cus + tiles - 1) / tiles));
     int64_t best = -1;
     for (int sp = 1; sp <= sp_max; ++sp) {
@@ -572,33 +560,20 @@ int32_t plan_wide(const cl_layer *L, int batch, const DeviceLimits &dl, WidePlan
     P.cost = best;
     P.xt_bytes = xt_bytes_for(L, P.Bp, false);
     P.tile_bytes = (size_t)L->n_panels * P.splits * kTile * P.Bp * sizeof(float);
-    if (P.two_pass) {
-        P.ent_bytes = ((size_t)L->nnz * sizeof(WideEntry) + 255) / 256 * 256;
-    }
+    P.ent_bytes = ((size_t)L->nnz * sizeof(WideEntry) + 255) / 256 * 256;
     P.part_bytes = P.tile_bytes + P.ent_bytes;
     return CL_OK;
 }
 
+template <int IPL>
 int32_t launch_wide_mul(const LayerDev &D, int panels, const WidePlan &P, const float *xt, float *part, const WideEntry *ent,
                         hipStream_t st)
 {
     static LdsLimit seen;
-    if (int32_t rc = ensure_lds((const void *)wide_mul_kernel, P.lds, seen)) return rc;
-    dim3 grid;
-    GRID_TRY(grid, (int64_t)panels * P.splits * (P.Bp / 256));
-    hipLaunchKernelGGL(wide_mul_kernel, grid, dim3(kWideThreads), P.lds, st, D, xt, ent, part, panels, P.splits, P.Bp);
-    HIP_TRY(hipGetLastError());
-    return CL_OK;
-}
-
-template <int IPL>
-int32_t launch_wide_as(const LayerDev &D, int panels, const WidePlan &P, const float *xt, float *part, hipStream_t st)
-{
-    static LdsLimit seen;
-    if (int32_t rc = ensure_lds((const void *)fc_wide_kernel<IPL>, P.lds, seen)) return rc;
+    if (int32_t rc = ensure_lds((const void *)wide_mul_kernel<IPL>, P.lds, seen)) return rc;
     dim3 grid;
     GRID_TRY(grid, (int64_t)panels * P.splits * (P.Bp / (64 * IPL)));
-    hipLaunchKernelGGL(fc_wide_kernel<IPL>, grid, dim3(kWideThreads), P.lds, st, D, xt, part, panels, P.splits, P.Bp, P.cap);
+    hipLaunchKernelGGL(wide_mul_kernel<IPL>, grid, dim3(kWideThreads), P.lds, st, D, xt, ent, part, panels, P.splits, P.Bp);
     HIP_TRY(hipGetLastError());
     return CL_OK;
 }
@@ -766,11 +741,12 @@ static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPl
     return CL_OK;
 }
 
-// The decoding launch of the 256-image wide path for up to kExpandJobs layers at once, each
+// The decoding launch of the wide path for up to kExpandJobs layers at once, each
 // into its own list.  Layers without chunks are skipped (their lists are empty).
-static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *const *ents, int n, hipStream_t st)
+static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *const *ents, int n, int ipl, hipStream_t st)
 {
     ExpandJobs jobs{};
+    jobs.ipl = (uint32_t)ipl;
     size_t lds = 0;
     int64_t wgs = 0;
     int used = 0;
@@ -796,9 +772,9 @@ static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *cons
     return CL_OK;
 }
 
-// One layer on the wide sparse path with launch shape P; arguments as run_mfma_layer.  On the
-// two-launch form the entry list is `ent`; with expanded it has been written already (by a
-// launch_wide_expand that took several layers of a stack together).
+// One layer on the wide sparse path with launch shape P; arguments as run_mfma_layer.  The
+// entry list is `ent`; with expanded it has been written already (by a launch_wide_expand
+// that took several layers of a stack together).
 static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePlan &P, const float *d_X, float *xt, float *part,
                               WideEntry *ent, bool expanded, const float *d_bias, float *d_Y, int next_bp, int batch, int relu,
                               hipStream_t st)
@@ -810,18 +786,13 @@ static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePl
         HIP_TRY(hipGetLastError());
     }
     int32_t rc = CL_EINVAL;
-    if (P.two_pass) {
-        if (!expanded)
-            if ((rc = launch_wide_expand(&L, &ent, 1, st))) return rc;
-        timing_begin(st);
-        rc = launch_wide_mul(D, L->n_panels, P, xt, part, ent, st);
-    } else {
-        timing_begin(st);
-        switch (P.ipl) {
-        case 1: rc = launch_wide_as<1>(D, L->n_panels, P, xt, part, st); break;
-        case 2: rc = launch_wide_as<2>(D, L->n_panels, P, xt, part, st); break;
-        case 4: rc = launch_wide_as<4>(D, L->n_panels, P, xt, part, st); break;
-        }
+    if (!expanded)
+        if ((rc = launch_wide_expand(&L, &ent, 1, P.ipl, st))) return rc;
+    timing_begin(st);
+    switch (P.ipl) {
+    case 1: rc = launch_wide_mul<1>(D, L->n_panels, P, xt, part, ent, st); break;
+    case 2: rc = launch_wide_mul<2>(D, L->n_panels, P, xt, part, ent, st); break;
+    case 4: rc = launch_wide_mul<4>(D, L->n_panels, P, xt, part, ent, st); break;
     }
     if (rc) return rc;
     timing_end(st, 1);
@@ -909,7 +880,7 @@ struct StackPlan {
     std::vector<SparsePlan> sparse;   // per layer on the sparse path
     std::vector<char> xt_in;          // layer reads its transposed activations straight from the layer before
     std::vector<char> fold_in;        // layer adds up the partial tiles of the layer before itself (both on the sparse path)
-    std::vector<size_t> ent_off;      // per layer on the two-launch wide path: its entry list in the area behind the rotating buffers
+    std::vector<size_t> ent_off;      // per layer on the wide path: its entry list in the area behind the rotating buffers
     size_t xt_bytes = 0, part_bytes = 0, act_bytes = 0, ent_bytes = 0;
     int regions = 1;                  // copies of each buffer, used in rotation
     size_t total() const { return (size_t)regions * (xt_bytes + part_bytes + act_bytes) + ent_bytes; }
@@ -1006,7 +977,7 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
     const int R = P.regions;
     auto region = [&](size_t base, size_t bytes, int i) { return ws + base + (size_t)(i % R) * bytes; };
     const size_t xt0 = 0, part0 = (size_t)R * P.xt_bytes, act0 = part0 + (size_t)R * P.part_bytes;
-    // The layers on the two-launch wide path are decoded up front, kExpandJobs to a launch: the
+    // The layers on the wide path are decoded up front, kExpandJobs to a launch: the
     // lists depend on the weights only, and one launch for two layers is shorter than two
     // (the fixed part of such a launch - start, tables, the dependent loads - is a third of fc7's).
     const size_t ent0 = act0 + (size_t)R * P.act_bytes;
@@ -1014,16 +985,17 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
     {
         const cl_layer *todo[kExpandJobs];
         WideEntry *ents[kExpandJobs];
-        int n = 0;
+        int n = 0, ipl_of_stack = 4;                 // (the images per lane follow from the batch: the same for every layer)
         for (int i = 0; i <= n_layers; ++i) {
-            const bool mine = i < n_layers && P.path[i] == CL_PATH_SPARSE_WIDE && P.wide[i].two_pass;
+            const bool mine = i < n_layers && P.path[i] == CL_PATH_SPARSE_WIDE;
             if (mine) {
                 todo[n] = layers[i];
                 ents[n] = ent_of(i);
+                ipl_of_stack = P.wide[i].ipl;
                 ++n;
             }
             if (n == kExpandJobs || (i == n_layers && n > 0)) {
-                if (int32_t rc = launch_wide_expand(todo, ents, n, st)) return rc;
+                if (int32_t rc = launch_wide_expand(todo, ents, n, ipl_of_stack, st)) return rc;
                 n = 0;
             }
         }

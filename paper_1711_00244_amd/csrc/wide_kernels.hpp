@@ -1,131 +1,15 @@
 // Large batches on the vector ALUs: the sparse product of Algorithm 2 step 12 as written -
 // one multiply-add per surviving weight and image, no dense tile - with the images across
-// the lanes.  fc_wide_kernel and its finishing kernel.
+// the lanes (lane l: images IPL l .. IPL l + IPL - 1 of a tile of 64 IPL images, IPL = 1, 2
+// or 4).  wide_expand_kernel, wide_mul_kernel and the finishing kernel.
 // Part of the device translation unit: included by device.hip inside namespace cl,
 // in the order given there.
 #pragma once
 
-// Workgroup (block row p, split j of its blocks, image tile nb of 64 IPL images) of
-// sixteen wavefronts in two roles that meet at one barrier per phase.
-//   Decoders (wavefronts 12-15, one per SIMD) decode block i + 1 - a chunk per wavefront
-//   at a time, decode / scan as everywhere - into an entry list in LDS: the block's
-//   surviving weights in the order of the stream (row by row), 16 bits each (column in
-//   the block, value index), the padding entries dropped; and a pointer array that says
-//   where in the list each half row starts (half row h = 2 row + (column >= 64): the
-//   positions of a block run row by row, so h never decreases along the list).
-//   Multipliers (wavefronts 0-11) own kWideRows rows of the block row each and hold
-//   their sums for all images of the tile in registers (lane l: images IPL l .. IPL l +
-//   IPL - 1) for the whole split.  An entry is uniform across the wavefront: its column
-//   picks a row of the activation slab in LDS ([column][image], one ds_read of IPL floats
-//   per lane), its weight multiplies that into the sums of its row.  The rows are walked
-//   in program order (so which registers a row's sums live in is static), a row's
-//   entries in groups of four.
-// The activations of a block's 128 columns and 256 images are 128 KB, so a block is
-// taken in two phases of 64 columns (one for blocks of at most 64 columns): two slabs
-// of 64 x (64 IPL) floats alternate, the slab of phase s + 1 is loaded during phase s
-// by all sixteen wavefronts, and the half-row pointers give each phase its entries.
-// The entry list and pointers of two blocks alternate likewise.
 constexpr int kWideWaves = 16;
-constexpr int kWideDecoders = 4;
-constexpr int kWideMults = kWideWaves - kWideDecoders;
 constexpr int kWideThreads = kWideWaves * 64;
-constexpr int kWideRows = (kTile + kWideMults - 1) / kWideMults;       // rows of a block row per multiplying wavefront
 constexpr int kHalf = 64;                                               // columns per slab
-constexpr int kHalfKeys = 2 * kTile;                                    // half rows of a block
-constexpr int kHalfPtrStride = (kHalfKeys + 1 + 7) / 8 * 8;             // 16-bit pointers per buffer, kept 16-byte aligned
 constexpr int kSlabRowsPerWave = kHalf / kWideWaves;                    // rows of a slab each wavefront copies
-
-// bytes of LDS after the table image: two pointer arrays, two entry lists, two slabs
-static size_t wide_lds_bytes(size_t tables, int cap, int ipl)
-{
-    return tables + 2 * (size_t)kHalfPtrStride * 2 + 2 * (size_t)cap * 2 + 2 * (size_t)kHalf * 64 * ipl * 4;
-}
-
-// 1 in every byte of x that is not zero
-__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t x)
-{
-    return ((x | ((x & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u) >> 7;
-}
-
-// Half row of a position of block g: 2 row + (column >= kHalf); column in c.
-__device__ __forceinline__ int half_row(uint32_t pos, const BlockGeom &g, uint32_t &c)
-{
-    uint32_t r;
-    split_pos(pos, g, r, c);
-    return (int)(2u * r + (c >= (uint32_t)kHalf ? 1u : 0u));
-}
-
-// Decoder wavefront d of kWideDecoders: the chunks cb0 + d, cb0 + d + kWideDecoders, ...
-// of block b into list / hp (Algorithm 2 steps 5-9, the "arrange" of step 9 being the
-// list order).  Every one of the kHalfKeys + 1 pointers is written for every block:
-// by the entry that starts a half row (for all half rows since the entry before it,
-// whichever chunk that was in - its position is this entry's minus the gap), and
-// after the block's last entry up to the end by the wavefront that decodes the last
-// chunk; a block without entries gets all pointers zero from decoder 0.
-__device__ __forceinline__ void wide_decode_block(const LayerDev &L, const Tables &T, uint32_t b, int d, int lane,
-                                                  uint16_t *list, uint16_t *hp, int cap)
-{
-    const uint32_t cb0 = L.block_chunk[b], cb1 = L.block_chunk[b + 1];
-    if (cb0 == cb1) {
-        if (d == 0)
-            for (int k = lane; k <= kHalfKeys; k += 64) hp[k] = 0;
-        return;
-    }
-    const BlockGeom g = block_geom(L, b);
-    const uint32_t nz0 = L.chunk_nz[cb0];
-    // one chunk ahead: the head and record of the next chunk are requested before this one is decoded
-    uint32_t c = cb0 + (uint32_t)d;
-    ChunkHead h{};
-    LaneRecord rec{};
-    uint32_t nzc = 0;
-    if (c < cb1) {
-        h = load_head(L, c);
-        rec = load_record(L, h, lane);
-        nzc = L.chunk_nz[c];
-    }
-    while (c < cb1) {
-        const uint32_t cn = c + (uint32_t)kWideDecoders;
-        ChunkHead hn{};
-        LaneRecord recn{};
-        uint32_t nzn = 0;
-        if (cn < cb1) {
-            hn = load_head(L, cn);
-            recn = load_record(L, hn, lane);
-            nzn = L.chunk_nz[cn];
-        }
-        const Symbols y = decode_record(rec, T);
-        // entries of the lane that are not padding; with the lane's advance in one scan
-        uint32_t nzl = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) nzl = __builtin_amdgcn_sad_u8(nonzero_bytes(y.v[w]), 0u, nzl);
-        const uint32_t mine = nzl | (y.adv << 10);
-        const uint32_t incl = wave_incl_scan(mine);
-        uint32_t rank = nzc - nz0 + ((incl - mine) & 1023u);
-        const uint32_t sum = h.m.pos0 + ((incl - mine) >> 10);
-        // half row of the entry before the lane's first (none before the block's first)
-        uint32_t cc;
-        int pkey = sum == 0u ? -1 : half_row(sum - 1u, g, cc);
-        for_each_entry(y, sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-            const int key = half_row(pos, g, cc);
-            for (int k = pkey + 1; k <= key; ++k) hp[k] = (uint16_t)rank;
-            pkey = key;
-            if (v != 0u) {
-                list[min(rank, (uint32_t)cap - 1u)] = (uint16_t)((cc << 8) | v);
-                ++rank;
-            }
-        });
-        if (c + 1u == cb1) {
-            // the block's last chunk: the half rows after its last entry start at the end of the list
-            const uint32_t total = nzc - nz0 + ((uint32_t)__builtin_amdgcn_readlane((int)incl, 63) & 1023u);
-            const int klast = (int)wave_max((uint32_t)(y.n ? pkey : 0));
-            for (int k = klast + 1 + lane; k <= kHalfKeys; k += 64) hp[k] = (uint16_t)total;
-        }
-        c = cn;
-        h = hn;
-        rec = recn;
-        nzc = nzn;
-    }
-}
 
 // IPL consecutive floats from LDS / to LDS / from global memory with one access.
 template <int IPL> struct WideVec {
@@ -135,20 +19,206 @@ template <> struct WideVec<1> {
     typedef float type;
 };
 
-template <int IPL>
-__global__ __launch_bounds__(kWideThreads) void fc_wide_kernel(LayerDev L, const float *__restrict__ XT, float *part, int panels,
-                                                               int splits, int Bp, int cap)
+// ------------------------------------------------------------------------- //
+// Two launches: decode to an entry list, then multiply
+// ------------------------------------------------------------------------- //
+// wide_expand_kernel decodes the whole layer once per call (Algorithm 2 steps 5-9, one
+// wavefront per chunk as in decode_kernel) into a list in global memory: a block's
+// surviving weights - the padding entries dropped - in the order the multiplying kernel
+// takes them: first those in the block's columns 0-63, then those in columns 64-127,
+// each half row by row.  Where a chunk's entries go in that order does not depend on the
+// activations: the layer carries, per chunk, the list position of its first surviving
+// weight of each half (chunk_half), and, per block and half, where each group of eight
+// rows starts (group_ptr), both counted when the layer was loaded.  An entry is one word:
+// the value index (bits 16-23), the column within the half (bits 8-13) and IPL times the
+// row within its group of eight (bits 0-7: the offset of the row's sums among the
+// multiplying wavefront's sum registers).
+// wide_mul_kernel then holds no decode tables, decodes nothing and waits for no decoder:
+// sixteen wavefronts multiply, each owning the eight rows of one group, the weights looked
+// up in the codebook (Algorithm 2 step 8) 64 entries at a time, and every image tile of a
+// large batch reads the same list.
+typedef uint32_t WideEntry;
+constexpr int kMulRows = kTile / kWideWaves;            // rows of a block row per wavefront: a group
+constexpr int kGroupPtrs = 2 * (kWideWaves + 1);        // group_ptr words per block
+
+// (One launch can decode several layers - those of a stack that take this path - each into
+// its own list: workgroups wg0[i] .. wg0[i + 1] - 1 belong to job i.)
+constexpr int kExpandJobs = 4;
+struct ExpandJobs {
+    LayerDev L[kExpandJobs];
+    WideEntry *ent[kExpandJobs];
+    uint32_t wg0[kExpandJobs + 1];
+    uint32_t ipl;                   // images per lane of the multiplying kernel: the row offsets count its sum registers
+};
+
+__global__ __launch_bounds__(kThreads) void wide_expand_kernel(ExpandJobs jobs)
 {
-    typedef typename WideVec<IPL>::type vec_t;
-    constexpr int kImages = 64 * IPL;
-    constexpr int kBatch = 4;                                         // entries whose activations are requested together
+    int job = 0;
+#pragma unroll
+    for (int i = 1; i < kExpandJobs; ++i)
+        if (blockIdx.x >= jobs.wg0[i]) job = i;
+    const LayerDev &L = jobs.L[job];
+    WideEntry *ent = jobs.ent[job];
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
-    uint16_t *hp = (uint16_t *)s.extra;                                 // [2][kHalfPtrStride]
-    uint16_t *lists = hp + 2 * kHalfPtrStride;                          // [2][cap]
-    float *slabs = (float *)(lists + 2 * (size_t)cap);                  // [2][kHalf][kImages]
-    // consecutive workgroups take the splits of one block row: with the usual eight
-    // splits the workgroups that share a range of activation rows share a die's L2
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63);
+    const uint32_t c = (blockIdx.x - jobs.wg0[job]) * kWaves + (uint32_t)wave;
+    const bool have = c < L.n_chunks;
+    ChunkHead h{};
+    LaneRecord rec{};
+    uint32_t base0 = 0, base1 = 0;
+    if (have) {
+        h = load_head(L, c);
+        rec = load_record(L, h, lane);
+        base0 = L.chunk_half[2 * (size_t)c];
+        base1 = L.chunk_half[2 * (size_t)c + 1];
+    }
+    store_tables(s, L, fetch_tables(L));
+    __syncthreads();
+    if (!have) return;
+    const BlockGeom g = block_geom(L, h.m.blk);
+    const Symbols y = decode_record(rec, s.T);
+    const LaneStart st = lane_starts(y, h.m.pos0);
+    // the lane's surviving weights per half, then where its first of each half goes
+    uint32_t mine = 0;
+    for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+        uint32_t r, cc;
+        split_pos(pos, g, r, cc);
+        if (v != 0u) mine += cc >= (uint32_t)kHalf ? 0x10000u : 1u;
+    });
+    const uint32_t excl = wave_incl_scan(mine) - mine;
+    uint32_t at0 = base0 + (excl & 0xffffu), at1 = base1 + (excl >> 16);
+    for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+        uint32_t r, cc;
+        split_pos(pos, g, r, cc);
+        if (v == 0u) return;
+        const WideEntry e = (v << 16) | ((cc & (uint32_t)(kHalf - 1)) << 8) | ((r & (uint32_t)(kMulRows - 1)) * jobs.ipl);
+        if (cc >= (uint32_t)kHalf) ent[at1++] = e;
+        else ent[at0++] = e;
+    });
+}
+
+// The multiply-add of up to 64 entries, one per lane of (entry word, weight) - lanes past
+// the last entry holding a copy of the last one with weight zero - into the sums of the
+// entries' rows: sums[IPL r + q] += w * x[column][IPL lane + q].  The rows differ from entry to entry
+// and the sums live in registers, so the register a product is added to is picked at run
+// time: the sums sit in v[64:95], the additions run in the vector-register index mode
+// with the entry's row offset as the index (destination and addend relative), and
+// everything between switching the mode on and off is written out here.  Entries are
+// taken four at a time, the activations of the next four requested from LDS (into
+// v[96:127], alternating halves) before the products of the present four are formed, so
+// that the loads and the arithmetic overlap from one end of the list to the other
+// whatever the rows' lengths.
+// (X = images per lane, 4, 2 or 1: the slab row is 256 X bytes, the LDS read X floats wide,
+// X multiply-adds per entry, the row offset in the entry word X (row mod 8).)
+#define WM_RL(i, slot)                                                                       \
+    "v_readlane_b32 %[c" #slot "], %[vat], " #i "\n"                                         \
+    "v_readlane_b32 %[w" #slot "], %[vw], " #i "\n"
+#define WM_AD_4(slot, tmp)                                                                   \
+    "s_and_b32 %[" #tmp "], %[c" #slot "], 0x3f00\n"                                         \
+    "v_lshl_add_u32 v[" #slot "*4+96], %[" #tmp "], 2, %[base]\n"
+#define WM_AD_2(slot, tmp)                                                                   \
+    "s_and_b32 %[" #tmp "], %[c" #slot "], 0x3f00\n"                                         \
+    "v_lshl_add_u32 v[" #slot "*4+96], %[" #tmp "], 1, %[base]\n"
+#define WM_AD_1(slot, tmp)                                                                   \
+    "s_and_b32 %[" #tmp "], %[c" #slot "], 0x3f00\n"                                         \
+    "v_add_u32 v[" #slot "*4+96], %[" #tmp "], %[base]\n"
+#define WM_RD_4(slot) "ds_read_b128 v[" #slot "*4+96:" #slot "*4+99], v[" #slot "*4+96]\n"
+#define WM_RD_2(slot) "ds_read_b64 v[" #slot "*4+96:" #slot "*4+97], v[" #slot "*4+96]\n"
+#define WM_RD_1(slot) "ds_read_b32 v[" #slot "*4+96], v[" #slot "*4+96]\n"
+#define WM_FMA1_4(slot)                                                                      \
+    "s_set_gpr_idx_on %[c" #slot "], 0xc\n"                                                  \
+    "v_fma_f32 v64, %[w" #slot "], v[" #slot "*4+96], v64\n"                                 \
+    "v_fma_f32 v65, %[w" #slot "], v[" #slot "*4+97], v65\n"                                 \
+    "v_fma_f32 v66, %[w" #slot "], v[" #slot "*4+98], v66\n"                                 \
+    "v_fma_f32 v67, %[w" #slot "], v[" #slot "*4+99], v67\n"
+#define WM_FMA1_2(slot)                                                                      \
+    "s_set_gpr_idx_on %[c" #slot "], 0xc\n"                                                  \
+    "v_fma_f32 v64, %[w" #slot "], v[" #slot "*4+96], v64\n"                                 \
+    "v_fma_f32 v65, %[w" #slot "], v[" #slot "*4+97], v65\n"
+#define WM_FMA1_1(slot)                                                                      \
+    "s_set_gpr_idx_on %[c" #slot "], 0xc\n"                                                  \
+    "v_fma_f32 v64, %[w" #slot "], v[" #slot "*4+96], v64\n"
+#define WM_LOAD4(X, i0, i1, i2, i3, s0, s1, s2, s3)                                          \
+    WM_RL(i0, s0) WM_RL(i1, s1) WM_RL(i2, s2) WM_RL(i3, s3)                                  \
+    WM_AD_##X(s0, t) WM_AD_##X(s1, t2) WM_AD_##X(s2, t) WM_AD_##X(s3, t2)                    \
+    WM_RD_##X(s0) WM_RD_##X(s1) WM_RD_##X(s2) WM_RD_##X(s3)
+#define WM_FMA4(X, s0, s1, s2, s3) WM_FMA1_##X(s0) WM_FMA1_##X(s1) WM_FMA1_##X(s2) WM_FMA1_##X(s3) "s_set_gpr_idx_off\n"
+// entries i0 .. i0 + 3 are in flight in slots (a); request i0 + 4 .. i0 + 7 into slots (b), then add (a)
+#define WM_STEP(X, prio, n_done, j0, j1, j2, j3, a0, a1, a2, a3, b0, b1, b2, b3)             \
+    "s_setprio " #prio "\n"                                                                  \
+    WM_LOAD4(X, j0, j1, j2, j3, b0, b1, b2, b3)                                              \
+    "s_waitcnt lgkmcnt(4)\n"                                                                 \
+    WM_FMA4(X, a0, a1, a2, a3)                                                               \
+    "s_cmp_le_u32 %[n], " #n_done "\n"                                                       \
+    "s_cbranch_scc1 1f\n"
+#define WM_LAST(X, a0, a1, a2, a3)                                                           \
+    "s_waitcnt lgkmcnt(0)\n"                                                                 \
+    WM_FMA4(X, a0, a1, a2, a3)
+// The four wavefronts of a SIMD would otherwise be served oldest first, finish a list one
+// after the other, and the last, alone, cannot keep the vector unit busy (one wavefront
+// issues an instruction every four to five cycles, of which 7 in 12 are vector
+// arithmetic here): each lowers its priority every few steps of its list, so that one
+// that is ahead yields to the others and all four advance together.
+#define WM_BODY(X)                                                                           \
+    WM_LOAD4(X, 0, 1, 2, 3, 0, 1, 2, 3)                                                      \
+    WM_STEP(X, 3, 4, 4, 5, 6, 7, 0, 1, 2, 3, 4, 5, 6, 7)                                     \
+    WM_STEP(X, 3, 8, 8, 9, 10, 11, 4, 5, 6, 7, 0, 1, 2, 3)                                   \
+    WM_STEP(X, 3, 12, 12, 13, 14, 15, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_STEP(X, 2, 16, 16, 17, 18, 19, 4, 5, 6, 7, 0, 1, 2, 3)                                \
+    WM_STEP(X, 2, 20, 20, 21, 22, 23, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_STEP(X, 2, 24, 24, 25, 26, 27, 4, 5, 6, 7, 0, 1, 2, 3)                                \
+    WM_STEP(X, 1, 28, 28, 29, 30, 31, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_STEP(X, 1, 32, 32, 33, 34, 35, 4, 5, 6, 7, 0, 1, 2, 3)                                \
+    WM_STEP(X, 1, 36, 36, 37, 38, 39, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_STEP(X, 0, 40, 40, 41, 42, 43, 4, 5, 6, 7, 0, 1, 2, 3)                                \
+    WM_STEP(X, 0, 44, 44, 45, 46, 47, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_STEP(X, 0, 48, 48, 49, 50, 51, 4, 5, 6, 7, 0, 1, 2, 3)                                \
+    WM_STEP(X, 0, 52, 52, 53, 54, 55, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_STEP(X, 0, 56, 56, 57, 58, 59, 4, 5, 6, 7, 0, 1, 2, 3)                                \
+    WM_STEP(X, 0, 60, 60, 61, 62, 63, 0, 1, 2, 3, 4, 5, 6, 7)                                \
+    WM_LAST(X, 4, 5, 6, 7)                                                                   \
+    "1:\n"                                                                                   \
+    "s_waitcnt lgkmcnt(0)\n"                                                                 \
+    "s_setprio 0\n"
+#define WM_OPERANDS                                                                                                           \
+    : "+{v[64:95]}"(sums), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [c4] "=&s"(c4), [c5] "=&s"(c5),   \
+      [c6] "=&s"(c6), [c7] "=&s"(c7), [w0] "=&s"(w0), [w1] "=&s"(w1), [w2] "=&s"(w2), [w3] "=&s"(w3), [w4] "=&s"(w4),         \
+      [w5] "=&s"(w5), [w6] "=&s"(w6), [w7] "=&s"(w7), [t] "=&s"(t), [t2] "=&s"(t2)                                            \
+    : [vat] "v"(vat), [vw] "v"(vw), [base] "v"(base), [n] "s"(n)                                                              \
+    : "memory", "scc", "m0", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107",      \
+      "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", \
+      "v123", "v124", "v125", "v126", "v127"
+
+typedef float WideSums __attribute__((ext_vector_type(32)));
+
+template <int IPL>
+__device__ __forceinline__ void wide_fma_entries(WideSums &sums, uint32_t vat, uint32_t vw, uint32_t base, int n)
+{
+    uint32_t c0, c1, c2, c3, c4, c5, c6, c7, w0, w1, w2, w3, w4, w5, w6, w7, t, t2;
+    if constexpr (IPL == 4) asm volatile(WM_BODY(4) WM_OPERANDS);
+    else if constexpr (IPL == 2) asm volatile(WM_BODY(2) WM_OPERANDS);
+    else asm volatile(WM_BODY(1) WM_OPERANDS);
+}
+
+// Workgroup (block row p, split j of its blocks, image tile nb) of sixteen wavefronts, one
+// to a CU.  A phase is half a block: its 64 columns' activations for the 256 images sit
+// in one of two 64 KB slabs, every wavefront multiplies its group's entries of that half,
+// and meanwhile brings in its four rows of the next phase's slab (registers first, LDS
+// after its arithmetic) and the first 64 of its next entries; one barrier ends the phase.
+template <int IPL>
+__global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, const float *__restrict__ XT,
+                                                                const WideEntry *__restrict__ ent, float *part, int panels,
+                                                                int splits, int Bp)
+{
+    constexpr int kImages = 64 * IPL;
+    typedef typename WideVec<IPL>::type vec_t;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    float *slabs = (float *)smem_raw;                                   // [2][kHalf][kImages]
+    float *cb = slabs + 2 * kHalf * kImages;                            // [ncode]
+    // consecutive workgroups take the splits of one block row: with the usual eight splits the
+    // workgroups that share a range of activation rows share a die's L2
     const int j = (int)blockIdx.x % splits, rest = (int)blockIdx.x / splits;
     const int p = rest % panels, nb = rest / panels;
     const int pj = p * splits + j;
@@ -158,168 +228,140 @@ __global__ __launch_bounds__(kWideThreads) void fc_wide_kernel(LayerDev L, const
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     const int nh = L.bw > kHalf ? 2 : 1;
     const int phases = (blk_hi - blk_lo) * nh;
-    const bool decoder = wave >= kWideMults;
 
-    // a wavefront's share of a slab: rows 4 wave .. 4 wave + 3, IPL floats per lane and row
-    const float *xsrc = XT + (size_t)nb * kImages + (size_t)lane * IPL;
-    auto slab_row0 = [&](int ph) { return (size_t)(blk_lo + ph / nh) * kTile + (size_t)(ph % nh) * kHalf; };
-    // (a multiplying wavefront, short of registers, takes its rows in two halves: one during
-    // each half of its phase)
-    vec_t stage[kSlabRowsPerWave];
-    auto slab_fetch = [&](int ph, int q0, int q1) {
-        const float *src = xsrc + (slab_row0(ph) + (size_t)wave * kSlabRowsPerWave) * (size_t)Bp;
+    // A wavefront's share of a slab: rows 4 wave .. 4 wave + 3, four floats per lane and row.  The
+    // slab of phase ph starts at row (blk_lo + ph / nh) 128 + (ph % nh) 64 of the activations: a
+    // uniform base that moves from phase to phase, and per lane a constant byte offset per row.
+    const char *xbase = (const char *)(XT + (size_t)nb * kImages);
+    uint32_t xoff[kSlabRowsPerWave];
 #pragma unroll
-        for (int q = q0; q < q1; ++q) stage[q] = *(const vec_t *)(src + (size_t)q * Bp);
+    for (int q = 0; q < kSlabRowsPerWave; ++q) xoff[q] = (uint32_t)((wave * kSlabRowsPerWave + q) * Bp + lane * IPL) * 4u;
+    vec_t stage[kSlabRowsPerWave];
+    auto slab_fetch = [&](int ph) {
+        const char *src = xbase + ((size_t)(blk_lo + ph / nh) * kTile + (size_t)(ph % nh) * kHalf) * (size_t)Bp * 4;
+#pragma unroll
+        for (int q = 0; q < kSlabRowsPerWave; ++q) stage[q] = *(const vec_t *)(src + xoff[q]);
     };
-    auto slab_store = [&](int ph, int q0, int q1) {
+    auto slab_store = [&](int ph) {
         float *dst = slabs + (size_t)(ph & 1) * kHalf * kImages + (size_t)(wave * kSlabRowsPerWave) * kImages + lane * IPL;
 #pragma unroll
-        for (int q = q0; q < q1; ++q) *(vec_t *)(dst + q * kImages) = stage[q];
+        for (int q = 0; q < kSlabRowsPerWave; ++q) *(vec_t *)(dst + q * kImages) = stage[q];
     };
-    constexpr int kStageHalf = kSlabRowsPerWave / 2;
+    // The wavefront's part of the list in each phase - its group of rows in that half of that
+    // block - for 64 phases at a time, phase ph0 + lane in lane `lane`: fetched ahead of
+    // the loop so that no phase starts by waiting for a pointer.
+    uint32_t seg_a = 0, seg_e = 0;
+    auto segments = [&](int ph0) {
+        const int ph = min(ph0 + lane, phases - 1);
+        const uint32_t b = pb0 + (uint32_t)(blk_lo + ph / nh);
+        const uint32_t *gp = L.group_ptr + ((size_t)b * 2 + (size_t)(ph % nh)) * (kWideWaves + 1) + wave;
+        seg_a = gp[0];
+        seg_e = gp[1];
+    };
+    auto segment = [&](int ph, uint32_t &a, uint32_t &e) {
+        a = (uint32_t)__builtin_amdgcn_readlane((int)seg_a, ph & 63);
+        e = (uint32_t)__builtin_amdgcn_readlane((int)seg_e, ph & 63);
+    };
+    // up to 64 entries from list position a on, one per lane
+    const uint32_t lane4 = (uint32_t)lane * 4u;
+    auto window = [&](uint32_t a, uint32_t e) {
+        uint32_t v = 0u;
+        if ((uint32_t)lane < e - a) v = *(const uint32_t *)((const char *)(ent + a) + lane4);
+        return v;
+    };
+    auto weight_of = [&](uint32_t entry) { return cb[(entry >> 16) & 0xffu]; };
 
-    if (phases > 0) slab_fetch(0, 0, kSlabRowsPerWave);
-    if (threadIdx.x < kThreads) store_tables(s, L, fetch_tables(L));
-    if (phases > 0) slab_store(0, 0, kSlabRowsPerWave);
-    if (decoder) {
-        // The decoders' side of every barrier below, in a loop of their own: a shared loop
-        // would keep the multipliers' sums alive in the decoders' registers.
-        __builtin_amdgcn_s_setprio(3);
-        __syncthreads();                                    // tables stored
-        if (phases > 0) wide_decode_block(L, s.T, pb0 + (uint32_t)blk_lo, wave - kWideMults, lane, lists, hp, cap);
-        __syncthreads();                                    // first block's list, first slab
-        for (int ph = 0; ph < phases; ++ph) {
-            const int i = ph / nh, h = ph - i * nh;
-            const bool more = ph + 1 < phases;
-            if (more) slab_fetch(ph + 1, 0, kSlabRowsPerWave);
-            if (h == 0 && i + 1 < blk_hi - blk_lo)
-                wide_decode_block(L, s.T, pb0 + (uint32_t)(blk_lo + i + 1), wave - kWideMults, lane,
-                                  lists + (size_t)((i + 1) & 1) * cap, hp + ((i + 1) & 1) * kHalfPtrStride, cap);
-            if (more) slab_store(ph + 1, 0, kSlabRowsPerWave);
-            __syncthreads();
-        }
-        return;
-    }
-
-    float acc[kWideRows][IPL];
+    WideSums sums;
 #pragma unroll
-    for (int r = 0; r < kWideRows; ++r)
-#pragma unroll
-        for (int q = 0; q < IPL; ++q) acc[r][q] = 0.0f;
-    __syncthreads();                                        // tables stored
-    __syncthreads();                                        // first block's list, first slab
-    uint32_t hpv = 0;                                       // the wavefront's half-row pointers, one per lane
-    for (int ph = 0; ph < phases; ++ph) {
-        const int i = ph / nh, h = ph - i * nh;
-        const bool more = ph + 1 < phases;
-        {
-            if (more) slab_fetch(ph + 1, 0, kStageHalf);
-            const uint16_t *list = lists + (size_t)(i & 1) * cap;
-            const float *slab = slabs + (size_t)(ph & 1) * kHalf * kImages + lane * IPL;
-            if (h == 0) hpv = hp[(i & 1) * kHalfPtrStride + min(2 * kWideRows * wave + lane, kHalfKeys)];
-            // the rows in two groups: the entries of a group's rows in this phase, one per lane, and
-            // their weights are fetched together, then the rows are walked one after the other
-            constexpr int kGroup = (kWideRows + 1) / 2;
-#pragma unroll
-            for (int r0 = 0; r0 < kWideRows; r0 += kGroup) {
-                if (r0 > 0 && more) {
-                    slab_store(ph + 1, 0, kStageHalf);
-                    slab_fetch(ph + 1, kStageHalf, kSlabRowsPerWave);
-                }
-                uint32_t ev[kGroup];
-                float wv[kGroup];
-                int cnt[kGroup];
-#pragma unroll
-                for (int g = 0; g < kGroup; ++g) {
-                    const int r = r0 + g;
-                    if (r >= kWideRows) break;
-                    const int a = __builtin_amdgcn_readlane((int)hpv, 2 * r + h), e = __builtin_amdgcn_readlane((int)hpv, 2 * r + h + 1);
-                    cnt[g] = e - a;
-                    ev[g] = lane < cnt[g] ? (uint32_t)list[min(a + lane, cap - 1)] : 0u;
-                }
-#pragma unroll
-                for (int g = 0; g < kGroup; ++g)
-                    if (r0 + g < kWideRows) wv[g] = s.T.cb[ev[g] & 0xffu];
-#pragma unroll
-                for (int g = 0; g < kGroup; ++g) {
-                    const int r = r0 + g;
-                    if (r >= kWideRows) break;
-                    const int n = cnt[g];
-                    auto one = [&](int jj, vec_t &x, float &w) {
-                        const uint32_t se = (uint32_t)__builtin_amdgcn_readlane((int)ev[g], jj);
-                        w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wv[g]), jj));
-                        x = *(const vec_t *)(slab + ((se >> 8) & (uint32_t)(kHalf - 1)) * kImages);
-                    };
-                    auto fma = [&](const vec_t &x, float w) {
-                        if constexpr (IPL == 1) acc[r][0] += w * x;
-                        else {
-#pragma unroll
-                            for (int q = 0; q < IPL; ++q) acc[r][q] += w * x[q];
-                        }
-                    };
-                    int jj = 0;
-                    if constexpr (kBatch == 8) {
-                        // the first eight entries in one piece without a branch: a slot past the row's
-                        // last entry takes that entry's activations again with weight 0
-                        if (n > 0) {
-                            vec_t x[8];
-                            float w[8];
-#pragma unroll
-                            for (int u = 0; u < 8; ++u) {
-                                one(min(u, n - 1), x[u], w[u]);
-                                w[u] = u < n ? w[u] : 0.0f;
-                            }
-#pragma unroll
-                            for (int u = 0; u < 8; ++u) fma(x[u], w[u]);
-                        }
-                        for (jj = 8; jj < n; ++jj) {
-                            vec_t x;
-                            float w;
-                            one(jj, x, w);
-                            fma(x, w);
-                        }
-                        continue;
-                    } else {
-                        for (; jj + 4 <= n; jj += 4) {
-                            vec_t x[4];
-                            float w[4];
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) one(jj + u, x[u], w[u]);
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) fma(x[u], w[u]);
-                        }
-                    }
-                    if (n & 2) {
-                        vec_t x[2];
-                        float w[2];
-#pragma unroll
-                        for (int u = 0; u < 2; ++u) one(jj + u, x[u], w[u]);
-#pragma unroll
-                        for (int u = 0; u < 2; ++u) fma(x[u], w[u]);
-                        jj += 2;
-                    }
-                    if (n & 1) {
-                        vec_t x;
-                        float w;
-                        one(jj, x, w);
-                        fma(x, w);
-                    }
+    for (int q = 0; q < 32; ++q) sums[q] = 0.0f;
+    if (phases > 0) {
+        // Requests run two phases ahead of the arithmetic: while phase ph is multiplied, the slab
+        // rows and the first 64 entries of phase ph + 1 are in registers or on their way, and
+        // those of ph + 2 are requested at the end of ph - after the rows of ph + 1 have gone
+        // from their registers into LDS - by each wavefront as it gets there, not by all
+        // sixteen at once behind the barrier.
+        // (two sets of registers take turns, the loop is written out for an even and an odd phase:
+        // handing a set on from phase to phase would make each phase wait for what it has just requested)
+        struct Ahead {
+            uint32_t a = 0, e = 0;      // the wavefront's part of the list in that phase
+            uint32_t ev = 0;            // its first 64 entries, one per lane
+            float w = 0.0f;             // and their weights
+        } even, odd;
+        // The entries are requested behind the compiler's back and waited for by hand (arrived): a
+        // wait of the compiler's own would stand at the top of the next phase, where it would stall
+        // on what was requested a moment before.
+        auto request_entries = [&](int ph, Ahead &x) {
+            x = Ahead{};
+            if (ph >= phases) return;
+            if (ph > 0 && (ph & 63) == 0) segments(ph);
+            segment(ph, x.a, x.e);
+            if ((uint32_t)lane < x.e - x.a && x.e > x.a) {
+                const uint32_t *src = (const uint32_t *)((const char *)(ent + x.a) + lane4);
+                asm volatile("global_load_dword %0, %1, off" : "=v"(x.ev) : "v"(src) : "memory");
+            }
+        };
+        auto request = [&](int ph, Ahead &x) {
+            request_entries(ph, x);
+            if (ph < phases) slab_fetch(ph);
+        };
+        // (nothing younger than the entries is in flight where this is called, so the wait is for them alone)
+        auto arrived = [&](Ahead &x) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
+            asm volatile("" : "+v"(x.ev) : : "memory");
+        };
+        auto phase = [&](int ph, Ahead &cur, Ahead &nxt) {
+            const uint32_t base = (uint32_t)(uintptr_t)(slabs + (size_t)(ph & 1) * kHalf * kImages) + (uint32_t)lane * (IPL * 4);
+            // 64 entries at a time; a second 64 (a group of rows with more than 64 surviving weights
+            // in 64 columns) are waited for where they are requested, so that the wait in front of
+            // the first counts only what was requested before it
+            uint32_t v = cur.ev;
+            float w = cur.w;
+            for (uint32_t a = cur.a; a < cur.e;) {
+                const int n = (int)min(64u, cur.e - a);
+                // lanes past the last entry: that entry again with weight zero
+                const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)v, n - 1);
+                const uint32_t vat = lane < n ? v : last, vw = lane < n ? __builtin_bit_cast(uint32_t, w) : 0u;
+                wide_fma_entries<IPL>(sums, vat, vw, base, n);
+                a += 64u;
+                if (a < cur.e) {
+                    v = window(a, cur.e);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+                    w = weight_of(v);
                 }
             }
-            if (more) slab_store(ph + 1, kStageHalf, kSlabRowsPerWave);
-        }
+            if (ph + 1 < phases) slab_store(ph + 1);
+            arrived(nxt);
+            nxt.w = weight_of(nxt.ev);
+            asm volatile("" : "+v"(nxt.w));                             // looked up here, not behind the requests below
+            request(ph + 2, cur);
+            __syncthreads();
+        };
+        // what the first phase needs, all requested before anything is waited for: the first slab
+        // rows, the pointers, the codebook; then the entries (they need the pointers)
+        slab_fetch(0);
+        segments(0);
+        const float cbv = (int)threadIdx.x < L.ncode ? L.codebook[threadIdx.x] : 0.0f;
+        request_entries(0, even);
+        if ((int)threadIdx.x < L.ncode) cb[threadIdx.x] = cbv;
+        slab_store(0);
+        arrived(even);
+        request(1, odd);
         __syncthreads();
+        even.w = weight_of(even.ev);
+        for (int ph = 0; ph < phases; ph += 2) {
+            phase(ph, even, odd);
+            if (ph + 1 < phases) phase(ph + 1, odd, even);
+        }
     }
     // the wavefront's rows of the workgroup's partial tile, part[pj][row][Bp]: a row's images are contiguous
-    float *mine = part + ((size_t)pj * kTile + (size_t)wave * kWideRows) * (size_t)Bp + (size_t)nb * kImages + (size_t)lane * IPL;
+    float *mine = part + ((size_t)pj * kTile + (size_t)wave * kMulRows) * (size_t)Bp + (size_t)nb * kImages + (size_t)lane * IPL;
 #pragma unroll
-    for (int r = 0; r < kWideRows; ++r) {
-        if (wave * kWideRows + r >= kTile) break;
+    for (int r = 0; r < kMulRows; ++r) {
         vec_t v;
-        if constexpr (IPL == 1) v = acc[r][0];
+        if constexpr (IPL == 1) v = sums[r];
         else {
 #pragma unroll
-            for (int q = 0; q < IPL; ++q) v[q] = acc[r][q];
+            for (int q = 0; q < IPL; ++q) v[q] = sums[r * IPL + q];
         }
         *(vec_t *)(mine + (size_t)r * Bp) = v;
     }
@@ -391,327 +433,5 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(LayerDev L, const floa
             const int r = r0 + t4 + u;
             if (r < bhp) Y[(size_t)img * L.M + row_id + r] = tile[t4 + u][ti + 32 * half];
         }
-    }
-}
-
-// ------------------------------------------------------------------------- //
-// The wide path for tiles of 256 images, in two launches: decode to an entry
-// list, then multiply
-// ------------------------------------------------------------------------- //
-// wide_expand_kernel decodes the whole layer once per call (Algorithm 2 steps 5-9, one
-// wavefront per chunk as in decode_kernel) into a list in global memory: a block's
-// surviving weights - the padding entries dropped - in the order the multiplying kernel
-// takes them: first those in the block's columns 0-63, then those in columns 64-127,
-// each half row by row.  Where a chunk's entries go in that order does not depend on the
-// activations: the layer carries, per chunk, the list position of its first surviving
-// weight of each half (chunk_half), and, per block and half, where each group of eight
-// rows starts (group_ptr), both counted when the layer was loaded.  An entry is one word:
-// the value index (bits 16-23), the column within the half (bits 8-13) and four times the
-// row within its group of eight (bits 0-7).
-// wide_mul_kernel then holds no decode tables, decodes nothing and waits for no decoder:
-// sixteen wavefronts multiply, each owning the eight rows of one group, the weights looked
-// up in the codebook (Algorithm 2 step 8) 64 entries at a time, and every image tile of a
-// large batch reads the same list.
-typedef uint32_t WideEntry;
-constexpr int kMulRows = kTile / kWideWaves;            // rows of a block row per wavefront: a group
-constexpr int kGroupPtrs = 2 * (kWideWaves + 1);        // group_ptr words per block
-
-// (One launch can decode several layers - those of a stack that take this path - each into
-// its own list: workgroups wg0[i] .. wg0[i + 1] - 1 belong to job i.)
-constexpr int kExpandJobs = 4;
-struct ExpandJobs {
-    LayerDev L[kExpandJobs];
-    WideEntry *ent[kExpandJobs];
-    uint32_t wg0[kExpandJobs + 1];
-};
-
-__global__ __launch_bounds__(kThreads) void wide_expand_kernel(ExpandJobs jobs)
-{
-    int job = 0;
-#pragma unroll
-    for (int i = 1; i < kExpandJobs; ++i)
-        if (blockIdx.x >= jobs.wg0[i]) job = i;
-    const LayerDev &L = jobs.L[job];
-    WideEntry *ent = jobs.ent[job];
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    const Smem s = carve(smem_raw, L);
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int lane = (int)(threadIdx.x & 63);
-    const uint32_t c = (blockIdx.x - jobs.wg0[job]) * kWaves + (uint32_t)wave;
-    const bool have = c < L.n_chunks;
-    ChunkHead h{};
-    LaneRecord rec{};
-    uint32_t base0 = 0, base1 = 0;
-    if (have) {
-        h = load_head(L, c);
-        rec = load_record(L, h, lane);
-        base0 = L.chunk_half[2 * (size_t)c];
-        base1 = L.chunk_half[2 * (size_t)c + 1];
-    }
-    store_tables(s, L, fetch_tables(L));
-    __syncthreads();
-    if (!have) return;
-    const BlockGeom g = block_geom(L, h.m.blk);
-    const Symbols y = decode_record(rec, s.T);
-    const LaneStart st = lane_starts(y, h.m.pos0);
-    // the lane's surviving weights per half, then where its first of each half goes
-    uint32_t mine = 0;
-    for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-        uint32_t r, cc;
-        split_pos(pos, g, r, cc);
-        if (v != 0u) mine += cc >= (uint32_t)kHalf ? 0x10000u : 1u;
-    });
-    const uint32_t excl = wave_incl_scan(mine) - mine;
-    uint32_t at0 = base0 + (excl & 0xffffu), at1 = base1 + (excl >> 16);
-    for_each_entry(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-        uint32_t r, cc;
-        split_pos(pos, g, r, cc);
-        if (v == 0u) return;
-        const WideEntry e = (v << 16) | ((cc & (uint32_t)(kHalf - 1)) << 8) | ((r & (uint32_t)(kMulRows - 1)) * 4u);
-        if (cc >= (uint32_t)kHalf) ent[at1++] = e;
-        else ent[at0++] = e;
-    });
-}
-
-// The multiply-add of up to 64 entries, one per lane of (entry word, weight) - lanes past
-// the last entry holding a copy of the last one with weight zero - into the sums of the
-// entries' rows: sums[4 r + q] += w * x[column][4 lane + q].  The rows differ from entry to entry
-// and the sums live in registers, so the register a product is added to is picked at run
-// time: the sums sit in v[64:95], the additions run in the vector-register index mode
-// with the entry's row offset as the index (destination and addend relative), and
-// everything between switching the mode on and off is written out here.  Entries are
-// taken four at a time, the activations of the next four requested from LDS (into
-// v[96:127], alternating halves) before the products of the present four are formed, so
-// that the loads and the arithmetic overlap from one end of the list to the other
-// whatever the rows' lengths.
-#define WM_RL(i, slot)                                                                       \
-    "v_readlane_b32 %[c" #slot "], %[vat], " #i "\n"                                         \
-    "v_readlane_b32 %[w" #slot "], %[vw], " #i "\n"
-#define WM_AD(slot, tmp)                                                                     \
-    "s_and_b32 %[" #tmp "], %[c" #slot "], 0x3f00\n"                                        \
-    "v_lshl_add_u32 v[" #slot "*4+96], %[" #tmp "], 2, %[base]\n"
-#define WM_RD(slot) "ds_read_b128 v[" #slot "*4+96:" #slot "*4+99], v[" #slot "*4+96]\n"
-#define WM_FMA1(slot)                                                                        \
-    "s_set_gpr_idx_on %[c" #slot "], 0xc\n"                                                  \
-    "v_fma_f32 v64, %[w" #slot "], v[" #slot "*4+96], v64\n"                                 \
-    "v_fma_f32 v65, %[w" #slot "], v[" #slot "*4+97], v65\n"                                 \
-    "v_fma_f32 v66, %[w" #slot "], v[" #slot "*4+98], v66\n"                                 \
-    "v_fma_f32 v67, %[w" #slot "], v[" #slot "*4+99], v67\n"
-#define WM_LOAD4(i0, i1, i2, i3, s0, s1, s2, s3)                                             \
-    WM_RL(i0, s0) WM_RL(i1, s1) WM_RL(i2, s2) WM_RL(i3, s3)                                  \
-    WM_AD(s0, t) WM_AD(s1, t2) WM_AD(s2, t) WM_AD(s3, t2)                                    \
-    WM_RD(s0) WM_RD(s1) WM_RD(s2) WM_RD(s3)
-#define WM_FMA4(s0, s1, s2, s3) WM_FMA1(s0) WM_FMA1(s1) WM_FMA1(s2) WM_FMA1(s3) "s_set_gpr_idx_off\n"
-// entries i0 .. i0 + 3 are in flight in slots (a); request i0 + 4 .. i0 + 7 into slots (b), then add (a)
-#define WM_STEP(prio, n_done, j0, j1, j2, j3, a0, a1, a2, a3, b0, b1, b2, b3)                \
-    "s_setprio " #prio "\n"                                                                  \
-    WM_LOAD4(j0, j1, j2, j3, b0, b1, b2, b3)                                                 \
-    "s_waitcnt lgkmcnt(4)\n"                                                                 \
-    WM_FMA4(a0, a1, a2, a3)                                                                  \
-    "s_cmp_le_u32 %[n], " #n_done "\n"                                                       \
-    "s_cbranch_scc1 1f\n"
-#define WM_LAST(a0, a1, a2, a3)                                                              \
-    "s_waitcnt lgkmcnt(0)\n"                                                                 \
-    WM_FMA4(a0, a1, a2, a3)
-// The four wavefronts of a SIMD would otherwise be served oldest first, finish a list one
-// after the other, and the last, alone, cannot keep the vector unit busy (one wavefront
-// issues an instruction every four to five cycles, of which 7 in 12 are vector
-// arithmetic here): each raises and lowers its priority from step to step (p0..p3), and
-// as the four are never at the same step for long, all four advance together.
-#define WM_BODY(p0, p1, p2, p3)                                                              \
-    WM_LOAD4(0, 1, 2, 3, 0, 1, 2, 3)                                                         \
-    WM_STEP(p0, 4, 4, 5, 6, 7, 0, 1, 2, 3, 4, 5, 6, 7)                                       \
-    WM_STEP(p0, 8, 8, 9, 10, 11, 4, 5, 6, 7, 0, 1, 2, 3)                                     \
-    WM_STEP(p0, 12, 12, 13, 14, 15, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_STEP(p1, 16, 16, 17, 18, 19, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
-    WM_STEP(p1, 20, 20, 21, 22, 23, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_STEP(p1, 24, 24, 25, 26, 27, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
-    WM_STEP(p2, 28, 28, 29, 30, 31, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_STEP(p2, 32, 32, 33, 34, 35, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
-    WM_STEP(p2, 36, 36, 37, 38, 39, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_STEP(p3, 40, 40, 41, 42, 43, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
-    WM_STEP(p3, 44, 44, 45, 46, 47, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_STEP(p3, 48, 48, 49, 50, 51, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
-    WM_STEP(p3, 52, 52, 53, 54, 55, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_STEP(p3, 56, 56, 57, 58, 59, 4, 5, 6, 7, 0, 1, 2, 3)                                  \
-    WM_STEP(p3, 60, 60, 61, 62, 63, 0, 1, 2, 3, 4, 5, 6, 7)                                  \
-    WM_LAST(4, 5, 6, 7)                                                                      \
-    "1:\n"                                                                                   \
-    "s_waitcnt lgkmcnt(0)\n"                                                                 \
-    "s_setprio 0\n"
-#define WM_OPERANDS                                                                                                           \
-    : "+{v[64:95]}"(sums), [c0] "=&s"(c0), [c1] "=&s"(c1), [c2] "=&s"(c2), [c3] "=&s"(c3), [c4] "=&s"(c4), [c5] "=&s"(c5),   \
-      [c6] "=&s"(c6), [c7] "=&s"(c7), [w0] "=&s"(w0), [w1] "=&s"(w1), [w2] "=&s"(w2), [w3] "=&s"(w3), [w4] "=&s"(w4),         \
-      [w5] "=&s"(w5), [w6] "=&s"(w6), [w7] "=&s"(w7), [t] "=&s"(t), [t2] "=&s"(t2)                                            \
-    : [vat] "v"(vat), [vw] "v"(vw), [base] "v"(base), [n] "s"(n)                                                              \
-    : "memory", "scc", "m0", "v96", "v97", "v98", "v99", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107",      \
-      "v108", "v109", "v110", "v111", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", \
-      "v123", "v124", "v125", "v126", "v127"
-
-typedef float WideSums __attribute__((ext_vector_type(32)));
-
-__device__ __forceinline__ void wide_fma_entries(WideSums &sums, uint32_t vat, uint32_t vw, uint32_t base, int n)
-{
-    uint32_t c0, c1, c2, c3, c4, c5, c6, c7, w0, w1, w2, w3, w4, w5, w6, w7, t, t2;
-    asm volatile(WM_BODY(3, 2, 1, 0) WM_OPERANDS);
-}
-
-// Workgroup (block row p, split j of its blocks, image tile nb) of sixteen wavefronts, one
-// to a CU.  A phase is half a block: its 64 columns' activations for the 256 images sit
-// in one of two 64 KB slabs, every wavefront multiplies its group's entries of that half,
-// and meanwhile brings in its four rows of the next phase's slab (registers first, LDS
-// after its arithmetic) and the first 64 of its next entries; one barrier ends the phase.
-__global__ __launch_bounds__(kWideThreads) void wide_mul_kernel(LayerDev L, const float *__restrict__ XT,
-                                                                const WideEntry *__restrict__ ent, float *part, int panels,
-                                                                int splits, int Bp)
-{
-    constexpr int IPL = 4, kImages = 64 * IPL;
-    typedef typename WideVec<IPL>::type vec_t;
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    float *slabs = (float *)smem_raw;                                   // [2][kHalf][kImages]
-    float *cb = slabs + 2 * kHalf * kImages;                            // [ncode]
-    // consecutive workgroups take the splits of one block row (see fc_wide_kernel)
-    const int j = (int)blockIdx.x % splits, rest = (int)blockIdx.x / splits;
-    const int p = rest % panels, nb = rest / panels;
-    const int pj = p * splits + j;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int lane = (int)(threadIdx.x & 63);
-    const int blk_lo = (int)(((int64_t)L.nbw * j) / splits), blk_hi = (int)(((int64_t)L.nbw * (j + 1)) / splits);
-    const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
-    const int nh = L.bw > kHalf ? 2 : 1;
-    const int phases = (blk_hi - blk_lo) * nh;
-
-    // A wavefront's share of a slab: rows 4 wave .. 4 wave + 3, four floats per lane and row.  The
-    // slab of phase ph starts at row (blk_lo + ph / nh) 128 + (ph % nh) 64 of the activations: a
-    // uniform base that moves from phase to phase, and per lane a constant byte offset per row.
-    const char *xbase = (const char *)(XT + (size_t)nb * kImages);
-    uint32_t xoff[kSlabRowsPerWave];
-#pragma unroll
-    for (int q = 0; q < kSlabRowsPerWave; ++q) xoff[q] = (uint32_t)((wave * kSlabRowsPerWave + q) * Bp + lane * IPL) * 4u;
-    vec_t stage[kSlabRowsPerWave];
-    auto slab_fetch = [&](int ph) {
-        const char *src = xbase + ((size_t)(blk_lo + ph / nh) * kTile + (size_t)(ph % nh) * kHalf) * (size_t)Bp * 4;
-#pragma unroll
-        for (int q = 0; q < kSlabRowsPerWave; ++q) stage[q] = *(const vec_t *)(src + xoff[q]);
-    };
-    auto slab_store = [&](int ph) {
-        float *dst = slabs + (size_t)(ph & 1) * kHalf * kImages + (size_t)(wave * kSlabRowsPerWave) * kImages + lane * IPL;
-#pragma unroll
-        for (int q = 0; q < kSlabRowsPerWave; ++q) *(vec_t *)(dst + q * kImages) = stage[q];
-    };
-    // The wavefront's part of the list in each phase - its group of rows in that half of that
-    // block - for 64 phases at a time, phase ph0 + lane in lane `lane`: fetched ahead of
-    // the loop so that no phase starts by waiting for a pointer.
-    uint32_t seg_a = 0, seg_e = 0;
-    auto segments = [&](int ph0) {
-        const int ph = min(ph0 + lane, phases - 1);
-        const uint32_t b = pb0 + (uint32_t)(blk_lo + ph / nh);
-        const uint32_t *gp = L.group_ptr + ((size_t)b * 2 + (size_t)(ph % nh)) * (kWideWaves + 1) + wave;
-        seg_a = gp[0];
-        seg_e = gp[1];
-    };
-    auto segment = [&](int ph, uint32_t &a, uint32_t &e) {
-        a = (uint32_t)__builtin_amdgcn_readlane((int)seg_a, ph & 63);
-        e = (uint32_t)__builtin_amdgcn_readlane((int)seg_e, ph & 63);
-    };
-    // up to 64 entries from list position a on, one per lane
-    const uint32_t lane4 = (uint32_t)lane * 4u;
-    auto window = [&](uint32_t a, uint32_t e) {
-        uint32_t v = 0u;
-        if ((uint32_t)lane < e - a) v = *(const uint32_t *)((const char *)(ent + a) + lane4);
-        return v;
-    };
-    auto weight_of = [&](uint32_t entry) { return cb[(entry >> 16) & 0xffu]; };
-
-    WideSums sums;
-#pragma unroll
-    for (int q = 0; q < kMulRows * IPL; ++q) sums[q] = 0.0f;
-    if (phases > 0) {
-        // Requests run two phases ahead of the arithmetic: while phase ph is multiplied, the slab
-        // rows and the first 64 entries of phase ph + 1 are in registers or on their way, and
-        // those of ph + 2 are requested at the end of ph - after the rows of ph + 1 have gone
-        // from their registers into LDS - by each wavefront as it gets there, not by all
-        // sixteen at once behind the barrier.
-        // (two sets of registers take turns, the loop is written out for an even and an odd phase:
-        // handing a set on from phase to phase would make each phase wait for what it has just requested)
-        struct Ahead {
-            uint32_t a = 0, e = 0;      // the wavefront's part of the list in that phase
-            uint32_t ev = 0;            // its first 64 entries, one per lane
-            float w = 0.0f;             // and their weights
-        } even, odd;
-        // The entries are requested behind the compiler's back and waited for by hand (arrived): a
-        // wait of the compiler's own would stand at the top of the next phase, where it would stall
-        // on what was requested a moment before.
-        auto request_entries = [&](int ph, Ahead &x) {
-            x = Ahead{};
-            if (ph >= phases) return;
-            if (ph > 0 && (ph & 63) == 0) segments(ph);
-            segment(ph, x.a, x.e);
-            if ((uint32_t)lane < x.e - x.a && x.e > x.a) {
-                const uint32_t *src = (const uint32_t *)((const char *)(ent + x.a) + lane4);
-                asm volatile("global_load_dword %0, %1, off" : "=v"(x.ev) : "v"(src) : "memory");
-            }
-        };
-        auto request = [&](int ph, Ahead &x) {
-            request_entries(ph, x);
-            if (ph < phases) slab_fetch(ph);
-        };
-        // (nothing younger than the entries is in flight where this is called, so the wait is for them alone)
-        auto arrived = [&](Ahead &x) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
-            asm volatile("" : "+v"(x.ev) : : "memory");
-        };
-        auto phase = [&](int ph, Ahead &cur, Ahead &nxt) {
-            const uint32_t base = (uint32_t)(uintptr_t)(slabs + (size_t)(ph & 1) * kHalf * kImages) + (uint32_t)lane * (IPL * 4);
-            // 64 entries at a time; a second 64 (a group of rows with more than 64 surviving weights
-            // in 64 columns) are waited for where they are requested, so that the wait in front of
-            // the first counts only what was requested before it
-            uint32_t v = cur.ev;
-            float w = cur.w;
-            for (uint32_t a = cur.a; a < cur.e;) {
-                const int n = (int)min(64u, cur.e - a);
-                // lanes past the last entry: that entry again with weight zero
-                const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)v, n - 1);
-                const uint32_t vat = lane < n ? v : last, vw = lane < n ? __builtin_bit_cast(uint32_t, w) : 0u;
-                wide_fma_entries(sums, vat, vw, base, n);
-                a += 64u;
-                if (a < cur.e) {
-                    v = window(a, cur.e);
-                    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
-                    w = weight_of(v);
-                }
-            }
-            if (ph + 1 < phases) slab_store(ph + 1);
-            arrived(nxt);
-            nxt.w = weight_of(nxt.ev);
-            asm volatile("" : "+v"(nxt.w));                             // looked up here, not behind the requests below
-            request(ph + 2, cur);
-            __syncthreads();
-        };
-        // what the first phase needs, all requested before anything is waited for: the first slab
-        // rows, the pointers, the codebook; then the entries (they need the pointers)
-        slab_fetch(0);
-        segments(0);
-        const float cbv = (int)threadIdx.x < L.ncode ? L.codebook[threadIdx.x] : 0.0f;
-        request_entries(0, even);
-        if ((int)threadIdx.x < L.ncode) cb[threadIdx.x] = cbv;
-        slab_store(0);
-        arrived(even);
-        request(1, odd);
-        __syncthreads();
-        even.w = weight_of(even.ev);
-        for (int ph = 0; ph < phases; ph += 2) {
-            phase(ph, even, odd);
-            if (ph + 1 < phases) phase(ph + 1, odd, even);
-        }
-    }
-    // the wavefront's rows of the workgroup's partial tile, part[pj][row][Bp]: a row's images are contiguous
-    float *mine = part + ((size_t)pj * kTile + (size_t)wave * kMulRows) * (size_t)Bp + (size_t)nb * kImages + (size_t)lane * IPL;
-#pragma unroll
-    for (int r = 0; r < kMulRows; ++r) {
-        vec_t v;
-#pragma unroll
-        for (int q = 0; q < IPL; ++q) v[q] = sums[r * IPL + q];
-        *(vec_t *)(mine + (size_t)r * Bp) = v;
     }
 }

@@ -125,9 +125,8 @@ def test_fc_forward_wide_path(M, K, bh, bw, d, r, k, B):
     images across the lanes): image tiles of 64, 128 and 256 images with ragged batches,
     ragged last block row and column, blocks narrower than a slab (one phase per block),
     wider (two), lower than a tile, empty and nearly empty layers (blocks without
-    entries, rows without entries), a block dense enough for several chunks per
-    decoding wavefront; from 129 images on the two-launch form (entry list in the
-    workspace); both gates, and run-to-run identical."""
+    entries, rows without entries), groups of rows with more than 64 entries in a
+    phase; both gates, and run-to-run identical."""
     torch = torch_cuda()
     rng = np.random.default_rng(M + K * 3 + B)
     W = rand_pruned(rng, M, K, d)
