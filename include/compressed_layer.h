@@ -54,7 +54,7 @@ enum {
 
 /* Kernel selection for the forward entry points. */
 enum {
-    CL_PATH_AUTO = 0,     /* CL_PATH_SPARSE for up to 4 images and for blocks above      */
+    CL_PATH_AUTO = 0,     /* CL_PATH_SPARSE for up to 8 images and for blocks above      */
                           /*   128 x 128; else whichever of CL_PATH_MFMA_F32 and        */
                           /*   CL_PATH_SPARSE_WIDE the library's launch models price    */
                           /*   lower for this layer and batch (the dense tile multiplies */
@@ -250,10 +250,12 @@ int32_t cl_fc_resolved_path(const cl_layer *layer, int32_t batch, int32_t path, 
  *  d_X     batch x K fp32        d_bias  M fp32 or NULL
  *  d_Y     batch x M fp32, overwritten
  *  relu    non-zero applies max(0, .)
- *  path    CL_PATH_*.  CL_PATH_SPARSE adds lane sums into an LDS tile with
- *          floating-point atomics, so the last bits of Y can differ between runs;
- *          the tiles of a block row are then added up in a fixed order.  The MFMA
- *          paths are run-to-run identical.
+ *  path    CL_PATH_*.  CL_PATH_SPARSE takes up to 8 images per launch in a fixed
+ *          summation order when block_h <= 256 (run-to-run identical); a launch for
+ *          9-16 images at once, or a layer with taller blocks, adds lane sums into
+ *          a shared LDS tile with floating-point atomics, so the last bits of Y can
+ *          differ between runs.  The tiles of a block row are added up in a fixed
+ *          order either way.  The other paths are run-to-run identical.
  *  d_workspace / workspace_bytes   at least cl_fc_workspace_bytes(); may be NULL
  *          when that is 0
  * Errors: CL_EINVAL (null pointers, batch < 1, workspace too small, layer not

@@ -309,10 +309,15 @@ struct SparsePlan {
     size_t fixed = 0;        // LDS bytes of tables + codebook
     size_t part_bytes = 0;   // partial-tile buffer in the workspace
     int xcap_for(int bt) const { return (size_t)xwant * 4 * bt <= 32 * 1024 ? xwant : 0; }
-    size_t lds_for(const cl_layer *L, int bt) const { return fixed + ((size_t)L->desc.block_h + xcap_for(bt)) * 4 * bt; }
+    size_t lds_for(const cl_layer *L, int bt) const
+    {
+        const size_t tiles = private_tiles(L->desc.block_h, bt) ? kWaves : 1;
+        return fixed + (tiles * L->desc.block_h + xcap_for(bt)) * 4 * bt;
+    }
 };
 
-int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
+// (one_tile: the caller wants the whole batch, up to 16 images, in one batch tile)
+int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P, bool one_tile = false)
 {
     P.fixed = table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits);
     P.xwant = (int)std::min<int64_t>(L->desc.K, (1 + 2 * kSparseChunksPerWave) * (int64_t)L->desc.block_w);
@@ -320,7 +325,8 @@ int32_t plan_sparse(const cl_layer *L, int batch, size_t max_lds, SparsePlan &P)
     size_t budget = std::min<size_t>(max_lds, 64 * 1024);
     if (P.lds_for(L, 1) > budget) budget = max_lds;
     if (P.lds_for(L, 1) > budget) return fail(CL_EUNSUPPORTED, "block_h %d needs more LDS than a workgroup has", L->desc.block_h);
-    P.bt_max = 16;
+    // two launches with a tile per wavefront are faster than one of 16 images through atomics
+    P.bt_max = !one_tile && private_tiles(L->desc.block_h, kPrivateTileBT) ? kPrivateTileBT : 16;
     while (P.bt_max > 1 && (P.lds_for(L, P.bt_max) > budget || P.bt_max / 2 >= batch)) P.bt_max >>= 1;
     P.wg_per_panel = (int)((L->max_panel_chunks + kWaves * kSparseChunksPerWave - 1) / (kWaves * kSparseChunksPerWave));
     P.part_bytes = (size_t)L->n_panels * P.wg_per_panel * L->desc.block_h * P.bt_max * sizeof(float);
@@ -578,16 +584,16 @@ int32_t launch_wide_mul(const LayerDev &D, int panels, const WidePlan &P, const 
     return CL_OK;
 }
 
-// CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images; above, when the blocks
-// fit a tile, whichever of the dense-tile path and the wide sparse path the two launch
-// models price lower (same units, both fitted to measured launches).  Measured on the
-// AlexNet-shaped stack (fc6 / fc7 / fc8, ms per layer call): sparse 0.037 / 0.024 / 0.019
-// at 4 images and 0.061 / 0.038 / 0.028 at 5-8 (its batch tile is a power of two); dense
-// tiles of 32 images 0.048 / 0.028 / 0.021; at 256 images dense tiles 0.176 / 0.095 /
-// 0.044, wide sparse 0.102 / 0.061 / 0.054 - the dense tile multiplies eleven times the
-// necessary products at a 9 % density but four at 25 %; at 128 images (the fused wide
-// kernel) dense tiles' 0.105 beat 0.118.
-constexpr int kAutoSparseBatch = 4;
+// CL_PATH_AUTO: the sparse path up to kAutoSparseBatch images (one batch tile of the kernel
+// with a tile per wavefront); above, when the blocks fit a tile, whichever of the dense-tile
+// path and the wide sparse path the two launch models price lower (same units, both fitted
+// to measured launches).  Measured on the AlexNet-shaped stack (fc6 / fc7 / fc8, ms per
+// layer call): sparse 0.019 / 0.015 / 0.015 at 4 images, 0.024 / 0.016 / 0.014 at 8 and
+// 0.054 / 0.034 / 0.024 at 9-16 (two batch tiles); dense tiles of 32 images 0.040 / 0.024 /
+// 0.019; at 256 images dense tiles 0.176 / 0.095 / 0.044, wide sparse 0.094 / 0.051 for fc6
+// and fc7 - the dense tile multiplies eleven times the necessary products at a 9 % density
+// but four at 25 %.
+constexpr int kAutoSparseBatch = 8;
 
 int resolve_path(const cl_layer *L, int batch, int path, const DeviceLimits &dl)
 {
@@ -663,26 +669,32 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
     dim3 grid;
     if (L->n_chunks > 0) GRID_TRY(grid, (int64_t)L->n_panels * P.wg_per_panel);
     for (int b0 = 0; b0 < batch;) {
+        // the smallest batch tile that holds the images left (its other images are zeros):
+        // one launch for 3 images, not two
+        const int nb = std::min(P.bt_max, batch - b0);
         int bt = P.bt_max;
-        while (bt > batch - b0) bt >>= 1;
+        while (bt / 2 >= nb) bt >>= 1;
         const float *x = d_X + (size_t)b0 * K;
         float *y = d_Y + (size_t)b0 * M;
         if (L->n_chunks > 0) {
             const size_t lds = P.lds_for(L, bt);
             const int xcap = P.xcap_for(bt);
             if (b0 == 0) timing_begin(st);      // benchmarks time the first main-kernel launch of a call
-#define CL_LAUNCH_SPARSE(BTV)                                                                                      \
+#define CL_LAUNCH_SPARSE(BTV, FOLDV)                                                                               \
     do {                                                                                                           \
         if (lds > 64 * 1024)                                                                                       \
-            HIP_TRY(hipFuncSetAttribute((const void *)fc_sparse_kernel<BTV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
-        hipLaunchKernelGGL(fc_sparse_kernel<BTV>, grid, dim3(kThreads), lds, st, D, x, part, P.wg_per_panel, xcap, from); \
+            HIP_TRY(hipFuncSetAttribute((const void *)fc_sparse_kernel<BTV, FOLDV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)); \
+        hipLaunchKernelGGL((fc_sparse_kernel<BTV, FOLDV>), grid, dim3(kThreads), lds, st, D, x, part, P.wg_per_panel, xcap, from, nb); \
     } while (0)
             switch (bt) {
-            case 16: CL_LAUNCH_SPARSE(16); break;
-            case 8: CL_LAUNCH_SPARSE(8); break;
-            case 4: CL_LAUNCH_SPARSE(4); break;
-            case 2: CL_LAUNCH_SPARSE(2); break;
-            default: CL_LAUNCH_SPARSE(1); break;
+            case 16: CL_LAUNCH_SPARSE(16, false); break;
+            case 8: CL_LAUNCH_SPARSE(8, false); break;
+            case 4: CL_LAUNCH_SPARSE(4, false); break;
+            case 2: CL_LAUNCH_SPARSE(2, false); break;
+            default:
+                if (prev) CL_LAUNCH_SPARSE(1, true);
+                else CL_LAUNCH_SPARSE(1, false);
+                break;
             }
 #undef CL_LAUNCH_SPARSE
             HIP_TRY(hipGetLastError());
@@ -690,12 +702,12 @@ static int32_t forward_sparse(const cl_layer *L, const LayerDev &D, const Device
         }
         if (finish) {
             dim3 rgrid;
-            GRID_TRY(rgrid, (int64_t)L->n_panels * bt);
+            GRID_TRY(rgrid, (int64_t)L->n_panels * nb);
             hipLaunchKernelGGL(fc_reduce_kernel, rgrid, dim3(kRedThreads), 0, st,
-                               D, part, d_bias, y, bt, bt, P.wg_per_panel, relu);
+                               D, part, d_bias, y, nb, bt, P.wg_per_panel, relu);
             HIP_TRY(hipGetLastError());
         }
-        b0 += bt;
+        b0 += nb;
     }
     return CL_OK;
 }
@@ -1070,7 +1082,7 @@ int32_t plan_group(const cl_layer_group *G, int batch, const DeviceLimits &dl, G
     const cl_layer *L = G->layers[0];
     if (batch < 1) return fail(CL_EINVAL, "batch must be positive");
     if (batch > 16 || (batch & (batch - 1))) return fail(CL_EUNSUPPORTED, "a group call takes 1, 2, 4, 8 or 16 images per layer");
-    if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P.sp)) return rc;
+    if (int32_t rc = plan_sparse(L, batch, dl.max_lds, P.sp, true)) return rc;
     if (P.sp.bt_max < batch) return fail(CL_EUNSUPPORTED, "%d images do not fit one batch tile of this layer shape", batch);
     const int bt = batch;
     P.sp.bt_max = bt;

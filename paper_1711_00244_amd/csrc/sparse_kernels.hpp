@@ -68,10 +68,47 @@ struct PrevSlots {
     int bh, wg_per_panel, part_b, relu;
 };
 
-// (wg: the workgroup's number within the layer's share of the grid)
+// Up to this batch tile, and for block rows of up to 256 rows, every wavefront of the small-
+// batch kernel has an output tile of its own in LDS and writes each row sum once, with a
+// plain store (see fc_sparse_body); above, the workgroup shares one tile through float atomics
+// (8 x bh x BT floats would crowd the CU, and those batch sizes belong to the tile kernels).
+constexpr int kPrivateTileBT = 8, kPrivateTileRows = 256;
+__host__ __device__ constexpr bool private_tiles(int bh, int bt) { return bt <= kPrivateTileBT && bh <= kPrivateTileRows; }
+
+// Inclusive sums over the lanes of a wavefront in segments: a lane with `start` begins a
+// segment.  (value, started) pairs combine as (b.started ? b.value : a.value + b.value,
+// a.started | b.started), which is associative, so the usual doubling steps apply.
 template <int BT>
+__device__ __forceinline__ void wave_segmented_sums(float (&v)[BT], bool start)
+{
+    uint32_t f = start ? 1u : 0u;
+#define CL_SEG_STEP(CTRL, ROWS)                                                                              \
+    {                                                                                                        \
+        const uint32_t tf = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)f, CTRL, ROWS, 0xf, false);        \
+        _Pragma("unroll") for (int b = 0; b < BT; ++b)                                                       \
+        {                                                                                                    \
+            const float tv = __builtin_bit_cast(                                                             \
+                float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[b]), CTRL, ROWS, 0xf, false)); \
+            v[b] = f ? v[b] : v[b] + tv;                                                                     \
+        }                                                                                                    \
+        f |= tf;                                                                                             \
+    }
+    CL_SEG_STEP(0x111, 0xf)   // row_shr:1
+    CL_SEG_STEP(0x112, 0xf)   // row_shr:2
+    CL_SEG_STEP(0x114, 0xf)   // row_shr:4
+    CL_SEG_STEP(0x118, 0xf)   // row_shr:8
+    CL_SEG_STEP(0x142, 0xa)   // row_bcast:15 into rows 1, 3
+    CL_SEG_STEP(0x143, 0xc)   // row_bcast:31 into rows 2, 3
+#undef CL_SEG_STEP
+}
+
+// (wg: the workgroup's number within the layer's share of the grid; nb <= BT: images that X
+// holds - the tile's other images are zeros; FOLD: the input may be the partial tiles of the
+// layer before - an instantiation of its own, so that the code for it does not weigh on the
+// registers of the others)
+template <int BT, bool FOLD>
 __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *__restrict__ X, float *part, int wg_per_panel,
-                                               int xcap, const PrevSlots &prev, uint32_t wg)
+                                               int xcap, const PrevSlots &prev, uint32_t wg, int nb)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     const Smem s = carve(smem_raw, L);
@@ -98,8 +135,10 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
         }
     }
     const TableRegs tr = fetch_tables(L);
-    float *ytile = s.extra;                  // [BT][bh]
-    float *xs = ytile + (size_t)L.bh * BT;   // [xcap][BT]: a column's BT images side by side, one LDS read per entry
+    const bool priv = private_tiles(L.bh, BT);
+    const int n_tiles = priv ? kWaves : 1;
+    float *ytile = s.extra;                  // [n_tiles][BT][bh]
+    float *xs = ytile + (size_t)n_tiles * L.bh * BT;   // [xcap][BT]: a column's BT images side by side, one LDS read per entry
     // activation columns of the blocks this workgroup's chunks belong to
     const uint32_t pb0 = (uint32_t)p * (uint32_t)L.nbw;
     const uint32_t c_last = min(pc1, my0 + (uint32_t)(kWaves * kSparseChunksPerWave)) - 1u;
@@ -107,7 +146,7 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
     const int col_b = min(L.K, (int)(L.meta[c_last].blk - pb0 + 1u) * L.bw);
     const int width = col_b - col_a;
     const bool slab = width <= xcap;
-    if (slab && prev.part) {
+    if (FOLD && slab && prev.part) {
         // (the host takes this form only for layers whose every workgroup has a slab)
         constexpr uint32_t kPerWg = kWaves * kSparseChunksPerWave;
         for (int t = threadIdx.x; t < width; t += blockDim.x) {
@@ -134,9 +173,9 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
     } else if (slab) {
 #pragma unroll
         for (int b = 0; b < BT; ++b)
-            for (int t = threadIdx.x; t < width; t += blockDim.x) xs[t * BT + b] = X[(size_t)b * L.K + col_a + t];
+            for (int t = threadIdx.x; t < width; t += blockDim.x) xs[t * BT + b] = b < nb ? X[(size_t)b * L.K + col_a + t] : 0.0f;
     }
-    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
+    for (int t = threadIdx.x; t < n_tiles * L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
     store_tables(s, L, tr);
     __syncthreads();
 #pragma unroll
@@ -150,7 +189,7 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
         // of the block.  The instantiations differ in where the activations come from
         // (LDS stays LDS: no generic pointers) and in how a position splits into row and
         // column (shift and mask for a power-of-two block width).
-        auto entries = [&](auto load_x, auto split) {
+        auto entries_shared = [&](auto load_x, auto split) {
             uint32_t cur = 0;
             float acc[BT];
 #pragma unroll
@@ -175,6 +214,70 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
 #pragma unroll
             for (int b = 0; b < BT; ++b) atomicAdd(ytile + b * L.bh + cur, acc[b]);
         };
+        // The same into the wavefront's own tile, without atomics (an LDS float atomic costs about
+        // three cycles per lane here: half of the kernel at four images).  The chunk's entries
+        // run row by row across the lanes, so a row's terms sit in one lane or in a run of
+        // neighbouring lanes: a row that begins and ends inside a lane is stored by that lane; a
+        // lane's first row may continue the previous lane's last one, and the run of lanes that
+        // have nothing but that row is summed with a segmented scan - the row is then stored
+        // once, by the lane where it ends.  No two lanes store the same row, and the tile
+        // receives this chunk only, so plain stores do.
+        auto entries_private = [&](auto load_x, auto split) {
+            static_assert(kSparseChunksPerWave == 1, "a wavefront's tile takes one chunk: plain stores");
+            constexpr uint32_t kNone = 0xffffffffu;
+            float *tile = ytile + (size_t)wave * L.bh * BT;
+            uint32_t cur = kNone, first_row = kNone;
+            bool several = false;                       // the lane has left its first row
+            float acc[BT], head[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) acc[b] = head[b] = 0.0f;
+            for_each_entry<false>(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                uint32_t r, cc;
+                split(pos, r, cc);
+                if (r != cur) {
+                    if (cur == kNone) first_row = r;
+                    else if (!several) {
+#pragma unroll
+                        for (int b = 0; b < BT; ++b) head[b] = acc[b];
+                        several = true;
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < BT; ++b) tile[b * L.bh + cur] = acc[b];
+                    }
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
+                    cur = r;
+                }
+                const float w = s.T.cb[v];
+                float x[BT];
+                load_x((int)cc, x);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) acc[b] += w * x[b];
+            });
+            // cur: the lane's last row (kNone for a lane without a record), acc its sum so far
+            // (every lane takes part in the exchange: a lane that sat it out would hand its
+            // neighbour a zero)
+            const uint32_t from_prev = (uint32_t)__shfl_up((int)cur, 1), from_next = (uint32_t)__shfl_down((int)first_row, 1);
+            const uint32_t prev_last = lane == 0 ? kNone : from_prev;
+            const uint32_t next_first = lane == 63 ? kNone : from_next;
+            const bool joins = first_row != kNone && first_row == prev_last;
+            wave_segmented_sums<BT>(acc, !(joins && !several));
+            float before[BT];                           // the run that ends in the lane before
+#pragma unroll
+            for (int b = 0; b < BT; ++b) before[b] = __shfl_up(acc[b], 1);
+            if (several) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) tile[b * L.bh + first_row] = joins ? head[b] + before[b] : head[b];
+            }
+            if (cur != kNone && next_first != cur) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) tile[b * L.bh + cur] = acc[b];
+            }
+        };
+        auto entries = [&](auto load_x, auto split) {
+            if (priv) entries_private(load_x, split);
+            else entries_shared(load_x, split);
+        };
         auto with_split = [&](auto load_x) {
             if (g.shift >= 0) {
                 const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u, rmax = (uint32_t)g.bhp - 1u;
@@ -194,20 +297,24 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             const float *xg = X + g.col_id;
             with_split([&](int cc, float (&x)[BT]) {
 #pragma unroll
-                for (int b = 0; b < BT; ++b) x[b] = xg[(size_t)b * L.K + cc];
+                for (int b = 0; b < BT; ++b) x[b] = b < nb ? xg[(size_t)b * L.K + cc] : 0.0f;
             });
         }
     }
     __syncthreads();
     float *mine = part + (size_t)wg * L.bh * BT;
-    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) mine[t] = ytile[t];
+    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) {
+        float sum = ytile[t];
+        for (int w = 1; w < n_tiles; ++w) sum += ytile[(size_t)w * L.bh * BT + t];   // (wavefront order: the same every run)
+        mine[t] = sum;
+    }
 }
 
-template <int BT>
+template <int BT, bool FOLD>
 __global__ __launch_bounds__(kThreads) void fc_sparse_kernel(LayerDev L, const float *__restrict__ X, float *part,
-                                                             int wg_per_panel, int xcap, PrevSlots prev)
+                                                             int wg_per_panel, int xcap, PrevSlots prev, int nb)
 {
-    fc_sparse_body<BT>(L, X, part, wg_per_panel, xcap, prev, blockIdx.x);
+    fc_sparse_body<BT, FOLD>(L, X, part, wg_per_panel, xcap, prev, blockIdx.x, nb);
 }
 
 // Several layers of one shape in one grid (the same layer of several models, or layers
@@ -221,8 +328,8 @@ __global__ __launch_bounds__(kThreads) void fc_sparse_group_kernel(const LayerDe
 {
     const uint32_t job = blockIdx.x / wgs_per_layer, wg = blockIdx.x - job * wgs_per_layer;
     const LayerDev L = table[job];
-    fc_sparse_body<BT>(L, X + job * x_stride, part + job * part_stride, wg_per_panel, xcap,
-                       PrevSlots{nullptr, nullptr, nullptr, 1, 0, 0, 0}, wg);
+    fc_sparse_body<BT, false>(L, X + job * x_stride, part + job * part_stride, wg_per_panel, xcap,
+                       PrevSlots{nullptr, nullptr, nullptr, 1, 0, 0, 0}, wg, BT);
 }
 
 // Finishes the sparse path: adds up the partial tiles of each block row in a fixed

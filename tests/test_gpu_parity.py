@@ -270,6 +270,25 @@ def test_mfma_path_is_deterministic_and_refuses_big_blocks():
     assert_close(cl.compressed_fc_forward(L2, X).cpu().numpy(), ref, False)      # AUTO falls back to the sparse path
 
 
+@pytest.mark.parametrize("B", [1, 3, 5, 8, 13])
+def test_sparse_path_repeats_bit_for_bit_up_to_eight_images_a_launch(B):
+    """Batch tiles of up to 8 images sum every row in a fixed order (a tile per wavefront,
+    the tiles added in wavefront order): repeated calls agree bit for bit, also for a
+    batch that fills its tile only partly (3, 5) or takes two launches (13 = 8 + 5).
+    Rows whose entries lie in two chunks, runs of lanes inside one row and rows that
+    begin with a record are all present at this density and width."""
+    torch = torch_cuda()
+    rng = np.random.default_rng(50 + B)
+    W = rand_pruned(rng, 300, 400, 0.45)
+    L = cl.compress_layer(W, 5, 4, 128, 128, upload=True)
+    Xh = rng.standard_normal((B, 400)).astype(np.float32)
+    X = torch.from_numpy(Xh).cuda()
+    first = cl.compressed_fc_forward(L, X, path=cl.PATH_SPARSE).clone()
+    assert_close(first.cpu().numpy(), fc_ref(oracle.dense_weights(oracle.compress_layer(W, 5, 4, 128, 128)), Xh), False)
+    for _ in range(5):
+        assert torch.equal(cl.compressed_fc_forward(L, X, path=cl.PATH_SPARSE), first)
+
+
 def test_config3_alexnet_fc_stack_batch256():
     """configs[2] at full size, in the launch configuration the benchmark times:
     fc6 -> ReLU -> fc7 -> ReLU -> fc8 at batch 256 (AUTO: the wide sparse path for the
@@ -298,7 +317,7 @@ def test_config3_alexnet_fc_stack_batch256():
 
 
 STACK_PATHS = (cl.PATH_AUTO, cl.PATH_MFMA_F32, cl.PATH_MFMA_BF16, cl.PATH_SPARSE, cl.PATH_SPARSE_WIDE)
-ATOMIC_PATHS = (cl.PATH_SPARSE,)      # unordered LDS float atomics: tolerance-identical, not bit-identical, from run to run
+ATOMIC_PATHS = (cl.PATH_SPARSE,)      # may use unordered LDS float atomics (batch tiles of 16, tall blocks): held to tolerance, not bit for bit
 
 
 def _stack(dims, blocks, rng, density=0.12):
@@ -339,7 +358,7 @@ def test_fc_stack_forward(dims, blocks, B):
             a = cl.compressed_fc_forward(layers[li], given, bd[li], relu=li < n - 1, path=path)
             gate = assert_close_bf16 if path == cl.PATH_MFMA_BF16 else assert_close
             gate(a.cpu().numpy(), fc_ref(dense[li], given.cpu().numpy(), biases[li]), li < n - 1)
-        if path in ATOMIC_PATHS or (path == cl.PATH_AUTO and B <= 4):
+        if path in ATOMIC_PATHS or (path == cl.PATH_AUTO and B <= 8):
             assert rel_err(Y.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= TOL, path
         else:
             assert torch.equal(Y, a), path
@@ -803,20 +822,20 @@ def test_config5_vgg_fc_layers_full_size():
 
 
 def test_auto_path_on_both_sides_of_the_crossover():
-    """CL_PATH_AUTO picks the sparse kernel for 4 images and the MFMA kernel for 5:
+    """CL_PATH_AUTO picks the sparse kernel for 8 images and the MFMA kernel for 9:
     both results must match the oracle, and each must equal the result of naming
-    the path."""
+    the path (both are run-to-run identical at these sizes)."""
     torch = torch_cuda()
     rng = np.random.default_rng(11)
     W = rand_pruned(rng, 300, 520, 0.09)
     L, m, oW = check_decode(W, 5, 4, 128, 128)
-    for B, named in ((4, cl.PATH_SPARSE), (5, cl.PATH_MFMA_F32)):
+    for B, named in ((8, cl.PATH_SPARSE), (9, cl.PATH_MFMA_F32)):
         X = np.maximum(rng.standard_normal((B, 520)), 0).astype(np.float32)
         Xd = torch.from_numpy(X).cuda()
         Y = cl.compressed_fc_forward(L, Xd)
         assert_close(Y.cpu().numpy(), fc_ref(oW, X), False)
-        if named == cl.PATH_MFMA_F32:       # the MFMA path is run-to-run deterministic
-            assert torch.equal(Y, cl.compressed_fc_forward(L, Xd, path=named))
+        assert cl.fc_resolved_path(L, B, cl.PATH_AUTO) == named
+        assert torch.equal(Y, cl.compressed_fc_forward(L, Xd, path=named))
         assert cl.fc_workspace_bytes(L, B) == cl.fc_workspace_bytes(L, B, named)
 
 
