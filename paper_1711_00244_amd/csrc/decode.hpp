@@ -43,6 +43,18 @@ template <int W> __device__ __forceinline__ void load_floats(const float *p, flo
 
 template <> __device__ __forceinline__ void load_floats<1>(const float *p, float *dst) { dst[0] = *p; }
 
+// and the store
+template <int W> __device__ __forceinline__ void store_floats(float *p, const float *src)
+{
+    typedef float vec_t __attribute__((ext_vector_type(W)));
+    vec_t v;
+#pragma unroll
+    for (int i = 0; i < W; ++i) v[i] = src[i];
+    *(vec_t *)p = v;
+}
+
+template <> __device__ __forceinline__ void store_floats<1>(float *p, const float *src) { *p = src[0]; }
+
 // Decode tables and codebook in LDS.
 struct Tables {
     const lut_t *vlut;
@@ -225,6 +237,39 @@ template <class Look, class Put>
 __device__ __forceinline__ void place_entries(const Symbols &y, uint32_t sum, Look look, Put put)
 {
     place_from<0>(y, sum - 1u, look, put);
+}
+
+// The walk for callers that fetch something per entry and then work on it in order: the
+// entries are taken G at a time, fetch(u, v, position) is called for the G of them first (in
+// every lane, value index 0 and a position one further for entries a lane does not have),
+// so that what it loads is in flight together and waited for once; then use(u) for the
+// lane's own entries, in order.  fetch and use share their storage through the slot number
+// u < G.  Entries past the wavefront's longest record are skipped.
+template <int G, int J, class Fetch, class Use>
+__device__ __forceinline__ void groups_from(const Symbols &y, uint32_t pos, Fetch &fetch, Use &use)
+{
+    if constexpr (J < kMaxEntries) {
+        if ((uint32_t)J >= y.nmax) return;                                  // uniform, once per group
+        constexpr int N = kMaxEntries - J < G ? kMaxEntries - J : G;
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            if ((uint32_t)(J + u) < y.nmax) {                               // uniform
+                const uint32_t z = (y.z[(J + u) / 4] >> (8 * ((J + u) % 4))) & 0xffu, v = (y.v[(J + u) / 4] >> (8 * ((J + u) % 4))) & 0xffu;
+                pos += z + 1u;
+                fetch(u, v, pos);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < N; ++u)
+            if ((uint32_t)(J + u) < y.n) use(u);
+        groups_from<G, J + N>(y, pos, fetch, use);
+    }
+}
+
+template <int G, class Fetch, class Use>
+__device__ __forceinline__ void for_each_entry_grouped(const Symbols &y, uint32_t sum, Fetch fetch, Use use)
+{
+    groups_from<G, 0>(y, sum - 1u, fetch, use);
 }
 
 struct BlockGeom {

@@ -75,6 +75,17 @@ struct PrevSlots {
 constexpr int kPrivateTileBT = 8, kPrivateTileRows = 256;
 __host__ __device__ constexpr bool private_tiles(int bh, int bt) { return bt <= kPrivateTileBT && bh <= kPrivateTileRows; }
 
+// Where a column's BT images lie in the LDS slab: as 16-byte groups of four, and for BT > 4 the
+// groups of a column rotated by the column number.  Lanes that read group g of 64 arbitrary
+// columns then spread over all 32 banks; unrotated, a column stride of 32 or 64 bytes would put
+// them on half or a quarter of the banks.
+template <int BT> __device__ __forceinline__ int x_group(int col, int g)
+{
+    if constexpr (BT == 8) return (g + (col >> 2)) & 1;
+    else if constexpr (BT == 16) return (g + (col >> 1)) & 3;
+    else return g;
+}
+
 // Inclusive sums over the lanes of a wavefront in segments: a lane with `start` begins a
 // segment.  (value, started) pairs combine as (b.started ? b.value : a.value + b.value,
 // a.started | b.started), which is associative, so the usual doubling steps apply.
@@ -170,12 +181,30 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
                 xs[t * BT + b] = prev.relu ? fmaxf(acc, 0.0f) : acc;
             }
         }
-    } else if (slab) {
+    } else if (slab && BT < 4) {
 #pragma unroll
         for (int b = 0; b < BT; ++b)
             for (int t = threadIdx.x; t < width; t += blockDim.x) xs[t * BT + b] = b < nb ? X[(size_t)b * L.K + col_a + t] : 0.0f;
+    } else if (slab) {
+        // a column's images are requested together and stored together
+        for (int t = threadIdx.x; t < width; t += blockDim.x) {
+            float v[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) v[b] = b < nb ? X[(size_t)b * L.K + col_a + t] : 0.0f;
+            constexpr int kW = BT < 4 ? BT : 4;
+#pragma unroll
+            for (int q = 0; q < BT / kW; ++q) store_floats<kW>(xs + t * BT + x_group<BT>(t, q) * kW, v + q * kW);
+        }
     }
-    for (int t = threadIdx.x; t < n_tiles * L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
+    // (16 bytes at a time, and four outputs per thread at the end, pay from four images on -
+    // measured; below, they cost a microsecond of a step)
+    if (BT >= 4) {
+        const int n = n_tiles * L.bh * BT;          // a multiple of 4
+        float4 *z4 = (float4 *)ytile;
+        for (int t = threadIdx.x; t < n / 4; t += blockDim.x) z4[t] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    } else {
+        for (int t = threadIdx.x; t < n_tiles * L.bh * BT; t += blockDim.x) ytile[t] = 0.0f;
+    }
     store_tables(s, L, tr);
     __syncthreads();
 #pragma unroll
@@ -231,9 +260,8 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             float acc[BT], head[BT];
 #pragma unroll
             for (int b = 0; b < BT; ++b) acc[b] = head[b] = 0.0f;
-            for_each_entry<false>(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
-                uint32_t r, cc;
-                split(pos, r, cc);
+            // a change of row: the first row's sum is kept for the end, later ones are stored
+            auto enter_row = [&](uint32_t r) {
                 if (r != cur) {
                     if (cur == kNone) first_row = r;
                     else if (!several) {
@@ -248,12 +276,35 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
                     for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
                     cur = r;
                 }
-                const float w = s.T.cb[v];
-                float x[BT];
-                load_x((int)cc, x);
+            };
+            constexpr int G = BT <= 2 || BT > 8 ? 1 : 3;
+            if constexpr (G == 1) {
+                for_each_entry<false>(y, st.sum, [&](uint32_t, uint32_t v, uint32_t, uint32_t pos) {
+                    uint32_t r, cc;
+                    split(pos, r, cc);
+                    enter_row(r);
+                    const float w = s.T.cb[v];
+                    float x[BT];
+                    load_x((int)cc, x);
 #pragma unroll
-                for (int b = 0; b < BT; ++b) acc[b] += w * x[b];
-            });
+                    for (int b = 0; b < BT; ++b) acc[b] += w * x[b];
+                });
+            } else {
+                // the codebook and activation reads of G entries go out together: the row logic
+                // is all branches, behind which the compiler leaves each read where it is used
+                uint32_t rows[G];
+                float ws[G], xv[G][BT];
+                for_each_entry_grouped<G>(y, st.sum, [&](int u, uint32_t v, uint32_t pos) {
+                    uint32_t cc;
+                    split(pos, rows[u], cc);
+                    ws[u] = s.T.cb[v];
+                    load_x((int)cc, xv[u]);
+                }, [&](int u) {
+                    enter_row(rows[u]);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) acc[b] += ws[u] * xv[u][b];
+                });
+            }
             // cur: the lane's last row (kNone for a lane without a record), acc its sum so far
             // (every lane takes part in the exchange: a lane that sat it out would hand its
             // neighbour a zero)
@@ -291,7 +342,7 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             with_split([&](int cc, float (&x)[BT]) {
                 constexpr int kW = BT < 4 ? BT : 4;
 #pragma unroll
-                for (int q = 0; q < BT / kW; ++q) load_floats<kW>(xs + (xoff + cc) * BT + q * kW, x + q * kW);
+                for (int q = 0; q < BT / kW; ++q) load_floats<kW>(xs + (xoff + cc) * BT + x_group<BT>(xoff + cc, q) * kW, x + q * kW);
             });
         } else {
             const float *xg = X + g.col_id;
@@ -303,10 +354,25 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
     }
     __syncthreads();
     float *mine = part + (size_t)wg * L.bh * BT;
-    for (int t = threadIdx.x; t < L.bh * BT; t += blockDim.x) {
-        float sum = ytile[t];
-        for (int w = 1; w < n_tiles; ++w) sum += ytile[(size_t)w * L.bh * BT + t];   // (wavefront order: the same every run)
-        mine[t] = sum;
+    // (tiles added in wavefront order: the same every run; four outputs per thread where a tile's size allows)
+    const int per_tile = L.bh * BT;
+    if (BT >= 4) {
+        for (int t = threadIdx.x; t < per_tile / 4; t += blockDim.x) {
+            float4 v[kWaves];
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) v[w] = w < n_tiles ? ((const float4 *)(ytile + (size_t)w * per_tile))[t] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            float4 sum = v[0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w)
+                if (w < n_tiles) { sum.x += v[w].x; sum.y += v[w].y; sum.z += v[w].z; sum.w += v[w].w; }
+            ((float4 *)mine)[t] = sum;
+        }
+    } else {
+        for (int t = threadIdx.x; t < per_tile; t += blockDim.x) {
+            float sum = ytile[t];
+            for (int w = 1; w < n_tiles; ++w) sum += ytile[(size_t)w * per_tile + t];
+            mine[t] = sum;
+        }
     }
 }
 
