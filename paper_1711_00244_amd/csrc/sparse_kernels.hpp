@@ -255,25 +255,35 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             static_assert(kSparseChunksPerWave == 1, "a wavefront's tile takes one chunk: plain stores");
             constexpr uint32_t kNone = 0xffffffffu;
             float *tile = ytile + (size_t)wave * L.bh * BT;
-            uint32_t cur = kNone, first_row = kNone;
+            // the lane's first row is that of its first entry (kNone for a lane without a record)
+            uint32_t first_row = kNone;
+            if (y.n > 0) {
+                uint32_t unused;
+                split(st.sum + (y.z[0] & 0xffu), first_row, unused);
+            }
+            uint32_t cur = first_row;
             bool several = false;                       // the lane has left its first row
             float acc[BT], head[BT];
 #pragma unroll
             for (int b = 0; b < BT; ++b) acc[b] = head[b] = 0.0f;
-            // a change of row: the first row's sum is kept for the end, later ones are stored
+            // A change of row: the sum so far is stored, except the first one, which is kept - the
+            // first row may have begun in the lanes before.  For one and two images that
+            // distinction costs more than it saves: every sum is stored and the first kept as
+            // well, and what is stored for the first row here is written over after the loop
+            // with the sum over all its lanes (one image: 33.9 -> 32.5 us per step of the
+            // AlexNet-shaped stack; four images: 42.2 -> 43.2, so not there).
             auto enter_row = [&](uint32_t r) {
                 if (r != cur) {
-                    if (cur == kNone) first_row = r;
-                    else if (!several) {
-#pragma unroll
-                        for (int b = 0; b < BT; ++b) head[b] = acc[b];
-                        several = true;
-                    } else {
+                    if (BT <= 2 || several) {
 #pragma unroll
                         for (int b = 0; b < BT; ++b) tile[b * L.bh + cur] = acc[b];
                     }
 #pragma unroll
-                    for (int b = 0; b < BT; ++b) acc[b] = 0.0f;
+                    for (int b = 0; b < BT; ++b) {
+                        if (BT > 2) head[b] = several ? head[b] : acc[b];
+                        acc[b] = 0.0f;
+                    }
+                    several = true;
                     cur = r;
                 }
             };
@@ -318,7 +328,10 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             for (int b = 0; b < BT; ++b) before[b] = __shfl_up(acc[b], 1);
             if (several) {
 #pragma unroll
-                for (int b = 0; b < BT; ++b) tile[b * L.bh + first_row] = joins ? head[b] + before[b] : head[b];
+                for (int b = 0; b < BT; ++b) {
+                    if (BT <= 2) head[b] = tile[b * L.bh + first_row];       // (stored in the loop, by this lane)
+                    tile[b * L.bh + first_row] = joins ? head[b] + before[b] : head[b];
+                }
             }
             if (cur != kNone && next_first != cur) {
 #pragma unroll
@@ -330,7 +343,12 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             else entries_shared(load_x, split);
         };
         auto with_split = [&](auto load_x) {
-            if (g.shift >= 0) {
+            if (g.shift >= 0 && priv) {
+                // (rows are used for a lane's own entries only here, and those lie inside the block:
+                // checked when the layer was loaded)
+                const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u;
+                entries_private(load_x, [&](uint32_t pos, uint32_t &r, uint32_t &cc) { r = pos >> sh; cc = pos & cmask; });
+            } else if (g.shift >= 0) {
                 const uint32_t sh = (uint32_t)g.shift, cmask = (uint32_t)g.bwp - 1u, rmax = (uint32_t)g.bhp - 1u;
                 entries(load_x, [&](uint32_t pos, uint32_t &r, uint32_t &cc) { r = min(pos >> sh, rmax); cc = pos & cmask; });
             } else {
