@@ -755,13 +755,28 @@ static int32_t run_mfma_layer(const cl_layer *L, const LayerDev &D, const MfmaPl
 
 // The decoding launch of the wide path for up to kExpandJobs layers at once, each
 // into its own list.  Layers without chunks are skipped (their lists are empty).
-static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *const *ents, int n, int ipl, hipStream_t st)
+// (xt_of: the layer whose activations d_X, batch x K, the launch lays out as well, into xt
+// with the image axis padded to bp - or null)
+static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *const *ents, int n, int ipl, hipStream_t st,
+                                  const cl_layer *xt_of = nullptr, const float *d_X = nullptr, float *xt = nullptr, int batch = 0,
+                                  int bp = 0)
 {
     ExpandJobs jobs{};
     jobs.ipl = (uint32_t)ipl;
     size_t lds = 0;
     int64_t wgs = 0;
     int used = 0;
+    if (xt_of) {
+        jobs.X = d_X;
+        jobs.XT = xt;
+        jobs.B = batch;
+        jobs.K = xt_of->desc.K;
+        jobs.Bp = bp;
+        jobs.bw = xt_of->desc.block_w;
+        jobs.rows = xt_of->nbw * kTile;
+        jobs.t_wgs = (uint32_t)(((int64_t)(jobs.rows / 32) * (bp / 32) + 1) / 2);
+        wgs = jobs.t_wgs;
+    }
     for (int i = 0; i < n; ++i) {
         const cl_layer *L = layers[i];
         if (L->n_chunks == 0) continue;
@@ -772,9 +787,15 @@ static int32_t launch_wide_expand(const cl_layer *const *layers, WideEntry *cons
         lds = std::max(lds, table_image_bytes(L->val_lut_bits, L->idx_lut_bits, 1 << L->desc.weight_bits));
         ++used;
     }
-    if (!used) return CL_OK;
+    if (!used && !jobs.t_wgs) return CL_OK;
     for (int i = used; i <= kExpandJobs; ++i) jobs.wg0[i] = i == used ? (uint32_t)wgs : UINT32_MAX;
-    for (int i = used; i < kExpandJobs; ++i) jobs.L[i] = jobs.L[0];
+    if (!used) {
+        // nothing to decode: the launch only lays the activations out (the job table names the
+        // first layer, whose range of workgroups is empty)
+        jobs.L[0] = make_dev(xt_of);
+        jobs.wg0[0] = (uint32_t)wgs;
+    }
+    for (int i = std::max(used, 1); i < kExpandJobs; ++i) jobs.L[i] = jobs.L[0];
     static LdsLimit seen;
     if (int32_t rc = ensure_lds((const void *)wide_expand_kernel, lds, seen)) return rc;
     dim3 egrid;
@@ -791,15 +812,16 @@ static int32_t run_wide_layer(const cl_layer *L, const LayerDev &D, const WidePl
                               WideEntry *ent, bool expanded, const float *d_bias, float *d_Y, int next_bp, int batch, int relu,
                               hipStream_t st)
 {
-    if (d_X) {
+    int32_t rc = CL_EINVAL;
+    if (!expanded) {
+        // one launch decodes the layer and lays its activations out
+        if ((rc = launch_wide_expand(&L, &ent, 1, P.ipl, st, d_X ? L : nullptr, d_X, xt, batch, P.Bp))) return rc;
+    } else if (d_X) {
         const int rows = L->nbw * kTile;
         hipLaunchKernelGGL(transpose_pad_kernel, dim3((unsigned)(rows / 32), (unsigned)(P.Bp / 32)), dim3(256), 0, st,
                            d_X, xt, batch, L->desc.K, P.Bp, L->desc.block_w, rows);
         HIP_TRY(hipGetLastError());
     }
-    int32_t rc = CL_EINVAL;
-    if (!expanded)
-        if ((rc = launch_wide_expand(&L, &ent, 1, P.ipl, st))) return rc;
     timing_begin(st);
     switch (P.ipl) {
     case 1: rc = launch_wide_mul<1>(D, L->n_panels, P, xt, part, ent, st); break;
@@ -994,6 +1016,9 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
     // (the fixed part of such a launch - start, tables, the dependent loads - is a third of fc7's).
     const size_t ent0 = act0 + (size_t)R * P.act_bytes;
     auto ent_of = [&](int i) { return (WideEntry *)(ws + ent0 + P.ent_off[i]); };
+    // (the first of these launches also lays out the input of the stack when its first layer is
+    // one of them)
+    bool x_laid_out = false;
     {
         const cl_layer *todo[kExpandJobs];
         WideEntry *ents[kExpandJobs];
@@ -1007,12 +1032,16 @@ extern "C" int32_t cl_compressed_fc_stack_forward(const cl_layer *const *layers,
                 ++n;
             }
             if (n == kExpandJobs || (i == n_layers && n > 0)) {
-                if (int32_t rc = launch_wide_expand(todo, ents, n, ipl_of_stack, st)) return rc;
+                const bool with_x = !x_laid_out && P.path[0] == CL_PATH_SPARSE_WIDE;
+                if (int32_t rc = launch_wide_expand(todo, ents, n, ipl_of_stack, st, with_x ? layers[0] : nullptr, d_X,
+                                                    (float *)region(xt0, P.xt_bytes, 0), batch, P.wide[0].Bp))
+                    return rc;
+                x_laid_out = x_laid_out || with_x;
                 n = 0;
             }
         }
     }
-    const float *in = d_X;              // the layer's input as batch x K, or null when it sits in its xt region
+    const float *in = x_laid_out ? nullptr : d_X;    // the layer's input as batch x K, or null when it sits in its xt region
     for (int i = 0; i < n_layers; ++i) {
         const cl_layer *L = layers[i];
         const LayerDev D = make_dev(L);

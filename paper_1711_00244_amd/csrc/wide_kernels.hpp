@@ -49,10 +49,34 @@ struct ExpandJobs {
     WideEntry *ent[kExpandJobs];
     uint32_t wg0[kExpandJobs + 1];
     uint32_t ipl;                   // images per lane of the multiplying kernel: the row offsets count its sum registers
+    // The same launch can lay out the activations of the first layer (what transpose_pad_kernel
+    // does: XT rows x Bp from X B x K): its first t_wgs workgroups do that, two 32 x 32 tiles
+    // each, and are through while the decoding workgroups wait for their records.
+    const float *X;
+    float *XT;
+    int B, K, Bp, bw, rows;
+    uint32_t t_wgs;
 };
 
 __global__ __launch_bounds__(kThreads) void wide_expand_kernel(ExpandJobs jobs)
 {
+    if (blockIdx.x < jobs.t_wgs) {
+        __shared__ float t[2][32][33];
+        const int half = (int)(threadIdx.x >> 8), tid = (int)(threadIdx.x & 255);
+        const int row_tiles = jobs.rows / 32, tile = (int)blockIdx.x * 2 + half;
+        const bool real = tile < row_tiles * (jobs.Bp / 32);
+        const int r0 = (tile % row_tiles) * 32, b0 = (tile / row_tiles) * 32;
+        const int tx = tid & 31, ty = tid >> 5;       // 32 x 8
+        if (real)
+            for (int i = ty; i < 32; i += 8) {
+                const int b = b0 + i, k = xt_row_to_k(r0 + tx, jobs.bw, jobs.K);
+                t[half][i][tx] = (b < jobs.B && k >= 0) ? jobs.X[(size_t)b * jobs.K + k] : 0.0f;
+            }
+        __syncthreads();
+        if (real)
+            for (int i = ty; i < 32; i += 8) jobs.XT[(size_t)(r0 + i) * jobs.Bp + b0 + tx] = t[half][tx][i];
+        return;
+    }
     int job = 0;
 #pragma unroll
     for (int i = 1; i < kExpandJobs; ++i)
