@@ -268,9 +268,9 @@ __device__ __forceinline__ void fc_sparse_body(const LayerDev &L, const float *_
             for (int b = 0; b < BT; ++b) acc[b] = head[b] = 0.0f;
             // A change of row: the sum so far is stored, except the first one, which is kept - the
             // first row may have begun in the lanes before.  For one and two images that
-            // distinction costs more than it saves: every sum is stored and the first kept as
-            // well, and what is stored for the first row here is written over after the loop
-            // with the sum over all its lanes (one image: 33.9 -> 32.5 us per step of the
+            // distinction costs more than it saves: every sum is stored, the first row's too, and
+            // that one is read back after the loop and written over with the sum over all its
+            // lanes (one image: 33.9 -> 32.5 us per step of the
             // AlexNet-shaped stack; four images: 42.2 -> 43.2, so not there).
             auto enter_row = [&](uint32_t r) {
                 if (r != cur) {
