@@ -372,3 +372,14 @@ def test_conv_block_h_divides_a_groups_filters():
     for oc, g, bh in [(384, 2, 128), (60, 3, 16), (26, 2, 128)]:
         h = cl.conv_block_h(oc, g, bh)
         assert (oc // g) % h == 0 and h <= bh
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box of this build has one GPU: the benchmark says so and exits without touching
+    a device when asked for more."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
